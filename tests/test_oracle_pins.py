@@ -1,0 +1,374 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests calls the HIP library.  Every check compares the oracle
+with something other than itself: hand values of the Code equation, numpy
+one-liners, a dict-of-lists brute-force clustering, a textbook dense attention,
+a full argsort, and closed-form special cases.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import sik_workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bits_of(x, dtype):
+    return W.to_bits(np.asarray(x, np.float32), dtype)
+
+
+def f64(bits, dtype):
+    return W.from_bits(bits, dtype).astype(np.float64)
+
+
+def small_cfg(**kw):
+    base = dict(batch=2, n_kv_heads=2, n_q_heads=4, head_dim=32, context=200, top_k=17, dtype="bf16",
+                sigma="lognormal", outlier_frac=0.05, outlier_scale=8.0, seed=11)
+    base.update(kw)
+    return W.scaled(W.CONFIGS["C2"], **base)
+
+
+def dense_attention(q, K, V, scale):
+    """Textbook softmax(q K^T * scale) V for one head, fp64."""
+    z = (K @ q) * scale
+    p = np.exp(z - z.max())
+    p /= p.sum()
+    return p @ V
+
+
+# --------------------------------------------------------------------------- widening
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_widen_all_bit_patterns(oracle, dtype):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    got = oracle.widen(bits, dtype)
+    with np.errstate(all="ignore"):
+        want = f64(bits, dtype)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok], want[ok])
+    assert np.array_equal(np.signbit(got[ok]), np.signbit(want[ok]))
+
+
+# --------------------------------------------------------------------------- Code / pack
+def test_code_hand_values_eq3(oracle):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "eq3_sign_codes.txt")) if l[0] in "+-"]
+    assert len(rows) == 16
+    for dtype in ("fp16", "bf16"):
+        for g in range(8):  # place the pattern in group g of a D=32 key, all other dims negative
+            for *signs, code in rows:
+                k = -np.ones((1, 1, 1, 32), np.float32)
+                for e, s in enumerate(signs):
+                    k[0, 0, 0, 4 * g + e] = 1.5 if s == "+" else -0.25
+                c = oracle.encode(bits_of(k, dtype), dtype, np.zeros((1, 1, 32), np.float32), 0, 1)
+                byte = int(c[0, 0, 0, g // 2])
+                nib = (byte >> 4) if g % 2 == 0 else (byte & 15)
+                assert nib == int(code), (dtype, g, signs)
+                other = (byte & 15) if g % 2 == 0 else (byte >> 4)
+                assert other == 0
+                assert int(c.sum()) == byte  # nothing leaked into other bytes
+
+
+def test_plane_size_matches_overhead_analysis(oracle):
+    d, nbytes = [l.split() for l in open(os.path.join(GOLDEN, "memory_model.txt")) if l[0].isdigit()][0]
+    cfg = small_cfg(head_dim=int(d), context=40, batch=1, n_kv_heads=1, n_q_heads=1)
+    K, _ = W.make_cache(cfg)
+    c = oracle.encode(K, cfg.dtype, np.zeros((1, 1, int(d)), np.float32), 0, 40)
+    assert c.shape[-1] == int(nbytes) and c.nbytes == 40 * int(d) // 8
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_sign_bits_match_numpy_and_round_trip(oracle, dtype):
+    cfg = small_cfg(dtype=dtype, head_dim=64)
+    K, _ = W.make_cache(cfg, channel_offset_std=2.0)
+    rng = np.random.default_rng(5)
+    mu = rng.normal(0, 2, size=(cfg.batch, cfg.n_kv_heads, 64)).astype(np.float32)
+    codes = oracle.encode(K, dtype, mu, 0, cfg.context)
+    want_bits = f64(K, dtype) >= mu[:, :, None, :].astype(np.float64)
+    got_bits = np.unpackbits(codes, axis=-1, bitorder="big").astype(bool)
+    assert np.array_equal(got_bits, want_bits)
+    assert np.array_equal(np.packbits(got_bits, axis=-1, bitorder="big"), codes)
+
+
+def test_sign_of_zero_and_ties_with_mu(oracle):
+    # K == mu and -0 >= +0 both count as "+"
+    k = np.array([0.0, -0.0, 1.0, -1.0, 0.5, 0.5, 0.25, -0.25], np.float32).reshape(1, 1, 1, 8)
+    mu = np.array([0.0, 0.0, 1.0, -1.0, 0.5, 0.75, 0.25, 0.0], np.float32).reshape(1, 1, 8)
+    c = oracle.encode(bits_of(k, "fp16"), "fp16", mu, 0, 1)
+    assert int(c[0, 0, 0, 0]) == 0b11111010
+
+
+def test_reflection_flips_every_bit(oracle):
+    cfg = small_cfg(dtype="fp16", sigma="unit", outlier_frac=0.0, outlier_count=0)
+    K, _ = W.make_cache(cfg)
+    Kf = W.from_bits(K, "fp16")
+    mu = np.zeros((cfg.batch, cfg.n_kv_heads, cfg.head_dim), np.float32)
+    c1 = oracle.encode(K, "fp16", mu, 0, cfg.context)
+    c2 = oracle.encode(bits_of(-Kf, "fp16"), "fp16", mu, 0, cfg.context)
+    nz = np.packbits(Kf != 0, axis=-1, bitorder="big")
+    assert np.array_equal((c1 ^ c2) & nz, nz)
+
+
+def test_encode_range_only_touches_requested_tokens(oracle):
+    cfg = small_cfg()
+    K, _ = W.make_cache(cfg)
+    mu = np.zeros((cfg.batch, cfg.n_kv_heads, cfg.head_dim), np.float32)
+    full = oracle.encode(K, cfg.dtype, mu, 0, cfg.context)
+    part = np.full_like(full, 0xAA)
+    oracle.encode(K, cfg.dtype, mu, 50, 7, part)
+    assert np.array_equal(part[:, :, 50:57], full[:, :, 50:57])
+    assert np.all(part[:, :, :50] == 0xAA) and np.all(part[:, :, 57:] == 0xAA)
+
+
+# --------------------------------------------------------------------------- mu
+def test_mean_matches_numpy_and_centres(oracle):
+    cfg = small_cfg(context=333)
+    K, _ = W.make_cache(cfg, capacity=340, channel_offset_std=2.0)
+    sl = np.array([333, 150], np.int32)
+    mu = oracle.mean(K, cfg.dtype, sl)
+    Kd = f64(K, cfg.dtype)
+    for b in range(2):
+        want = Kd[b, :, :sl[b]].mean(axis=1)
+        assert np.array_equal(mu[b], want.astype(np.float32))
+        centred = Kd[b, :, :sl[b]] - mu[b][:, None, :]
+        assert np.abs(centred.mean(axis=1)).max() <= 1e-6 * np.abs(Kd).max()
+
+
+def test_centring_balances_signs_max_entropy_condition(oracle):
+    L = 4096
+    cfg = small_cfg(batch=1, n_kv_heads=1, n_q_heads=1, context=L, head_dim=32, sigma="unit",
+                    outlier_frac=0.0, outlier_count=0)
+    K, _ = W.make_cache(cfg, channel_offset_std=2.0)
+    sl = np.array([L], np.int32)
+    mu = oracle.mean(K, cfg.dtype, sl)
+    frac = np.unpackbits(oracle.encode(K, cfg.dtype, mu, 0, L), axis=-1, bitorder="big").mean(axis=2)
+    assert np.abs(frac - 0.5).max() <= 4 / np.sqrt(L)          # P(+) = P(-) = 1/2 after centring
+    raw = np.unpackbits(oracle.encode(K, cfg.dtype, 0 * mu, 0, L), axis=-1, bitorder="big").mean(axis=2)
+    assert np.abs(raw - 0.5).max() > 0.2                        # and visibly not without it
+
+
+# --------------------------------------------------------------------------- codebook
+def test_codebook_brute_force_and_invariants(oracle):
+    cfg = small_cfg(context=257)
+    K, _ = W.make_cache(cfg, capacity=260, channel_offset_std=1.0)
+    sl = np.array([257, 31], np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    Kd = f64(K, cfg.dtype)
+    G = cfg.head_dim // 4
+    for b in range(cfg.batch):
+        for h in range(cfg.n_kv_heads):
+            Kp = Kd[b, h, :sl[b]] - mu[b, h].astype(np.float64)
+            assert cnt[b, h].sum(axis=1).tolist() == [sl[b]] * G
+            for g in range(G):
+                clusters = {}
+                for i in range(sl[b]):
+                    sub = Kp[i, 4 * g:4 * g + 4]
+                    j = int("".join("1" if x >= 0 else "0" for x in sub), 2)
+                    clusters.setdefault(j, []).append(sub)
+                for j in range(16):
+                    members = clusters.get(j, [])
+                    assert cnt[b, h, g, j] == len(members)
+                    want = np.mean(members, axis=0) if members else np.zeros(4)
+                    assert np.array_equal(cb[b, h, g, j], want.astype(np.float32))
+                    # a centroid lies in the orthant of its own sign pattern (or is zero)
+                    for e in range(4):
+                        c = cb[b, h, g, j, e]
+                        assert c == 0 or (c > 0) == bool((j >> (3 - e)) & 1)
+            # sum_j |C_j| c_j = sum_i K'_i, which is ~0 after centring
+            tot = (cnt[b, h][..., None] * cb[b, h].astype(np.float64)).sum(axis=1).reshape(-1)
+            assert np.allclose(tot, Kp.sum(axis=0), atol=1e-4 * sl[b])
+
+
+def test_codes_passed_to_codebook_are_the_ones_used(oracle):
+    # a codebook built from all-zero codes puts every member into cluster 0
+    cfg = small_cfg(batch=1, n_kv_heads=1, n_q_heads=1, context=50)
+    K, _ = W.make_cache(cfg)
+    sl = np.array([50], np.int32)
+    mu = oracle.mean(K, cfg.dtype, sl)
+    cb, cnt = oracle.codebook(K, cfg.dtype, sl, mu, np.zeros((1, 1, 50, cfg.head_dim // 8), np.uint8))
+    assert np.all(cnt[..., 0] == 50) and np.all(cnt[..., 1:] == 0)
+    Kp = f64(K, cfg.dtype)[0, 0] - mu[0, 0]
+    assert np.allclose(cb[0, 0, :, 0, :].reshape(-1), Kp.mean(axis=0), rtol=1e-6, atol=1e-7)
+
+
+# --------------------------------------------------------------------------- table + score
+def test_score_equals_reconstruct_then_dot(oracle):
+    cfg = small_cfg(context=300, head_dim=64)
+    K, _ = W.make_cache(cfg, channel_offset_std=1.0)
+    sl = np.array([300, 123], np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    s = oracle.score(q, cfg.dtype, cb, codes, sl)
+    qd = f64(q, cfg.dtype)
+    R = cfg.n_q_heads // cfg.n_kv_heads
+    G = cfg.head_dim // 4
+    nib = np.stack([codes >> 4, codes & 15], axis=-1).reshape(*codes.shape[:3], G)  # [B,H,L,G]
+    for b in range(cfg.batch):
+        for hq in range(cfg.n_q_heads):
+            h = hq // R
+            # K_hat_i = concat_g c[g, code_i(g)]
+            Khat = cb[b, h][np.arange(G)[None, :], nib[b, h, :sl[b]]].reshape(sl[b], -1).astype(np.float64)
+            want = Khat @ qd[b, hq]
+            assert np.allclose(s[b, hq, :sl[b]], want, rtol=1e-12, atol=1e-12)
+            assert np.all(np.isneginf(s[b, hq, sl[b]:]))
+
+
+def test_singleton_clusters_make_scores_exact(oracle):
+    # 16 keys whose sub-vectors take 16 distinct sign patterns in every group: each occupied
+    # cluster has one member, so K_hat = K' and the LUT score is q.K' = q.K - q.mu exactly.
+    D, L = 32, 16
+    rng = np.random.default_rng(3)
+    mag = rng.uniform(0.5, 2.0, size=(L, D)).astype(np.float32)
+    K = np.empty((L, D), np.float32)
+    for g in range(D // 4):
+        perm = rng.permutation(16)
+        for i in range(L):
+            for e in range(4):
+                K[i, 4 * g + e] = mag[i, 4 * g + e] * (1 if (perm[i] >> (3 - e)) & 1 else -1)
+    Kb = bits_of(K, "fp16").reshape(1, 1, L, D)
+    sl = np.array([L], np.int32)
+    mu = np.zeros((1, 1, D), np.float32)  # encode against zero so the patterns are the ones built
+    codes = oracle.encode(Kb, "fp16", mu, 0, L)
+    cb, cnt = oracle.codebook(Kb, "fp16", sl, mu, codes)
+    assert cnt.max() == 1
+    q = bits_of(rng.normal(size=(1, 2, D)), "fp16")
+    s = oracle.score(q, "fp16", cb, codes, sl)
+    exact = f64(q, "fp16")[0] @ f64(Kb, "fp16")[0, 0].T
+    assert np.allclose(s[0], exact, rtol=1e-6, atol=1e-6)
+    got = oracle.topk(s, sl, 5)
+    for hq in range(2):
+        assert set(got[0, hq]) == set(np.argsort(-exact[hq])[:5])
+
+
+def test_gqa_mapping_query_head_reads_its_own_kv_head(oracle):
+    cfg = small_cfg(batch=1, n_kv_heads=2, n_q_heads=6, context=64)
+    K, V = W.make_cache(cfg)
+    sl = np.array([64], np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    s = oracle.score(q, cfg.dtype, cb, codes, sl)
+    for hq in range(6):
+        alone = oracle.score(q[:, hq:hq + 1], cfg.dtype, cb[:, hq // 3:hq // 3 + 1],
+                             codes[:, hq // 3:hq // 3 + 1], sl)
+        assert np.array_equal(alone[0, 0], s[0, hq])
+
+
+# --------------------------------------------------------------------------- top-k
+def test_topk_matches_full_sort(oracle):
+    rng = np.random.default_rng(9)
+    s = rng.normal(size=(2, 3, 500))
+    s[0, 1, 100:140] = s[0, 1, 7]          # a block of exact ties
+    sl = np.array([500, 77], np.int32)
+    for k in (1, 5, 77, 130, 500, 600):
+        idx = oracle.topk(s, sl, k)
+        for b in range(2):
+            for h in range(3):
+                L = sl[b]
+                order = np.lexsort((np.arange(L), -s[b, h, :L]))  # score desc, then index asc
+                want = list(order[:k]) + [-1] * max(0, k - L)
+                assert idx[b, h].tolist() == want
+    assert oracle.topk(s, sl, 1)[0, 0, 0] == np.argmax(s[0, 0])
+    assert sorted(oracle.topk(s, sl, 500)[0, 2].tolist()) == list(range(500))
+
+
+# --------------------------------------------------------------------------- attention
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_attention_over_everything_is_dense_attention(oracle, dtype):
+    cfg = small_cfg(dtype=dtype, context=150, head_dim=64, n_kv_heads=2, n_q_heads=6)
+    K, V = W.make_cache(cfg, capacity=160)
+    q, _, _ = W.make_step_inputs(cfg, 1)
+    L = 150
+    idx = np.tile(np.arange(L, dtype=np.int32), (cfg.batch, cfg.n_q_heads, 1))
+    out = oracle.sparse_attn(q, K, V, dtype, idx)
+    Kd, Vd, qd = f64(K, dtype), f64(V, dtype), f64(q, dtype)
+    for b in range(cfg.batch):
+        for hq in range(cfg.n_q_heads):
+            h = hq // 3
+            want = dense_attention(qd[b, hq], Kd[b, h, :L], Vd[b, h, :L], 1 / np.sqrt(64))
+            assert np.allclose(out[b, hq], want, rtol=1e-12, atol=1e-13)
+    # a custom scale is honoured
+    out2 = oracle.sparse_attn(q, K, V, dtype, idx, scale=0.37)
+    want = dense_attention(qd[0, 0], Kd[0, 0, :L], Vd[0, 0, :L], 0.37)
+    assert np.allclose(out2[0, 0], want, rtol=1e-12, atol=1e-13)
+
+
+def test_attention_special_cases(oracle):
+    cfg = small_cfg(context=90)
+    K, V = W.make_cache(cfg)
+    q, _, _ = W.make_step_inputs(cfg, 2)
+    Vd = f64(V, cfg.dtype)
+    rng = np.random.default_rng(1)
+    # |S| = 1: the output is that V row
+    one = rng.integers(0, 90, size=(cfg.batch, cfg.n_q_heads, 1)).astype(np.int32)
+    out = oracle.sparse_attn(q, K, V, cfg.dtype, one)
+    for b in range(cfg.batch):
+        for hq in range(cfg.n_q_heads):
+            assert np.array_equal(out[b, hq], Vd[b, hq // 2, one[b, hq, 0]])
+    # convex combination, order invariance, -1 padding ignored, empty -> 0
+    idx = np.stack([[rng.permutation(90)[:20] for _ in range(cfg.n_q_heads)] for _ in range(cfg.batch)]).astype(np.int32)
+    out = oracle.sparse_attn(q, K, V, cfg.dtype, idx)
+    for b in range(cfg.batch):
+        for hq in range(cfg.n_q_heads):
+            sel = Vd[b, hq // 2, idx[b, hq]]
+            assert np.all(out[b, hq] <= sel.max(axis=0) + 1e-12) and np.all(out[b, hq] >= sel.min(axis=0) - 1e-12)
+    perm = rng.permutation(20)
+    assert np.allclose(oracle.sparse_attn(q, K, V, cfg.dtype, idx[:, :, perm]), out, rtol=1e-12, atol=1e-13)
+    padded = np.concatenate([idx, -np.ones_like(idx[:, :, :5])], axis=2)
+    assert np.allclose(oracle.sparse_attn(q, K, V, cfg.dtype, padded), out, rtol=1e-12, atol=1e-13)
+    empty = -np.ones((cfg.batch, cfg.n_q_heads, 3), np.int32)
+    assert np.all(oracle.sparse_attn(q, K, V, cfg.dtype, empty) == 0)
+
+
+def test_attention_unchanged_by_channel_shift_of_keys(oracle):
+    # softmax(x - c) = softmax(x): shifting every key by the same vector adds q.c to all logits
+    rng = np.random.default_rng(4)
+    L, D = 40, 32
+    K = rng.integers(-40, 40, size=(1, 1, L, D)).astype(np.float32) / 8
+    shift = rng.integers(-16, 16, size=D).astype(np.float32) / 8
+    V = rng.normal(size=(1, 1, L, D)).astype(np.float32)
+    q = rng.integers(-8, 8, size=(1, 2, D)).astype(np.float32) / 4
+    idx = np.tile(np.arange(0, L, 2, dtype=np.int32), (1, 2, 1))
+    a = oracle.sparse_attn(bits_of(q, "bf16"), bits_of(K, "bf16"), bits_of(V, "bf16"), "bf16", idx)
+    b = oracle.sparse_attn(bits_of(q, "bf16"), bits_of(K - shift, "bf16"), bits_of(V, "bf16"), "bf16", idx)
+    assert np.array_equal(W.from_bits(bits_of(K - shift, "bf16"), "bf16"), K - shift)  # exactly representable
+    assert np.allclose(a, b, rtol=1e-10, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- decode step
+def test_decode_step_with_k_equal_context_is_dense_attention_and_appends(oracle):
+    cfg = small_cfg(context=120, top_k=121)
+    K, V = W.make_cache(cfg, capacity=128, channel_offset_std=1.5)
+    sl = np.array([120, 120], np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    K0 = K.copy()
+    out, idx = oracle.decode_step(q, kn, vn, K, V, cfg.dtype, sl, mu, cb, codes, 121)
+    assert sl.tolist() == [121, 121]
+    assert np.array_equal(K[:, :, 120], kn) and np.array_equal(V[:, :, 120], vn)
+    assert np.array_equal(K[:, :, :120], K0[:, :, :120])
+    want_code = np.packbits(f64(kn, cfg.dtype) >= mu.astype(np.float64), axis=-1, bitorder="big")
+    assert np.array_equal(codes[:, :, 120], want_code)
+    Kd, Vd, qd = f64(K, cfg.dtype), f64(V, cfg.dtype), f64(q, cfg.dtype)
+    for b in range(2):
+        for hq in range(cfg.n_q_heads):
+            assert sorted(idx[b, hq].tolist()) == list(range(121))
+            want = dense_attention(qd[b, hq], Kd[b, hq // 2, :121], Vd[b, hq // 2, :121], 1 / np.sqrt(cfg.head_dim))
+            assert np.allclose(out[b, hq], want, rtol=1e-11, atol=1e-13)
+
+
+def test_retrieval_quality_sanity(oracle):
+    # not a parity pin (the paper prints no recall value): the compressed-domain top-k must
+    # overlap the exact q.K top-k far more than chance.
+    cfg = W.scaled(W.CONFIGS["C2"], batch=1, n_kv_heads=2, n_q_heads=8, context=4096, top_k=128)
+    K, V = W.make_cache(cfg)
+    sl = np.array([4096], np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    idx = oracle.topk(oracle.score(q, cfg.dtype, cb, codes, sl), sl, 128)
+    Kd, qd = f64(K, cfg.dtype), f64(q, cfg.dtype)
+    rec = []
+    for hq in range(8):
+        exact = set(np.argsort(-(Kd[0, hq // 4] @ qd[0, hq]))[:128])
+        rec.append(len(exact & set(idx[0, hq])) / 128)
+    assert np.mean(rec) > 10 * 128 / 4096
