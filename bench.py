@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the Self-Indexing KV cache decode step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: [quantise-append]
+-> lookup table -> LUT-GEMV scores over the 1-bit code plane -> per-head top-k -> sparse attention
+over the selected 16-bit K/V rows, for one attention layer.  The default workload is the
+Llama-3-8B-shaped 32K-context layer decode (batch 1, 8 KV heads, 32 query heads, head_dim 128,
+top-k 1024, bf16).  Inputs are resident in HBM before the timed region; steps rotate over several
+distinct layer states so that the working set exceeds the 256 MB Infinity Cache.
+
+Prints ONE JSON line (see README / DESIGN for the fields).  One GPU only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0
+KERNELS = ("prep_kernel", "score_kernel", "select_kernel", "attn_kernel")
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--layers", type=int, default=0, help="distinct layer states to rotate over (0 = auto)")
+    ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of HIP-graph replay")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (the path has no cross-GPU exchange; see DESIGN.md); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2603_14224_amd as sik
+    import sik_workloads as W
+    from helpers import dev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    B, Hkv, Hq, D, L, k = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.context, cfg.top_k
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float16
+    per_layer = 2 * B * Hkv * L * D * 2 + B * Hkv * L * (D // 8)
+    n_layers = args.layers or max(2, min(16, -(-2 * 256 * 2 ** 20 // per_layer)))
+    total_steps = args.warmup + args.steps
+    # capacity: room for the appended rows of every step that lands on a layer
+    cap = L + (-(-total_steps * 3 // n_layers) + 8 if cfg.append else 0)
+    cap = (cap + 7) // 8 * 8
+    lay = sik.make_layout(B, Hkv, Hq, D, cap, tdt, tdt)
+    ws = sik.alloc_workspace(lay, k)
+
+    # ---- resident state: n_layers independent draws of the recipe, quantised by the library itself
+    layers = []
+    t0 = time.time()
+    for li in range(n_layers):
+        Kb, Vb = W.make_cache(cfg, capacity=cap, layer=li)
+        st = dict(K=dev(Kb, cfg.dtype), V=dev(Vb, cfg.dtype),
+                  sl=torch.full((B,), L, dtype=torch.int32, device="cuda"),
+                  mu=torch.empty(B, Hkv, D, device="cuda"),
+                  cb=torch.empty(B, Hkv, D // 4, 16, 4, device="cuda"),
+                  cnt=torch.empty(B, Hkv, D // 4, 16, dtype=torch.int32, device="cuda"),
+                  codes=torch.zeros(B, Hkv, cap, D // 8, dtype=torch.uint8, device="cuda"))
+        sik.sik_quantize_keys(lay, st["K"], st["sl"], 0, 0, sik.SIK_Q_FIT, st["mu"], st["cb"], st["cnt"],
+                              st["codes"], ws)
+        if li == 0:
+            host0 = (Kb, Vb)
+        layers.append(st)
+    torch.cuda.synchronize()
+    n_q = 8
+    qs, kns, vns = [], [], []
+    for s in range(n_q):
+        q, kn, vn = W.make_step_inputs(cfg, s)
+        qs.append(dev(q, cfg.dtype)); kns.append(dev(kn, cfg.dtype)); vns.append(dev(vn, cfg.dtype))
+    out = torch.empty(B, Hq, D, dtype=tdt, device="cuda")
+    gen_s = time.time() - t0
+
+    def step(i, profiled=False):
+        st = layers[i % n_layers]
+        j = i % n_q
+        fn = sik.sik_decode_step_profiled if profiled else sik.sik_decode_step
+        return fn(lay, qs[j], kns[j] if cfg.append else None, vns[j] if cfg.append else None, st["K"], st["V"],
+                  st["sl"], st["mu"], st["cb"], st["codes"], k, 0.0, out, None, ws)
+
+    def reset_lengths():
+        for st in layers:
+            st["sl"].fill_(L)
+
+    # ---- warm-up (untimed), then the timed region: exactly --steps steps between two synchronisations
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    def timed_stream():
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / args.steps
+
+    launch = "stream"
+    sec_stream = timed_stream()
+    sec_step = sec_stream
+    sec_graph = None
+    if not args.no_graph:
+        # one graph = one step on every layer in turn; replayed steps / n_layers times
+        reps = max(1, args.steps // n_layers)
+        reset_lengths()
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            for i in range(n_layers):
+                step(i)
+            torch.cuda.synchronize()
+            reset_lengths()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                for i in range(n_layers):
+                    step(i)
+        torch.cuda.synchronize()
+        reset_lengths()
+        for _ in range(max(1, args.warmup // n_layers)):
+            g.replay()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        sec_graph = (time.perf_counter() - t) / (reps * n_layers)
+        if sec_graph < sec_stream:
+            sec_step, launch = sec_graph, "hipgraph"
+    reset_lengths()
+
+    # ---- per-kernel durations, HIP events on the launch stream, same steps as the timed region
+    kus = np.zeros(4)
+    n_prof = min(args.steps, 200)
+    for i in range(n_prof):
+        kus += np.array(step(args.warmup + i, profiled=True))
+    kus /= n_prof
+    reset_lengths()
+
+    ab = W.algorithmic_bytes(cfg)
+    alg_by_kernel = {"prep_kernel": (B * Hkv * (2 * D * 2 + D // 8)) if cfg.append else 0,
+                     "score_kernel": ab["codes"], "select_kernel": 0, "attn_kernel": ab["gathered"]}
+    dom = max((1, 3), key=lambda i: kus[i])  # the two kernels that move the algorithmic bytes
+    dom_name = KERNELS[dom]
+    dom_bytes = alg_by_kernel[dom_name]
+    achieved = dom_bytes / (kus[dom] * 1e-6) / 1e9
+
+    step_us = sec_step * 1e6
+    result = {
+        "metric": "us per sparse decode step (and effective HBM GB/s)",
+        "value": round(step_us, 3),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sec_step * 1e3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "head_dim": D,
+                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "append": cfg.append,
+                   "layers_rotated": n_layers, "launch": launch},
+        "effective_hbm_GBps": round(ab["total"] / sec_step / 1e9, 1),
+        "effective_hbm_frac_of_8TBps": round(ab["total"] / sec_step / 1e9 / HBM_PEAK_GBPS, 4),
+        "algorithmic_bytes_per_step": ab["total"],
+        "us_per_step_stream_launch": round(sec_stream * 1e6, 3),
+        "us_per_step_hipgraph": None if sec_graph is None else round(sec_graph * 1e6, 3),
+        "kernel_us_hip_events": {KERNELS[i]: round(float(kus[i]), 3) for i in range(4)},
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": dom_bytes},
+        "setup_seconds": round(gen_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, host0, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, host0, budget_s):
+    """The CPU oracle, as it stands, on the same workload's layer 0: whole decode steps on the host
+    cores of this machine (OpenMP over batch x head), as many as fit the time budget."""
+    import numpy as np
+
+    import sik_workloads as W
+    from oracle import sik_oracle as oracle
+
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    used = oracle.set_threads(cores)
+    K, V = host0
+    B, cap = K.shape[0], K.shape[2]
+    sl = np.full(B, cfg.context, np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    n, t_total = 0, 0.0
+    while True:
+        q, kn, vn = W.make_step_inputs(cfg, n)
+        t = time.perf_counter()
+        if cfg.append and sl.max() < cap:
+            oracle.decode_step(q, kn, vn, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+        else:
+            oracle.decode_step(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+        t_total += time.perf_counter() - t
+        n += 1
+        if t_total >= budget_s or n >= 64:
+            break
+    oracle.set_threads(1)
+    return {"value": round(t_total / n * 1e6, 1), "unit": "us/step", "cores": used, "kind": "oracle",
+            "sample": f"{n} whole decode step(s) of layer 0 of the same workload (fp64 oracle, OpenMP over batch x head)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,158 @@
+/*
+ * sik.h -- C ABI of the Self-Indexing KV cache decode path for AMD MI355X (gfx950).
+ *
+ * The library implements the decode-time path of "Self-Indexing KVCache: Predicting
+ * Sparse Attention from Compressed Keys": sign-based 1-bit vector quantisation of the
+ * key cache, scoring of a query against the packed sign codes through per-group
+ * 16-entry lookup tables, per-query-head top-k selection, and softmax attention over
+ * only the selected tokens.
+ *
+ * General rules
+ *   - Every tensor pointer is a DEVICE pointer unless marked (host).  Buffers are
+ *     caller-owned, contiguous, row-major, 16-byte aligned.  The library never
+ *     allocates or frees device memory and keeps no state between calls.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  No call synchronises with the host.
+ *   - Return value: SIK_OK (0) or a negative sik_status.  Arguments are validated on
+ *     the host before anything is launched; a failed call launches nothing.
+ *   - seq_len[b] (device, int32) is the number of valid tokens of sequence b; tokens
+ *     at or beyond it are never read.  Values must lie in [0, max_len].
+ *
+ * Notation: B batch, Hkv KV heads, Hq query heads, R = Hq / Hkv (query head hq reads
+ * KV head hq / R), D head_dim, G = D / 4 sign groups, Lmax = max_len token capacity.
+ *
+ * Layouts
+ *   K, V      [B, Hkv, Lmax, D]      kv_dtype (one row = D 16-bit values)
+ *   q         [B, Hq, D]             kv_dtype
+ *   k_new, v_new [B, Hkv, D]         kv_dtype
+ *   mu        [B, Hkv, D]            float   channel means of K
+ *   codebook  [B, Hkv, G, 16, 4]     float   centroid j of group g, 4 components
+ *   counts    [B, Hkv, G, 16]        int32   members per centroid
+ *   codes     [B, Hkv, Lmax, D / 8]  uint8   packed sign bits, see sik_quantize_keys
+ *   scores    [B, Hq, Lmax]          float
+ *   idx       [B, Hq, k]             int32   selected token indices, -1 = empty slot
+ *   out       [B, Hq, D]             out_dtype
+ */
+#ifndef SIK_H
+#define SIK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SIK_F16 = 0, SIK_BF16 = 1, SIK_F32 = 2 } sik_dtype;
+
+typedef enum {
+    SIK_OK = 0,
+    SIK_ERR_NULL = -1,      /* a required pointer is NULL                                   */
+    SIK_ERR_SHAPE = -2,     /* bad batch / heads / head_dim / max_len combination           */
+    SIK_ERR_DTYPE = -3,     /* kv_dtype not F16/BF16, or out_dtype not kv_dtype/F32         */
+    SIK_ERR_K_RANGE = -4,   /* k < 1 or k > max_len                                          */
+    SIK_ERR_CAPACITY = -5,  /* token range outside [0, max_len]                              */
+    SIK_ERR_WORKSPACE = -6, /* workspace NULL, misaligned or smaller than sik_workspace_bytes */
+    SIK_ERR_LAUNCH = -7,    /* the HIP runtime reported an error while enqueueing           */
+    SIK_ERR_FLAGS = -8      /* unknown quantiser mode                                        */
+} sik_status;
+
+/* Shape of one attention layer's cache.  head_dim must be 128 (the head size of every
+ * model the paper evaluates); n_q_heads must be a multiple of n_kv_heads. */
+typedef struct {
+    int32_t batch;
+    int32_t n_kv_heads;
+    int32_t n_q_heads;
+    int32_t head_dim;
+    int32_t max_len;
+    int32_t kv_dtype;  /* sik_dtype: SIK_F16 or SIK_BF16 -- type of K, V, q, k_new, v_new */
+    int32_t out_dtype; /* sik_dtype: kv_dtype or SIK_F32  -- type of out                   */
+} sik_layout;
+
+/* Quantiser modes for sik_quantize_keys. */
+enum {
+    SIK_Q_FIT = 1,   /* prefill-compress: fit mu and codebook on tokens [0, seq_len[b]), encode them */
+    SIK_Q_ENCODE = 2 /* encode tokens [t0, t0 + n) against the given mu; codebook untouched          */
+};
+
+/* Human-readable text for a status code (host pointer to a static string). */
+const char *sik_strerror(int status);
+
+/* Library version, major * 100 + minor. */
+int sik_version(void);
+
+/* Size in bytes of the scratch buffer the calls below need for this layout and k
+ * (k may be 0 for sik_quantize_keys / sik_score only).  The same buffer may be
+ * reused by every call on one stream; calls sharing it must not overlap in time.
+ * Contents need not be initialised and are not preserved.  Returns 0 on a bad layout. */
+size_t sik_workspace_bytes(const sik_layout *layout, int32_t k);
+
+/* One-pass sign-based quantiser of the key cache (sections "One-Pass Sign-Based
+ * Clustering" and "Entropy-Aware Normalization").
+ *
+ *   SIK_Q_FIT    mu[b,h,d] = mean over tokens i < seq_len[b] of K[b,h,i,d]  (normalisation
+ *                equation, fp64 accumulation, stored as float); sign bit of (i, d) is 1 iff
+ *                K[b,h,i,d] >= mu[b,h,d]; every group of 4 channels gives the 4-bit Code of
+ *                the Code equation (first channel = most significant bit); codebook[b,h,g,j,:]
+ *                = mean of K - mu over the tokens whose Code in group g is j (centroid
+ *                equation; empty cluster -> 0) and counts[b,h,g,j] their number.  t0 and n are
+ *                ignored.  mu, codebook, counts and codes[.., 0:seq_len[b], :] are written.
+ *   SIK_Q_ENCODE encodes tokens t0 <= i < t0 + n of every (b, h) against the mu passed in
+ *                (read only); codebook and counts may be NULL and are not touched.
+ *
+ * Packing: byte j of a token's 16 bytes holds Code(group 2j) in its high nibble and
+ * Code(group 2j+1) in its low nibble, i.e. bit (7 - e) of byte j is the sign bit of
+ * channel 8j + e.  Inputs must be finite. */
+int sik_quantize_keys(const sik_layout *layout, const void *K, const int32_t *seq_len, int32_t t0,
+                      int32_t n, int mode, float *mu, float *codebook, int32_t *counts,
+                      uint8_t *codes, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Compressed-domain scores (section "Compressed-Domain Top-k Retrieval", retrieval
+ * equation): Table[b,hq,g,j] = sum_e q[b,hq,4g+e] * codebook[b,hq/R,g,j,e] and
+ * scores[b,hq,i] = sum_g Table[b,hq,g,Code_g(codes[b,hq/R,i])] for i < seq_len[b]
+ * (fp32 table, fp32 sum in increasing g).  Entries i >= seq_len[b] are not written. */
+int sik_score(const sik_layout *layout, const void *q, const float *codebook, const uint8_t *codes,
+              const int32_t *seq_len, float *scores, void *stream);
+
+/* Per query head, the indices of the k largest scores among i < seq_len[b] (the
+ * selection step that follows the retrieval equation).  Exact selection; equal scores are
+ * resolved toward the smaller index; the order inside idx[b,hq,:] is unspecified.  If
+ * k >= seq_len[b] every valid token is returned and the rest of the row is -1.
+ * Scores must not be NaN. */
+int sik_topk(const sik_layout *layout, const float *scores, const int32_t *seq_len, int32_t k,
+             int32_t *idx, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Sparse attention over the selected tokens (section "Background and Preliminaries",
+ * softmax(q K^T / sqrt(d)) V restricted to the set idx[b,hq,:]): entries < 0 are skipped,
+ * repeated entries count as repeats, entries must be < max_len.  softmax_scale <= 0 means
+ * 1 / sqrt(head_dim).  fp32 accumulation; an empty selection gives a zero row. */
+int sik_sparse_attn(const sik_layout *layout, const void *q, const void *K, const void *V,
+                    const int32_t *idx, int32_t k, float softmax_scale, void *out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* One decode step of one layer: [append] -> table -> scores -> top-k -> sparse attention.
+ * If k_new and v_new are non-NULL (both or neither) the new key/value row of every (b, h)
+ * is written to row seq_len[b] of K and V, its sign code is written to codes (encoded
+ * against the frozen mu; codebook unchanged), and seq_len[b] is incremented on the device,
+ * so that the new token competes in the selection (seq_len[b] < max_len is required).
+ * idx_out ([B,Hq,k], may be NULL) receives the selected indices as in sik_topk. */
+int sik_decode_step(const sik_layout *layout, const void *q, const void *k_new, const void *v_new,
+                    void *K, void *V, int32_t *seq_len, const float *mu, const float *codebook,
+                    uint8_t *codes, int32_t k, float softmax_scale, void *out, int32_t *idx_out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Measurement aid for benchmarks (not for serving loops): runs exactly the kernels of
+ * sik_decode_step with the same arguments, bracketing each with a HIP event on `stream`, then
+ * waits for the stream and returns the kernels' durations in microseconds in kernel_us (host
+ * pointer, SIK_N_KERNELS floats, in launch order: prep/append, score, select, attention). */
+#define SIK_N_KERNELS 4
+int sik_decode_step_profiled(const sik_layout *layout, const void *q, const void *k_new,
+                             const void *v_new, void *K, void *V, int32_t *seq_len, const float *mu,
+                             const float *codebook, uint8_t *codes, int32_t k, float softmax_scale,
+                             void *out, int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                             void *stream, float *kernel_us);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIK_H */

@@ -1,0 +1,148 @@
+"""Thin ctypes binding of libsik.so (C ABI in include/sik.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  torch is used for
+device memory and streams; tensors are passed as raw device pointers.  There is no CPU fallback:
+if the shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsik.so")
+
+SIK_F16, SIK_BF16, SIK_F32 = 0, 1, 2
+SIK_Q_FIT, SIK_Q_ENCODE = 1, 2
+_TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: SIK_F32}
+
+EXPORTS = ("sik_strerror", "sik_version", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
+           "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_profiled")
+
+
+class SikError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"sik status {status}: {text}")
+        self.status = status
+
+
+class Layout(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("max_len", ctypes.c_int32), ("kv_dtype", ctypes.c_int32),
+                ("out_dtype", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libsik.so (built in-tree by paper_2603_14224_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not built: run `python -m paper_2603_14224_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t, ctypes.c_float
+        lp = ctypes.POINTER(Layout)
+        L.sik_strerror.restype = ctypes.c_char_p
+        L.sik_strerror.argtypes = [ctypes.c_int]
+        L.sik_version.restype = ctypes.c_int
+        L.sik_workspace_bytes.restype = sz
+        L.sik_workspace_bytes.argtypes = [lp, i32]
+        L.sik_quantize_keys.restype = ctypes.c_int
+        L.sik_quantize_keys.argtypes = [lp, vp, vp, i32, i32, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
+        L.sik_score.restype = ctypes.c_int
+        L.sik_score.argtypes = [lp, vp, vp, vp, vp, vp, vp]
+        L.sik_topk.restype = ctypes.c_int
+        L.sik_topk.argtypes = [lp, vp, vp, i32, vp, vp, sz, vp]
+        L.sik_sparse_attn.restype = ctypes.c_int
+        L.sik_sparse_attn.argtypes = [lp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+        L.sik_decode_step.restype = ctypes.c_int
+        L.sik_decode_step.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
+        L.sik_decode_step_profiled.restype = ctypes.c_int
+        L.sik_decode_step_profiled.argtypes = L.sik_decode_step.argtypes + [ctypes.POINTER(ctypes.c_float)]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise SikError(rc, lib().sik_strerror(rc).decode())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "sik tensors must be contiguous"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    # Without a GPU the C side still validates arguments first; any launch then reports SIK_ERR_LAUNCH.
+    if not torch.cuda.is_available():
+        return None
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_layout(batch, n_kv_heads, n_q_heads, head_dim, max_len, kv_dtype, out_dtype=None) -> Layout:
+    kd = _TORCH2SIK[kv_dtype] if isinstance(kv_dtype, torch.dtype) else int(kv_dtype)
+    od = kd if out_dtype is None else (_TORCH2SIK[out_dtype] if isinstance(out_dtype, torch.dtype) else int(out_dtype))
+    return Layout(batch, n_kv_heads, n_q_heads, head_dim, max_len, kd, od)
+
+
+def sik_strerror(status: int) -> str:
+    return lib().sik_strerror(status).decode()
+
+
+def sik_workspace_bytes(layout: Layout, k: int) -> int:
+    return int(lib().sik_workspace_bytes(ctypes.byref(layout), int(k)))
+
+
+def alloc_workspace(layout: Layout, k: int, device="cuda") -> torch.Tensor:
+    n = sik_workspace_bytes(layout, k)
+    if n == 0:
+        raise SikError(-2, "sik_workspace_bytes rejected the layout / k")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def sik_quantize_keys(layout, K, seq_len, t0, n, mode, mu, codebook, counts, codes, workspace):
+    _check(lib().sik_quantize_keys(ctypes.byref(layout), _ptr(K), _ptr(seq_len), int(t0), int(n), int(mode),
+                                   _ptr(mu), _ptr(codebook), _ptr(counts), _ptr(codes), _ptr(workspace),
+                                   workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def sik_score(layout, q, codebook, codes, seq_len, scores):
+    _check(lib().sik_score(ctypes.byref(layout), _ptr(q), _ptr(codebook), _ptr(codes), _ptr(seq_len),
+                           _ptr(scores), _stream()))
+
+
+def sik_topk(layout, scores, seq_len, k, idx, workspace):
+    _check(lib().sik_topk(ctypes.byref(layout), _ptr(scores), _ptr(seq_len), int(k), _ptr(idx),
+                          _ptr(workspace), workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def sik_sparse_attn(layout, q, K, V, idx, k, softmax_scale, out, workspace):
+    _check(lib().sik_sparse_attn(ctypes.byref(layout), _ptr(q), _ptr(K), _ptr(V), _ptr(idx), int(k),
+                                 float(softmax_scale), _ptr(out), _ptr(workspace),
+                                 workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def sik_decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out, idx_out,
+                    workspace):
+    _check(lib().sik_decode_step(ctypes.byref(layout), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V),
+                                 _ptr(seq_len), _ptr(mu), _ptr(codebook), _ptr(codes), int(k),
+                                 float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(workspace),
+                                 workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def sik_decode_step_profiled(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,
+                             idx_out, workspace):
+    """Runs one decode step with per-kernel HIP events; returns the 4 kernel durations in microseconds."""
+    us = (ctypes.c_float * 4)()
+    _check(lib().sik_decode_step_profiled(ctypes.byref(layout), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K),
+                                          _ptr(V), _ptr(seq_len), _ptr(mu), _ptr(codebook), _ptr(codes), int(k),
+                                          float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(workspace),
+                                          workspace.numel() if workspace is not None else 0, _stream(), us))
+    return list(us)

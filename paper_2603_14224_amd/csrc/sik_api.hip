@@ -1,0 +1,217 @@
+// C ABI of the Self-Indexing KV cache decode path: host-side validation, workspace carving and
+// kernel sequencing.  Declarations and argument contracts live in include/sik.h.
+#include "sik_device.h"
+#include "sik_internal.h"
+
+namespace sik {
+
+static size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+static int check_layout(const sik_layout* l, Dims* d) {
+    if (!l) return SIK_ERR_NULL;
+    if (l->batch < 1 || l->n_kv_heads < 1 || l->n_q_heads < 1 || l->max_len < 1) return SIK_ERR_SHAPE;
+    if (l->head_dim != kD) return SIK_ERR_SHAPE;
+    if (l->n_q_heads % l->n_kv_heads != 0) return SIK_ERR_SHAPE;
+    if (static_cast<int64_t>(l->batch) * l->n_q_heads > (1 << 20)) return SIK_ERR_SHAPE;
+    if (l->kv_dtype != SIK_F16 && l->kv_dtype != SIK_BF16) return SIK_ERR_DTYPE;
+    if (l->out_dtype != l->kv_dtype && l->out_dtype != SIK_F32) return SIK_ERR_DTYPE;
+    d->B = l->batch;
+    d->Hkv = l->n_kv_heads;
+    d->Hq = l->n_q_heads;
+    d->R = l->n_q_heads / l->n_kv_heads;
+    d->D = l->head_dim;
+    d->Lmax = l->max_len;
+    d->kv_dtype = l->kv_dtype;
+    d->out_dtype = l->out_dtype;
+    return SIK_OK;
+}
+
+Workspace carve(const Dims& d, int k, void* base) {
+    Workspace w{};
+    char* p = static_cast<char*>(base);
+    size_t off = 0;
+    const size_t rows = static_cast<size_t>(d.rows()), units = static_cast<size_t>(d.units());
+    auto take = [&](size_t bytes) {
+        char* r = p ? p + off : nullptr;
+        off += align256(bytes);
+        return r;
+    };
+    w.hist = reinterpret_cast<uint32_t*>(take(rows * kBins * 4));
+    w.counters = reinterpret_cast<uint32_t*>(take(rows * 8 * 4));
+    w.zero_begin = w.hist;
+    w.zero_words = off / 4;
+    w.binp = reinterpret_cast<float*>(take(rows * 2 * 4));
+    w.cand = reinterpret_cast<uint32_t*>(take(rows * kCandCap * 2 * 4));
+    w.idx = reinterpret_cast<int32_t*>(take(rows * static_cast<size_t>(k > 0 ? k : 1) * 4));
+    w.partial = reinterpret_cast<float*>(take(rows * kMaxSplit * (kD + 2) * 4));
+    w.scores = reinterpret_cast<float*>(take(rows * static_cast<size_t>(d.Lmax) * 4));
+    w.colsum = reinterpret_cast<double*>(take(units * kFitMaxWg * kD * 8));
+    w.csum = reinterpret_cast<double*>(take(units * kG * 64 * 8));
+    w.total_bytes = off;
+    return w;
+}
+
+static int check_ws(const Dims& d, int k, void* ws, size_t bytes, Workspace* w) {
+    if (!ws) return SIK_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return SIK_ERR_WORKSPACE;
+    *w = carve(d, k, ws);
+    if (bytes < w->total_bytes) return SIK_ERR_WORKSPACE;
+    return SIK_OK;
+}
+
+static int launched(hipError_t e) { return e == hipSuccess ? SIK_OK : SIK_ERR_LAUNCH; }
+
+}  // namespace sik
+
+using namespace sik;
+
+extern "C" {
+
+const char* sik_strerror(int status) {
+    switch (status) {
+        case SIK_OK: return "ok";
+        case SIK_ERR_NULL: return "a required pointer is NULL";
+        case SIK_ERR_SHAPE: return "unsupported layout (head_dim must be 128, n_q_heads a multiple of n_kv_heads, sizes positive)";
+        case SIK_ERR_DTYPE: return "unsupported dtype (kv_dtype F16/BF16; out_dtype kv_dtype or F32)";
+        case SIK_ERR_K_RANGE: return "k outside [1, max_len]";
+        case SIK_ERR_CAPACITY: return "token range outside [0, max_len]";
+        case SIK_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or smaller than sik_workspace_bytes";
+        case SIK_ERR_LAUNCH: return "HIP runtime error while enqueueing";
+        case SIK_ERR_FLAGS: return "unknown quantiser mode";
+        default: return "unknown status";
+    }
+}
+
+int sik_version(void) { return 100; }
+
+size_t sik_workspace_bytes(const sik_layout* layout, int32_t k) {
+    Dims d;
+    if (check_layout(layout, &d) != SIK_OK || k < 0 || k > d.Lmax) return 0;
+    return carve(d, k, nullptr).total_bytes;
+}
+
+int sik_quantize_keys(const sik_layout* layout, const void* K, const int32_t* seq_len, int32_t t0, int32_t n,
+                      int mode, float* mu, float* codebook, int32_t* counts, uint8_t* codes, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (mode != SIK_Q_FIT && mode != SIK_Q_ENCODE) return SIK_ERR_FLAGS;
+    if (!K || !mu || !codes) return SIK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (mode == SIK_Q_ENCODE) {
+        if (t0 < 0 || n < 0 || static_cast<int64_t>(t0) + n > d.Lmax) return SIK_ERR_CAPACITY;
+        return launched(launch_encode(d, K, t0, n, mu, codes, s));
+    }
+    if (!seq_len || !codebook || !counts) return SIK_ERR_NULL;
+    Workspace w;
+    rc = check_ws(d, 0, workspace, workspace_bytes, &w);
+    if (rc) return rc;
+    return launched(launch_fit(d, w, K, seq_len, mu, codebook, counts, codes, s));
+}
+
+int sik_score(const sik_layout* layout, const void* q, const float* codebook, const uint8_t* codes,
+              const int32_t* seq_len, float* scores, void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (!q || !codebook || !codes || !seq_len || !scores) return SIK_ERR_NULL;
+    return launched(launch_score(d, q, codebook, codes, seq_len, scores, nullptr, nullptr,
+                                 static_cast<hipStream_t>(stream)));
+}
+
+int sik_topk(const sik_layout* layout, const float* scores, const int32_t* seq_len, int32_t k, int32_t* idx,
+             void* workspace, size_t workspace_bytes, void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (!scores || !seq_len || !idx) return SIK_ERR_NULL;
+    if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    Workspace w;
+    rc = check_ws(d, k, workspace, workspace_bytes, &w);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_prep(d, w, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    if (e == hipSuccess) e = launch_topk_hist(d, w, scores, seq_len, s);
+    if (e == hipSuccess) e = launch_select(d, w, scores, seq_len, k, idx, s);
+    return launched(e);
+}
+
+int sik_sparse_attn(const sik_layout* layout, const void* q, const void* K, const void* V, const int32_t* idx,
+                    int32_t k, float softmax_scale, void* out, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (!q || !K || !V || !idx || !out) return SIK_ERR_NULL;
+    if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    Workspace w;
+    rc = check_ws(d, k, workspace, workspace_bytes, &w);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_prep(d, w, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
+    return launched(e);
+}
+
+static int decode_step_impl(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
+                            void* K, void* V, int32_t* seq_len, const float* mu, const float* codebook,
+                            uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
+                            void* workspace, size_t workspace_bytes, void* stream, hipEvent_t* ev) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (!q || !K || !V || !seq_len || !codebook || !codes || !out) return SIK_ERR_NULL;
+    if ((k_new == nullptr) != (v_new == nullptr)) return SIK_ERR_NULL;
+    if (k_new && !mu) return SIK_ERR_NULL;
+    if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    Workspace w;
+    rc = check_ws(d, k, workspace, workspace_bytes, &w);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t* idx = idx_out ? idx_out : w.idx;
+    auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
+    hipError_t e = mark(0);
+    if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
+    if (e == hipSuccess) e = mark(1);
+    if (e == hipSuccess) e = launch_score(d, q, codebook, codes, seq_len, w.scores, w.hist, w.binp, s);
+    if (e == hipSuccess) e = mark(2);
+    if (e == hipSuccess) e = launch_select(d, w, w.scores, seq_len, k, idx, s);
+    if (e == hipSuccess) e = mark(3);
+    if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
+    if (e == hipSuccess) e = mark(4);
+    return launched(e);
+}
+
+int sik_decode_step(const sik_layout* layout, const void* q, const void* k_new, const void* v_new, void* K,
+                    void* V, int32_t* seq_len, const float* mu, const float* codebook, uint8_t* codes, int32_t k,
+                    float softmax_scale, void* out, int32_t* idx_out, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+    return decode_step_impl(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,
+                            idx_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
+                             void* K, void* V, int32_t* seq_len, const float* mu, const float* codebook,
+                             uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
+                             void* workspace, size_t workspace_bytes, void* stream, float* kernel_us) {
+    if (!kernel_us) return SIK_ERR_NULL;
+    hipEvent_t ev[SIK_N_KERNELS + 1];
+    int made = 0;
+    for (; made <= SIK_N_KERNELS; ++made)
+        if (hipEventCreate(&ev[made]) != hipSuccess) break;
+    int rc = made == SIK_N_KERNELS + 1 ? SIK_OK : SIK_ERR_LAUNCH;
+    if (rc == SIK_OK)
+        rc = decode_step_impl(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,
+                              idx_out, workspace, workspace_bytes, stream, ev);
+    if (rc == SIK_OK && hipEventSynchronize(ev[SIK_N_KERNELS]) != hipSuccess) rc = SIK_ERR_LAUNCH;
+    for (int i = 0; rc == SIK_OK && i < SIK_N_KERNELS; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) rc = SIK_ERR_LAUNCH;
+        kernel_us[i] = ms * 1000.0f;
+    }
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    return rc;
+}
+
+}  // extern "C"

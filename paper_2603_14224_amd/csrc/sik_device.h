@@ -1,0 +1,108 @@
+// Device-side helpers shared by the gfx950 kernels of the Self-Indexing KV cache path.
+// Wavefront = 64 lanes; a key/value row of D = 128 16-bit values is 256 B = 16 lanes x 16 B.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sik {
+
+constexpr int kD = 128;           // head_dim the kernels are specialised for
+constexpr int kG = kD / 4;        // sign groups per key ("Codebook Construction": G = D / 4)
+constexpr int kCodeBytes = kD / 8;  // 16 B of packed sign bits per key ("Overhead Analysis" (i))
+constexpr int kWave = 64;
+constexpr int kBlock = 256;       // threads per workgroup in every kernel
+constexpr int kBins = 1024;       // first-level selection histogram bins per query head
+constexpr int kCandCap = 1024;    // candidates of the threshold bin resolved by ranking
+constexpr int kMaxSplit = 64;     // upper bound of attention splits per query head
+constexpr float kNegBig = -1.0e30f;
+
+enum : int { kF16 = 0, kBF16 = 1, kF32 = 2 };
+
+// ---- 16-bit storage <-> fp32 (both widenings are exact) -------------------------------
+template <int DT>
+__device__ __forceinline__ float widen16(uint32_t h16) {
+    if constexpr (DT == kBF16) {
+        return __uint_as_float(h16 << 16);
+    } else {
+        const _Float16 h = __builtin_bit_cast(_Float16, static_cast<uint16_t>(h16));
+        return static_cast<float>(h);
+    }
+}
+
+// Eight consecutive 16-bit values held in a 128-bit register quad -> fp32.
+template <int DT>
+__device__ __forceinline__ void widen8(const uint4 v, float (&f)[8]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = widen16<DT>(w[i] & 0xffffu);
+        f[2 * i + 1] = widen16<DT>(w[i] >> 16);
+    }
+}
+
+// fp32 -> 16-bit storage, round to nearest even (finite inputs).
+template <int DT>
+__device__ __forceinline__ uint32_t narrow16(float f) {
+    if constexpr (DT == kBF16) {
+        const uint32_t u = __float_as_uint(f);
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    } else {
+        const _Float16 h = static_cast<_Float16>(f);
+        return __builtin_bit_cast(uint16_t, h);
+    }
+}
+
+// Order-preserving map fp32 -> uint32 (larger float <=> larger key; -0 and +0 share a key,
+// as they compare equal).
+__device__ __forceinline__ uint32_t float_to_key(float f) {
+    const uint32_t u = f == 0.0f ? 0u : __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t k) {
+    const uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __uint_as_float(u);
+}
+
+// Histogram bin of a score: a non-decreasing function of s for fixed (lo, scale >= 0), so that
+// "bin above the threshold bin" implies "score above every score of the threshold bin".
+__device__ __forceinline__ int score_bin(float s, float lo, float scale) {
+    const float x = (s - lo) * scale;
+    int b = static_cast<int>(floorf(x));
+    b = b < 0 ? 0 : b;
+    return b > kBins - 1 ? kBins - 1 : b;
+}
+
+// Agent-scope relaxed atomics on global memory.
+__device__ __forceinline__ uint32_t atomic_add_u32(uint32_t* p, uint32_t v) {
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t atomic_max_u32(uint32_t* p, uint32_t v) {
+    return __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// "Last workgroup to arrive" ticket: every workgroup publishes its global writes, then takes a
+// ticket; the one that draws total-1 may read what all the others wrote.  Call from all threads.
+__device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, int* lds_flag) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *lds_flag = (t == total - 1u) ? 1 : 0;
+    }
+    __syncthreads();
+    const bool last = *lds_flag != 0;
+    if (last) __threadfence();
+    return last;
+}
+
+// Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15); every lane gets the total.
+__device__ __forceinline__ float row16_sum(float v) {
+    v += __shfl_xor(v, 8, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 1, 64);
+    return v;
+}
+
+}  // namespace sik

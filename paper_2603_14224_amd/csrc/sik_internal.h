@@ -1,0 +1,59 @@
+// Host-side plan (grid shapes, workspace carving) and kernel launchers behind the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/sik.h"
+
+namespace sik {
+
+struct Dims {
+    int B, Hkv, Hq, R, D, Lmax;
+    int kv_dtype, out_dtype;
+    int rows() const { return B * Hq; }
+    int units() const { return B * Hkv; }
+};
+
+// Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
+struct Workspace {
+    // zeroed by the prep kernel at the start of every call that selects or attends
+    uint32_t* zero_begin;   // start of the zero-initialised region
+    size_t zero_words;      // its length in 32-bit words
+    uint32_t* hist;         // [rows][kBins]      first-level score histogram
+    uint32_t* counters;     // [rows][8]          0 sel_cnt, 1 cand_cnt, 2 select ticket, 3 attn ticket,
+                            //                    4 ~min key, 5 max key (stand-alone top-k only)
+    // plain scratch
+    float* binp;            // [rows][2]          histogram scale, offset
+    uint32_t* cand;         // [rows][kCandCap][2] (key, index) of threshold-bin members
+    int32_t* idx;           // [rows][k]          selection when the caller passes no idx_out
+    float* partial;         // [rows][kMaxSplit][D + 2]  split softmax partials (m, l, o[D])
+    float* scores;          // [rows][Lmax]       decode step only
+    // quantiser fit
+    double* colsum;         // [units][kFitMaxWg][D]
+    double* csum;           // [units][G*16*4]    cluster sums (zeroed by the fit's own kernel)
+    size_t total_bytes;
+};
+
+constexpr int kFitMaxWg = 64;
+
+Workspace carve(const Dims& d, int k, void* base);
+
+// launchers (return hipError_t of the launch)
+hipError_t launch_prep(const Dims& d, const Workspace& w, const void* k_new, const void* v_new, void* K,
+                       void* V, int32_t* seq_len, const float* mu, uint8_t* codes, hipStream_t s);
+hipError_t launch_score(const Dims& d, const void* q, const float* codebook, const uint8_t* codes,
+                        const int32_t* seq_len, float* scores, uint32_t* hist, float* binp, hipStream_t s);
+hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
+                            hipStream_t s);
+hipError_t launch_select(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
+                         int k, int32_t* idx, hipStream_t s);
+hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
+                       const int32_t* idx, int k, float scale, void* out, hipStream_t s);
+hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,
+                      float* codebook, int32_t* counts, uint8_t* codes, hipStream_t s);
+hipError_t launch_encode(const Dims& d, const void* K, int t0, int n, const float* mu, uint8_t* codes,
+                         hipStream_t s);
+
+}  // namespace sik

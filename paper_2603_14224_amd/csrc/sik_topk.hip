@@ -1,0 +1,313 @@
+// Exact per-query-head top-k selection on gfx950 without sorting (the selection step after the
+// retrieval equation in "Compressed-Domain Top-k Retrieval").
+//
+// Level 1: a 1024-bin histogram of a monotone map of the score (built while scoring, or by the
+// two stand-alone kernels below) locates the threshold bin b*: every token in a bin above b* is
+// selected; tokens inside b* are candidates.
+// Level 2: the candidates (typically L / 1000 of them) are gathered by all workgroups of the
+// query head and ranked exactly by (score desc, index asc) by the last workgroup to finish, which
+// fills the remaining k - c_gt slots.  If the threshold bin holds more than kCandCap tokens
+// (degenerate score distributions, e.g. all scores equal) the same workgroup falls back to an
+// 8-bit radix select over the bin's members, still exact.
+#include "sik_device.h"
+#include "sik_internal.h"
+
+namespace sik {
+
+constexpr int kSelChunkMax = 2048;  // scores scanned per select workgroup (bounds its LDS lists)
+
+// ---- stand-alone level 1, pass A: per-row min and max of the order-preserving keys ---------
+__global__ __launch_bounds__(kBlock) void minmax_kernel(const float* __restrict__ scores,
+                                                        const int32_t* __restrict__ seq_len,
+                                                        uint32_t* __restrict__ counters, int Hq, int Lmax,
+                                                        int nchunk, int chunk) {
+    __shared__ uint32_t smin[kBlock / kWave], smax[kBlock / kWave];
+    const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
+    int L = seq_len[row / Hq];
+    L = L > Lmax ? Lmax : L;
+    const int start = c * chunk, end = min(L, start + chunk);
+    if (start >= end) return;
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+    const float* s = scores + static_cast<size_t>(row) * Lmax;
+    for (int i = start + tid; i < end; i += kBlock) {
+        const uint32_t key = float_to_key(s[i]);
+        kmin = min(kmin, key);
+        kmax = max(kmax, key);
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        kmin = min(kmin, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmin), o, 64)));
+        kmax = max(kmax, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmax), o, 64)));
+    }
+    if ((tid & 63) == 0) {
+        smin[tid >> 6] = kmin;
+        smax[tid >> 6] = kmax;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < kBlock / kWave; ++w) {
+            kmin = min(kmin, smin[w]);
+            kmax = max(kmax, smax[w]);
+        }
+        atomic_max_u32(&counters[row * 8 + 4], ~kmin);  // the region starts at zero: keep ~min
+        atomic_max_u32(&counters[row * 8 + 5], kmax);
+    }
+}
+
+// ---- stand-alone level 1, pass B: histogram over [min, max] ---------------------------------
+__global__ __launch_bounds__(kBlock) void hist_kernel(const float* __restrict__ scores,
+                                                      const int32_t* __restrict__ seq_len,
+                                                      const uint32_t* __restrict__ counters,
+                                                      uint32_t* __restrict__ hist, float* __restrict__ binp,
+                                                      int Hq, int Lmax, int nchunk, int chunk) {
+    __shared__ uint32_t lhist[kBins];
+    const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
+    int L = seq_len[row / Hq];
+    L = L > Lmax ? Lmax : L;
+    const int start = c * chunk, end = min(L, start + chunk);
+    if (start >= end) return;
+    const float lo = key_to_float(~counters[row * 8 + 4]);
+    const float hi = key_to_float(counters[row * 8 + 5]);
+    const float span = hi - lo;
+    const float scale = (span > 1e-30f && span < 3.0e38f) ? static_cast<float>(kBins) / span : 0.0f;
+    if (c == 0 && tid == 0) {
+        binp[row * 2] = lo;
+        binp[row * 2 + 1] = scale;
+    }
+    for (int e = tid; e < kBins; e += kBlock) lhist[e] = 0u;
+    __syncthreads();
+    const float* s = scores + static_cast<size_t>(row) * Lmax;
+    for (int i = start + tid; i < end; i += kBlock) atomicAdd(&lhist[score_bin(s[i], lo, scale)], 1u);
+    __syncthreads();
+    for (int e = tid; e < kBins; e += kBlock) {
+        const uint32_t v = lhist[e];
+        if (v) atomic_add_u32(&hist[static_cast<size_t>(row) * kBins + e], v);
+    }
+}
+
+// ---- level 2 fallback: radix select inside the threshold bin, one workgroup -----------------
+// Picks the `need` largest (score, then smaller index) among {i < L : bin(s_i) == bstar} and
+// writes their indices to out[0 .. need).
+__device__ void radix_select_in_bin(const float* __restrict__ s, int L, float lo, float scale, int bstar,
+                                    int need, int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, mask = 0;
+    uint32_t remaining = static_cast<uint32_t>(need);
+    for (int pass = 3; pass >= 0; --pass) {
+        h256[tid] = 0u;
+        __syncthreads();
+        for (int i = tid; i < L; i += kBlock) {
+            const float v = s[i];
+            const uint32_t key = float_to_key(v);
+            if (score_bin(v, lo, scale) == bstar && (key & mask) == prefix)
+                atomicAdd(&h256[(key >> (8 * pass)) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0;
+            int dsel = 0;
+            for (int dgt = 255; dgt >= 0; --dgt) {
+                const uint32_t cnt = h256[dgt];
+                if (cum < remaining && remaining <= cum + cnt) {
+                    dsel = dgt;
+                    break;
+                }
+                cum += cnt;
+            }
+            sh[0] = static_cast<uint32_t>(dsel);
+            sh[1] = remaining - cum;
+        }
+        __syncthreads();
+        prefix |= sh[0] << (8 * pass);
+        mask |= 255u << (8 * pass);
+        remaining = sh[1];
+        __syncthreads();
+    }
+    // prefix is now the key of the need-th largest member; `remaining` members equal to it are
+    // taken in increasing index order, every larger member is taken.
+    const uint32_t tau = prefix, need_eq = remaining;
+    const uint32_t n_gt = static_cast<uint32_t>(need) - need_eq;
+    if (tid == 0) {
+        sh[2] = 0u;  // running count of larger members written
+        sh[3] = 0u;  // running count of equal members seen
+    }
+    __syncthreads();
+    for (int base = 0; base < L; base += kBlock) {
+        const int i = base + tid;
+        bool gt = false, eq = false;
+        if (i < L) {
+            const float v = s[i];
+            const uint32_t key = float_to_key(v);
+            if (score_bin(v, lo, scale) == bstar) {
+                gt = key > tau;
+                eq = key == tau;
+            }
+        }
+        if (gt) out[atomicAdd(&sh[2], 1u)] = i;
+        // ordered rank of the equal members of this tile
+        const uint64_t bal = __ballot(eq);
+        const int lane = tid & 63, wv = tid >> 6;
+        if (lane == 0) h256[wv] = static_cast<uint32_t>(__popcll(bal));
+        __syncthreads();
+        uint32_t before = sh[3];
+        for (int w = 0; w < wv; ++w) before += h256[w];
+        const uint32_t ord = before + static_cast<uint32_t>(__popcll(bal & ((1ull << lane) - 1ull)));
+        if (eq && ord < need_eq) out[n_gt + ord] = i;
+        __syncthreads();
+        if (tid == 0) sh[3] += h256[0] + h256[1] + h256[2] + h256[3];
+        __syncthreads();
+    }
+}
+
+// ---- select: threshold bin from the histogram, compaction, exact resolution -----------------
+__global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict__ scores,
+                                                        const int32_t* __restrict__ seq_len,
+                                                        const uint32_t* __restrict__ hist,
+                                                        const float* __restrict__ binp,
+                                                        uint32_t* __restrict__ counters,
+                                                        uint32_t* __restrict__ cand,
+                                                        int32_t* __restrict__ idx, int Hq, int Lmax, int k,
+                                                        int nchunk, int chunk) {
+    __shared__ uint32_t scan[kBlock];
+    __shared__ int32_t l_sel[kSelChunkMax];
+    __shared__ uint32_t l_cand[2 * kCandCap];
+    __shared__ int s_bstar, s_cgt, s_nb, s_flag;
+    __shared__ uint32_t s_nsel, s_ncand, s_base[2], sh[4];
+
+    const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
+    int L = seq_len[row / Hq];
+    L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
+    const int kk = min(k, L);
+    const float* s = scores + static_cast<size_t>(row) * Lmax;
+    int32_t* out = idx + static_cast<size_t>(row) * k;
+
+    if (tid == 0) {
+        s_bstar = -1;  // "every bin is above the threshold": select all
+        s_cgt = L;
+        s_nb = 0;
+        s_nsel = 0u;
+        s_ncand = 0u;
+    }
+    __syncthreads();
+    if (kk < L) {
+        // suffix sums of the histogram: thread t owns bins 4t .. 4t+3
+        const uint4 h4 = reinterpret_cast<const uint4*>(hist + static_cast<size_t>(row) * kBins)[tid];
+        const uint32_t own = h4.x + h4.y + h4.z + h4.w;
+        scan[tid] = own;
+        __syncthreads();
+        for (int o = 1; o < kBlock; o <<= 1) {  // inclusive suffix scan
+            const uint32_t add = tid + o < kBlock ? scan[tid + o] : 0u;
+            __syncthreads();
+            scan[tid] += add;
+            __syncthreads();
+        }
+        uint32_t cum = scan[tid] - own;  // tokens in bins owned by higher threads
+        const uint32_t hb[4] = {h4.x, h4.y, h4.z, h4.w};
+#pragma unroll
+        for (int e = 3; e >= 0; --e) {
+            if (cum < static_cast<uint32_t>(kk) && static_cast<uint32_t>(kk) <= cum + hb[e]) {
+                s_bstar = 4 * tid + e;
+                s_cgt = static_cast<int>(cum);
+                s_nb = static_cast<int>(hb[e]);
+            }
+            cum += hb[e];
+        }
+        __syncthreads();
+    }
+    const int bstar = s_bstar, cgt = s_cgt, nb = s_nb;
+    const bool ranked = nb <= kCandCap;
+    const float lo = binp[row * 2], scale = binp[row * 2 + 1];
+
+    const int start = c * chunk, end = min(L, start + chunk);
+    for (int i = start + tid; i < end; i += kBlock) {
+        const float v = s[i];
+        const int bin = bstar < 0 ? 0 : score_bin(v, lo, scale);
+        if (bin > bstar) {
+            l_sel[atomicAdd(&s_nsel, 1u)] = i;
+        } else if (bin == bstar && ranked) {
+            const uint32_t pos = atomicAdd(&s_ncand, 1u);
+            if (pos < static_cast<uint32_t>(kCandCap)) {
+                l_cand[2 * pos] = float_to_key(v);
+                l_cand[2 * pos + 1] = static_cast<uint32_t>(i);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        s_base[0] = s_nsel ? atomic_add_u32(&counters[row * 8 + 0], s_nsel) : 0u;
+        s_base[1] = s_ncand ? atomic_add_u32(&counters[row * 8 + 1], s_ncand) : 0u;
+    }
+    __syncthreads();
+    for (uint32_t j = tid; j < s_nsel; j += kBlock) {
+        const uint32_t pos = s_base[0] + j;
+        if (pos < static_cast<uint32_t>(k)) out[pos] = l_sel[j];
+    }
+    const uint32_t ncand = min(s_ncand, static_cast<uint32_t>(kCandCap));
+    uint32_t* crow = cand + static_cast<size_t>(row) * kCandCap * 2;
+    for (uint32_t j = tid; j < ncand; j += kBlock) {
+        const uint32_t pos = s_base[1] + j;
+        if (pos < static_cast<uint32_t>(kCandCap)) {
+            crow[2 * pos] = l_cand[2 * j];
+            crow[2 * pos + 1] = l_cand[2 * j + 1];
+        }
+    }
+
+    if (!last_arriver(&counters[row * 8 + 2], static_cast<uint32_t>(nchunk), &s_flag)) return;
+
+    // ---- last workgroup of this query head: resolve the threshold bin, pad the row ----------
+    const int need = kk - min(cgt, kk);
+    if (need > 0) {
+        if (ranked) {
+            const int n = min(nb, kCandCap);
+            for (int j = tid; j < 2 * n; j += kBlock) l_cand[j] = crow[j];
+            __syncthreads();
+            for (int a = tid; a < n; a += kBlock) {
+                const uint32_t ka = l_cand[2 * a], ia = l_cand[2 * a + 1];
+                int rank = 0;
+                for (int o = 0; o < n; ++o) {
+                    const uint32_t ko = l_cand[2 * o], io = l_cand[2 * o + 1];
+                    rank += (ko > ka || (ko == ka && io < ia)) ? 1 : 0;
+                }
+                if (rank < need) out[cgt + rank] = static_cast<int32_t>(ia);
+            }
+        } else {
+            radix_select_in_bin(s, L, lo, scale, bstar, need, out + cgt, scan, sh);
+        }
+    }
+    for (int j = kk + tid; j < k; j += kBlock) out[j] = -1;
+}
+
+// ---------------------------------------------------------------------------------------
+static void select_plan(const Dims& d, int* nchunk, int* chunk) {
+    const int rows = d.rows();
+    int want = (1024 + rows - 1) / rows;
+    int ch = (d.Lmax + want - 1) / want;
+    ch = (ch + kBlock - 1) / kBlock * kBlock;
+    if (ch < kBlock) ch = kBlock;
+    if (ch > kSelChunkMax) ch = kSelChunkMax;
+    *chunk = ch;
+    *nchunk = (d.Lmax + ch - 1) / ch;
+}
+
+hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
+                            hipStream_t s) {
+    int nchunk, chunk;
+    select_plan(d, &nchunk, &chunk);
+    chunk *= 4;  // the histogram passes keep no per-chunk lists
+    nchunk = (d.Lmax + chunk - 1) / chunk;
+    const int grid = nchunk * d.rows();
+    minmax_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, d.Hq, d.Lmax, nchunk, chunk);
+    hist_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, w.hist, w.binp, d.Hq, d.Lmax, nchunk, chunk);
+    return hipGetLastError();
+}
+
+hipError_t launch_select(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
+                         int k, int32_t* idx, hipStream_t s) {
+    int nchunk, chunk;
+    select_plan(d, &nchunk, &chunk);
+    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, seq_len, w.hist, w.binp, w.counters, w.cand, idx,
+                                                       d.Hq, d.Lmax, k, nchunk, chunk);
+    return hipGetLastError();
+}
+
+}  // namespace sik

@@ -1,0 +1,85 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments before touching a device (no GPU needed: validation happens first)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2603_14224_amd as sik
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "sik.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sik_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sik.lib()
+    names = header_symbols()
+    assert set(names) == set(sik.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_strerror():
+    assert sik.lib().sik_version() >= 100
+    for code in range(0, -9, -1):
+        assert sik.sik_strerror(code) not in ("", "unknown status")
+    assert sik.sik_strerror(-99) == "unknown status"
+
+
+def L(**kw):
+    base = dict(batch=1, n_kv_heads=8, n_q_heads=32, head_dim=128, max_len=4096, kv_dtype=sik.SIK_BF16)
+    base.update(kw)
+    return sik.make_layout(**base)
+
+
+def test_workspace_bytes_and_layout_validation():
+    assert sik.sik_workspace_bytes(L(), 256) > 0
+    assert sik.sik_workspace_bytes(L(), 256) % 256 == 0
+    assert sik.sik_workspace_bytes(L(batch=32), 256) > sik.sik_workspace_bytes(L(), 256)
+    for bad in (L(head_dim=96), L(n_q_heads=30), L(batch=0), L(max_len=0), L(kv_dtype=sik.SIK_F32),
+                L(out_dtype=sik.SIK_F16)):
+        assert sik.sik_workspace_bytes(bad, 16) == 0
+    assert sik.sik_workspace_bytes(L(), 5000) == 0  # k > max_len
+
+
+FAKE = ctypes.c_void_p(256 * 1000)  # never dereferenced: validation fails first
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    lib = sik.lib()
+    lay = L()
+    ref = ctypes.byref(lay)
+    assert lib.sik_score(ref, None, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert lib.sik_score(ctypes.byref(L(head_dim=64)), FAKE, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert lib.sik_score(ctypes.byref(L(kv_dtype=2)), FAKE, FAKE, FAKE, FAKE, FAKE, None) == -3
+    assert lib.sik_topk(ref, FAKE, FAKE, 0, FAKE, FAKE, 1 << 30, None) == -4
+    assert lib.sik_topk(ref, FAKE, FAKE, 4097, FAKE, FAKE, 1 << 30, None) == -4
+    assert lib.sik_topk(ref, FAKE, FAKE, 16, FAKE, None, 1 << 30, None) == -6
+    assert lib.sik_topk(ref, FAKE, FAKE, 16, FAKE, FAKE, 64, None) == -6
+    assert lib.sik_topk(ref, FAKE, FAKE, 16, FAKE, ctypes.c_void_p(256 * 1000 + 8), 1 << 30, None) == -6
+    assert lib.sik_sparse_attn(ref, FAKE, FAKE, None, FAKE, 16, 0.0, FAKE, FAKE, 1 << 30, None) == -1
+    assert lib.sik_sparse_attn(ref, FAKE, FAKE, FAKE, FAKE, 16, 0.0, FAKE, FAKE, 10, None) == -6
+    assert lib.sik_quantize_keys(ref, FAKE, FAKE, 0, 1, 7, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == -8
+    assert lib.sik_quantize_keys(ref, FAKE, FAKE, 4000, 200, sik.SIK_Q_ENCODE, FAKE, None, None, FAKE, None, 0, None) == -5
+    assert lib.sik_quantize_keys(ref, FAKE, FAKE, -1, 2, sik.SIK_Q_ENCODE, FAKE, None, None, FAKE, None, 0, None) == -5
+    assert lib.sik_quantize_keys(ref, FAKE, FAKE, 0, 0, sik.SIK_Q_FIT, FAKE, None, FAKE, FAKE, FAKE, 1 << 30, None) == -1
+    assert lib.sik_decode_step(ref, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, 0.0, FAKE, None,
+                               FAKE, 1 << 30, None) == -1  # k_new without v_new
+    assert lib.sik_decode_step(ref, FAKE, None, None, FAKE, FAKE, FAKE, None, FAKE, FAKE, 0, 0.0, FAKE, None,
+                               FAKE, 1 << 30, None) == -4
+    assert lib.sik_decode_step(None, FAKE, None, None, FAKE, FAKE, FAKE, None, FAKE, FAKE, 4, 0.0, FAKE, None,
+                               FAKE, 1 << 30, None) == -1
+
+
+def test_binding_raises_on_error_status():
+    import torch
+    lay = L()
+    with pytest.raises(sik.SikError):
+        sik.sik_topk(lay, torch.zeros(4), torch.zeros(1, dtype=torch.int32), 0, torch.zeros(4, dtype=torch.int32),
+                     torch.zeros(256, dtype=torch.uint8))

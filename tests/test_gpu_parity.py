@@ -1,0 +1,355 @@
+"""Parity of the HIP library (through the C ABI) against the CPU oracle, stage by stage and fused.
+
+Bars (written here as the tests use them):
+  codes            byte-for-byte equal given the same mu
+  mu               |mu_gpu - mu_ref| <= 1e-6 * max(1, max|K_d|)
+  codebook         |c_gpu - c_ref| <= 1e-5 * max_i |K'_{i,d}| per channel, counts equal
+  scores           |s_gpu - s_ref| <= 1e-5 * max(|s_ref|, RMS(s_ref))
+  top-k            identical sets except oracle ties within 1e-5 relative of the k-th score
+  attention fp32   max|d| / max|out_ref| <= 1e-5 per (b, hq)
+  attention 16-bit max|d| <= 2e-3, or the correctly rounded 16-bit value where the 16-bit grid is
+                   coarser than 2e-3 (bf16 half-ulp is 3.9e-3 at |x| = 1): |d| <= half-ulp + 1e-5 max|ref|
+"""
+import numpy as np
+import pytest
+import torch
+
+import sik_workloads as W
+from helpers import bits_of_tensor, dev, f64, topk_sets_agree
+
+pytestmark = pytest.mark.gpu
+
+import paper_2603_14224_amd as sik  # noqa: E402
+
+TDT = {"fp16": torch.float16, "bf16": torch.bfloat16}
+
+
+def cfg_small(name="C2", **kw):
+    return W.scaled(W.CONFIGS[name], **kw)
+
+
+class GpuState:
+    """Device mirror of one layer's cache plus the oracle's quantiser state for it."""
+
+    def __init__(self, cfg, oracle, capacity=None, seq_len=None, offset_std=0.0, out_dtype=None):
+        self.cfg, self.o = cfg, oracle
+        self.K, self.V = W.make_cache(cfg, capacity=capacity, channel_offset_std=offset_std)
+        B, H, cap, D = self.K.shape
+        self.cap = cap
+        self.sl = np.full(B, cfg.context, np.int32) if seq_len is None else np.asarray(seq_len, np.int32)
+        self.mu, self.codes, self.cb, self.cnt = oracle.fit(self.K, cfg.dtype, self.sl)
+        self.layout = sik.make_layout(B, H, cfg.n_q_heads, D, cap, TDT[cfg.dtype], out_dtype)
+        self.dK, self.dV = dev(self.K, cfg.dtype), dev(self.V, cfg.dtype)
+        self.dsl = torch.from_numpy(self.sl.copy()).cuda()
+        self.dmu = torch.from_numpy(self.mu).cuda()
+        self.dcb = torch.from_numpy(self.cb).cuda()
+        self.dcodes = torch.from_numpy(self.codes).cuda()
+        self.ws = sik.alloc_workspace(self.layout, min(cfg.top_k, cap))
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+# --------------------------------------------------------------------------- quantiser
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_encode_codes_bit_exact(oracle, dtype):
+    cfg = cfg_small(batch=2, n_kv_heads=3, n_q_heads=6, context=1237, dtype=dtype, seed=21)
+    K, _ = W.make_cache(cfg, capacity=1300, channel_offset_std=2.0)
+    sl = np.array([1237, 1237], np.int32)
+    mu = oracle.mean(K, dtype, sl)
+    lay = sik.make_layout(2, 3, 6, 128, 1300, TDT[dtype])
+    dK, dmu = dev(K, dtype), torch.from_numpy(mu).cuda()
+    for t0, n in ((0, 1237), (5, 1), (100, 999), (1299, 1), (17, 0)):
+        want = np.full((2, 3, 1300, 16), 0x5A, np.uint8)
+        oracle.encode(K, dtype, mu, t0, n, want)
+        got = torch.full((2, 3, 1300, 16), 0x5A, dtype=torch.uint8, device="cuda")
+        sik.sik_quantize_keys(lay, dK, None, t0, n, sik.SIK_Q_ENCODE, dmu, None, None, got, None)
+        sync()
+        assert np.array_equal(got.cpu().numpy(), want), (t0, n)
+
+
+@pytest.mark.parametrize("dtype,offset", [("bf16", 0.0), ("bf16", 2.0), ("fp16", 2.0)])
+def test_fit_mu_codes_codebook(oracle, dtype, offset):
+    cfg = cfg_small(batch=2, n_kv_heads=4, n_q_heads=8, context=5000, dtype=dtype, seed=22)
+    K, _ = W.make_cache(cfg, capacity=5003, channel_offset_std=offset)
+    sl = np.array([5000, 1531], np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, dtype, sl)
+    lay = sik.make_layout(2, 4, 8, 128, 5003, TDT[dtype])
+    ws = sik.alloc_workspace(lay, 0)
+    dK, dsl = dev(K, dtype), torch.from_numpy(sl).cuda()
+    dmu = torch.empty(2, 4, 128, device="cuda")
+    dcb = torch.empty(2, 4, 32, 16, 4, device="cuda")
+    dcnt = torch.empty(2, 4, 32, 16, dtype=torch.int32, device="cuda")
+    dcodes = torch.zeros(2, 4, 5003, 16, dtype=torch.uint8, device="cuda")
+    sik.sik_quantize_keys(lay, dK, dsl, 0, 0, sik.SIK_Q_FIT, dmu, dcb, dcnt, dcodes, ws)
+    sync()
+    Kd = f64(K, dtype)
+    gmu = dmu.cpu().numpy()
+    assert np.abs(gmu - mu).max() <= 1e-6 * max(1.0, np.abs(Kd).max())
+    # fp64 accumulation on both sides: the fp32 means are expected to be the same bits
+    n_mu_diff = int((gmu != mu).sum())
+    gcodes = dcodes.cpu().numpy()
+    mism = 0
+    for b in range(2):
+        mism += int((gcodes[b, :, :sl[b]] != codes[b, :, :sl[b]]).sum())
+        assert not gcodes[b, :, sl[b]:].any()  # tokens beyond seq_len untouched
+    print(f"fit: mu entries differing {n_mu_diff}, code bytes differing {mism}")
+    assert n_mu_diff == 0 and mism == 0
+    assert np.array_equal(dcnt.cpu().numpy(), cnt)
+    gcb = dcb.cpu().numpy()
+    for b in range(2):
+        Kp = np.abs(Kd[b, :, :sl[b]] - mu[b][:, None, :]).max(axis=1)  # [H, D] max |K'|
+        tol = 1e-5 * Kp.reshape(4, 32, 1, 4)
+        assert np.all(np.abs(gcb[b] - cb[b]) <= tol)
+
+
+# --------------------------------------------------------------------------- scores
+@pytest.mark.parametrize("name,kw", [
+    ("C1", dict(context=4096)),
+    ("C2", dict(batch=2, n_kv_heads=2, n_q_heads=8, context=3001)),
+    ("C5", dict(batch=1, n_kv_heads=2, n_q_heads=16, context=2500)),      # GQA 8:1 -> two tables
+    ("C2", dict(batch=1, n_kv_heads=2, n_q_heads=6, context=777)),        # R = 3: padded head block
+    ("C2", dict(batch=1, n_kv_heads=1, n_q_heads=12, context=600)),       # R = 12: two head blocks
+])
+def test_scores(oracle, name, kw):
+    cfg = cfg_small(name, **kw)
+    B = cfg.batch
+    sl = np.full(B, cfg.context, np.int32)
+    if B > 1:
+        sl[1] = cfg.context // 3
+    st = GpuState(cfg, oracle, capacity=cfg.context + 5, seq_len=sl, offset_std=1.0)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    ref = oracle.score(q, cfg.dtype, st.cb, st.codes, sl)
+    got = torch.full((B, cfg.n_q_heads, st.cap), 123.0, device="cuda")
+    sik.sik_score(st.layout, dev(q, cfg.dtype), st.dcb, st.dcodes, st.dsl, got)
+    sync()
+    got = got.cpu().numpy()
+    for b in range(B):
+        for hq in range(cfg.n_q_heads):
+            r = ref[b, hq, :sl[b]]
+            tol = 1e-5 * np.maximum(np.abs(r), np.sqrt(np.mean(r * r)))
+            assert np.all(np.abs(got[b, hq, :sl[b]] - r) <= tol)
+            assert np.all(got[b, hq, sl[b]:] == 123.0)  # not written beyond seq_len
+
+
+# --------------------------------------------------------------------------- top-k
+def run_topk(scores_np, sl, k):
+    B, Hq, Lmax = scores_np.shape
+    lay = sik.make_layout(B, 1, Hq, 128, Lmax, torch.bfloat16)
+    ws = sik.alloc_workspace(lay, k)
+    idx = torch.full((B, Hq, k), -7, dtype=torch.int32, device="cuda")
+    sik.sik_topk(lay, torch.from_numpy(scores_np).cuda(), torch.from_numpy(np.asarray(sl, np.int32)).cuda(), k, idx, ws)
+    sync()
+    return idx.cpu().numpy()
+
+
+@pytest.mark.parametrize("L,k", [(5000, 128), (5000, 1), (5000, 4999), (5000, 5000), (300, 512), (70001, 2048)])
+def test_topk_random_scores(oracle, L, k):
+    rng = np.random.default_rng(L + k)
+    Lmax = max(L, k) + 3
+    s = rng.normal(size=(2, 3, Lmax)).astype(np.float32)
+    s[0, 1] *= 1e-3
+    s[1, 2] = s[1, 2] * 50 + 1000      # far from zero: bins must resolve a narrow relative range
+    sl = [L, max(1, L // 2)]
+    got = run_topk(s, sl, k)
+    ref = oracle.topk(s.astype(np.float64), np.asarray(sl, np.int32), k)
+    for b in range(2):
+        for h in range(3):
+            # identical fp32 scores on both sides: the sets must be identical
+            assert sorted(got[b, h].tolist()) == sorted(ref[b, h].tolist())
+
+
+def test_topk_ties_and_degenerate_rows(oracle):
+    rng = np.random.default_rng(77)
+    L, k = 6000, 200
+    s = rng.normal(size=(1, 6, L)).astype(np.float32)
+    s[0, 0] = 1.25                                   # all equal: threshold bin holds everything
+    s[0, 1] = np.where(rng.random(L) < 0.5, 2.0, -1.0)  # two values, thousands of ties at the cut
+    s[0, 2, :] = np.round(s[0, 2] * 4) / 4           # heavy quantisation: many exact ties
+    s[0, 3, 100:1500] = s[0, 3].max() + 1.0          # a plateau of 1400 ties above everything else
+    s[0, 4] = 0.0
+    s[0, 4, ::7] = -0.0                              # signed zeros compare equal
+    s[0, 5, :] = np.arange(L, dtype=np.float32)      # strictly increasing
+    got = run_topk(s, [L], k)
+    ref = oracle.topk(s.astype(np.float64), np.array([L], np.int32), k)
+    for h in range(6):
+        assert sorted(got[0, h].tolist()) == sorted(ref[0, h].tolist()), h
+
+
+def test_topk_is_deterministic(oracle):
+    rng = np.random.default_rng(5)
+    s = rng.normal(size=(1, 4, 40000)).astype(np.float32)
+    a = np.sort(run_topk(s, [40000], 1024), axis=-1)
+    for _ in range(3):
+        assert np.array_equal(np.sort(run_topk(s, [40000], 1024), axis=-1), a)
+
+
+def test_topk_empty_sequence(oracle):
+    s = np.zeros((2, 2, 64), np.float32)
+    got = run_topk(s, [0, 64], 16)
+    assert np.all(got[0] == -1)
+    assert sorted(got[1, 0].tolist()) == list(range(16))
+
+
+# --------------------------------------------------------------------------- attention
+@pytest.mark.parametrize("dtype,out_f32", [("bf16", True), ("fp16", True), ("bf16", False), ("fp16", False)])
+def test_sparse_attention_on_oracle_indices(oracle, dtype, out_f32):
+    cfg = cfg_small(batch=2, n_kv_heads=2, n_q_heads=8, context=3000, top_k=333, dtype=dtype, seed=31)
+    st = GpuState(cfg, oracle, capacity=3010, out_dtype=torch.float32 if out_f32 else None)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    rng = np.random.default_rng(2)
+    k = 333
+    idx = np.stack([[rng.permutation(3000)[:k] for _ in range(8)] for _ in range(2)]).astype(np.int32)
+    idx[0, 1, 300:] = -1          # padded row
+    idx[1, 0, :] = -1             # empty selection
+    idx[1, 2, 5] = idx[1, 2, 6]   # a repeated entry counts twice
+    ref = oracle.sparse_attn(q, st.K, st.V, dtype, idx)
+    out = torch.empty(2, 8, 128, dtype=torch.float32 if out_f32 else TDT[dtype], device="cuda")
+    sik.sik_sparse_attn(st.layout, dev(q, dtype), st.dK, st.dV, torch.from_numpy(idx).cuda(), k, 0.0, out, st.ws)
+    sync()
+    got = out.float().cpu().numpy().astype(np.float64)
+    check_attention(got, ref, out_f32, dtype)
+    assert np.all(got[1, 0] == 0)
+
+
+def half_ulp(x, dtype):
+    """Half a unit in the last place of the 16-bit type at |x| (8 significand bits bf16, 11 fp16)."""
+    e = np.floor(np.log2(np.maximum(np.abs(x), 1e-30)))
+    return np.exp2(e - (8 if dtype == "bf16" else 11))
+
+
+def check_attention(got, ref, out_f32, dtype="bf16"):
+    """fp32 output: max|d| <= 1e-5 * max|ref| per (b, hq).  16-bit output: max|d| <= 2e-3, except
+    where the 16-bit grid itself is coarser than that (|out| above ~1 for bf16): there the value must
+    be the correctly rounded one up to the fp32 error, |d| <= half-ulp(ref) + 1e-5 * max|ref|."""
+    for b in range(ref.shape[0]):
+        for hq in range(ref.shape[1]):
+            d = np.abs(got[b, hq] - ref[b, hq])
+            scale = max(np.abs(ref[b, hq]).max(), 1e-30)
+            if out_f32:
+                assert d.max() <= 1e-5 * scale, (b, hq, float(d.max()), scale)
+            else:
+                bar = np.maximum(2e-3, half_ulp(ref[b, hq], dtype) + 1e-5 * scale)
+                worst = float((d / bar).max())
+                assert worst <= 1.0, (b, hq, worst, float(d.max()))
+
+
+def test_sparse_attention_all_tokens_matches_dense(oracle):
+    # k = L: the sparse kernel must reproduce dense attention (oracle pinned to the textbook form)
+    cfg = cfg_small(batch=1, n_kv_heads=2, n_q_heads=4, context=1500, top_k=1500, seed=32)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    idx = np.tile(np.arange(1500, dtype=np.int32), (1, 4, 1))
+    ref = oracle.sparse_attn(q, st.K, st.V, cfg.dtype, idx, scale=0.11)
+    out = torch.empty(1, 4, 128, device="cuda")
+    sik.sik_sparse_attn(st.layout, dev(q, cfg.dtype), st.dK, st.dV, torch.from_numpy(idx).cuda(), 1500, 0.11, out, st.ws)
+    sync()
+    check_attention(out.cpu().numpy().astype(np.float64), ref, True)
+
+
+# --------------------------------------------------------------------------- fused decode step
+def run_decode_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0, seq_len=None, out_f32=True,
+                         sample_rows=None):
+    st = GpuState(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=offset_std,
+                  out_dtype=torch.float32 if out_f32 else None)
+    B, Hq, k = cfg.batch, cfg.n_q_heads, min(cfg.top_k, capacity)
+    K, V, codes, sl = st.K, st.V, st.codes, st.sl.copy()
+    out = torch.empty(B, Hq, 128, dtype=torch.float32 if out_f32 else TDT[cfg.dtype], device="cuda")
+    idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
+    total_diff = 0
+    for step in range(steps):
+        q, kn, vn = W.make_step_inputs(cfg, step)
+        dq = dev(q, cfg.dtype)
+        dkn = dev(kn, cfg.dtype) if append else None
+        dvn = dev(vn, cfg.dtype) if append else None
+        sik.sik_decode_step(st.layout, dq, dkn, dvn, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, k, 0.0, out,
+                            idx, st.ws)
+        sync()
+        # oracle: same step on the host copies (appends in place)
+        if append:
+            ref_out, ref_idx = oracle.decode_step(q, kn, vn, K, V, cfg.dtype, sl, st.mu, st.cb, codes, k)
+        else:
+            ref_out, ref_idx = oracle.decode_step(q, None, None, K, V, cfg.dtype, sl, st.mu, st.cb, codes, k)
+        assert np.array_equal(st.dsl.cpu().numpy(), sl)
+        if append:
+            for b in range(B):
+                t = sl[b] - 1
+                assert np.array_equal(bits_of_tensor(st.dK[b, :, t]), K[b, :, t])
+                assert np.array_equal(bits_of_tensor(st.dV[b, :, t]), V[b, :, t])
+                assert np.array_equal(st.dcodes[b, :, t].cpu().numpy(), codes[b, :, t])
+        g_idx = idx.cpu().numpy()
+        s_ref = oracle.score(q, cfg.dtype, st.cb, codes, sl)
+        for b in range(B):
+            for hq in range(Hq):
+                total_diff += topk_sets_agree(g_idx[b, hq], ref_idx[b, hq], s_ref[b, hq], int(sl[b]), k)
+        # attention is compared on the GPU's own (tie-legal) index set
+        ref_on_gpu_set = oracle.sparse_attn(q, K, V, cfg.dtype, g_idx)
+        check_attention(out.float().cpu().numpy().astype(np.float64), ref_on_gpu_set, out_f32, cfg.dtype)
+    return total_diff
+
+
+def test_decode_step_c1_full(oracle):
+    cfg = W.CONFIGS["C1"]
+    run_decode_and_check(oracle, cfg, capacity=4096, steps=2, append=False)
+
+
+def test_decode_step_c1_16bit_out(oracle):
+    run_decode_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=1, append=False, out_f32=False)
+
+
+def test_decode_step_c2_shape_reduced(oracle):
+    cfg = cfg_small("C2", context=8192, top_k=256)
+    run_decode_and_check(oracle, cfg, capacity=8192, steps=2, append=False, offset_std=1.0)
+
+
+def test_decode_step_c3_shape_reduced_with_append(oracle):
+    cfg = cfg_small("C3", context=9000, top_k=300)
+    run_decode_and_check(oracle, cfg, capacity=9004, steps=3, append=True, offset_std=1.0)
+
+
+def test_decode_step_c4_shape_reduced_ragged_batch(oracle):
+    cfg = cfg_small("C4", batch=4, context=2048, top_k=512)
+    run_decode_and_check(oracle, cfg, capacity=2050, steps=1, append=True, seq_len=[2048, 1, 511, 700])
+
+
+def test_decode_step_c5_shape_reduced_gqa8(oracle):
+    cfg = cfg_small("C5", batch=2, n_kv_heads=2, n_q_heads=16, context=6000, top_k=1536)
+    run_decode_and_check(oracle, cfg, capacity=6016, steps=3, append=True)
+
+
+def test_decode_step_k_not_below_context(oracle):
+    # k >= L: everything is selected and the result is dense attention
+    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=700, top_k=1024)
+    run_decode_and_check(oracle, cfg, capacity=1100, steps=1, append=True)
+
+
+def test_decode_step_zero_query_all_scores_equal(oracle):
+    # q = 0 makes every score equal: the selector must still return k distinct smallest indices
+    cfg = cfg_small("C2", n_kv_heads=1, n_q_heads=4, context=3000, top_k=100)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q = np.zeros((1, 4, 128), np.uint16)
+    out = torch.empty(1, 4, 128, device="cuda")
+    idx = torch.empty(1, 4, 100, dtype=torch.int32, device="cuda")
+    sik.sik_decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes,
+                        100, 0.0, out, idx, st.ws)
+    sync()
+    g = idx.cpu().numpy()
+    for hq in range(4):
+        assert sorted(g[0, hq].tolist()) == list(range(100))
+    ref = oracle.sparse_attn(q, st.K, st.V, cfg.dtype, g)
+    check_attention(out.cpu().numpy().astype(np.float64), ref, True)
+
+
+def test_decode_step_without_idx_out_matches(oracle):
+    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=5000, top_k=200)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    dq = dev(q, cfg.dtype)
+    a = torch.empty(1, 8, 128, device="cuda")
+    b = torch.empty(1, 8, 128, device="cuda")
+    idx = torch.empty(1, 8, 200, dtype=torch.int32, device="cuda")
+    sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 200, 0.0, a, idx, st.ws)
+    sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 200, 0.0, b, None, st.ws)
+    sync()
+    assert torch.allclose(a, b, rtol=1e-5, atol=1e-6)
