@@ -13,6 +13,7 @@ static int check_layout(const sik_layout* l, Dims* d) {
     if (l->head_dim != kD) return SIK_ERR_SHAPE;
     if (l->n_q_heads % l->n_kv_heads != 0) return SIK_ERR_SHAPE;
     if (static_cast<int64_t>(l->batch) * l->n_q_heads > (1 << 20)) return SIK_ERR_SHAPE;
+    if (l->max_len > (1 << 22)) return SIK_ERR_SHAPE;  // 64 chunks of at most 65535 tokens per head
     if (l->kv_dtype != SIK_F16 && l->kv_dtype != SIK_BF16) return SIK_ERR_DTYPE;
     if (l->out_dtype != l->kv_dtype && l->out_dtype != SIK_F32) return SIK_ERR_DTYPE;
     d->B = l->batch;
@@ -36,10 +37,15 @@ Workspace carve(const Dims& d, int k, void* base) {
         off += align256(bytes);
         return r;
     };
-    w.hist = reinterpret_cast<uint32_t*>(take(rows * kBins * 4));
     w.counters = reinterpret_cast<uint32_t*>(take(rows * 8 * 4));
-    w.zero_begin = w.hist;
+    w.zero_begin = w.counters;
     w.zero_words = off / 4;
+    int nhb, nc_score, nc_hist, ch;
+    score_plan(d, &nhb, &nc_score, &ch);
+    hist_plan(d, &nc_hist, &ch);
+    const size_t nc = static_cast<size_t>(nc_score > nc_hist ? nc_score : nc_hist);
+    w.parthist = reinterpret_cast<uint32_t*>(take(rows * nc * (kBins / 2) * 4));
+    w.thr = reinterpret_cast<int32_t*>(take(rows * 4 * 4));
     w.binp = reinterpret_cast<float*>(take(rows * 2 * 4));
     w.cand = reinterpret_cast<uint32_t*>(take(rows * kCandCap * 2 * 4));
     w.idx = reinterpret_cast<int32_t*>(take(rows * static_cast<size_t>(k > 0 ? k : 1) * 4));
@@ -116,7 +122,7 @@ int sik_score(const sik_layout* layout, const void* q, const float* codebook, co
     int rc = check_layout(layout, &d);
     if (rc) return rc;
     if (!q || !codebook || !codes || !seq_len || !scores) return SIK_ERR_NULL;
-    return launched(launch_score(d, q, codebook, codes, seq_len, scores, nullptr, nullptr,
+    return launched(launch_score(d, nullptr, 0, q, codebook, codes, seq_len, scores,
                                  static_cast<hipStream_t>(stream)));
 }
 
@@ -132,7 +138,7 @@ int sik_topk(const sik_layout* layout, const float* scores, const int32_t* seq_l
     if (rc) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = launch_prep(d, w, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
-    if (e == hipSuccess) e = launch_topk_hist(d, w, scores, seq_len, s);
+    if (e == hipSuccess) e = launch_topk_hist(d, w, scores, seq_len, k, s);
     if (e == hipSuccess) e = launch_select(d, w, scores, seq_len, k, idx, s);
     return launched(e);
 }
@@ -174,7 +180,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     hipError_t e = mark(0);
     if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
     if (e == hipSuccess) e = mark(1);
-    if (e == hipSuccess) e = launch_score(d, q, codebook, codes, seq_len, w.scores, w.hist, w.binp, s);
+    if (e == hipSuccess) e = launch_score(d, &w, k, q, codebook, codes, seq_len, w.scores, s);
     if (e == hipSuccess) e = mark(2);
     if (e == hipSuccess) e = launch_select(d, w, w.scores, seq_len, k, idx, s);
     if (e == hipSuccess) e = mark(3);

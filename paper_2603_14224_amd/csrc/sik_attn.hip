@@ -147,22 +147,24 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
     float* prow = partial + (static_cast<size_t>(row) * kMaxSplit) * kPartStride;
     if (tid < kD) {
         float* pp = prow + static_cast<size_t>(sp) * kPartStride;
-        pp[2 + tid] = o;
+        st_agent(&pp[2 + tid], o);
         if (tid == 0) {
-            pp[0] = M;
-            pp[1] = Lsum;
+            st_agent(&pp[0], M);
+            st_agent(&pp[1], Lsum);
         }
     }
     if (!last_arriver(&counters[row * 8 + 3], static_cast<uint32_t>(nsplit), &s_flag)) return;
     if (tid < kD) {
         float Mg = kNegBig;
-        for (int s2 = 0; s2 < nsplit; ++s2) Mg = fmaxf(Mg, prow[static_cast<size_t>(s2) * kPartStride]);
+#pragma unroll 8
+        for (int s2 = 0; s2 < nsplit; ++s2) Mg = fmaxf(Mg, ld_agent(&prow[static_cast<size_t>(s2) * kPartStride]));
         float lt = 0.0f, ot = 0.0f;
+#pragma unroll 8
         for (int s2 = 0; s2 < nsplit; ++s2) {  // fixed order: the result does not depend on arrival order
             const float* pp = prow + static_cast<size_t>(s2) * kPartStride;
-            const float a = exp2f(pp[0] - Mg);
-            lt += pp[1] * a;
-            ot += pp[2 + tid] * a;
+            const float a = exp2f(ld_agent(&pp[0]) - Mg);
+            lt += ld_agent(&pp[1]) * a;
+            ot += ld_agent(&pp[2 + tid]) * a;
         }
         store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, lt > 0.0f ? ot / lt : 0.0f);
     }

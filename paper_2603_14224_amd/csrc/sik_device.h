@@ -12,7 +12,7 @@ constexpr int kG = kD / 4;        // sign groups per key ("Codebook Construction
 constexpr int kCodeBytes = kD / 8;  // 16 B of packed sign bits per key ("Overhead Analysis" (i))
 constexpr int kWave = 64;
 constexpr int kBlock = 256;       // threads per workgroup in every kernel
-constexpr int kBins = 1024;       // first-level selection histogram bins per query head
+constexpr int kBins = 512;        // first-level selection histogram bins per query head
 constexpr int kCandCap = 1024;    // candidates of the threshold bin resolved by ranking
 constexpr int kMaxSplit = 64;     // upper bound of attention splits per query head
 constexpr float kNegBig = -1.0e30f;
@@ -81,19 +81,38 @@ __device__ __forceinline__ uint32_t atomic_max_u32(uint32_t* p, uint32_t v) {
     return __hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// "Last workgroup to arrive" ticket: every workgroup publishes its global writes, then takes a
-// ticket; the one that draws total-1 may read what all the others wrote.  Call from all threads.
+// ---- exchange between workgroups of one launch ---------------------------------------------
+// MI355X has one L2 per XCD, so data handed from one workgroup to another inside a launch must
+// not sit dirty in the writer's L2 or stale in the reader's.  A full agent-scope release fence
+// (write back the whole L2) per workgroup costs more than the kernels themselves, so the exchange
+// buffers are written and read with relaxed agent-scope atomic accesses instead (write-through
+// stores, coherent loads), and ordering comes from waiting for the stores to complete before the
+// workgroup takes its ticket.
+__device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
+    return __hip_atomic_load(const_cast<uint32_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __uint_as_float(__hip_atomic_load(reinterpret_cast<uint32_t*>(const_cast<float*>(p)),
+                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// "Last workgroup to arrive" ticket.  Every workgroup first writes what it hands over with
+// st_agent, then calls this from all its threads; the workgroup that draws total-1 may read what
+// all the others wrote with ld_agent.  The ticket must start at zero.
 __device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, int* lds_flag) {
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);  // every store of this lane has been acknowledged
     __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        *lds_flag = (t == total - 1u) ? 1 : 0;
-    }
+    if (threadIdx.x == 0) *lds_flag = (atomic_add_u32(ticket, 1u) == total - 1u) ? 1 : 0;
     __syncthreads();
-    const bool last = *lds_flag != 0;
-    if (last) __threadfence();
-    return last;
+    return *lds_flag != 0;
 }
 
 // Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15); every lane gets the total.

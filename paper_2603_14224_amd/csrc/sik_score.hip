@@ -5,12 +5,57 @@
 // group and a contiguous chunk of tokens.  The tables live in LDS as float4 entries holding the
 // same (g, j) entry of four query heads: the 16 entries of a group span 256 B = all 64 LDS
 // banks once, so the data-dependent ds_read_b128 of a wavefront (all lanes are at the same g)
-// is bank-conflict free whatever the codes are.  Each lane owns one token: a single 128-bit
-// load brings its 32 codes, i.e. a wavefront streams 1 KB of the code plane per load.
+// is bank-conflict free whatever the codes are.  Each lane owns one token per load: a single
+// 128-bit load brings its 32 codes, i.e. a wavefront streams 1 KB of the code plane per load;
+// four such loads per lane are in flight while the previous four tokens are scored.
+//
+// With HIST the kernel also builds the first level of the selection: a histogram of a monotone
+// map of each query head's scores, published per chunk; the last workgroup of the head block to
+// finish adds the chunks up and writes the threshold bin for the select kernel.
 #include "sik_device.h"
 #include "sik_internal.h"
+#include "sik_select.h"
 
 namespace sik {
+
+constexpr int kTokPerIter = 4;  // tokens per lane per loop iteration
+
+template <int NT>
+__device__ __forceinline__ void score_token(const uint4 code, const float4 (*lut)[kG * 16], float* acc) {
+    constexpr int HB = 4 * NT;
+#pragma unroll
+    for (int s = 0; s < HB; ++s) acc[s] = 0.0f;
+    const uint32_t w[4] = {code.x, code.y, code.z, code.w};
+#pragma unroll
+    for (int dw = 0; dw < 4; ++dw) {
+#pragma unroll
+        for (int by = 0; by < 4; ++by) {
+            // byte (4 dw + by) of the token: high nibble = Code of group g, low nibble = group g+1
+            const int g = 8 * dw + 2 * by;
+            const uint32_t bits = w[dw] >> (8 * by);
+            const uint32_t off_hi = bits & 0xf0u;  // Code * 16 B
+            const uint32_t off_lo = (bits & 0x0fu) << 4;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const float4 v =
+                    *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(&lut[t][g * 16]) + off_hi);
+                acc[4 * t + 0] += v.x;
+                acc[4 * t + 1] += v.y;
+                acc[4 * t + 2] += v.z;
+                acc[4 * t + 3] += v.w;
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const float4 v = *reinterpret_cast<const float4*>(
+                    reinterpret_cast<const char*>(&lut[t][(g + 1) * 16]) + off_lo);
+                acc[4 * t + 0] += v.x;
+                acc[4 * t + 1] += v.y;
+                acc[4 * t + 2] += v.z;
+                acc[4 * t + 3] += v.w;
+            }
+        }
+    }
+}
 
 template <int DT, int NT, bool HIST>
 __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restrict__ q,
@@ -18,14 +63,18 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
                                                        const uint8_t* __restrict__ codes,
                                                        const int32_t* __restrict__ seq_len,
                                                        float* __restrict__ scores,
-                                                       uint32_t* __restrict__ hist,
-                                                       float* __restrict__ binp, int Hkv, int Hq, int R,
-                                                       int Lmax, int nchunk, int chunk, int nhb) {
+                                                       uint32_t* __restrict__ parthist,
+                                                       uint32_t* __restrict__ counters,
+                                                       float* __restrict__ binp, int32_t* __restrict__ thr,
+                                                       int k, int Hkv, int Hq, int R, int Lmax, int nchunk,
+                                                       int chunk, int nhb) {
     constexpr int HB = 4 * NT;
     __shared__ float4 lut[NT][kG * 16];
     __shared__ float qs[HB][kD];
     __shared__ float bp[HB][2];
     __shared__ uint32_t lhist[HIST ? HB * kBins : 1];
+    __shared__ uint32_t lds4[4];
+    __shared__ int s_flag;
 
     const int tid = threadIdx.x;
     const int c = blockIdx.x % nchunk;
@@ -34,32 +83,42 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     const int unit = u / nhb;
     const int h = unit % Hkv, b = unit / Hkv;
     int L = seq_len[b];
-    L = L > Lmax ? Lmax : L;
+    L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const int start = c * chunk;
-    if (start >= L && c != 0) return;
+    if (start >= L && c != 0) return;  // chunk 0 always runs: it owns the per-head outputs
     const int end = min(L, start + chunk);
     const int hq0 = h * R + hb * HB;
     const int nh = min(HB, R - hb * HB);
     const size_t row0 = static_cast<size_t>(b) * Hq + hq0;
 
-    // first code load goes out before the table build so that its latency is hidden
+    // every global load this workgroup needs before it can score goes out now, together
     const uint4* cp = reinterpret_cast<const uint4*>(codes + static_cast<size_t>(unit) * Lmax * kCodeBytes);
-    int i = start + tid;
-    uint4 cur = make_uint4(0u, 0u, 0u, 0u);
-    if (i < end) cur = cp[i];
-
-    for (int e = tid; e < HB * kD; e += kBlock) {
-        const int s = e / kD, dd = e % kD;
-        qs[s][dd] = s < nh ? widen16<DT>(q[(row0 + s) * kD + dd]) : 0.0f;
+    uint4 cur[kTokPerIter];
+#pragma unroll
+    for (int j = 0; j < kTokPerIter; ++j) {
+        const int i = start + j * kBlock + tid;
+        cur[j] = i < end ? cp[i] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    const float4 cj0 = reinterpret_cast<const float4*>(codebook)[static_cast<size_t>(unit) * kG * 16 + tid];
+    const float4 cj1 =
+        reinterpret_cast<const float4*>(codebook)[static_cast<size_t>(unit) * kG * 16 + tid + kBlock];
+    if (tid < HB * 16) {  // 16 lanes x 16 B per query row
+        const int s = tid >> 4, p = tid & 15;
+        float f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (s < nh) widen8<DT>(reinterpret_cast<const uint4*>(q + (row0 + s) * kD)[p], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qs[s][8 * p + e] = f[e];
     }
     if constexpr (HIST)
         for (int e = tid; e < HB * kBins; e += kBlock) lhist[e] = 0u;
     __syncthreads();
 
     // Table^(g)[j] for the HB query heads, fp32
-    for (int e = tid; e < kG * 16; e += kBlock) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        const int e = tid + half * kBlock;
         const int g = e >> 4;
-        const float4 cj = reinterpret_cast<const float4*>(codebook)[static_cast<size_t>(unit) * kG * 16 + e];
+        const float4 cj = half ? cj1 : cj0;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             float o[4];
@@ -78,28 +137,33 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     __syncthreads();
 
     if constexpr (HIST) {
-        // Every score of head s lies in [sum_g min_j T, sum_g max_j T]; spread the bins over it.
+        // Bins are spread over mean +- 4.5 sigma of the score of a key whose 32 codes are uniform
+        // and independent (mean = sum_g mean_j T, var = sum_g var_j T); scores outside fall into the
+        // end bins.  Any (lo, scale) is correct, this one keeps the threshold bin small.
         if (tid < HB * 32) {
             const int s = tid >> 5, g = tid & 31;
-            float mx = -INFINITY, mn = INFINITY;
+            float sum = 0.0f, sq = 0.0f;
             for (int j = 0; j < 16; ++j) {
                 const float4 v = lut[s >> 2][g * 16 + j];
                 const float x = (s & 3) == 0 ? v.x : (s & 3) == 1 ? v.y : (s & 3) == 2 ? v.z : v.w;
-                mx = fmaxf(mx, x);
-                mn = fminf(mn, x);
+                sum += x;
+                sq = fmaf(x, x, sq);
             }
+            float mean = sum * (1.0f / 16.0f);
+            float var = fmaxf(sq * (1.0f / 16.0f) - mean * mean, 0.0f);
 #pragma unroll
             for (int o = 16; o >= 1; o >>= 1) {
-                mx += __shfl_xor(mx, o, 32);
-                mn += __shfl_xor(mn, o, 32);
+                mean += __shfl_xor(mean, o, 32);
+                var += __shfl_xor(var, o, 32);
             }
             if (g == 0) {
-                const float span = mx - mn;
-                const float scale = span > 1e-30f ? static_cast<float>(kBins) / span : 0.0f;
-                bp[s][0] = mn;
+                const float span = 9.0f * sqrtf(var);
+                const float lo = mean - 0.5f * span;
+                const float scale = (span > 1e-30f && span < 3.0e38f) ? static_cast<float>(kBins) / span : 0.0f;
+                bp[s][0] = lo;
                 bp[s][1] = scale;
                 if (c == 0 && s < nh) {
-                    binp[(row0 + s) * 2] = mn;
+                    binp[(row0 + s) * 2] = lo;
                     binp[(row0 + s) * 2 + 1] = scale;
                 }
             }
@@ -107,51 +171,31 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         __syncthreads();
     }
 
-    for (int base = start; base < end; base += kBlock) {
-        const bool valid = i < end;
-        const uint4 code = cur;
-        i += kBlock;
-        if (i < end) cur = cp[i];  // prefetch the next token's codes
-        float acc[HB];
+    for (int base = start; base < end; base += kTokPerIter * kBlock) {
+        uint4 code[kTokPerIter];
 #pragma unroll
-        for (int s = 0; s < HB; ++s) acc[s] = 0.0f;
-        const uint32_t w[4] = {code.x, code.y, code.z, code.w};
+        for (int j = 0; j < kTokPerIter; ++j) code[j] = cur[j];
+        const int nbase = base + kTokPerIter * kBlock;
+        if (nbase < end) {
 #pragma unroll
-        for (int dw = 0; dw < 4; ++dw) {
-#pragma unroll
-            for (int by = 0; by < 4; ++by) {
-                // byte (4 dw + by) of the token: high nibble = Code of group g, low nibble = group g+1
-                const int g = 8 * dw + 2 * by;
-                const uint32_t bits = w[dw] >> (8 * by);
-                const uint32_t off_hi = bits & 0xf0u;        // Code * 16 B
-                const uint32_t off_lo = (bits & 0x0fu) << 4;
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const float4 v = *reinterpret_cast<const float4*>(
-                        reinterpret_cast<const char*>(&lut[t][g * 16]) + off_hi);
-                    acc[4 * t + 0] += v.x;
-                    acc[4 * t + 1] += v.y;
-                    acc[4 * t + 2] += v.z;
-                    acc[4 * t + 3] += v.w;
-                }
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const float4 v = *reinterpret_cast<const float4*>(
-                        reinterpret_cast<const char*>(&lut[t][(g + 1) * 16]) + off_lo);
-                    acc[4 * t + 0] += v.x;
-                    acc[4 * t + 1] += v.y;
-                    acc[4 * t + 2] += v.z;
-                    acc[4 * t + 3] += v.w;
-                }
+            for (int j = 0; j < kTokPerIter; ++j) {
+                const int i = nbase + j * kBlock + tid;
+                if (i < end) cur[j] = cp[i];
             }
         }
-        if (valid) {
-            const int tok = i - kBlock;
 #pragma unroll
-            for (int s = 0; s < HB; ++s) {
-                if (s < nh) {
-                    scores[(row0 + s) * Lmax + tok] = acc[s];
-                    if constexpr (HIST) atomicAdd(&lhist[s * kBins + score_bin(acc[s], bp[s][0], bp[s][1])], 1u);
+        for (int j = 0; j < kTokPerIter; ++j) {
+            const int tok = base + j * kBlock + tid;
+            float acc[HB];
+            score_token<NT>(code[j], lut, acc);
+            if (tok < end) {
+#pragma unroll
+                for (int s = 0; s < HB; ++s) {
+                    if (s < nh) {
+                        scores[(row0 + s) * Lmax + tok] = acc[s];
+                        if constexpr (HIST)
+                            atomicAdd(&lhist[s * kBins + score_bin(acc[s], bp[s][0], bp[s][1])], 1u);
+                    }
                 }
             }
         }
@@ -159,40 +203,54 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
 
     if constexpr (HIST) {
         __syncthreads();
-        for (int e = tid; e < nh * kBins; e += kBlock) {
-            const uint32_t v = lhist[e];
-            if (v) atomic_add_u32(&hist[row0 * kBins + e], v);
-        }
+        for (int s = 0; s < nh; ++s)
+            publish_hist(&lhist[s * kBins], parthist + ((row0 + s) * nchunk + c) * kHistWords);
+        const int nact = L > 0 ? (L + chunk - 1) / chunk : 1;  // chunks that run for this sequence
+        if (!last_arriver(&counters[row0 * 8 + 6], static_cast<uint32_t>(nact), &s_flag)) return;
+        for (int s = 0; s < nh; ++s)
+            find_threshold(parthist + (row0 + s) * nchunk * kHistWords, nact, min(k, L), L,
+                           thr + (row0 + s) * 4, lds4);
     }
 }
 
-// Tokens per workgroup: aim at ~4 workgroups per compute unit, at least 256 tokens each.
-static void score_plan(const Dims& d, int nhb, int* nchunk, int* chunk) {
+// Tokens per workgroup: about two workgroups per compute unit, at least 1024 tokens each (so that
+// the table build and the 2 KB histogram per head are amortised), at most kMaxChunks per head.
+void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
+    const int NT = d.R > 4 ? 2 : 1;
+    const int HB = 4 * NT;
+    const int nhb = (d.R + HB - 1) / HB;
     const int units = d.units() * nhb;
-    int want = (1024 + units - 1) / units;  // chunks per unit
+    int want = (512 + units - 1) / units;
+    if (want > kMaxChunks) want = kMaxChunks;
     int ch = (d.Lmax + want - 1) / want;
     ch = (ch + kBlock - 1) / kBlock * kBlock;
-    if (ch < kBlock) ch = kBlock;
-    if (ch > 16384) ch = 16384;
+    if (ch < 1024) ch = 1024;
+    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += kBlock;
+    *nhb_out = nhb;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
 }
 
+bool score_plan_ok(const Dims& d) {
+    int nhb, nchunk, chunk;
+    score_plan(d, &nhb, &nchunk, &chunk);
+    return chunk <= kMaxChunkTokens;
+}
+
 template <int DT>
-static hipError_t launch_score_t(const Dims& d, const void* q, const float* codebook, const uint8_t* codes,
-                                 const int32_t* seq_len, float* scores, uint32_t* hist, float* binp,
-                                 hipStream_t s) {
+static hipError_t launch_score_t(const Dims& d, const Workspace* w, int k, const void* q, const float* codebook,
+                                 const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s) {
+    int nhb, nchunk, chunk;
+    score_plan(d, &nhb, &nchunk, &chunk);
     const int NT = d.R > 4 ? 2 : 1;
-    const int HB = 4 * NT;
-    const int nhb = (d.R + HB - 1) / HB;
-    int nchunk, chunk;
-    score_plan(d, nhb, &nchunk, &chunk);
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
-#define SIK_SCORE(NTV, HV)                                                                              \
-    score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(qp, codebook, codes, seq_len, scores, hist, binp, \
-                                                      d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
-    if (hist) {
+#define SIK_SCORE(NTV, HV)                                                                                   \
+    score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(qp, codebook, codes, seq_len, scores,                  \
+                                                      w ? w->parthist : nullptr, w ? w->counters : nullptr, \
+                                                      w ? w->binp : nullptr, w ? w->thr : nullptr, k, d.Hkv, \
+                                                      d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
+    if (w) {
         if (NT == 1) SIK_SCORE(1, true); else SIK_SCORE(2, true);
     } else {
         if (NT == 1) SIK_SCORE(1, false); else SIK_SCORE(2, false);
@@ -201,10 +259,10 @@ static hipError_t launch_score_t(const Dims& d, const void* q, const float* code
     return hipGetLastError();
 }
 
-hipError_t launch_score(const Dims& d, const void* q, const float* codebook, const uint8_t* codes,
-                        const int32_t* seq_len, float* scores, uint32_t* hist, float* binp, hipStream_t s) {
-    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, q, codebook, codes, seq_len, scores, hist, binp, s)
-                               : launch_score_t<kF16>(d, q, codebook, codes, seq_len, scores, hist, binp, s);
+hipError_t launch_score(const Dims& d, const Workspace* w, int k, const void* q, const float* codebook,
+                        const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s) {
+    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, k, q, codebook, codes, seq_len, scores, s)
+                               : launch_score_t<kF16>(d, w, k, q, codebook, codes, seq_len, scores, s);
 }
 
 }  // namespace sik

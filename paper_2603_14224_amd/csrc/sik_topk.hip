@@ -1,7 +1,7 @@
 // Exact per-query-head top-k selection on gfx950 without sorting (the selection step after the
 // retrieval equation in "Compressed-Domain Top-k Retrieval").
 //
-// Level 1: a 1024-bin histogram of a monotone map of the score (built while scoring, or by the
+// Level 1: a 512-bin histogram of a monotone map of the score (built while scoring, or by the
 // two stand-alone kernels below) locates the threshold bin b*: every token in a bin above b* is
 // selected; tokens inside b* are candidates.
 // Level 2: the candidates (typically L / 1000 of them) are gathered by all workgroups of the
@@ -11,10 +11,11 @@
 // 8-bit radix select over the bin's members, still exact.
 #include "sik_device.h"
 #include "sik_internal.h"
+#include "sik_select.h"
 
 namespace sik {
 
-constexpr int kSelChunkMax = 2048;  // scores scanned per select workgroup (bounds its LDS lists)
+constexpr int kSelChunkMax = 4096;  // scores scanned per select workgroup (bounds its LDS list)
 
 // ---- stand-alone level 1, pass A: per-row min and max of the order-preserving keys ---------
 __global__ __launch_bounds__(kBlock) void minmax_kernel(const float* __restrict__ scores,
@@ -29,6 +30,7 @@ __global__ __launch_bounds__(kBlock) void minmax_kernel(const float* __restrict_
     if (start >= end) return;
     uint32_t kmin = 0xffffffffu, kmax = 0u;
     const float* s = scores + static_cast<size_t>(row) * Lmax;
+#pragma unroll 8
     for (int i = start + tid; i < end; i += kBlock) {
         const uint32_t key = float_to_key(s[i]);
         kmin = min(kmin, key);
@@ -54,18 +56,21 @@ __global__ __launch_bounds__(kBlock) void minmax_kernel(const float* __restrict_
     }
 }
 
-// ---- stand-alone level 1, pass B: histogram over [min, max] ---------------------------------
+// ---- stand-alone level 1, pass B: histogram over [min, max] and threshold bin ---------------
 __global__ __launch_bounds__(kBlock) void hist_kernel(const float* __restrict__ scores,
                                                       const int32_t* __restrict__ seq_len,
-                                                      const uint32_t* __restrict__ counters,
-                                                      uint32_t* __restrict__ hist, float* __restrict__ binp,
-                                                      int Hq, int Lmax, int nchunk, int chunk) {
+                                                      uint32_t* __restrict__ counters,
+                                                      uint32_t* __restrict__ parthist,
+                                                      float* __restrict__ binp, int32_t* __restrict__ thr,
+                                                      int k, int Hq, int Lmax, int nchunk, int chunk) {
     __shared__ uint32_t lhist[kBins];
+    __shared__ uint32_t lds4[4];
+    __shared__ int s_flag;
     const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
     int L = seq_len[row / Hq];
-    L = L > Lmax ? Lmax : L;
+    L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const int start = c * chunk, end = min(L, start + chunk);
-    if (start >= end) return;
+    if (start >= L && c != 0) return;
     const float lo = key_to_float(~counters[row * 8 + 4]);
     const float hi = key_to_float(counters[row * 8 + 5]);
     const float span = hi - lo;
@@ -77,12 +82,14 @@ __global__ __launch_bounds__(kBlock) void hist_kernel(const float* __restrict__ 
     for (int e = tid; e < kBins; e += kBlock) lhist[e] = 0u;
     __syncthreads();
     const float* s = scores + static_cast<size_t>(row) * Lmax;
+#pragma unroll 8
     for (int i = start + tid; i < end; i += kBlock) atomicAdd(&lhist[score_bin(s[i], lo, scale)], 1u);
     __syncthreads();
-    for (int e = tid; e < kBins; e += kBlock) {
-        const uint32_t v = lhist[e];
-        if (v) atomic_add_u32(&hist[static_cast<size_t>(row) * kBins + e], v);
-    }
+    publish_hist(lhist, parthist + (static_cast<size_t>(row) * nchunk + c) * kHistWords);
+    const int nact = L > 0 ? (L + chunk - 1) / chunk : 1;
+    if (!last_arriver(&counters[row * 8 + 6], static_cast<uint32_t>(nact), &s_flag)) return;
+    find_threshold(parthist + static_cast<size_t>(row) * nchunk * kHistWords, nact, min(k, L), L, thr + row * 4,
+                   lds4);
 }
 
 // ---- level 2 fallback: radix select inside the threshold bin, one workgroup -----------------
@@ -159,68 +166,41 @@ __device__ void radix_select_in_bin(const float* __restrict__ s, int L, float lo
     }
 }
 
-// ---- select: threshold bin from the histogram, compaction, exact resolution -----------------
+// ---- select: compaction against the threshold bin, exact resolution of the bin ---------------
 __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict__ scores,
                                                         const int32_t* __restrict__ seq_len,
-                                                        const uint32_t* __restrict__ hist,
+                                                        const int32_t* __restrict__ thr,
                                                         const float* __restrict__ binp,
                                                         uint32_t* __restrict__ counters,
                                                         uint32_t* __restrict__ cand,
                                                         int32_t* __restrict__ idx, int Hq, int Lmax, int k,
                                                         int nchunk, int chunk) {
-    __shared__ uint32_t scan[kBlock];
+    __shared__ uint32_t h256[kBlock];
     __shared__ int32_t l_sel[kSelChunkMax];
     __shared__ uint32_t l_cand[2 * kCandCap];
-    __shared__ int s_bstar, s_cgt, s_nb, s_flag;
+    __shared__ int s_flag;
     __shared__ uint32_t s_nsel, s_ncand, s_base[2], sh[4];
 
     const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
     int L = seq_len[row / Hq];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
+    const int start = c * chunk, end = min(L, start + chunk);
+    if (start >= L && c != 0) return;  // chunk 0 always runs: it may have to pad the row
     const int kk = min(k, L);
     const float* s = scores + static_cast<size_t>(row) * Lmax;
     int32_t* out = idx + static_cast<size_t>(row) * k;
 
+    // scores of this chunk: four independent 128-bit loads per lane per round
+    const int bstar = thr[row * 4], cgt = thr[row * 4 + 1], nb = thr[row * 4 + 2];
+    const float lo = binp[row * 2], scale = binp[row * 2 + 1];
+    const bool ranked = nb <= kCandCap;
     if (tid == 0) {
-        s_bstar = -1;  // "every bin is above the threshold": select all
-        s_cgt = L;
-        s_nb = 0;
         s_nsel = 0u;
         s_ncand = 0u;
     }
     __syncthreads();
-    if (kk < L) {
-        // suffix sums of the histogram: thread t owns bins 4t .. 4t+3
-        const uint4 h4 = reinterpret_cast<const uint4*>(hist + static_cast<size_t>(row) * kBins)[tid];
-        const uint32_t own = h4.x + h4.y + h4.z + h4.w;
-        scan[tid] = own;
-        __syncthreads();
-        for (int o = 1; o < kBlock; o <<= 1) {  // inclusive suffix scan
-            const uint32_t add = tid + o < kBlock ? scan[tid + o] : 0u;
-            __syncthreads();
-            scan[tid] += add;
-            __syncthreads();
-        }
-        uint32_t cum = scan[tid] - own;  // tokens in bins owned by higher threads
-        const uint32_t hb[4] = {h4.x, h4.y, h4.z, h4.w};
-#pragma unroll
-        for (int e = 3; e >= 0; --e) {
-            if (cum < static_cast<uint32_t>(kk) && static_cast<uint32_t>(kk) <= cum + hb[e]) {
-                s_bstar = 4 * tid + e;
-                s_cgt = static_cast<int>(cum);
-                s_nb = static_cast<int>(hb[e]);
-            }
-            cum += hb[e];
-        }
-        __syncthreads();
-    }
-    const int bstar = s_bstar, cgt = s_cgt, nb = s_nb;
-    const bool ranked = nb <= kCandCap;
-    const float lo = binp[row * 2], scale = binp[row * 2 + 1];
 
-    const int start = c * chunk, end = min(L, start + chunk);
-    for (int i = start + tid; i < end; i += kBlock) {
-        const float v = s[i];
+    auto classify = [&](float v, int i) {
         const int bin = bstar < 0 ? 0 : score_bin(v, lo, scale);
         if (bin > bstar) {
             l_sel[atomicAdd(&s_nsel, 1u)] = i;
@@ -231,6 +211,29 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
                 l_cand[2 * pos + 1] = static_cast<uint32_t>(i);
             }
         }
+    };
+    if ((Lmax & 3) == 0) {  // rows are 16-byte aligned: vector loads
+        const float4* s4 = reinterpret_cast<const float4*>(s);
+        const int q0 = start >> 2, q1 = (end + 3) >> 2;  // start is a multiple of 256
+        for (int base = q0; base < q1; base += 4 * kBlock) {
+            float4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int qi = base + j * kBlock + tid;
+                v[j] = qi < q1 ? s4[qi] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = (base + j * kBlock + tid) * 4;
+                if (i < end) classify(v[j].x, i);
+                if (i + 1 < end) classify(v[j].y, i + 1);
+                if (i + 2 < end) classify(v[j].z, i + 2);
+                if (i + 3 < end) classify(v[j].w, i + 3);
+            }
+        }
+    } else {
+#pragma unroll 4
+        for (int i = start + tid; i < end; i += kBlock) classify(s[i], i);
     }
     __syncthreads();
     if (tid == 0) {
@@ -247,19 +250,20 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     for (uint32_t j = tid; j < ncand; j += kBlock) {
         const uint32_t pos = s_base[1] + j;
         if (pos < static_cast<uint32_t>(kCandCap)) {
-            crow[2 * pos] = l_cand[2 * j];
-            crow[2 * pos + 1] = l_cand[2 * j + 1];
+            st_agent(&crow[2 * pos], l_cand[2 * j]);
+            st_agent(&crow[2 * pos + 1], l_cand[2 * j + 1]);
         }
     }
 
-    if (!last_arriver(&counters[row * 8 + 2], static_cast<uint32_t>(nchunk), &s_flag)) return;
+    const int nact = L > 0 ? (L + chunk - 1) / chunk : 1;
+    if (!last_arriver(&counters[row * 8 + 2], static_cast<uint32_t>(nact), &s_flag)) return;
 
     // ---- last workgroup of this query head: resolve the threshold bin, pad the row ----------
     const int need = kk - min(cgt, kk);
     if (need > 0) {
         if (ranked) {
             const int n = min(nb, kCandCap);
-            for (int j = tid; j < 2 * n; j += kBlock) l_cand[j] = crow[j];
+            for (int j = tid; j < 2 * n; j += kBlock) l_cand[j] = ld_agent(&crow[j]);
             __syncthreads();
             for (int a = tid; a < n; a += kBlock) {
                 const uint32_t ka = l_cand[2 * a], ia = l_cand[2 * a + 1];
@@ -271,33 +275,44 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
                 if (rank < need) out[cgt + rank] = static_cast<int32_t>(ia);
             }
         } else {
-            radix_select_in_bin(s, L, lo, scale, bstar, need, out + cgt, scan, sh);
+            radix_select_in_bin(s, L, lo, scale, bstar, need, out + cgt, h256, sh);
         }
     }
     for (int j = kk + tid; j < k; j += kBlock) out[j] = -1;
 }
 
 // ---------------------------------------------------------------------------------------
-static void select_plan(const Dims& d, int* nchunk, int* chunk) {
+void select_plan(const Dims& d, int* nchunk, int* chunk) {
     const int rows = d.rows();
-    int want = (1024 + rows - 1) / rows;
+    int want = (512 + rows - 1) / rows;
     int ch = (d.Lmax + want - 1) / want;
     ch = (ch + kBlock - 1) / kBlock * kBlock;
-    if (ch < kBlock) ch = kBlock;
+    if (ch < 1024) ch = 1024;
     if (ch > kSelChunkMax) ch = kSelChunkMax;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
 }
 
-hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
+void hist_plan(const Dims& d, int* nchunk, int* chunk) {
+    const int rows = d.rows();
+    int want = (512 + rows - 1) / rows;
+    if (want > kMaxChunks) want = kMaxChunks;
+    int ch = (d.Lmax + want - 1) / want;
+    ch = (ch + kBlock - 1) / kBlock * kBlock;
+    if (ch < 2048) ch = 2048;
+    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += kBlock;
+    *chunk = ch;
+    *nchunk = (d.Lmax + ch - 1) / ch;
+}
+
+hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len, int k,
                             hipStream_t s) {
     int nchunk, chunk;
-    select_plan(d, &nchunk, &chunk);
-    chunk *= 4;  // the histogram passes keep no per-chunk lists
-    nchunk = (d.Lmax + chunk - 1) / chunk;
+    hist_plan(d, &nchunk, &chunk);
     const int grid = nchunk * d.rows();
     minmax_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, d.Hq, d.Lmax, nchunk, chunk);
-    hist_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, w.hist, w.binp, d.Hq, d.Lmax, nchunk, chunk);
+    hist_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, w.parthist, w.binp, w.thr, k, d.Hq, d.Lmax,
+                                        nchunk, chunk);
     return hipGetLastError();
 }
 
@@ -305,7 +320,7 @@ hipError_t launch_select(const Dims& d, const Workspace& w, const float* scores,
                          int k, int32_t* idx, hipStream_t s) {
     int nchunk, chunk;
     select_plan(d, &nchunk, &chunk);
-    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, seq_len, w.hist, w.binp, w.counters, w.cand, idx,
+    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, seq_len, w.thr, w.binp, w.counters, w.cand, idx,
                                                        d.Hq, d.Lmax, k, nchunk, chunk);
     return hipGetLastError();
 }
