@@ -45,7 +45,6 @@ Workspace carve(const Dims& d, int k, void* base) {
     hist_plan(d, &nc_hist, &ch);
     const size_t nc = static_cast<size_t>(nc_score > nc_hist ? nc_score : nc_hist);
     w.parthist = reinterpret_cast<uint32_t*>(take(rows * nc * (kBins / 2) * 4));
-    w.thr = reinterpret_cast<int32_t*>(take(rows * 4 * 4));
     w.binp = reinterpret_cast<float*>(take(rows * 2 * 4));
     w.cand = reinterpret_cast<uint32_t*>(take(rows * kCandCap * 2 * 4));
     w.idx = reinterpret_cast<int32_t*>(take(rows * static_cast<size_t>(k > 0 ? k : 1) * 4));
@@ -122,7 +121,7 @@ int sik_score(const sik_layout* layout, const void* q, const float* codebook, co
     int rc = check_layout(layout, &d);
     if (rc) return rc;
     if (!q || !codebook || !codes || !seq_len || !scores) return SIK_ERR_NULL;
-    return launched(launch_score(d, nullptr, 0, q, codebook, codes, seq_len, scores,
+    return launched(launch_score(d, nullptr, q, codebook, codes, seq_len, scores,
                                  static_cast<hipStream_t>(stream)));
 }
 
@@ -138,8 +137,8 @@ int sik_topk(const sik_layout* layout, const float* scores, const int32_t* seq_l
     if (rc) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = launch_prep(d, w, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
-    if (e == hipSuccess) e = launch_topk_hist(d, w, scores, seq_len, k, s);
-    if (e == hipSuccess) e = launch_select(d, w, scores, seq_len, k, idx, s);
+    if (e == hipSuccess) e = launch_topk_hist(d, w, scores, seq_len, s);
+    if (e == hipSuccess) e = launch_select(d, w, false, scores, seq_len, k, idx, s);
     return launched(e);
 }
 
@@ -180,9 +179,9 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     hipError_t e = mark(0);
     if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
     if (e == hipSuccess) e = mark(1);
-    if (e == hipSuccess) e = launch_score(d, &w, k, q, codebook, codes, seq_len, w.scores, s);
+    if (e == hipSuccess) e = launch_score(d, &w, q, codebook, codes, seq_len, w.scores, s);
     if (e == hipSuccess) e = mark(2);
-    if (e == hipSuccess) e = launch_select(d, w, w.scores, seq_len, k, idx, s);
+    if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
     if (e == hipSuccess) e = mark(3);
     if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
     if (e == hipSuccess) e = mark(4);

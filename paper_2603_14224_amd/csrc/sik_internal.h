@@ -22,10 +22,9 @@ struct Workspace {
     uint32_t* zero_begin;   // start of the zero-initialised region
     size_t zero_words;      // its length in 32-bit words
     uint32_t* counters;     // [rows][8]          0 sel_cnt, 1 cand_cnt, 2 select ticket, 3 attn ticket,
-                            //                    4 ~min key, 5 max key (stand-alone top-k), 6 histogram ticket
+                            //                    4 ~min key, 5 max key (stand-alone top-k), 
     // plain scratch
     uint32_t* parthist;     // [rows][nchunk][kBins/2]  per-chunk histograms, two 16-bit counts per word
-    int32_t* thr;           // [rows][4]          threshold bin, tokens above it, tokens in it
     float* binp;            // [rows][2]          histogram origin, scale
     uint32_t* cand;         // [rows][kCandCap][2] (key, index) of threshold-bin members
     int32_t* idx;           // [rows][k]          selection when the caller passes no idx_out
@@ -44,17 +43,18 @@ Workspace carve(const Dims& d, int k, void* base);
 // launchers (return hipError_t of the launch)
 hipError_t launch_prep(const Dims& d, const Workspace& w, const void* k_new, const void* v_new, void* K,
                        void* V, int32_t* seq_len, const float* mu, uint8_t* codes, hipStream_t s);
-// w == nullptr: scores only; otherwise also the selection histogram and threshold for top-k `k`
-hipError_t launch_score(const Dims& d, const Workspace* w, int k, const void* q, const float* codebook,
+// w == nullptr: scores only; otherwise also the per-chunk selection histograms
+hipError_t launch_score(const Dims& d, const Workspace* w, const void* q, const float* codebook,
                         const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s);
-hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len, int k,
+hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
                             hipStream_t s);
 void score_plan(const Dims& d, int* nhb, int* nchunk, int* chunk);
 bool score_plan_ok(const Dims& d);
 void hist_plan(const Dims& d, int* nchunk, int* chunk);
 void select_plan(const Dims& d, int* nchunk, int* chunk);
-hipError_t launch_select(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
-                         int k, int32_t* idx, hipStream_t s);
+// hist_from_score: the chunk histograms come from the scoring kernel (else from launch_topk_hist)
+hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score, const float* scores,
+                         const int32_t* seq_len, int k, int32_t* idx, hipStream_t s);
 hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                        const int32_t* idx, int k, float scale, void* out, hipStream_t s);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,

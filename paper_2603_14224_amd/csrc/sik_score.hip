@@ -10,8 +10,7 @@
 // four such loads per lane are in flight while the previous four tokens are scored.
 //
 // With HIST the kernel also builds the first level of the selection: a histogram of a monotone
-// map of each query head's scores, published per chunk; the last workgroup of the head block to
-// finish adds the chunks up and writes the threshold bin for the select kernel.
+// map of each query head's scores, published per chunk for the select kernel.
 #include "sik_device.h"
 #include "sik_internal.h"
 #include "sik_select.h"
@@ -64,17 +63,13 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
                                                        const int32_t* __restrict__ seq_len,
                                                        float* __restrict__ scores,
                                                        uint32_t* __restrict__ parthist,
-                                                       uint32_t* __restrict__ counters,
-                                                       float* __restrict__ binp, int32_t* __restrict__ thr,
-                                                       int k, int Hkv, int Hq, int R, int Lmax, int nchunk,
-                                                       int chunk, int nhb) {
+                                                       float* __restrict__ binp, int Hkv, int Hq, int R,
+                                                       int Lmax, int nchunk, int chunk, int nhb) {
     constexpr int HB = 4 * NT;
     __shared__ float4 lut[NT][kG * 16];
     __shared__ float qs[HB][kD];
     __shared__ float bp[HB][2];
     __shared__ uint32_t lhist[HIST ? HB * kBins : 1];
-    __shared__ uint32_t lds4[4];
-    __shared__ int s_flag;
 
     const int tid = threadIdx.x;
     const int c = blockIdx.x % nchunk;
@@ -205,11 +200,6 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         __syncthreads();
         for (int s = 0; s < nh; ++s)
             publish_hist(&lhist[s * kBins], parthist + ((row0 + s) * nchunk + c) * kHistWords);
-        const int nact = L > 0 ? (L + chunk - 1) / chunk : 1;  // chunks that run for this sequence
-        if (!last_arriver(&counters[row0 * 8 + 6], static_cast<uint32_t>(nact), &s_flag)) return;
-        for (int s = 0; s < nh; ++s)
-            find_threshold(parthist + (row0 + s) * nchunk * kHistWords, nact, min(k, L), L,
-                           thr + (row0 + s) * 4, lds4);
     }
 }
 
@@ -238,7 +228,7 @@ bool score_plan_ok(const Dims& d) {
 }
 
 template <int DT>
-static hipError_t launch_score_t(const Dims& d, const Workspace* w, int k, const void* q, const float* codebook,
+static hipError_t launch_score_t(const Dims& d, const Workspace* w, const void* q, const float* codebook,
                                  const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s) {
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
@@ -246,10 +236,9 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, int k, const
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
 #define SIK_SCORE(NTV, HV)                                                                                   \
-    score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(qp, codebook, codes, seq_len, scores,                  \
-                                                      w ? w->parthist : nullptr, w ? w->counters : nullptr, \
-                                                      w ? w->binp : nullptr, w ? w->thr : nullptr, k, d.Hkv, \
-                                                      d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
+    score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(qp, codebook, codes, seq_len, scores,                \
+                                                      w ? w->parthist : nullptr, w ? w->binp : nullptr, \
+                                                      d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
     if (w) {
         if (NT == 1) SIK_SCORE(1, true); else SIK_SCORE(2, true);
     } else {
@@ -259,10 +248,10 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, int k, const
     return hipGetLastError();
 }
 
-hipError_t launch_score(const Dims& d, const Workspace* w, int k, const void* q, const float* codebook,
+hipError_t launch_score(const Dims& d, const Workspace* w, const void* q, const float* codebook,
                         const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s) {
-    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, k, q, codebook, codes, seq_len, scores, s)
-                               : launch_score_t<kF16>(d, w, k, q, codebook, codes, seq_len, scores, s);
+    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, q, codebook, codes, seq_len, scores, s)
+                               : launch_score_t<kF16>(d, w, q, codebook, codes, seq_len, scores, s);
 }
 
 }  // namespace sik

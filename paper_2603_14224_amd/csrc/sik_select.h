@@ -12,15 +12,17 @@ constexpr int kHistWords = kBins / 2;  // 32-bit words per (query head, chunk): 
 constexpr int kMaxChunks = 64;         // chunks per query head in the histogram-producing kernels
 constexpr int kMaxChunkTokens = 65535; // a 16-bit count per bin must hold a whole chunk
 
-// thr[row] = { threshold bin b* (-1: select everything), tokens in bins above b*, tokens in b*, 0 }
 struct Threshold {
-    int bstar, cgt, nb;
+    int bstar;  // threshold bin, -1: every token is selected
+    int cgt;    // tokens in bins above bstar (all of them selected)
+    int nb;     // tokens inside bstar (candidates)
 };
 
-// Publish this workgroup's LDS histogram (kBins 32-bit counts) of one query head.
+// Publish this workgroup's LDS histogram (kBins 32-bit counts) of one query head; the kernel that
+// follows in the stream reads it.
 __device__ __forceinline__ void publish_hist(const uint32_t* lhist, uint32_t* part) {
     const int t = threadIdx.x;
-    st_agent(&part[t], lhist[2 * t] | (lhist[2 * t + 1] << 16));
+    part[t] = lhist[2 * t] | (lhist[2 * t + 1] << 16);
 }
 
 // Inclusive suffix sum over the 256 threads of the workgroup (thread t gets sum over u >= t).
@@ -31,7 +33,6 @@ __device__ __forceinline__ uint32_t block_suffix_sum(uint32_t v, uint32_t* lds4)
         const uint32_t up = static_cast<uint32_t>(__shfl_down(static_cast<int>(v), o, 64));
         if (lane + o < 64) v += up;
     }
-    __syncthreads();  // lds4 may still be read from an earlier call
     if (lane == 0) lds4[wv] = v;
     __syncthreads();
 #pragma unroll
@@ -40,40 +41,70 @@ __device__ __forceinline__ uint32_t block_suffix_sum(uint32_t v, uint32_t* lds4)
     return v;
 }
 
-// Called by all threads of the last workgroup of a query head: add up the `nact` published chunk
-// histograms and find the bin where the count from the top reaches kk = min(k, L).
-__device__ __forceinline__ void find_threshold(const uint32_t* part_row, int nact, int kk, int L,
-                                               int32_t* thr_row, uint32_t* lds4) {
-    const int t = threadIdx.x;
-    if (kk >= L) {  // uniform
-        if (t == 0) {
-            thr_row[0] = -1;
-            thr_row[1] = L;
-            thr_row[2] = 0;
-        }
-        return;
-    }
-    uint32_t c0 = 0, c1 = 0;
+// The chunk histograms of one query head, as four 128-bit loads per lane in flight at a time:
+// wavefront w takes chunks w, w+4, ...; lane l the words 4l .. 4l+3 (bins 8l .. 8l+7).
+struct HistLoads {
+    uint32_t cnt[8];
+};
+__device__ __forceinline__ HistLoads load_chunk_hists(const uint32_t* part_row, int nact) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    HistLoads h;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h.cnt[e] = 0u;
+    const uint4* p4 = reinterpret_cast<const uint4*>(part_row);
 #pragma unroll 8
-    for (int cc = 0; cc < nact; ++cc) {
-        const uint32_t v = ld_agent(&part_row[cc * kHistWords + t]);
-        c0 += v & 0xffffu;
-        c1 += v >> 16;
+    for (int cc = wv; cc < nact; cc += kBlock / kWave) {
+        const uint4 v = p4[cc * (kHistWords / 4) + lane];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h.cnt[2 * e] += w[e] & 0xffffu;
+            h.cnt[2 * e + 1] += w[e] >> 16;
+        }
+    }
+    return h;
+}
+
+// Called by all threads: add the chunk histograms up and find the bin where the count from the
+// top reaches kk = min(k, L).  red: LDS [4][kBins] words, lds4: LDS [4], sthr: LDS [3].
+__device__ __forceinline__ Threshold find_threshold(const HistLoads& h, int kk, int L, uint32_t* red,
+                                                    uint32_t* lds4, int* sthr) {
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    Threshold r;
+    if (kk >= L) {  // uniform: everything is selected
+        r.bstar = -1;
+        r.cgt = L;
+        r.nb = 0;
+        return r;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[wv * kBins + lane * 8 + e] = h.cnt[e];
+    __syncthreads();
+    uint32_t c0 = 0, c1 = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / kWave; ++w) {
+        c0 += red[w * kBins + 2 * t];
+        c1 += red[w * kBins + 2 * t + 1];
     }
     const uint32_t own = c0 + c1;
     uint32_t cum = block_suffix_sum(own, lds4) - own;  // tokens in bins owned by higher threads
     const uint32_t ukk = static_cast<uint32_t>(kk);
     if (cum < ukk && ukk <= cum + c1) {
-        thr_row[0] = 2 * t + 1;
-        thr_row[1] = static_cast<int32_t>(cum);
-        thr_row[2] = static_cast<int32_t>(c1);
+        sthr[0] = 2 * t + 1;
+        sthr[1] = static_cast<int>(cum);
+        sthr[2] = static_cast<int>(c1);
     }
     cum += c1;
     if (cum < ukk && ukk <= cum + c0) {
-        thr_row[0] = 2 * t;
-        thr_row[1] = static_cast<int32_t>(cum);
-        thr_row[2] = static_cast<int32_t>(c0);
+        sthr[0] = 2 * t;
+        sthr[1] = static_cast<int>(cum);
+        sthr[2] = static_cast<int>(c0);
     }
+    __syncthreads();
+    r.bstar = sthr[0];
+    r.cgt = sthr[1];
+    r.nb = sthr[2];
+    return r;
 }
 
 }  // namespace sik

@@ -56,16 +56,14 @@ __global__ __launch_bounds__(kBlock) void minmax_kernel(const float* __restrict_
     }
 }
 
-// ---- stand-alone level 1, pass B: histogram over [min, max] and threshold bin ---------------
+// ---- stand-alone level 1, pass B: per-chunk histograms over [min, max] -----------------------
 __global__ __launch_bounds__(kBlock) void hist_kernel(const float* __restrict__ scores,
                                                       const int32_t* __restrict__ seq_len,
-                                                      uint32_t* __restrict__ counters,
+                                                      const uint32_t* __restrict__ counters,
                                                       uint32_t* __restrict__ parthist,
-                                                      float* __restrict__ binp, int32_t* __restrict__ thr,
-                                                      int k, int Hq, int Lmax, int nchunk, int chunk) {
+                                                      float* __restrict__ binp, int Hq, int Lmax, int nchunk,
+                                                      int chunk) {
     __shared__ uint32_t lhist[kBins];
-    __shared__ uint32_t lds4[4];
-    __shared__ int s_flag;
     const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
     int L = seq_len[row / Hq];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
@@ -86,10 +84,6 @@ __global__ __launch_bounds__(kBlock) void hist_kernel(const float* __restrict__ 
     for (int i = start + tid; i < end; i += kBlock) atomicAdd(&lhist[score_bin(s[i], lo, scale)], 1u);
     __syncthreads();
     publish_hist(lhist, parthist + (static_cast<size_t>(row) * nchunk + c) * kHistWords);
-    const int nact = L > 0 ? (L + chunk - 1) / chunk : 1;
-    if (!last_arriver(&counters[row * 8 + 6], static_cast<uint32_t>(nact), &s_flag)) return;
-    find_threshold(parthist + static_cast<size_t>(row) * nchunk * kHistWords, nact, min(k, L), L, thr + row * 4,
-                   lds4);
 }
 
 // ---- level 2 fallback: radix select inside the threshold bin, one workgroup -----------------
@@ -169,8 +163,8 @@ __device__ void radix_select_in_bin(const float* __restrict__ s, int L, float lo
 // ---- select: compaction against the threshold bin, exact resolution of the bin ---------------
 __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict__ scores,
                                                         const int32_t* __restrict__ seq_len,
-                                                        const int32_t* __restrict__ thr,
-                                                        const float* __restrict__ binp,
+                                                        const uint32_t* __restrict__ parthist, int hchunks,
+                                                        int hchunk, const float* __restrict__ binp,
                                                         uint32_t* __restrict__ counters,
                                                         uint32_t* __restrict__ cand,
                                                         int32_t* __restrict__ idx, int Hq, int Lmax, int k,
@@ -178,7 +172,8 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     __shared__ uint32_t h256[kBlock];
     __shared__ int32_t l_sel[kSelChunkMax];
     __shared__ uint32_t l_cand[2 * kCandCap];
-    __shared__ int s_flag;
+    __shared__ uint32_t red[(kBlock / kWave) * kBins];
+    __shared__ int s_flag, sthr[3];
     __shared__ uint32_t s_nsel, s_ncand, s_base[2], sh[4];
 
     const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
@@ -190,14 +185,17 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     const float* s = scores + static_cast<size_t>(row) * Lmax;
     int32_t* out = idx + static_cast<size_t>(row) * k;
 
-    // scores of this chunk: four independent 128-bit loads per lane per round
-    const int bstar = thr[row * 4], cgt = thr[row * 4 + 1], nb = thr[row * 4 + 2];
+    // threshold bin of this query head from the chunk histograms of the producing kernel
     const float lo = binp[row * 2], scale = binp[row * 2 + 1];
-    const bool ranked = nb <= kCandCap;
     if (tid == 0) {
         s_nsel = 0u;
         s_ncand = 0u;
     }
+    const int hact = L > 0 ? (L + hchunk - 1) / hchunk : 1;  // chunks the producer ran for this sequence
+    const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hact);
+    const Threshold th = find_threshold(hl, kk, L, red, sh, sthr);
+    const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
+    const bool ranked = nb <= kCandCap;
     __syncthreads();
 
     auto classify = [&](float v, int i) {
@@ -305,23 +303,27 @@ void hist_plan(const Dims& d, int* nchunk, int* chunk) {
     *nchunk = (d.Lmax + ch - 1) / ch;
 }
 
-hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len, int k,
+hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
                             hipStream_t s) {
     int nchunk, chunk;
     hist_plan(d, &nchunk, &chunk);
     const int grid = nchunk * d.rows();
     minmax_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, d.Hq, d.Lmax, nchunk, chunk);
-    hist_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, w.parthist, w.binp, w.thr, k, d.Hq, d.Lmax,
-                                        nchunk, chunk);
+    hist_kernel<<<grid, kBlock, 0, s>>>(scores, seq_len, w.counters, w.parthist, w.binp, d.Hq, d.Lmax, nchunk,
+                                        chunk);
     return hipGetLastError();
 }
 
-hipError_t launch_select(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
-                         int k, int32_t* idx, hipStream_t s) {
-    int nchunk, chunk;
+hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score, const float* scores,
+                         const int32_t* seq_len, int k, int32_t* idx, hipStream_t s) {
+    int nchunk, chunk, hchunks, hchunk, nhb;
     select_plan(d, &nchunk, &chunk);
-    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, seq_len, w.thr, w.binp, w.counters, w.cand, idx,
-                                                       d.Hq, d.Lmax, k, nchunk, chunk);
+    if (hist_from_score)
+        score_plan(d, &nhb, &hchunks, &hchunk);
+    else
+        hist_plan(d, &hchunks, &hchunk);
+    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, seq_len, w.parthist, hchunks, hchunk, w.binp,
+                                                       w.counters, w.cand, idx, d.Hq, d.Lmax, k, nchunk, chunk);
     return hipGetLastError();
 }
 
