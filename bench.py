@@ -148,11 +148,14 @@ def main():
     reset_lengths()
 
     # ---- per-kernel durations, HIP events on the launch stream, same steps as the timed region
-    kus = np.zeros(4)
+    # (each interval includes the cost of the event pair; an empty interval measured in the same call
+    # is subtracted)
+    raw = np.zeros(5)
     n_prof = min(args.steps, 200)
     for i in range(n_prof):
-        kus += np.array(step(args.warmup + i, profiled=True))
-    kus /= n_prof
+        raw += np.array(step(args.warmup + i, profiled=True))
+    raw /= n_prof
+    kus = np.maximum(raw[:4] - raw[4], 0.05)
     reset_lengths()
 
     ab = W.algorithmic_bytes(cfg)
@@ -186,6 +189,7 @@ def main():
         "us_per_step_stream_launch": round(sec_stream * 1e6, 3),
         "us_per_step_hipgraph": None if sec_graph is None else round(sec_graph * 1e6, 3),
         "kernel_us_hip_events": {KERNELS[i]: round(float(kus[i]), 3) for i in range(4)},
+        "hip_event_pair_overhead_us": round(float(raw[4]), 3),
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "algorithmic_bytes_per_launch": dom_bytes},

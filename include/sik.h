@@ -143,8 +143,10 @@ int sik_decode_step(const sik_layout *layout, const void *q, const void *k_new, 
 
 /* Measurement aid for benchmarks (not for serving loops): runs exactly the kernels of
  * sik_decode_step with the same arguments, bracketing each with a HIP event on `stream`, then
- * waits for the stream and returns the kernels' durations in microseconds in kernel_us (host
- * pointer, SIK_N_KERNELS floats, in launch order: prep/append, score, select, attention). */
+ * waits for the stream and returns the event-to-event intervals in microseconds in kernel_us
+ * (host pointer, SIK_N_KERNELS + 1 floats: prep/append, score, select, attention in launch
+ * order, then one EMPTY interval between two back-to-back events, i.e. the cost of the event pair
+ * itself, which the caller subtracts from the others). */
 #define SIK_N_KERNELS 4
 int sik_decode_step_profiled(const sik_layout *layout, const void *q, const void *k_new,
                              const void *v_new, void *K, void *V, int32_t *seq_len, const float *mu,

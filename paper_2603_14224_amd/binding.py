@@ -139,8 +139,9 @@ def sik_decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes,
 
 def sik_decode_step_profiled(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,
                              idx_out, workspace):
-    """Runs one decode step with per-kernel HIP events; returns the 4 kernel durations in microseconds."""
-    us = (ctypes.c_float * 4)()
+    """Runs one decode step with per-kernel HIP events; returns the 4 event-to-event intervals and the
+    empty-interval cost of an event pair, in microseconds."""
+    us = (ctypes.c_float * 5)()
     _check(lib().sik_decode_step_profiled(ctypes.byref(layout), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K),
                                           _ptr(V), _ptr(seq_len), _ptr(mu), _ptr(codebook), _ptr(codes), int(k),
                                           float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(workspace),

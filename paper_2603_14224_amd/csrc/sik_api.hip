@@ -185,6 +185,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if (e == hipSuccess) e = mark(3);
     if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
     if (e == hipSuccess) e = mark(4);
+    if (e == hipSuccess && ev) e = hipEventRecord(ev[5], s);  // empty interval: cost of an event pair
     return launched(e);
 }
 
@@ -201,16 +202,17 @@ int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void
                              uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
                              void* workspace, size_t workspace_bytes, void* stream, float* kernel_us) {
     if (!kernel_us) return SIK_ERR_NULL;
-    hipEvent_t ev[SIK_N_KERNELS + 1];
+    constexpr int kEvents = SIK_N_KERNELS + 2;
+    hipEvent_t ev[kEvents];
     int made = 0;
-    for (; made <= SIK_N_KERNELS; ++made)
+    for (; made < kEvents; ++made)
         if (hipEventCreate(&ev[made]) != hipSuccess) break;
-    int rc = made == SIK_N_KERNELS + 1 ? SIK_OK : SIK_ERR_LAUNCH;
+    int rc = made == kEvents ? SIK_OK : SIK_ERR_LAUNCH;
     if (rc == SIK_OK)
         rc = decode_step_impl(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,
                               idx_out, workspace, workspace_bytes, stream, ev);
-    if (rc == SIK_OK && hipEventSynchronize(ev[SIK_N_KERNELS]) != hipSuccess) rc = SIK_ERR_LAUNCH;
-    for (int i = 0; rc == SIK_OK && i < SIK_N_KERNELS; ++i) {
+    if (rc == SIK_OK && hipEventSynchronize(ev[SIK_N_KERNELS + 1]) != hipSuccess) rc = SIK_ERR_LAUNCH;
+    for (int i = 0; rc == SIK_OK && i <= SIK_N_KERNELS; ++i) {
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) rc = SIK_ERR_LAUNCH;
         kernel_us[i] = ms * 1000.0f;

@@ -12,6 +12,8 @@
 
 namespace sik {
 
+SIK_TL_DEFINE(sik_dbg_tl_attn)
+
 constexpr int kPartStride = kD + 2;
 
 struct SoftmaxState {
@@ -53,6 +55,7 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ int s_flag;
 
+    SIK_TL(16);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int slot = lane >> 4, p = lane & 15;
     const int row = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
@@ -116,6 +119,7 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
         st.m = mnew;
     }
 
+    SIK_TL(17);
     // the four 16-lane rows of the wavefront hold four independent partial softmaxes
     merge_from_lane(st, 16);
     merge_from_lane(st, 32);
@@ -153,7 +157,9 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
             st_agent(&pp[1], Lsum);
         }
     }
+    SIK_TL(18);
     if (!last_arriver(&counters[row * 8 + 3], static_cast<uint32_t>(nsplit), &s_flag)) return;
+    SIK_TL_ANY(19);
     if (tid < kD) {
         float Mg = kNegBig;
 #pragma unroll 8
@@ -168,6 +174,7 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
         }
         store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, lt > 0.0f ? ot / lt : 0.0f);
     }
+    SIK_TL_ANY(20);
 }
 
 static void attn_plan(const Dims& d, int k, int* nsplit, int* per) {

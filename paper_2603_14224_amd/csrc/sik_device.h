@@ -115,6 +115,38 @@ __device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, i
     return *lds_flag != 0;
 }
 
+// ---- optional phase timeline (debug builds only, -DSIK_TIMELINE) ------------------------------
+// SIK_TL(slot) stores the 100 MHz wall clock when thread 0 of the first, the middle or the last
+// workgroup of the grid passes the mark (plain stores, three columns); SIK_TL_ANY(slot) is for code
+// only one workgroup per row reaches (any of them may write: an approximate "latest").
+#ifdef SIK_TIMELINE
+#define SIK_TL_DEFINE(setter)                                                                     \
+    static __device__ unsigned long long* sik_tl_buf = nullptr;                                   \
+    extern "C" int setter(void* p) {                                                              \
+        return hipMemcpyToSymbol(HIP_SYMBOL(sik_tl_buf), &p, sizeof(p)) == hipSuccess ? 0 : -1;   \
+    }
+#define SIK_TL(slot)                                                                              \
+    do {                                                                                          \
+        if (threadIdx.x == 0 && sik_tl_buf) {                                                     \
+            const unsigned b_ = blockIdx.x, g_ = gridDim.x;                                       \
+            const int col_ = b_ == 0 ? 0 : (b_ == g_ / 2 ? 1 : (b_ == g_ - 1 ? 2 : -1));          \
+            if (col_ >= 0) sik_tl_buf[4 * (slot) + col_] = wall_clock64();                        \
+        }                                                                                         \
+    } while (0)
+#define SIK_TL_ANY(slot)                                                                          \
+    do {                                                                                          \
+        if (threadIdx.x == 0 && sik_tl_buf) sik_tl_buf[4 * (slot) + 3] = wall_clock64();          \
+    } while (0)
+#else
+#define SIK_TL_DEFINE(setter)
+#define SIK_TL(slot) \
+    do {             \
+    } while (0)
+#define SIK_TL_ANY(slot) \
+    do {                 \
+    } while (0)
+#endif
+
 // Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15); every lane gets the total.
 __device__ __forceinline__ float row16_sum(float v) {
     v += __shfl_xor(v, 8, 64);

@@ -17,6 +17,8 @@
 
 namespace sik {
 
+SIK_TL_DEFINE(sik_dbg_tl_score)
+
 constexpr int kTokPerIter = 4;  // tokens per lane per loop iteration
 
 template <int NT>
@@ -71,28 +73,27 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     __shared__ float bp[HB][2];
     __shared__ uint32_t lhist[HIST ? HB * kBins : 1];
 
+    SIK_TL(0);
     const int tid = threadIdx.x;
     const int c = blockIdx.x % nchunk;
     const int u = blockIdx.x / nchunk;
     const int hb = u % nhb;
     const int unit = u / nhb;
     const int h = unit % Hkv, b = unit / Hkv;
-    int L = seq_len[b];
-    L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const int start = c * chunk;
-    if (start >= L && c != 0) return;  // chunk 0 always runs: it owns the per-head outputs
-    const int end = min(L, start + chunk);
     const int hq0 = h * R + hb * HB;
     const int nh = min(HB, R - hb * HB);
     const size_t row0 = static_cast<size_t>(b) * Hq + hq0;
 
-    // every global load this workgroup needs before it can score goes out now, together
+    // every global load this workgroup needs before it can score goes out now, together; none of
+    // them waits for seq_len (codes up to the capacity are readable, stale ones are never used)
     const uint4* cp = reinterpret_cast<const uint4*>(codes + static_cast<size_t>(unit) * Lmax * kCodeBytes);
+    const int cap_end = min(Lmax, start + chunk);
     uint4 cur[kTokPerIter];
 #pragma unroll
     for (int j = 0; j < kTokPerIter; ++j) {
         const int i = start + j * kBlock + tid;
-        cur[j] = i < end ? cp[i] : make_uint4(0u, 0u, 0u, 0u);
+        cur[j] = i < cap_end ? cp[i] : make_uint4(0u, 0u, 0u, 0u);
     }
     const float4 cj0 = reinterpret_cast<const float4*>(codebook)[static_cast<size_t>(unit) * kG * 16 + tid];
     const float4 cj1 =
@@ -106,7 +107,12 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     }
     if constexpr (HIST)
         for (int e = tid; e < HB * kBins; e += kBlock) lhist[e] = 0u;
+    int L = seq_len[b];
+    L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
+    if (start >= L && c != 0) return;  // chunk 0 always runs: it owns the per-head outputs
+    const int end = min(L, start + chunk);
     __syncthreads();
+    SIK_TL(1);
 
     // Table^(g)[j] for the HB query heads, fp32
 #pragma unroll
@@ -137,10 +143,12 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         // end bins.  Any (lo, scale) is correct, this one keeps the threshold bin small.
         if (tid < HB * 32) {
             const int s = tid >> 5, g = tid & 31;
+            // entry j of group g, head s: lanes start at different j so that they hit different banks
+            const float* lf = reinterpret_cast<const float*>(&lut[s >> 2][g * 16]) + (s & 3);
             float sum = 0.0f, sq = 0.0f;
+#pragma unroll
             for (int j = 0; j < 16; ++j) {
-                const float4 v = lut[s >> 2][g * 16 + j];
-                const float x = (s & 3) == 0 ? v.x : (s & 3) == 1 ? v.y : (s & 3) == 2 ? v.z : v.w;
+                const float x = lf[((j + g) & 15) * 4];
                 sum += x;
                 sq = fmaf(x, x, sq);
             }
@@ -166,6 +174,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         __syncthreads();
     }
 
+    SIK_TL(2);
     for (int base = start; base < end; base += kTokPerIter * kBlock) {
         uint4 code[kTokPerIter];
 #pragma unroll
@@ -196,11 +205,13 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         }
     }
 
+    SIK_TL(3);
     if constexpr (HIST) {
         __syncthreads();
         for (int s = 0; s < nh; ++s)
             publish_hist(&lhist[s * kBins], parthist + ((row0 + s) * nchunk + c) * kHistWords);
     }
+    SIK_TL(4);
 }
 
 // Tokens per workgroup: about two workgroups per compute unit, at least 1024 tokens each (so that

@@ -15,6 +15,8 @@
 
 namespace sik {
 
+SIK_TL_DEFINE(sik_dbg_tl_topk)
+
 constexpr int kSelChunkMax = 4096;  // scores scanned per select workgroup (bounds its LDS list)
 
 // ---- stand-alone level 1, pass A: per-row min and max of the order-preserving keys ---------
@@ -176,6 +178,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     __shared__ int s_flag, sthr[3];
     __shared__ uint32_t s_nsel, s_ncand, s_base[2], sh[4];
 
+    SIK_TL(8);
     const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
     int L = seq_len[row / Hq];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
@@ -197,6 +200,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
     const bool ranked = nb <= kCandCap;
     __syncthreads();
+    SIK_TL(9);
 
     auto classify = [&](float v, int i) {
         const int bin = bstar < 0 ? 0 : score_bin(v, lo, scale);
@@ -234,6 +238,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
         for (int i = start + tid; i < end; i += kBlock) classify(s[i], i);
     }
     __syncthreads();
+    SIK_TL(10);
     if (tid == 0) {
         s_base[0] = s_nsel ? atomic_add_u32(&counters[row * 8 + 0], s_nsel) : 0u;
         s_base[1] = s_ncand ? atomic_add_u32(&counters[row * 8 + 1], s_ncand) : 0u;
@@ -253,9 +258,11 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
         }
     }
 
+    SIK_TL(11);
     const int nact = L > 0 ? (L + chunk - 1) / chunk : 1;
     if (!last_arriver(&counters[row * 8 + 2], static_cast<uint32_t>(nact), &s_flag)) return;
 
+    SIK_TL_ANY(12);
     // ---- last workgroup of this query head: resolve the threshold bin, pad the row ----------
     const int need = kk - min(cgt, kk);
     if (need > 0) {
@@ -277,6 +284,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
         }
     }
     for (int j = kk + tid; j < k; j += kBlock) out[j] = -1;
+    SIK_TL_ANY(13);
 }
 
 // ---------------------------------------------------------------------------------------
