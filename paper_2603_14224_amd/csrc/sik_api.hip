@@ -46,10 +46,13 @@ Workspace carve(const Dims& d, int k, void* base) {
     const size_t nc = static_cast<size_t>(nc_score > nc_hist ? nc_score : nc_hist);
     w.parthist = reinterpret_cast<uint32_t*>(take(rows * nc * (kBins / 2) * 4));
     w.binp = reinterpret_cast<float*>(take(rows * 2 * 4));
-    w.cand = reinterpret_cast<uint32_t*>(take(rows * kCandCap * 2 * 4));
+    size_t cand_words = rows * kCandCap * 2;
+    if (fused_cand_words(d, nc_score) > cand_words) cand_words = fused_cand_words(d, nc_score);
+    w.cand = reinterpret_cast<uint32_t*>(take(cand_words * 4));
     w.idx = reinterpret_cast<int32_t*>(take(rows * static_cast<size_t>(k > 0 ? k : 1) * 4));
     w.partial = reinterpret_cast<float*>(take(rows * kMaxSplit * (kD + 2) * 4));
-    w.scores = reinterpret_cast<float*>(take(rows * static_cast<size_t>(d.Lmax) * 4));
+    w.sstride = (d.Lmax + 3) & ~3;
+    w.scores = reinterpret_cast<float*>(take(rows * static_cast<size_t>(w.sstride) * 4));
     w.colsum = reinterpret_cast<double*>(take(units * kFitMaxWg * kD * 8));
     w.csum = reinterpret_cast<double*>(take(units * kG * 64 * 8));
     w.total_bytes = off;
@@ -181,9 +184,17 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if (e == hipSuccess) e = mark(1);
     if (e == hipSuccess) e = launch_score(d, &w, q, codebook, codes, seq_len, w.scores, s);
     if (e == hipSuccess) e = mark(2);
-    if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
-    if (e == hipSuccess) e = mark(3);
-    if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
+    int nhb, nchunk, chunk;
+    score_plan(d, &nhb, &nchunk, &chunk);
+    if (fused_chunk_ok(chunk)) {
+        // selection and attention in one launch (the event between them collapses to an empty interval)
+        if (e == hipSuccess) e = mark(3);
+        if (e == hipSuccess) e = launch_fused(d, w, q, K, V, seq_len, k, softmax_scale, idx_out, out, s);
+    } else {
+        if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
+        if (e == hipSuccess) e = mark(3);
+        if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
+    }
     if (e == hipSuccess) e = mark(4);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[5], s);  // empty interval: cost of an event pair
     return launched(e);

@@ -7,41 +7,13 @@
 // row with one 128-bit load per lane, so a wavefront load instruction covers 4 complete rows.
 // Softmax is computed online in fp32 (base-2 exponent, scale * log2(e) folded into q); partial
 // (m, l, o[D]) triples are merged by the last workgroup of the head to finish.
+#include "sik_attn_core.h"
 #include "sik_device.h"
 #include "sik_internal.h"
 
 namespace sik {
 
 SIK_TL_DEFINE(sik_dbg_tl_attn)
-
-constexpr int kPartStride = kD + 2;
-
-struct SoftmaxState {
-    float m, l;
-    float acc[8];
-};
-
-__device__ __forceinline__ void merge_from_lane(SoftmaxState& st, int xor_mask) {
-    const float mo = __shfl_xor(st.m, xor_mask, 64);
-    const float lo = __shfl_xor(st.l, xor_mask, 64);
-    const float M = fmaxf(st.m, mo);
-    const float a = exp2f(st.m - M), b = exp2f(mo - M);
-    st.l = st.l * a + lo * b;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float ao = __shfl_xor(st.acc[e], xor_mask, 64);
-        st.acc[e] = st.acc[e] * a + ao * b;
-    }
-    st.m = M;
-}
-
-template <int ODT>
-__device__ __forceinline__ void store_out(void* out, size_t pos, float v) {
-    if constexpr (ODT == kF32)
-        static_cast<float*>(out)[pos] = v;
-    else
-        static_cast<uint16_t*>(out)[pos] = static_cast<uint16_t>(narrow16<ODT>(v));
-}
 
 template <int DT, int ODT>
 __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict__ q,
@@ -71,79 +43,12 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
     for (int e = 0; e < 8; ++e) qf[e] *= scale_log2e;
 
     SoftmaxState st;
-    st.m = kNegBig;
-    st.l = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) st.acc[e] = 0.0f;
-
+    init_state(st);
     const int j0 = sp * per, j1 = min(k, j0 + per);
-    for (int base = j0 + wv * 16; base < j1; base += (kBlock / kWave) * 16) {
-        const int jj = base + p;
-        const int mine = jj < j1 ? ip[jj] : -1;
-        int id[4];
-        uint4 kv[4], vv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            id[u] = __shfl(mine, (lane & 48) + 4 * u + slot, 64);
-            const bool ok = id[u] >= 0 && id[u] < Lmax;
-            const size_t r = ok ? static_cast<size_t>(id[u]) : 0;
-            id[u] = ok ? id[u] : -1;
-            kv[u] = Kp[r * 16 + p];
-            vv[u] = Vp[r * 16 + p];
-        }
-        float z[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float kf[8];
-            widen8<DT>(kv[u], kf);
-            float dot = 0.0f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dot = fmaf(qf[e], kf[e], dot);
-            dot = row16_sum(dot);
-            z[u] = id[u] >= 0 ? dot : kNegBig;
-        }
-        const float mnew = fmaxf(fmaxf(st.m, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));
-        const float corr = exp2f(st.m - mnew);
-        st.l *= corr;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) st.acc[e] *= corr;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float pu = id[u] >= 0 ? exp2f(z[u] - mnew) : 0.0f;
-            float vf[8];
-            widen8<DT>(vv[u], vf);
-            st.l += pu;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) st.acc[e] = fmaf(pu, vf[e], st.acc[e]);
-        }
-        st.m = mnew;
-    }
-
+    attend_list<DT>([&](int j) { return ip[j0 + j]; }, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qf, Lmax, st);
     SIK_TL(17);
-    // the four 16-lane rows of the wavefront hold four independent partial softmaxes
-    merge_from_lane(st, 16);
-    merge_from_lane(st, 32);
-    if (slot == 0) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sacc[wv][8 * p + e] = st.acc[e];
-        if (p == 0) {
-            sm[wv] = st.m;
-            sl[wv] = st.l;
-        }
-    }
-    __syncthreads();
-
-    float M = kNegBig, Lsum = 0.0f, o = 0.0f;
-    if (tid < kD) {
-#pragma unroll
-        for (int w = 0; w < kBlock / kWave; ++w) M = fmaxf(M, sm[w]);
-#pragma unroll
-        for (int w = 0; w < kBlock / kWave; ++w) {
-            const float a = exp2f(sm[w] - M);
-            Lsum += sl[w] * a;
-            o += sacc[w][tid] * a;
-        }
-    }
+    float M, Lsum, o;
+    workgroup_merge(st, sm, sl, sacc, M, Lsum, o);
     if (nsplit == 1) {
         if (tid < kD) store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, Lsum > 0.0f ? o / Lsum : 0.0f);
         return;

@@ -1,0 +1,130 @@
+// Wavefront-level building blocks of the sparse attention kernels (gfx950): 16 lanes gather one
+// 256 B key/value row with one 128-bit load each, online softmax in fp32 with a base-2 exponent.
+#pragma once
+
+#include "sik_device.h"
+
+namespace sik {
+
+constexpr int kPartStride = kD + 2;
+
+struct SoftmaxState {
+    float m, l;
+    float acc[8];
+};
+
+__device__ __forceinline__ void merge_from_lane(SoftmaxState& st, int xor_mask) {
+    const float mo = __shfl_xor(st.m, xor_mask, 64);
+    const float lo = __shfl_xor(st.l, xor_mask, 64);
+    const float M = fmaxf(st.m, mo);
+    const float a = exp2f(st.m - M), b = exp2f(mo - M);
+    st.l = st.l * a + lo * b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float ao = __shfl_xor(st.acc[e], xor_mask, 64);
+        st.acc[e] = st.acc[e] * a + ao * b;
+    }
+    st.m = M;
+}
+
+template <int ODT>
+__device__ __forceinline__ void store_out(void* out, size_t pos, float v) {
+    if constexpr (ODT == kF32)
+        static_cast<float*>(out)[pos] = v;
+    else
+        static_cast<uint16_t*>(out)[pos] = static_cast<uint16_t>(narrow16<ODT>(v));
+}
+
+// Attend over token indices supplied by fetch(j): this wavefront takes entries first + it * step +
+// (0..15), it = 0, 1, ... while below n (a workgroup sharing one list uses first = 16 * wave,
+// step = 64; a wavefront with a private list first = 0, step = 16).  Negative or out-of-range
+// entries are skipped.  qf holds this lane's 8 query components already multiplied by
+// softmax_scale * log2(e).
+template <int DT, class Fetch>
+__device__ __forceinline__ void attend_list(Fetch fetch, int n, int first, int step,
+                                            const uint4* __restrict__ Kp, const uint4* __restrict__ Vp,
+                                            const float (&qf)[8], int Lmax, SoftmaxState& st) {
+    const int lane = threadIdx.x & 63;
+    const int slot = lane >> 4, p = lane & 15;
+    for (int base = first; base < n; base += step) {
+        const int jj = base + p;
+        const int mine = jj < n ? fetch(jj) : -1;
+        int id[4];
+        uint4 kv[4], vv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            id[u] = __shfl(mine, (lane & 48) + 4 * u + slot, 64);
+            const bool ok = id[u] >= 0 && id[u] < Lmax;
+            const size_t r = ok ? static_cast<size_t>(id[u]) : 0;
+            id[u] = ok ? id[u] : -1;
+            kv[u] = Kp[r * 16 + p];
+            vv[u] = Vp[r * 16 + p];
+        }
+        float z[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float kf[8];
+            widen8<DT>(kv[u], kf);
+            float dot = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf(qf[e], kf[e], dot);
+            dot = row16_sum(dot);
+            z[u] = id[u] >= 0 ? dot : kNegBig;
+        }
+        const float mnew = fmaxf(fmaxf(st.m, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));
+        const float corr = exp2f(st.m - mnew);
+        st.l *= corr;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.acc[e] *= corr;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float pu = id[u] >= 0 ? exp2f(z[u] - mnew) : 0.0f;
+            float vf[8];
+            widen8<DT>(vv[u], vf);
+            st.l += pu;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st.acc[e] = fmaf(pu, vf[e], st.acc[e]);
+        }
+        st.m = mnew;
+    }
+}
+
+// Combine the wavefronts' states into one (M, l, o[d]) triple of the workgroup: after the call
+// thread d < kD holds o[d]; M and l are returned to every thread.  sm/sl: LDS [4], sacc: LDS [4][kD].
+__device__ __forceinline__ void workgroup_merge(SoftmaxState& st, float* sm, float* sl, float (*sacc)[kD],
+                                                float& M, float& Lsum, float& o) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int slot = lane >> 4, p = lane & 15;
+    // the four 16-lane rows of the wavefront hold four independent partial softmaxes
+    merge_from_lane(st, 16);
+    merge_from_lane(st, 32);
+    if (slot == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sacc[wv][8 * p + e] = st.acc[e];
+        if (p == 0) {
+            sm[wv] = st.m;
+            sl[wv] = st.l;
+        }
+    }
+    __syncthreads();
+    M = kNegBig;
+    Lsum = 0.0f;
+    o = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kBlock / kWave; ++w) M = fmaxf(M, sm[w]);
+#pragma unroll
+    for (int w = 0; w < kBlock / kWave; ++w) {
+        const float a = exp2f(sm[w] - M);
+        Lsum += sl[w] * a;
+        if (tid < kD) o += sacc[w][tid] * a;
+    }
+}
+
+__device__ __forceinline__ void init_state(SoftmaxState& st) {
+    st.m = kNegBig;
+    st.l = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[e] = 0.0f;
+}
+
+}  // namespace sik

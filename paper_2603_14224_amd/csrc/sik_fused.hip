@@ -1,0 +1,319 @@
+// Fused selection + sparse attention for the decode step on gfx950: one launch turns the scores and
+// chunk histograms written by the scoring kernel into the attention output (the selection step of
+// "Compressed-Domain Top-k Retrieval" followed by softmax(q K_S^T / sqrt(d)) V_S of "Background and
+// Preliminaries").
+//
+// Workgroup (query head, token chunk):
+//   1. loads, all at once: the head's chunk histograms, its own chunk of scores, the query row;
+//   2. finds the threshold bin b* (every workgroup of the head finds the same one);
+//   3. each wavefront compacts the tokens of its score registers that lie in bins above b* into a
+//      private LDS list (ballot + popcount, deterministic order) and attends over them at once:
+//      the selected tokens never travel through an index list in memory;
+//   4. tokens inside b* ("candidates", about L/1000 of the head's tokens) are published with their
+//      score keys; the partial softmax (m, l, o[D]) of the chunk is published;
+//   5. the last workgroup of the head to arrive ranks the candidates exactly by (score desc, index
+//      asc), attends over the k - c_gt best of them, merges all partials and writes the output row.
+// Degenerate score distributions (more than kCandCap tokens in b*, or more than kWaveCand candidates
+// in one wavefront's share) take an exact radix-select fallback in step 5.
+#include "sik_attn_core.h"
+#include "sik_device.h"
+#include "sik_internal.h"
+#include "sik_select.h"
+
+namespace sik {
+
+SIK_TL_DEFINE(sik_dbg_tl_fused)
+
+// Candidate exchange area of one query head: regions = 4 * nchunk (one per chunk and wavefront);
+// word w of region r lives at cand_row[w * regions + r], so that the last workgroup, which reads one
+// region per lane, issues coalesced loads.  Word 0 = count, then (key, index) pairs.
+constexpr int kWaveCand = 16;                      // candidate slots per wavefront and chunk
+constexpr int kCandWaveWords = 1 + 2 * kWaveCand;  // words per region
+constexpr uint32_t kCandOverflow = 0xffffffffu;
+
+template <int DT, int ODT, int NQ>  // NQ float4 of scores per lane: chunk = 1024 * NQ tokens
+__global__ __launch_bounds__(kBlock) void select_attend_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    const float* __restrict__ scores, int sstride, const int32_t* __restrict__ seq_len,
+    const uint32_t* __restrict__ parthist, const float* __restrict__ binp, uint32_t* __restrict__ counters,
+    uint32_t* __restrict__ cand, float* __restrict__ partial, int32_t* __restrict__ idx_ws,
+    int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
+    int Lmax, int nchunk) {
+    constexpr int kChunk = 1024 * NQ;
+    __shared__ int32_t l_sel[kBlock / kWave][kChunk / 4];
+    __shared__ uint32_t red[(kBlock / kWave) * kBins];
+    __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 16];
+    __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
+    __shared__ float sacc[kBlock / kWave][kD];
+    __shared__ uint32_t lds4[4], sh[4];
+    __shared__ int sthr[3], s_flag, s_over;
+    __shared__ uint32_t s_ncand;
+
+    SIK_TL(24);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, p = lane & 15;
+    const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk;
+    const int b = row / Hq, hq = row % Hq;
+    const size_t unit = static_cast<size_t>(b) * Hkv + hq / R;
+    const int start = c * kChunk;
+
+    // ---- 1. every load that does not depend on another goes out now ---------------------------
+    const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * nchunk * kHistWords, nchunk);
+    const float4* s4 = reinterpret_cast<const float4*>(scores + static_cast<size_t>(row) * sstride + start);
+    float4 sv[NQ];
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const int i = start + (j * kBlock + tid) * 4;
+        sv[j] = i < sstride ? s4[j * kBlock + tid] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    float qf[8];
+    widen8<DT>(reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p], qf);
+    const float lo = binp[row * 2], scale = binp[row * 2 + 1];
+    int L = seq_len[b];
+    L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
+    const int nact = L > 0 ? (L + kChunk - 1) / kChunk : 1;
+    if (c >= nact) return;  // no token of this chunk is valid; the ticket below counts nact workgroups
+    const int end = min(L, start + kChunk);
+    const int kk = min(k, L);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qf[e] *= scale_log2e;
+    if (tid == 0) {
+        s_over = 0;
+        s_ncand = 0u;
+    }
+
+    // ---- 2. threshold bin ---------------------------------------------------------------------
+    const Threshold th = find_threshold(hl, kk, L, red, lds4, sthr);
+    const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
+    const bool ranked = nb <= kCandCap;
+    SIK_TL(25);
+
+    // ---- 3. wave-private compaction of the selected tokens, candidates aside -------------------
+    const uint4* Kp = reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
+    const uint4* Vp = reinterpret_cast<const uint4*>(V + unit * Lmax * kD);
+    int n_sel = 0, n_cand = 0;  // wave-uniform
+    const int regions = nchunk * (kBlock / kWave);
+    uint32_t* crow = cand + static_cast<size_t>(row) * regions * kCandWaveWords;
+    uint32_t* cw = crow + c * (kBlock / kWave) + wv;  // word w of this wavefront's region: cw[w * regions]
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < NQ; ++j) {
+        const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = start + (j * kBlock + tid) * 4 + e;
+            const int bin = (i < end) ? (bstar < 0 ? 0 : score_bin(v4[e], lo, scale)) : -2;
+            const bool sure = bin > bstar;
+            const bool cnd = bin == bstar && bstar >= 0;
+            const uint64_t bs = __ballot(sure);
+            if (sure) l_sel[wv][n_sel + __popcll(bs & lt_mask)] = i;
+            n_sel += __popcll(bs);
+            const uint64_t bc = __ballot(cnd);
+            if (bc != 0ull && ranked) {
+                const int pos = n_cand + __popcll(bc & lt_mask);
+                if (cnd && pos < kWaveCand) {
+                    st_agent(&cw[(1 + 2 * pos) * regions], float_to_key(v4[e]));
+                    st_agent(&cw[(2 + 2 * pos) * regions], static_cast<uint32_t>(i));
+                }
+                n_cand += __popcll(bc);
+            }
+        }
+    }
+    if (lane == 0) st_agent(&cw[0], n_cand > kWaveCand ? kCandOverflow : static_cast<uint32_t>(n_cand));
+    // optional index output: reserve this wave's slots now, write them after the gather
+    uint32_t out_base = 0u;
+    if (idx_out && n_sel > 0) {
+        if (lane == 0) out_base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(n_sel));
+    }
+    SIK_TL(26);
+
+    // ---- 4. attend over this wavefront's own tokens, publish the chunk's partial ---------------
+    SoftmaxState st;
+    init_state(st);
+    const int32_t* mylist = l_sel[wv];
+    attend_list<DT>([&](int j) { return mylist[j]; }, n_sel, 0, 16, Kp, Vp, qf, Lmax, st);
+    SIK_TL(27);
+    if (idx_out && n_sel > 0) {
+        out_base = static_cast<uint32_t>(__shfl(static_cast<int>(out_base), 0, 64));
+        for (int j = lane; j < n_sel; j += 64)
+            if (out_base + j < static_cast<uint32_t>(k)) idx_out[static_cast<size_t>(row) * k + out_base + j] = mylist[j];
+    }
+    float M, Lsum, o;
+    workgroup_merge(st, sm, sl, sacc, M, Lsum, o);
+    float* prow = partial + (static_cast<size_t>(row) * kMaxChunks) * kPartStride;
+    if (tid < kD) {
+        float* pp = prow + static_cast<size_t>(c) * kPartStride;
+        st_agent(&pp[2 + tid], o);
+        if (tid == 0) {
+            st_agent(&pp[0], M);
+            st_agent(&pp[1], Lsum);
+        }
+    }
+    SIK_TL(28);
+    if (!last_arriver(&counters[row * 8 + 3], static_cast<uint32_t>(nact), &s_flag)) return;
+    SIK_TL_ANY(29);
+
+    // ---- 5. last workgroup of the head: candidates, merge, output ------------------------------
+    // All exchange loads go out together: the (m, l) pair of every chunk (thread c), the first 32
+    // chunks' o[d] (thread d), and one candidate region per thread.
+    const int need = kk - min(cgt, kk);
+    int32_t* olist = (idx_out ? idx_out : idx_ws) + static_cast<size_t>(row) * k;
+    constexpr int kOPre = 32;
+    float o_pre[kOPre];
+    float pm = kNegBig, pl = 0.0f;
+    if (tid < nact) {
+        pm = ld_agent(&prow[static_cast<size_t>(tid) * kPartStride]);
+        pl = ld_agent(&prow[static_cast<size_t>(tid) * kPartStride + 1]);
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < kOPre; ++s2)
+        o_pre[s2] = (tid < kD && s2 < nact) ? ld_agent(&prow[static_cast<size_t>(s2) * kPartStride + 2 + tid]) : 0.0f;
+    const bool want_cands = need > 0 && ranked;
+    uint32_t cn = 0u, ent[2 * kWaveCand];
+    if (want_cands && tid < nact * 4) {
+        const uint32_t* reg = crow + tid;
+        cn = ld_agent(&reg[0]);
+#pragma unroll
+        for (int e = 0; e < 2 * kWaveCand; ++e) ent[e] = ld_agent(&reg[(1 + e) * regions]);
+    }
+    float* pml = reinterpret_cast<float*>(l_sel[0]);  // [2][kMaxChunks] in LDS (l_sel is free by now)
+    if (tid < kMaxChunks) {
+        pml[tid] = pm;
+        pml[kMaxChunks + tid] = pl;
+    }
+    init_state(st);
+    SIK_TL_ANY(32);
+    if (need > 0) {
+        bool use_radix = !ranked;
+        if (ranked) {
+            if (tid < nact * 4) {
+                if (cn == kCandOverflow) {
+                    s_over = 1;
+                } else if (cn > 0u) {
+                    const uint32_t base = atomicAdd(&s_ncand, cn);
+#pragma unroll
+                    for (int e = 0; e < kWaveCand; ++e) {
+                        if (static_cast<uint32_t>(e) < cn && base + e < static_cast<uint32_t>(kCandCap)) {
+                            l_cand[2 * (base + e)] = ent[2 * e];
+                            l_cand[2 * (base + e) + 1] = ent[2 * e + 1];
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            use_radix = s_over != 0;
+        }
+        if (!use_radix) {
+            const int n = min(static_cast<int>(s_ncand), kCandCap);
+            int32_t* chosen = reinterpret_cast<int32_t*>(red);  // reuse: rank r -> token index
+            // pad to a multiple of 8 with entries that outrank nothing, so that the ranking loop can
+            // keep eight LDS reads in flight
+            const int npad = (n + 7) & ~7;
+            if (tid < npad - n) {
+                l_cand[2 * (n + tid)] = 0u;
+                l_cand[2 * (n + tid) + 1] = 0xffffffffu;
+            }
+            __syncthreads();
+            const uint2* lc2 = reinterpret_cast<const uint2*>(l_cand);
+            for (int a = tid; a < n; a += kBlock) {
+                const uint2 me = lc2[a];
+                int rank = 0;
+                for (int x = 0; x < npad; x += 8) {
+                    uint2 o8[8];
+#pragma unroll
+                    for (int y = 0; y < 8; ++y) o8[y] = lc2[x + y];
+#pragma unroll
+                    for (int y = 0; y < 8; ++y) rank += (o8[y].x > me.x || (o8[y].x == me.x && o8[y].y < me.y)) ? 1 : 0;
+                }
+                if (rank < need) {
+                    chosen[rank] = static_cast<int32_t>(me.y);
+                    if (idx_out) olist[cgt + rank] = static_cast<int32_t>(me.y);
+                }
+            }
+            __syncthreads();
+            attend_list<DT>([&](int j) { return chosen[j]; }, min(need, n), wv * 16, (kBlock / kWave) * 16, Kp, Vp,
+                            qf, Lmax, st);
+        } else {
+            // exact fallback: radix select over the members of b* in the whole row of scores
+            radix_select_in_bin(scores + static_cast<size_t>(row) * sstride, L, lo, scale, bstar, need,
+                                olist + cgt, red, sh);
+            __threadfence_block();
+            __syncthreads();
+            const int32_t* gl = olist + cgt;
+            attend_list<DT>([&](int j) { return gl[j]; }, need, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qf, Lmax,
+                            st);
+        }
+    }
+    SIK_TL_ANY(31);
+    float M2, L2, o2;
+    workgroup_merge(st, sm, sl, sacc, M2, L2, o2);  // has a barrier: pml is visible afterwards
+    if (tid < kD) {
+        float Mg = M2;
+#pragma unroll 8
+        for (int s2 = 0; s2 < nact; ++s2) Mg = fmaxf(Mg, pml[s2]);
+        const float a2 = exp2f(M2 - Mg);
+        float lt = L2 * a2, ot = o2 * a2;
+#pragma unroll
+        for (int s2 = 0; s2 < kOPre; ++s2) {  // fixed order: the result does not depend on arrival order
+            if (s2 < nact) {
+                const float a = exp2f(pml[s2] - Mg);
+                lt += pml[kMaxChunks + s2] * a;
+                ot += o_pre[s2] * a;
+            }
+        }
+#pragma unroll 8
+        for (int s2 = kOPre; s2 < nact; ++s2) {
+            const float a = exp2f(pml[s2] - Mg);
+            lt += pml[kMaxChunks + s2] * a;
+            ot += ld_agent(&prow[static_cast<size_t>(s2) * kPartStride + 2 + tid]) * a;
+        }
+        store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, lt > 0.0f ? ot / lt : 0.0f);
+    }
+    if (idx_out)
+        for (int j = kk + tid; j < k; j += kBlock) olist[j] = -1;
+    SIK_TL_ANY(30);
+}
+
+// Chunk sizes the fused kernel is instantiated for (tokens per workgroup).
+bool fused_chunk_ok(int chunk) { return chunk == 1024 || chunk == 2048 || chunk == 4096 || chunk == 8192; }
+
+size_t fused_cand_words(const Dims& d, int nchunk) {
+    return static_cast<size_t>(d.rows()) * nchunk * (kBlock / kWave) * kCandWaveWords;
+}
+
+template <int DT, int ODT>
+static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
+                                 const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out,
+                                 hipStream_t s) {
+    int nhb, nchunk, chunk;
+    score_plan(d, &nhb, &nchunk, &chunk);
+    const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
+    const int grid = nchunk * d.rows();
+    auto qp = static_cast<const uint16_t*>(q);
+    auto Kp = static_cast<const uint16_t*>(K);
+    auto Vp = static_cast<const uint16_t*>(V);
+#define SIK_FUSED(NQV)                                                                                      \
+    select_attend_kernel<DT, ODT, NQV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, w.scores, w.sstride, seq_len,    \
+                                                               w.parthist, w.binp, w.counters, w.cand,      \
+                                                               w.partial, w.idx, idx_out, out, sl2, k,      \
+                                                               d.Hkv, d.Hq, d.R, d.Lmax, nchunk)
+    switch (chunk) {
+        case 1024: SIK_FUSED(1); break;
+        case 2048: SIK_FUSED(2); break;
+        case 4096: SIK_FUSED(4); break;
+        case 8192: SIK_FUSED(8); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef SIK_FUSED
+    return hipGetLastError();
+}
+
+hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
+                        const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out, hipStream_t s) {
+    if (d.kv_dtype == kBF16)
+        return d.out_dtype == kF32 ? launch_fused_t<kBF16, kF32>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s)
+                                   : launch_fused_t<kBF16, kBF16>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s);
+    return d.out_dtype == kF32 ? launch_fused_t<kF16, kF32>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s)
+                               : launch_fused_t<kF16, kF16>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s);
+}
+
+}  // namespace sik

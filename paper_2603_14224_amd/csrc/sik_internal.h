@@ -26,10 +26,12 @@ struct Workspace {
     // plain scratch
     uint32_t* parthist;     // [rows][nchunk][kBins/2]  per-chunk histograms, two 16-bit counts per word
     float* binp;            // [rows][2]          histogram origin, scale
-    uint32_t* cand;         // [rows][kCandCap][2] (key, index) of threshold-bin members
+    uint32_t* cand;         // per row: (key, index) of threshold-bin members; [kCandCap][2] words for the
+                            // stand-alone selector, [nchunk][136] words for the fused kernel
     int32_t* idx;           // [rows][k]          selection when the caller passes no idx_out
     float* partial;         // [rows][kMaxSplit][D + 2]  split softmax partials (m, l, o[D])
-    float* scores;          // [rows][Lmax]       decode step only
+    float* scores;          // [rows][sstride]    decode step only
+    int sstride;            // Lmax rounded up to a multiple of 4 (16-byte aligned score rows)
     // quantiser fit
     double* colsum;         // [units][kFitMaxWg][D]
     double* csum;           // [units][G*16*4]    cluster sums (zeroed by the fit's own kernel)
@@ -57,6 +59,11 @@ hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score
                          const int32_t* seq_len, int k, int32_t* idx, hipStream_t s);
 hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                        const int32_t* idx, int k, float scale, void* out, hipStream_t s);
+// select + attention in one launch; reads w.scores / w.parthist / w.binp written by launch_score
+hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
+                        const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out, hipStream_t s);
+bool fused_chunk_ok(int chunk);
+size_t fused_cand_words(const Dims& d, int nchunk);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,
                       float* codebook, int32_t* counts, uint8_t* codes, hipStream_t s);
 hipError_t launch_encode(const Dims& d, const void* K, int t0, int n, const float* mu, uint8_t* codes,

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
                                                        const float* __restrict__ codebook,
                                                        const uint8_t* __restrict__ codes,
                                                        const int32_t* __restrict__ seq_len,
-                                                       float* __restrict__ scores,
+                                                       float* __restrict__ scores, int sstride,
                                                        uint32_t* __restrict__ parthist,
                                                        float* __restrict__ binp, int Hkv, int Hq, int R,
                                                        int Lmax, int nchunk, int chunk, int nhb) {
@@ -109,7 +109,11 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         for (int e = tid; e < HB * kBins; e += kBlock) lhist[e] = 0u;
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
-    if (start >= L && c != 0) return;  // chunk 0 always runs: it owns the per-head outputs
+    if (start >= L && c != 0) {  // no valid token here (chunk 0 always runs: it owns the per-head outputs)
+        if constexpr (HIST)      // consumers read every chunk's histogram: publish an empty one
+            for (int s = 0; s < nh; ++s) parthist[((row0 + s) * nchunk + c) * kHistWords + tid] = 0u;
+        return;
+    }
     const int end = min(L, start + chunk);
     __syncthreads();
     SIK_TL(1);
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
 #pragma unroll
                 for (int s = 0; s < HB; ++s) {
                     if (s < nh) {
-                        scores[(row0 + s) * Lmax + tok] = acc[s];
+                        scores[(row0 + s) * sstride + tok] = acc[s];
                         if constexpr (HIST)
                             atomicAdd(&lhist[s * kBins + score_bin(acc[s], bp[s][0], bp[s][1])], 1u);
                     }
@@ -223,10 +227,8 @@ void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
     const int units = d.units() * nhb;
     int want = (512 + units - 1) / units;
     if (want > kMaxChunks) want = kMaxChunks;
-    int ch = (d.Lmax + want - 1) / want;
-    ch = (ch + kBlock - 1) / kBlock * kBlock;
-    if (ch < 1024) ch = 1024;
-    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += kBlock;
+    int ch = 1024;  // power of two so that the fused select + attention kernel can take the same chunks
+    while (static_cast<int64_t>(ch) * want < d.Lmax || (d.Lmax + ch - 1) / ch > kMaxChunks) ch *= 2;
     *nhb_out = nhb;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
@@ -248,8 +250,9 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, const void* 
     auto qp = static_cast<const uint16_t*>(q);
 #define SIK_SCORE(NTV, HV)                                                                                   \
     score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(qp, codebook, codes, seq_len, scores,                \
-                                                      w ? w->parthist : nullptr, w ? w->binp : nullptr, \
-                                                      d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
+                                                      w ? w->sstride : d.Lmax, w ? w->parthist : nullptr, \
+                                                      w ? w->binp : nullptr, d.Hkv, d.Hq, d.R, d.Lmax,    \
+                                                      nchunk, chunk, nhb)
     if (w) {
         if (NT == 1) SIK_SCORE(1, true); else SIK_SCORE(2, true);
     } else {

@@ -107,4 +107,78 @@ __device__ __forceinline__ Threshold find_threshold(const HistLoads& h, int kk, 
     return r;
 }
 
+// ---- level 2 fallback: radix select inside the threshold bin, one workgroup -----------------
+// Picks the `need` largest (score, then smaller index) among {i < L : bin(s_i) == bstar} and
+// writes their indices to out[0 .. need).
+__device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, float lo, float scale, int bstar,
+                                    int need, int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, mask = 0;
+    uint32_t remaining = static_cast<uint32_t>(need);
+    for (int pass = 3; pass >= 0; --pass) {
+        h256[tid] = 0u;
+        __syncthreads();
+        for (int i = tid; i < L; i += kBlock) {
+            const float v = s[i];
+            const uint32_t key = float_to_key(v);
+            if (score_bin(v, lo, scale) == bstar && (key & mask) == prefix)
+                atomicAdd(&h256[(key >> (8 * pass)) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0;
+            int dsel = 0;
+            for (int dgt = 255; dgt >= 0; --dgt) {
+                const uint32_t cnt = h256[dgt];
+                if (cum < remaining && remaining <= cum + cnt) {
+                    dsel = dgt;
+                    break;
+                }
+                cum += cnt;
+            }
+            sh[0] = static_cast<uint32_t>(dsel);
+            sh[1] = remaining - cum;
+        }
+        __syncthreads();
+        prefix |= sh[0] << (8 * pass);
+        mask |= 255u << (8 * pass);
+        remaining = sh[1];
+        __syncthreads();
+    }
+    // prefix is now the key of the need-th largest member; `remaining` members equal to it are
+    // taken in increasing index order, every larger member is taken.
+    const uint32_t tau = prefix, need_eq = remaining;
+    const uint32_t n_gt = static_cast<uint32_t>(need) - need_eq;
+    if (tid == 0) {
+        sh[2] = 0u;  // running count of larger members written
+        sh[3] = 0u;  // running count of equal members seen
+    }
+    __syncthreads();
+    for (int base = 0; base < L; base += kBlock) {
+        const int i = base + tid;
+        bool gt = false, eq = false;
+        if (i < L) {
+            const float v = s[i];
+            const uint32_t key = float_to_key(v);
+            if (score_bin(v, lo, scale) == bstar) {
+                gt = key > tau;
+                eq = key == tau;
+            }
+        }
+        if (gt) out[atomicAdd(&sh[2], 1u)] = i;
+        // ordered rank of the equal members of this tile
+        const uint64_t bal = __ballot(eq);
+        const int lane = tid & 63, wv = tid >> 6;
+        if (lane == 0) h256[wv] = static_cast<uint32_t>(__popcll(bal));
+        __syncthreads();
+        uint32_t before = sh[3];
+        for (int w = 0; w < wv; ++w) before += h256[w];
+        const uint32_t ord = before + static_cast<uint32_t>(__popcll(bal & ((1ull << lane) - 1ull)));
+        if (eq && ord < need_eq) out[n_gt + ord] = i;
+        __syncthreads();
+        if (tid == 0) sh[3] += h256[0] + h256[1] + h256[2] + h256[3];
+        __syncthreads();
+    }
+}
+
 }  // namespace sik

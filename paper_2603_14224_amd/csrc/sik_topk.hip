@@ -88,82 +88,8 @@ __global__ __launch_bounds__(kBlock) void hist_kernel(const float* __restrict__ 
     publish_hist(lhist, parthist + (static_cast<size_t>(row) * nchunk + c) * kHistWords);
 }
 
-// ---- level 2 fallback: radix select inside the threshold bin, one workgroup -----------------
-// Picks the `need` largest (score, then smaller index) among {i < L : bin(s_i) == bstar} and
-// writes their indices to out[0 .. need).
-__device__ void radix_select_in_bin(const float* __restrict__ s, int L, float lo, float scale, int bstar,
-                                    int need, int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
-    const int tid = threadIdx.x;
-    uint32_t prefix = 0, mask = 0;
-    uint32_t remaining = static_cast<uint32_t>(need);
-    for (int pass = 3; pass >= 0; --pass) {
-        h256[tid] = 0u;
-        __syncthreads();
-        for (int i = tid; i < L; i += kBlock) {
-            const float v = s[i];
-            const uint32_t key = float_to_key(v);
-            if (score_bin(v, lo, scale) == bstar && (key & mask) == prefix)
-                atomicAdd(&h256[(key >> (8 * pass)) & 255u], 1u);
-        }
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t cum = 0;
-            int dsel = 0;
-            for (int dgt = 255; dgt >= 0; --dgt) {
-                const uint32_t cnt = h256[dgt];
-                if (cum < remaining && remaining <= cum + cnt) {
-                    dsel = dgt;
-                    break;
-                }
-                cum += cnt;
-            }
-            sh[0] = static_cast<uint32_t>(dsel);
-            sh[1] = remaining - cum;
-        }
-        __syncthreads();
-        prefix |= sh[0] << (8 * pass);
-        mask |= 255u << (8 * pass);
-        remaining = sh[1];
-        __syncthreads();
-    }
-    // prefix is now the key of the need-th largest member; `remaining` members equal to it are
-    // taken in increasing index order, every larger member is taken.
-    const uint32_t tau = prefix, need_eq = remaining;
-    const uint32_t n_gt = static_cast<uint32_t>(need) - need_eq;
-    if (tid == 0) {
-        sh[2] = 0u;  // running count of larger members written
-        sh[3] = 0u;  // running count of equal members seen
-    }
-    __syncthreads();
-    for (int base = 0; base < L; base += kBlock) {
-        const int i = base + tid;
-        bool gt = false, eq = false;
-        if (i < L) {
-            const float v = s[i];
-            const uint32_t key = float_to_key(v);
-            if (score_bin(v, lo, scale) == bstar) {
-                gt = key > tau;
-                eq = key == tau;
-            }
-        }
-        if (gt) out[atomicAdd(&sh[2], 1u)] = i;
-        // ordered rank of the equal members of this tile
-        const uint64_t bal = __ballot(eq);
-        const int lane = tid & 63, wv = tid >> 6;
-        if (lane == 0) h256[wv] = static_cast<uint32_t>(__popcll(bal));
-        __syncthreads();
-        uint32_t before = sh[3];
-        for (int w = 0; w < wv; ++w) before += h256[w];
-        const uint32_t ord = before + static_cast<uint32_t>(__popcll(bal & ((1ull << lane) - 1ull)));
-        if (eq && ord < need_eq) out[n_gt + ord] = i;
-        __syncthreads();
-        if (tid == 0) sh[3] += h256[0] + h256[1] + h256[2] + h256[3];
-        __syncthreads();
-    }
-}
-
 // ---- select: compaction against the threshold bin, exact resolution of the bin ---------------
-__global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict__ scores,
+__global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict__ scores, int sstride,
                                                         const int32_t* __restrict__ seq_len,
                                                         const uint32_t* __restrict__ parthist, int hchunks,
                                                         int hchunk, const float* __restrict__ binp,
@@ -173,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
                                                         int nchunk, int chunk) {
     __shared__ uint32_t h256[kBlock];
     __shared__ int32_t l_sel[kSelChunkMax];
-    __shared__ uint32_t l_cand[2 * kCandCap];
+    __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 16];
     __shared__ uint32_t red[(kBlock / kWave) * kBins];
     __shared__ int s_flag, sthr[3];
     __shared__ uint32_t s_nsel, s_ncand, s_base[2], sh[4];
@@ -185,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     const int start = c * chunk, end = min(L, start + chunk);
     if (start >= L && c != 0) return;  // chunk 0 always runs: it may have to pad the row
     const int kk = min(k, L);
-    const float* s = scores + static_cast<size_t>(row) * Lmax;
+    const float* s = scores + static_cast<size_t>(row) * sstride;
     int32_t* out = idx + static_cast<size_t>(row) * k;
 
     // threshold bin of this query head from the chunk histograms of the producing kernel
@@ -214,7 +140,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
             }
         }
     };
-    if ((Lmax & 3) == 0) {  // rows are 16-byte aligned: vector loads
+    if ((sstride & 3) == 0) {  // rows are 16-byte aligned: vector loads
         const float4* s4 = reinterpret_cast<const float4*>(s);
         const int q0 = start >> 2, q1 = (end + 3) >> 2;  // start is a multiple of 256
         for (int base = q0; base < q1; base += 4 * kBlock) {
@@ -268,16 +194,22 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     if (need > 0) {
         if (ranked) {
             const int n = min(nb, kCandCap);
-            for (int j = tid; j < 2 * n; j += kBlock) l_cand[j] = ld_agent(&crow[j]);
+            const int npad = (n + 7) & ~7;  // padding entries outrank nothing
+            for (int j = tid; j < 2 * npad; j += kBlock)
+                l_cand[j] = j < 2 * n ? ld_agent(&crow[j]) : ((j & 1) ? 0xffffffffu : 0u);
             __syncthreads();
+            const uint2* lc2 = reinterpret_cast<const uint2*>(l_cand);
             for (int a = tid; a < n; a += kBlock) {
-                const uint32_t ka = l_cand[2 * a], ia = l_cand[2 * a + 1];
+                const uint2 me = lc2[a];
                 int rank = 0;
-                for (int o = 0; o < n; ++o) {
-                    const uint32_t ko = l_cand[2 * o], io = l_cand[2 * o + 1];
-                    rank += (ko > ka || (ko == ka && io < ia)) ? 1 : 0;
+                for (int x = 0; x < npad; x += 8) {  // eight LDS reads in flight
+                    uint2 o8[8];
+#pragma unroll
+                    for (int y = 0; y < 8; ++y) o8[y] = lc2[x + y];
+#pragma unroll
+                    for (int y = 0; y < 8; ++y) rank += (o8[y].x > me.x || (o8[y].x == me.x && o8[y].y < me.y)) ? 1 : 0;
                 }
-                if (rank < need) out[cgt + rank] = static_cast<int32_t>(ia);
+                if (rank < need) out[cgt + rank] = static_cast<int32_t>(me.y);
             }
         } else {
             radix_select_in_bin(s, L, lo, scale, bstar, need, out + cgt, h256, sh);
@@ -330,7 +262,8 @@ hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score
         score_plan(d, &nhb, &hchunks, &hchunk);
     else
         hist_plan(d, &hchunks, &hchunk);
-    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, seq_len, w.parthist, hchunks, hchunk, w.binp,
+    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, hist_from_score ? w.sstride : d.Lmax, seq_len,
+                                                       w.parthist, hchunks, hchunk, w.binp,
                                                        w.counters, w.cand, idx, d.Hq, d.Lmax, k, nchunk, chunk);
     return hipGetLastError();
 }
