@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of HIP-graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run one plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB): under "
+                         "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counters' scale factor")
     return ap.parse_args()
 
 
@@ -53,6 +56,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(64 * 2 ** 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)  # one launch: 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
     cfg = W.CONFIGS[args.config]
     B, Hkv, Hq, D, L, k = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.context, cfg.top_k
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float16
