@@ -47,7 +47,7 @@ Workspace carve(const Dims& d, int k, void* base) {
     w.parthist = reinterpret_cast<uint32_t*>(take(rows * nc * (kBins / 2) * 4));
     w.binp = reinterpret_cast<float*>(take(rows * 2 * 4));
     size_t cand_words = rows * kCandCap * 2;
-    if (fused_cand_words(d, nc_score) > cand_words) cand_words = fused_cand_words(d, nc_score);
+    if (fused_cand_words(d) > cand_words) cand_words = fused_cand_words(d);
     w.cand = reinterpret_cast<uint32_t*>(take(cand_words * 4));
     w.idx = reinterpret_cast<int32_t*>(take(rows * static_cast<size_t>(k > 0 ? k : 1) * 4));
     w.partial = reinterpret_cast<float*>(take(rows * kMaxSplit * (kD + 2) * 4));
@@ -184,9 +184,8 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if (e == hipSuccess) e = mark(1);
     if (e == hipSuccess) e = launch_score(d, &w, q, codebook, codes, seq_len, w.scores, s);
     if (e == hipSuccess) e = mark(2);
-    int nhb, nchunk, chunk;
-    score_plan(d, &nhb, &nchunk, &chunk);
-    if (fused_chunk_ok(chunk)) {
+    int fchunks, fchunk;
+    if (fused_plan(d, &fchunks, &fchunk)) {
         // selection and attention in one launch (the event between them collapses to an empty interval)
         if (e == hipSuccess) e = mark(3);
         if (e == hipSuccess) e = launch_fused(d, w, q, K, V, seq_len, k, softmax_scale, idx_out, out, s);

@@ -118,7 +118,7 @@ __device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, i
 // ---- optional phase timeline (debug builds only, -DSIK_TIMELINE) ------------------------------
 // SIK_TL(slot) stores the 100 MHz wall clock when thread 0 of the first, the middle or the last
 // workgroup of the grid passes the mark (plain stores, three columns); SIK_TL_ANY(slot) is for code
-// only one workgroup per row reaches (any of them may write: an approximate "latest").
+// only one workgroup per row reaches: the one of row 0 writes (a variable `row` must be in scope).
 #ifdef SIK_TIMELINE
 #define SIK_TL_DEFINE(setter)                                                                     \
     static __device__ unsigned long long* sik_tl_buf = nullptr;                                   \
@@ -135,7 +135,7 @@ __device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, i
     } while (0)
 #define SIK_TL_ANY(slot)                                                                          \
     do {                                                                                          \
-        if (threadIdx.x == 0 && sik_tl_buf) sik_tl_buf[4 * (slot) + 3] = wall_clock64();          \
+        if (threadIdx.x == 0 && sik_tl_buf && row == 0) sik_tl_buf[4 * (slot) + 3] = wall_clock64(); \
     } while (0)
 #else
 #define SIK_TL_DEFINE(setter)

@@ -38,11 +38,11 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const uint32_t* __restrict__ parthist, const float* __restrict__ binp, uint32_t* __restrict__ counters,
     uint32_t* __restrict__ cand, float* __restrict__ partial, int32_t* __restrict__ idx_ws,
     int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
-    int Lmax, int nchunk) {
+    int Lmax, int nchunk, int hchunks) {
     constexpr int kChunk = 1024 * NQ;
     __shared__ int32_t l_sel[kBlock / kWave][kChunk / 4];
     __shared__ uint32_t red[(kBlock / kWave) * kBins];
-    __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 16];
+    __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 64];
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ uint32_t lds4[4], sh[4];
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const int start = c * kChunk;
 
     // ---- 1. every load that does not depend on another goes out now ---------------------------
-    const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * nchunk * kHistWords, nchunk);
+    const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hchunks);
     const float4* s4 = reinterpret_cast<const float4*>(scores + static_cast<size_t>(row) * sstride + start);
     float4 sv[NQ];
 #pragma unroll
@@ -86,6 +86,13 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
     const bool ranked = nb <= kCandCap;
     SIK_TL(25);
+#ifdef SIK_TIMELINE
+    if (tid == 0 && c == 0 && sik_tl_buf) {  // debug: candidate count and selected-above count of 4 rows
+        sik_tl_buf[4 * 40 + (row & 3)] = static_cast<unsigned long long>(nb);
+        sik_tl_buf[4 * 41 + (row & 3)] = static_cast<unsigned long long>(cgt);
+        sik_tl_buf[4 * 42 + (row & 3)] = static_cast<unsigned long long>(bstar);
+    }
+#endif
 
     // ---- 3. wave-private compaction of the selected tokens, candidates aside -------------------
     const uint4* Kp = reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
@@ -95,20 +102,26 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     uint32_t* crow = cand + static_cast<size_t>(row) * regions * kCandWaveWords;
     uint32_t* cw = crow + c * (kBlock / kWave) + wv;  // word w of this wavefront's region: cw[w * regions]
     const uint64_t lt_mask = (1ull << lane) - 1ull;
+    // bin(s) > b*  <=>  x >= b* + 1 and bin(s) == b*  <=>  b* <= x < b* + 1 with x = (s - lo) * scale,
+    // the clamped end bins taking everything beyond them (score_bin is floor + clamp of the same x)
+    const float hi_f = bstar < 0 ? -INFINITY : (bstar == kBins - 1 ? INFINITY : static_cast<float>(bstar + 1));
+    const float lo_f = bstar <= 0 ? -INFINITY : static_cast<float>(bstar);
+    const bool has_cand = bstar >= 0 && ranked;
 #pragma unroll
     for (int j = 0; j < NQ; ++j) {
         const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int i = start + (j * kBlock + tid) * 4 + e;
-            const int bin = (i < end) ? (bstar < 0 ? 0 : score_bin(v4[e], lo, scale)) : -2;
-            const bool sure = bin > bstar;
-            const bool cnd = bin == bstar && bstar >= 0;
+            const float x = (v4[e] - lo) * scale;
+            const bool valid = i < end;
+            const bool sure = valid && x >= hi_f;
             const uint64_t bs = __ballot(sure);
             if (sure) l_sel[wv][n_sel + __popcll(bs & lt_mask)] = i;
             n_sel += __popcll(bs);
+            const bool cnd = valid && !sure && x >= lo_f && has_cand;
             const uint64_t bc = __ballot(cnd);
-            if (bc != 0ull && ranked) {
+            if (bc != 0ull) {
                 const int pos = n_cand + __popcll(bc & lt_mask);
                 if (cnd && pos < kWaveCand) {
                     st_agent(&cw[(1 + 2 * pos) * regions], float_to_key(v4[e]));
@@ -200,36 +213,50 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
                 }
             }
             __syncthreads();
+            SIK_TL_ANY(33);
             use_radix = s_over != 0;
         }
         if (!use_radix) {
             const int n = min(static_cast<int>(s_ncand), kCandCap);
-            int32_t* chosen = reinterpret_cast<int32_t*>(red);  // reuse: rank r -> token index
-            // pad to a multiple of 8 with entries that outrank nothing, so that the ranking loop can
-            // keep eight LDS reads in flight
-            const int npad = (n + 7) & ~7;
-            if (tid < npad - n) {
-                l_cand[2 * (n + tid)] = 0u;
-                l_cand[2 * (n + tid) + 1] = 0xffffffffu;
+            uint32_t* rank_of = red;                                      // [kCandCap] partial-rank sums
+            int32_t* chosen = reinterpret_cast<int32_t*>(red + kCandCap);  // rank r -> token index
+            // Ranking by counting, spread over all 256 threads: P threads share one candidate and each
+            // scans a slice of the list, padded to a multiple of 8 with entries that outrank nothing so
+            // that eight LDS reads stay in flight.
+            const int P = n <= 64 ? 4 : (n <= 128 ? 2 : 1);
+            const int slice = ((n + P - 1) / P + 7) & ~7;
+            for (int j = tid; j < P * slice - n; j += kBlock) {
+                l_cand[2 * (n + j)] = 0u;
+                l_cand[2 * (n + j) + 1] = 0xffffffffu;
             }
+            for (int j = tid; j < n; j += kBlock) rank_of[j] = 0u;
             __syncthreads();
             const uint2* lc2 = reinterpret_cast<const uint2*>(l_cand);
-            for (int a = tid; a < n; a += kBlock) {
+            const int per = kBlock / P;  // candidates handled per pass
+            const int part = tid / per;
+            for (int a = tid % per; a < n; a += per) {
                 const uint2 me = lc2[a];
-                int rank = 0;
-                for (int x = 0; x < npad; x += 8) {
+                uint32_t rank = 0;
+                for (int x = part * slice; x < (part + 1) * slice; x += 8) {
                     uint2 o8[8];
 #pragma unroll
                     for (int y = 0; y < 8; ++y) o8[y] = lc2[x + y];
 #pragma unroll
-                    for (int y = 0; y < 8; ++y) rank += (o8[y].x > me.x || (o8[y].x == me.x && o8[y].y < me.y)) ? 1 : 0;
+                    for (int y = 0; y < 8; ++y) rank += (o8[y].x > me.x || (o8[y].x == me.x && o8[y].y < me.y)) ? 1u : 0u;
                 }
+                if (P > 1) atomicAdd(&rank_of[a], rank); else rank_of[a] = rank;
+            }
+            __syncthreads();
+            for (int a = tid; a < n; a += kBlock) {
+                const int rank = static_cast<int>(rank_of[a]);
                 if (rank < need) {
-                    chosen[rank] = static_cast<int32_t>(me.y);
-                    if (idx_out) olist[cgt + rank] = static_cast<int32_t>(me.y);
+                    const int32_t ia = static_cast<int32_t>(lc2[a].y);
+                    chosen[rank] = ia;
+                    if (idx_out) olist[cgt + rank] = ia;
                 }
             }
             __syncthreads();
+            SIK_TL_ANY(34);
             attend_list<DT>([&](int j) { return chosen[j]; }, min(need, n), wv * 16, (kBlock / kWave) * 16, Kp, Vp,
                             qf, Lmax, st);
         } else {
@@ -273,10 +300,21 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     SIK_TL_ANY(30);
 }
 
-// Chunk sizes the fused kernel is instantiated for (tokens per workgroup).
-bool fused_chunk_ok(int chunk) { return chunk == 1024 || chunk == 2048 || chunk == 4096 || chunk == 8192; }
+// Token chunk of the fused kernel: a power of two in [1024, 8192] (the instantiated sizes), aiming at
+// about 400 workgroups; independent of the scoring kernel's chunks, whose histograms are only summed.
+// Returns false when max_len needs more than kMaxChunks chunks of 8192 tokens.
+bool fused_plan(const Dims& d, int* nchunk, int* chunk) {
+    int want = (384 + d.rows() - 1) / d.rows();
+    int ch = 1024;
+    while (ch < 8192 && static_cast<int64_t>(ch) * want < d.Lmax) ch *= 2;
+    *chunk = ch;
+    *nchunk = (d.Lmax + ch - 1) / ch;
+    return *nchunk <= kMaxChunks;
+}
 
-size_t fused_cand_words(const Dims& d, int nchunk) {
+size_t fused_cand_words(const Dims& d) {
+    int nchunk, chunk;
+    if (!fused_plan(d, &nchunk, &chunk)) return 0;
     return static_cast<size_t>(d.rows()) * nchunk * (kBlock / kWave) * kCandWaveWords;
 }
 
@@ -284,8 +322,9 @@ template <int DT, int ODT>
 static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                                  const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out,
                                  hipStream_t s) {
-    int nhb, nchunk, chunk;
-    score_plan(d, &nhb, &nchunk, &chunk);
+    int nhb, hchunks, hchunk, nchunk, chunk;
+    score_plan(d, &nhb, &hchunks, &hchunk);
+    if (!fused_plan(d, &nchunk, &chunk)) return hipErrorInvalidValue;
     const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
     const int grid = nchunk * d.rows();
     auto qp = static_cast<const uint16_t*>(q);
@@ -295,7 +334,7 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     select_attend_kernel<DT, ODT, NQV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, w.scores, w.sstride, seq_len,    \
                                                                w.parthist, w.binp, w.counters, w.cand,      \
                                                                w.partial, w.idx, idx_out, out, sl2, k,      \
-                                                               d.Hkv, d.Hq, d.R, d.Lmax, nchunk)
+                                                               d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks)
     switch (chunk) {
         case 1024: SIK_FUSED(1); break;
         case 2048: SIK_FUSED(2); break;

@@ -62,8 +62,8 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
 // select + attention in one launch; reads w.scores / w.parthist / w.binp written by launch_score
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                         const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out, hipStream_t s);
-bool fused_chunk_ok(int chunk);
-size_t fused_cand_words(const Dims& d, int nchunk);
+bool fused_plan(const Dims& d, int* nchunk, int* chunk);
+size_t fused_cand_words(const Dims& d);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,
                       float* codebook, int32_t* counts, uint8_t* codes, hipStream_t s);
 hipError_t launch_encode(const Dims& d, const void* K, int t0, int n, const float* mu, uint8_t* codes,

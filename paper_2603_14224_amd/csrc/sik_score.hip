@@ -227,8 +227,9 @@ void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
     const int units = d.units() * nhb;
     int want = (512 + units - 1) / units;
     if (want > kMaxChunks) want = kMaxChunks;
-    int ch = 1024;  // power of two so that the fused select + attention kernel can take the same chunks
-    while (static_cast<int64_t>(ch) * want < d.Lmax || (d.Lmax + ch - 1) / ch > kMaxChunks) ch *= 2;
+    int ch = (d.Lmax + want - 1) / want;
+    ch = (ch + 1023) / 1024 * 1024;  // whole loop iterations of 4 tokens per lane
+    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += 1024;
     *nhb_out = nhb;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
