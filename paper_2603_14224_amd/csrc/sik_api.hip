@@ -124,7 +124,7 @@ int sik_score(const sik_layout* layout, const void* q, const float* codebook, co
     int rc = check_layout(layout, &d);
     if (rc) return rc;
     if (!q || !codebook || !codes || !seq_len || !scores) return SIK_ERR_NULL;
-    return launched(launch_score(d, nullptr, q, codebook, codes, seq_len, scores,
+    return launched(launch_score(d, nullptr, false, q, codebook, codes, seq_len, scores,
                                  static_cast<hipStream_t>(stream)));
 }
 
@@ -180,9 +180,11 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     int32_t* idx = idx_out ? idx_out : w.idx;
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
     hipError_t e = mark(0);
-    if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
+    // The prep launch (append one row per head, clear the per-call counters) is only needed when a
+    // row is appended; otherwise the scoring kernel clears the counters itself.
+    if (e == hipSuccess && k_new) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
     if (e == hipSuccess) e = mark(1);
-    if (e == hipSuccess) e = launch_score(d, &w, q, codebook, codes, seq_len, w.scores, s);
+    if (e == hipSuccess) e = launch_score(d, &w, k_new == nullptr, q, codebook, codes, seq_len, w.scores, s);
     if (e == hipSuccess) e = mark(2);
     int fchunks, fchunk;
     if (fused_plan(d, &fchunks, &fchunk)) {

@@ -45,9 +45,11 @@ Workspace carve(const Dims& d, int k, void* base);
 // launchers (return hipError_t of the launch)
 hipError_t launch_prep(const Dims& d, const Workspace& w, const void* k_new, const void* v_new, void* K,
                        void* V, int32_t* seq_len, const float* mu, uint8_t* codes, hipStream_t s);
-// w == nullptr: scores only; otherwise also the per-chunk selection histograms
-hipError_t launch_score(const Dims& d, const Workspace* w, const void* q, const float* codebook,
-                        const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s);
+// w == nullptr: scores only; otherwise also the per-chunk selection histograms, and with
+// zero_counters the per-head counters are cleared (decode step without a preceding prep launch)
+hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const void* q,
+                        const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
+                        hipStream_t s);
 hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
                             hipStream_t s);
 void score_plan(const Dims& d, int* nhb, int* nchunk, int* chunk);

@@ -65,8 +65,9 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
                                                        const int32_t* __restrict__ seq_len,
                                                        float* __restrict__ scores, int sstride,
                                                        uint32_t* __restrict__ parthist,
-                                                       float* __restrict__ binp, int Hkv, int Hq, int R,
-                                                       int Lmax, int nchunk, int chunk, int nhb) {
+                                                       float* __restrict__ binp,
+                                                       uint32_t* __restrict__ zero_counters, int Hkv, int Hq,
+                                                       int R, int Lmax, int nchunk, int chunk, int nhb) {
     constexpr int HB = 4 * NT;
     __shared__ float4 lut[NT][kG * 16];
     __shared__ float qs[HB][kD];
@@ -105,8 +106,12 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
 #pragma unroll
         for (int e = 0; e < 8; ++e) qs[s][8 * p + e] = f[e];
     }
-    if constexpr (HIST)
+    if constexpr (HIST) {
         for (int e = tid; e < HB * kBins; e += kBlock) lhist[e] = 0u;
+        // the kernels that follow count on zeroed per-head counters; when no prep launch precedes,
+        // chunk 0 of each head block clears those of its heads
+        if (zero_counters && c == 0 && tid < nh * 8) zero_counters[row0 * 8 + tid] = 0u;
+    }
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     if (start >= L && c != 0) {  // no valid token here (chunk 0 always runs: it owns the per-head outputs)
@@ -200,7 +205,8 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
 #pragma unroll
                 for (int s = 0; s < HB; ++s) {
                     if (s < nh) {
-                        scores[(row0 + s) * sstride + tok] = acc[s];
+                        // streamed once, read by the next kernel: keep it out of the way of the end-of-kernel write-back
+                        __builtin_nontemporal_store(acc[s], &scores[(row0 + s) * sstride + tok]);
                         if constexpr (HIST)
                             atomicAdd(&lhist[s * kBins + score_bin(acc[s], bp[s][0], bp[s][1])], 1u);
                     }
@@ -242,8 +248,9 @@ bool score_plan_ok(const Dims& d) {
 }
 
 template <int DT>
-static hipError_t launch_score_t(const Dims& d, const Workspace* w, const void* q, const float* codebook,
-                                 const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s) {
+static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, const void* q,
+                                 const float* codebook, const uint8_t* codes, const int32_t* seq_len,
+                                 float* scores, hipStream_t s) {
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
     const int NT = d.R > 4 ? 2 : 1;
@@ -252,8 +259,8 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, const void* 
 #define SIK_SCORE(NTV, HV)                                                                                   \
     score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(qp, codebook, codes, seq_len, scores,                \
                                                       w ? w->sstride : d.Lmax, w ? w->parthist : nullptr, \
-                                                      w ? w->binp : nullptr, d.Hkv, d.Hq, d.R, d.Lmax,    \
-                                                      nchunk, chunk, nhb)
+                                                      w ? w->binp : nullptr, zero ? w->counters : nullptr, \
+                                                      d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
     if (w) {
         if (NT == 1) SIK_SCORE(1, true); else SIK_SCORE(2, true);
     } else {
@@ -263,10 +270,11 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, const void* 
     return hipGetLastError();
 }
 
-hipError_t launch_score(const Dims& d, const Workspace* w, const void* q, const float* codebook,
-                        const uint8_t* codes, const int32_t* seq_len, float* scores, hipStream_t s) {
-    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, q, codebook, codes, seq_len, scores, s)
-                               : launch_score_t<kF16>(d, w, q, codebook, codes, seq_len, scores, s);
+hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const void* q,
+                        const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
+                        hipStream_t s) {
+    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, zero_counters, q, codebook, codes, seq_len, scores, s)
+                               : launch_score_t<kF16>(d, w, zero_counters, q, codebook, codes, seq_len, scores, s);
 }
 
 }  // namespace sik
