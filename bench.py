@@ -92,19 +92,26 @@ def main():
             host0 = (Kb, Vb)
         layers.append(st)
     torch.cuda.synchronize()
+    # step inputs: 8 distinct queries reused in turn; appended key/value rows are distinct for every
+    # step a layer sees (repeating a key would plant exact score ties that real decoding does not have)
     n_q = 8
-    qs, kns, vns = [], [], []
-    for s in range(n_q):
-        q, kn, vn = W.make_step_inputs(cfg, s)
-        qs.append(dev(q, cfg.dtype)); kns.append(dev(kn, cfg.dtype)); vns.append(dev(vn, cfg.dtype))
+    qs = [dev(W.make_step_inputs(cfg, s)[0], cfg.dtype) for s in range(n_q)]
+    n_new = (-(-total_steps // n_layers) + 2) if cfg.append else 1
+    kn_all, vn_all = [], []
+    for s in range(n_new):
+        _, kn, vn = W.make_step_inputs(cfg, 1000 + s)
+        kn_all.append(kn); vn_all.append(vn)
+    kns = dev(np.stack(kn_all), cfg.dtype)   # [n_new, B, Hkv, D]
+    vns = dev(np.stack(vn_all), cfg.dtype)
     out = torch.empty(B, Hq, D, dtype=tdt, device="cuda")
     gen_s = time.time() - t0
 
-    def step(i, profiled=False):
+    def step(i, profiled=False, base=0):
         st = layers[i % n_layers]
         j = i % n_q
+        a = ((i - base) // n_layers) % n_new  # how many rows this layer has been given since its reset
         fn = sik.sik_decode_step_profiled if profiled else sik.sik_decode_step
-        return fn(lay, qs[j], kns[j] if cfg.append else None, vns[j] if cfg.append else None, st["K"], st["V"],
+        return fn(lay, qs[j], kns[a] if cfg.append else None, vns[a] if cfg.append else None, st["K"], st["V"],
                   st["sl"], st["mu"], st["cb"], st["codes"], k, 0.0, out, None, ws)
 
     def reset_lengths():
@@ -129,30 +136,39 @@ def main():
     sec_step = sec_stream
     sec_graph = None
     if not args.no_graph:
-        # one graph = one step on every layer in turn; replayed steps / n_layers times
-        reps = max(1, args.steps // n_layers)
+        # one graph = `rounds` decode steps on every layer in turn.  With append, the graph first resets
+        # the lengths (one small fill per layer, inside the timed region) so that every replay appends
+        # the same `rounds` distinct rows at the same positions instead of piling up copies.
+        rounds = min(8, n_new - 1) if cfg.append else 1
+        per_graph = n_layers * rounds
+        reps = max(1, args.steps // per_graph)
+
+        def graph_body():
+            if cfg.append:
+                reset_lengths()
+            for i in range(per_graph):
+                step(i)
+
         reset_lengths()
         side = torch.cuda.Stream()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
-            for i in range(n_layers):
-                step(i)
+            graph_body()
             torch.cuda.synchronize()
             reset_lengths()
             torch.cuda.synchronize()
             with torch.cuda.graph(g, stream=side):
-                for i in range(n_layers):
-                    step(i)
+                graph_body()
         torch.cuda.synchronize()
         reset_lengths()
-        for _ in range(max(1, args.warmup // n_layers)):
+        for _ in range(max(1, args.warmup // per_graph)):
             g.replay()
         torch.cuda.synchronize()
         t = time.perf_counter()
         for _ in range(reps):
             g.replay()
         torch.cuda.synchronize()
-        sec_graph = (time.perf_counter() - t) / (reps * n_layers)
+        sec_graph = (time.perf_counter() - t) / (reps * per_graph)
         if sec_graph < sec_stream:
             sec_step, launch = sec_graph, "hipgraph"
     reset_lengths()

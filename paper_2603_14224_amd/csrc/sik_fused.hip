@@ -40,7 +40,8 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
     int Lmax, int nchunk, int hchunks) {
     constexpr int kChunk = 1024 * NQ;
-    __shared__ int32_t l_sel[kBlock / kWave][kChunk / 4];
+    constexpr int kListCap = 512;  // selected-token slots per wavefront; flushed to the gather when half full
+    __shared__ int32_t l_sel[kBlock / kWave][kListCap];
     __shared__ uint32_t red[(kBlock / kWave) * kBins];
     __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 64];
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
@@ -107,8 +108,28 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const float hi_f = bstar < 0 ? -INFINITY : (bstar == kBins - 1 ? INFINITY : static_cast<float>(bstar + 1));
     const float lo_f = bstar <= 0 ? -INFINITY : static_cast<float>(bstar);
     const bool has_cand = bstar >= 0 && ranked;
+    SoftmaxState st;
+    init_state(st);
+    int32_t* mylist = l_sel[wv];
 #pragma unroll
     for (int j = 0; j < NQ; ++j) {
+        if (n_sel > kListCap - 256) {
+            // the next four elements per lane may add up to 256 entries: gather the complete groups of 16
+            // now and keep the remainder (< 16 entries) at the front of the list
+            const int n16 = n_sel & ~15;
+            if (idx_out) {
+                uint32_t base = 0u;
+                if (lane == 0) base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(n16));
+                base = static_cast<uint32_t>(__shfl(static_cast<int>(base), 0, 64));
+                for (int t = lane; t < n16; t += 64)
+                    if (base + t < static_cast<uint32_t>(k)) idx_out[static_cast<size_t>(row) * k + base + t] = mylist[t];
+            }
+            attend_list<DT>([&](int t) { return mylist[t]; }, n16, 0, 16, Kp, Vp, qf, Lmax, st);
+            const int rem = n_sel - n16;
+            const int keep = lane < rem ? mylist[n16 + lane] : 0;
+            if (lane < rem) mylist[lane] = keep;
+            n_sel = rem;
+        }
         const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -117,7 +138,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
             const bool valid = i < end;
             const bool sure = valid && x >= hi_f;
             const uint64_t bs = __ballot(sure);
-            if (sure) l_sel[wv][n_sel + __popcll(bs & lt_mask)] = i;
+            if (sure) mylist[n_sel + __popcll(bs & lt_mask)] = i;
             n_sel += __popcll(bs);
             const bool cnd = valid && !sure && x >= lo_f && has_cand;
             const uint64_t bc = __ballot(cnd);
@@ -140,9 +161,6 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     SIK_TL(26);
 
     // ---- 4. attend over this wavefront's own tokens, publish the chunk's partial ---------------
-    SoftmaxState st;
-    init_state(st);
-    const int32_t* mylist = l_sel[wv];
     attend_list<DT>([&](int j) { return mylist[j]; }, n_sel, 0, 16, Kp, Vp, qf, Lmax, st);
     SIK_TL(27);
     if (idx_out && n_sel > 0) {

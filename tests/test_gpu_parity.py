@@ -324,6 +324,19 @@ def test_decode_step_k_not_below_context(oracle):
     run_decode_and_check(oracle, cfg, capacity=1100, steps=1, append=True)
 
 
+def test_decode_step_dense_selection_flushes_the_wave_lists(oracle):
+    # k = L with 4096-token chunks: every wavefront selects all 1024 tokens of its share, far more than
+    # its 512-slot list holds, so the list is gathered and refilled several times
+    cfg = cfg_small("C2", context=40000, top_k=40000)
+    run_decode_and_check(oracle, cfg, capacity=40000, steps=1, append=False)
+
+
+def test_decode_step_half_selected(oracle):
+    # k = L / 2: the threshold sits in the middle of the score distribution
+    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=30000, top_k=15000)
+    run_decode_and_check(oracle, cfg, capacity=30008, steps=1, append=True)
+
+
 def test_decode_step_zero_query_all_scores_equal(oracle):
     # q = 0 makes every score equal: the selector must still return k distinct smallest indices
     cfg = cfg_small("C2", n_kv_heads=1, n_q_heads=4, context=3000, top_k=100)
