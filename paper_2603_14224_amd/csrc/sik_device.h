@@ -147,12 +147,17 @@ __device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, i
     } while (0)
 #endif
 
-// Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15); every lane gets the total.
+// Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15); every lane gets the total.  Four
+// rotate-within-row DPP moves feeding adds: no LDS traffic, unlike ds_bpermute-based shuffles.
+template <int N>
+__device__ __forceinline__ float row_ror(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xf, 0xf, false));
+}
 __device__ __forceinline__ float row16_sum(float v) {
-    v += __shfl_xor(v, 8, 64);
-    v += __shfl_xor(v, 4, 64);
-    v += __shfl_xor(v, 2, 64);
-    v += __shfl_xor(v, 1, 64);
+    v += row_ror<8>(v);
+    v += row_ror<4>(v);
+    v += row_ror<2>(v);
+    v += row_ror<1>(v);
     return v;
 }
 

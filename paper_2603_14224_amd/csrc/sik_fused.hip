@@ -58,7 +58,8 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const int start = c * kChunk;
 
     // ---- 1. every load that does not depend on another goes out now ---------------------------
-    const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hchunks);
+    // (the histogram loads come last in program order because their values are consumed as they
+    // arrive: whatever is issued after them would wait for them)
     const float4* s4 = reinterpret_cast<const float4*>(scores + static_cast<size_t>(row) * sstride + start);
     float4 sv[NQ];
 #pragma unroll
@@ -66,9 +67,11 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
         const int i = start + (j * kBlock + tid) * 4;
         sv[j] = i < sstride ? s4[j * kBlock + tid] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    float qf[8];
-    widen8<DT>(reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p], qf);
+    const uint4 qraw = reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p];
     const float lo = binp[row * 2], scale = binp[row * 2 + 1];
+    const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hchunks);
+    float qf[8];
+    widen8<DT>(qraw, qf);
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const int nact = L > 0 ? (L + kChunk - 1) / kChunk : 1;
@@ -111,12 +114,68 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     SoftmaxState st;
     init_state(st);
     int32_t* mylist = l_sel[wv];
+    // Stage A: one branch-free pass over this lane's 4 * NQ scores marks, in two bit masks, the ones
+    // at or above the selection bound and the ones at or above the candidate bound (a few
+    // instructions per score; about 3 % are selected, about 0.1 % are candidates).
+    static_assert(4 * NQ <= 32, "one mask bit per score of the lane");
+    uint32_t smask = 0u, gmask = 0u;
+    if (start + kChunk <= end) {
 #pragma unroll
-    for (int j = 0; j < NQ; ++j) {
-        if (n_sel > kListCap - 256) {
-            // the next four elements per lane may add up to 256 entries: gather the complete groups of 16
-            // now and keep the remainder (< 16 entries) at the front of the list
-            const int n16 = n_sel & ~15;
+        for (int j = 0; j < NQ; ++j) {
+            const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float x = (v4[e] - lo) * scale;
+                smask |= (x >= hi_f ? 1u : 0u) << (4 * j + e);
+                gmask |= (x >= lo_f ? 1u : 0u) << (4 * j + e);
+            }
+        }
+    } else {  // last chunk of the sequence: slots at or beyond seq_len compare false (NaN)
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = start + (j * kBlock + tid) * 4 + e;
+                const float x = i < end ? (v4[e] - lo) * scale : __builtin_nanf("");
+                smask |= (x >= hi_f ? 1u : 0u) << (4 * j + e);
+                gmask |= (x >= lo_f ? 1u : 0u) << (4 * j + e);
+            }
+        }
+    }
+    uint32_t cmask = has_cand ? (gmask & ~smask) : 0u;
+    // candidates: rounds of one mask bit per lane, as in stage B below; the score of the popped slot is
+    // picked from the registers by a select chain (only wavefronts that hold candidates get here)
+    while (true) {
+        const bool has = cmask != 0u;
+        const uint64_t bc = __ballot(has);
+        if (bc == 0ull) break;
+        const int bit = has ? __ffs(static_cast<int>(cmask)) - 1 : 0;
+        cmask &= cmask - 1u;
+        float v = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v = bit == 4 * j + e ? v4[e] : v;
+        }
+        const int pos = n_cand + __popcll(bc & lt_mask);
+        if (has && pos < kWaveCand) {
+            st_agent(&cw[(1 + 2 * pos) * regions], float_to_key(v));
+            st_agent(&cw[(2 + 2 * pos) * regions],
+                     static_cast<uint32_t>(start + (((bit >> 2) * kBlock + tid) * 4 + (bit & 3))));
+        }
+        n_cand += __popcll(bc);
+    }
+    // Stage B: compaction of the marked scores into the wavefront's list, one mask bit per lane and
+    // round (as many rounds as the busiest lane has selected scores); the list is gathered whenever
+    // another round might not fit.
+    while (true) {
+        const bool has = smask != 0u;
+        const uint64_t bal = __ballot(has);
+        if (bal == 0ull) break;
+        if (n_sel > kListCap - 64) {
+            const int n16 = n_sel & ~15;  // complete groups of 16 now, the rest moves to the front
             if (idx_out) {
                 uint32_t base = 0u;
                 if (lane == 0) base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(n16));
@@ -130,27 +189,12 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
             if (lane < rem) mylist[lane] = keep;
             n_sel = rem;
         }
-        const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int i = start + (j * kBlock + tid) * 4 + e;
-            const float x = (v4[e] - lo) * scale;
-            const bool valid = i < end;
-            const bool sure = valid && x >= hi_f;
-            const uint64_t bs = __ballot(sure);
-            if (sure) mylist[n_sel + __popcll(bs & lt_mask)] = i;
-            n_sel += __popcll(bs);
-            const bool cnd = valid && !sure && x >= lo_f && has_cand;
-            const uint64_t bc = __ballot(cnd);
-            if (bc != 0ull) {
-                const int pos = n_cand + __popcll(bc & lt_mask);
-                if (cnd && pos < kWaveCand) {
-                    st_agent(&cw[(1 + 2 * pos) * regions], float_to_key(v4[e]));
-                    st_agent(&cw[(2 + 2 * pos) * regions], static_cast<uint32_t>(i));
-                }
-                n_cand += __popcll(bc);
-            }
+        if (has) {
+            const int bit = __ffs(static_cast<int>(smask)) - 1;
+            smask &= smask - 1u;
+            mylist[n_sel + __popcll(bal & lt_mask)] = start + (((bit >> 2) * kBlock + tid) * 4 + (bit & 3));
         }
+        n_sel += __popcll(bal);
     }
     if (lane == 0) st_agent(&cw[0], n_cand > kWaveCand ? kCandOverflow : static_cast<uint32_t>(n_cand));
     // optional index output: reserve this wave's slots now, write them after the gather
