@@ -54,7 +54,7 @@ Workspace carve(const Dims& d, int k, void* base) {
     w.sstride = (d.Lmax + 3) & ~3;
     w.scores = reinterpret_cast<float*>(take(rows * static_cast<size_t>(w.sstride) * 4));
     w.colsum = reinterpret_cast<double*>(take(units * kFitMaxWg * kD * 8));
-    w.csum = reinterpret_cast<double*>(take(units * kG * 64 * 8));
+    w.cpart = reinterpret_cast<float*>(take(units * kFitMaxWg * kG * 80 * 4));
     w.total_bytes = off;
     return w;
 }

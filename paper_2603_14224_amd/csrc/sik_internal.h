@@ -34,7 +34,7 @@ struct Workspace {
     int sstride;            // Lmax rounded up to a multiple of 4 (16-byte aligned score rows)
     // quantiser fit
     double* colsum;         // [units][kFitMaxWg][D]
-    double* csum;           // [units][G*16*4]    cluster sums (zeroed by the fit's own kernel)
+    float* cpart;           // [units][kFitMaxWg][G][16][5]  per-workgroup cluster sums and counts
     size_t total_bytes;
 };
 

@@ -107,107 +107,130 @@ __global__ __launch_bounds__(kBlock) void colsum_kernel(const uint16_t* __restri
     }
 }
 
-// fit step 2: mu = (sum of partials, fixed order) / L, and clear the cluster accumulators.
+// fit step 2: mu = (sum of partials, fixed order) / L.
 __global__ __launch_bounds__(kBlock) void mean_kernel(const double* __restrict__ colsum,
                                                       const int32_t* __restrict__ seq_len,
-                                                      float* __restrict__ mu, double* __restrict__ csum,
-                                                      int32_t* __restrict__ counts, int Hkv, int Lmax,
-                                                      int nwg) {
+                                                      float* __restrict__ mu, int Hkv, int Lmax, int nwg) {
     const int unit = blockIdx.x, tid = threadIdx.x;
     int L = seq_len[unit / Hkv];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     if (tid < kD) {
         double s = 0.0;
+#pragma unroll 8
         for (int w = 0; w < nwg; ++w) s += colsum[(static_cast<size_t>(unit) * kFitMaxWg + w) * kD + tid];
         mu[static_cast<size_t>(unit) * kD + tid] = L > 0 ? static_cast<float>(s / static_cast<double>(L)) : 0.0f;
     }
-    for (int e = tid; e < kG * 16 * 4; e += kBlock) csum[static_cast<size_t>(unit) * kG * 64 + e] = 0.0;
-    for (int e = tid; e < kG * 16; e += kBlock) counts[static_cast<size_t>(unit) * kG * 16 + e] = 0;
 }
 
 // fit step 3 / stand-alone encode: sign bits against mu, packed MSB-first; with CLUSTER also the
-// per-(group, code) sums of K - mu and member counts (LDS float atomics per workgroup, then one
-// fp64 global atomic per touched entry).
+// per-(group, code) sums of K - mu and the member counts of this workgroup's token range.
+//
+// One lane owns one sign group of one token: lane = 32 * half + g reads the 8 bytes holding channels
+// 4g .. 4g+3 (a wavefront load covers two complete 256 B rows) and derives the group's 4-bit Code.
+// The cluster accumulators are private to the lane - an LDS column tab[entry][lane], entry = 5 * Code
+// + component (4 sums, 1 count), always on the lane's own bank - so they are updated with plain
+// read-add-write in token order: no atomics (LDS float atomics ran this kernel at 0.4 TB/s) and a
+// sum order that does not depend on scheduling.  Workgroup partials go to part[unit][wg][g][80].
+constexpr int kEncThreads = 128;                 // two wavefronts
+constexpr int kEncEntries = 16 * 5;              // per group: 16 codes x (4 sums + count)
+constexpr int kEncTokPerIter = kEncThreads / 32;  // tokens a workgroup takes per step
+constexpr int kEncUnroll = 16;
+
 template <int DT, bool CLUSTER>
-__global__ __launch_bounds__(kBlock) void encode_kernel(const uint16_t* __restrict__ K,
-                                                        const int32_t* __restrict__ seq_len, int t0, int n,
-                                                        const float* __restrict__ mu,
-                                                        uint8_t* __restrict__ codes,
-                                                        double* __restrict__ csum,
-                                                        int32_t* __restrict__ counts, int Hkv, int Lmax,
-                                                        int nwg) {
-    __shared__ float lsum[CLUSTER ? kG * 64 : 1];
-    __shared__ uint32_t lcnt[CLUSTER ? kG * 16 : 1];
-    const int tid = threadIdx.x, p = tid & 15, r = tid >> 4;
+__global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t* __restrict__ K,
+                                                             const int32_t* __restrict__ seq_len, int t0, int n,
+                                                             const float* __restrict__ mu,
+                                                             uint8_t* __restrict__ codes,
+                                                             float* __restrict__ part, int Hkv, int Lmax,
+                                                             int nwg) {
+    __shared__ float tab[CLUSTER ? (kEncThreads / kWave) * kEncEntries * kWave : 1];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int g = lane & 31, sub = wv * 2 + (lane >> 5);  // sub: which of the 4 tokens of a step
     const int unit = blockIdx.x / nwg, wg = blockIdx.x % nwg;
     int lo, hi;
     if constexpr (CLUSTER) {
         int L = seq_len[unit / Hkv];
         lo = 0;
         hi = L < 0 ? 0 : (L > Lmax ? Lmax : L);
-        for (int e = tid; e < kG * 64; e += kBlock) lsum[e] = 0.0f;
-        for (int e = tid; e < kG * 16; e += kBlock) lcnt[e] = 0u;
-        __syncthreads();
     } else {
         lo = t0;
         hi = t0 + n;
     }
-    const int chunk = ((hi - lo + nwg - 1) / nwg + 15) & ~15;
+    const int chunk = ((hi - lo + nwg - 1) / nwg + kEncTokPerIter - 1) / kEncTokPerIter * kEncTokPerIter;
     const int start = lo + wg * chunk;
     const int end = min(hi, start + chunk);
-    const uint4* base = reinterpret_cast<const uint4*>(K + static_cast<size_t>(unit) * Lmax * kD);
+    const uint2* base = reinterpret_cast<const uint2*>(K + static_cast<size_t>(unit) * Lmax * kD);
     uint8_t* cbase = codes + static_cast<size_t>(unit) * Lmax * kCodeBytes;
-    const float4 m0 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * p];
-    const float4 m1 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * p + 1];
-    const float m[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-    for (int i = start + r; i < end; i += 16) {
-        float f[8];
-        widen8<DT>(base[static_cast<size_t>(i) * 16 + p], f);
-        uint32_t byte = 0;
+    const float4 m = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[g];
+    float* col = tab + (CLUSTER ? wv * kEncEntries * kWave + lane : 0);  // this lane's column, stride 64
+    if constexpr (CLUSTER) {
+#pragma unroll 8
+        for (int e = 0; e < kEncEntries; ++e) col[e * kWave] = 0.0f;
+    }
+    for (int i0 = start + sub; i0 < end; i0 += kEncTokPerIter * kEncUnroll) {
+        uint2 v[kEncUnroll];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) byte |= (f[e] >= m[e] ? 1u : 0u) << (7 - e);
-        cbase[static_cast<size_t>(i) * kCodeBytes + p] = static_cast<uint8_t>(byte);
-        if constexpr (CLUSTER) {
+        for (int u = 0; u < kEncUnroll; ++u) {
+            const int i = i0 + u * kEncTokPerIter;
+            v[u] = i < end ? base[static_cast<size_t>(i) * 32 + g] : make_uint2(0u, 0u);
+        }
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int g = 2 * p + c;
-                const int j = (byte >> (4 * (1 - c))) & 15;
-                const int slot = g * 16 + j;
-                atomicAdd(&lcnt[slot], 1u);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) unsafeAtomicAdd(&lsum[slot * 4 + e], f[4 * c + e] - m[4 * c + e]);
+        for (int u = 0; u < kEncUnroll; ++u) {
+            const int i = i0 + u * kEncTokPerIter;
+            if (i < end) {
+                const float f[4] = {widen16<DT>(v[u].x & 0xffffu), widen16<DT>(v[u].x >> 16),
+                                    widen16<DT>(v[u].y & 0xffffu), widen16<DT>(v[u].y >> 16)};
+                const int code = (f[0] >= m.x ? 8 : 0) | (f[1] >= m.y ? 4 : 0) | (f[2] >= m.z ? 2 : 0) |
+                                 (f[3] >= m.w ? 1 : 0);
+                // the neighbouring lane holds the other nibble of this byte (groups 2j, 2j+1)
+                const int other = __builtin_amdgcn_update_dpp(0, code, 0xB1 /* quad_perm:[1,0,3,2] */, 0xf, 0xf, false);
+                if ((g & 1) == 0) cbase[static_cast<size_t>(i) * kCodeBytes + (g >> 1)] = static_cast<uint8_t>((code << 4) | other);
+                if constexpr (CLUSTER) {
+                    float* ent = col + code * 5 * kWave;
+                    ent[0 * kWave] += f[0] - m.x;
+                    ent[1 * kWave] += f[1] - m.y;
+                    ent[2 * kWave] += f[2] - m.z;
+                    ent[3 * kWave] += f[3] - m.w;
+                    ent[4 * kWave] += 1.0f;
+                }
             }
         }
     }
     if constexpr (CLUSTER) {
         __syncthreads();
-        for (int e = tid; e < kG * 64; e += kBlock) {
-            const float v = lsum[e];
-            if (v != 0.0f) unsafeAtomicAdd(&csum[static_cast<size_t>(unit) * kG * 64 + e], static_cast<double>(v));
-        }
-        for (int e = tid; e < kG * 16; e += kBlock) {
-            const uint32_t c = lcnt[e];
-            if (c) atomicAdd(&counts[static_cast<size_t>(unit) * kG * 16 + e], static_cast<int32_t>(c));
+        float* pw = part + (static_cast<size_t>(unit) * kFitMaxWg + wg) * kG * kEncEntries;
+        for (int e = tid; e < kG * kEncEntries; e += kEncThreads) {
+            const int gg = e / kEncEntries, ent = e % kEncEntries;
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kEncThreads / kWave; ++w)
+                sum += tab[(w * kEncEntries + ent) * kWave + gg] + tab[(w * kEncEntries + ent) * kWave + 32 + gg];
+            pw[e] = sum;
         }
     }
 }
 
-// fit step 4: centroid = cluster sum / member count; empty cluster -> 0.
-__global__ __launch_bounds__(kBlock) void codebook_kernel(const double* __restrict__ csum,
-                                                          const int32_t* __restrict__ counts,
+// fit step 4: centroid = (sum of the workgroup partials, fixed order, fp64) / member count; empty -> 0.
+// Grid = units x 2; thread = one (group, code) entry.
+__global__ __launch_bounds__(kBlock) void codebook_kernel(const float* __restrict__ part, int nwg,
+                                                          int32_t* __restrict__ counts,
                                                           float* __restrict__ codebook) {
-    const size_t unit = blockIdx.x;
-    for (int e = threadIdx.x; e < kG * 16; e += kBlock) {
-        const int32_t c = counts[unit * kG * 16 + e];
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (c > 0) {
-            const double inv = static_cast<double>(c);
-            const double* s = csum + unit * kG * 64 + static_cast<size_t>(e) * 4;
-            o = make_float4(static_cast<float>(s[0] / inv), static_cast<float>(s[1] / inv),
-                            static_cast<float>(s[2] / inv), static_cast<float>(s[3] / inv));
-        }
-        reinterpret_cast<float4*>(codebook)[unit * kG * 16 + e] = o;
+    const size_t unit = blockIdx.x >> 1;
+    const int e = (blockIdx.x & 1) * kBlock + threadIdx.x;  // e = g * 16 + code
+    double s[5] = {0, 0, 0, 0, 0};
+    const float* p = part + (unit * kFitMaxWg * kG * 16 + e) * 5;
+#pragma unroll 4
+    for (int w = 0; w < nwg; ++w) {
+#pragma unroll
+        for (int c = 0; c < 5; ++c) s[c] += static_cast<double>(p[static_cast<size_t>(w) * kG * 16 * 5 + c]);
     }
+    const int32_t cnt = static_cast<int32_t>(s[4] + 0.5);
+    counts[unit * kG * 16 + e] = cnt;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (cnt > 0)
+        o = make_float4(static_cast<float>(s[0] / s[4]), static_cast<float>(s[1] / s[4]),
+                        static_cast<float>(s[2] / s[4]), static_cast<float>(s[3] / s[4]));
+    reinterpret_cast<float4*>(codebook)[unit * kG * 16 + e] = o;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -246,14 +269,14 @@ hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const in
         colsum_kernel<kBF16><<<units * nwg, kBlock, 0, s>>>(Kp, seq_len, w.colsum, d.Hkv, d.Lmax, nwg);
     else
         colsum_kernel<kF16><<<units * nwg, kBlock, 0, s>>>(Kp, seq_len, w.colsum, d.Hkv, d.Lmax, nwg);
-    mean_kernel<<<units, kBlock, 0, s>>>(w.colsum, seq_len, mu, w.csum, counts, d.Hkv, d.Lmax, nwg);
+    mean_kernel<<<units, kBlock, 0, s>>>(w.colsum, seq_len, mu, d.Hkv, d.Lmax, nwg);
     if (d.kv_dtype == kBF16)
-        encode_kernel<kBF16, true><<<units * nwg, kBlock, 0, s>>>(Kp, seq_len, 0, 0, mu, codes, w.csum, counts,
-                                                                  d.Hkv, d.Lmax, nwg);
+        encode_kernel<kBF16, true><<<units * nwg, kEncThreads, 0, s>>>(Kp, seq_len, 0, 0, mu, codes, w.cpart, d.Hkv,
+                                                                       d.Lmax, nwg);
     else
-        encode_kernel<kF16, true><<<units * nwg, kBlock, 0, s>>>(Kp, seq_len, 0, 0, mu, codes, w.csum, counts,
-                                                                 d.Hkv, d.Lmax, nwg);
-    codebook_kernel<<<units, kBlock, 0, s>>>(w.csum, counts, codebook);
+        encode_kernel<kF16, true><<<units * nwg, kEncThreads, 0, s>>>(Kp, seq_len, 0, 0, mu, codes, w.cpart, d.Hkv,
+                                                                      d.Lmax, nwg);
+    codebook_kernel<<<units * 2, kBlock, 0, s>>>(w.cpart, nwg, counts, codebook);
     return hipGetLastError();
 }
 
@@ -265,11 +288,11 @@ hipError_t launch_encode(const Dims& d, const void* K, int t0, int n, const floa
     if (nwg > cap) nwg = cap;
     auto Kp = static_cast<const uint16_t*>(K);
     if (d.kv_dtype == kBF16)
-        encode_kernel<kBF16, false><<<d.units() * nwg, kBlock, 0, s>>>(Kp, nullptr, t0, n, mu, codes, nullptr,
-                                                                       nullptr, d.Hkv, d.Lmax, nwg);
+        encode_kernel<kBF16, false><<<d.units() * nwg, kEncThreads, 0, s>>>(Kp, nullptr, t0, n, mu, codes, nullptr,
+                                                                            d.Hkv, d.Lmax, nwg);
     else
-        encode_kernel<kF16, false><<<d.units() * nwg, kBlock, 0, s>>>(Kp, nullptr, t0, n, mu, codes, nullptr,
-                                                                      nullptr, d.Hkv, d.Lmax, nwg);
+        encode_kernel<kF16, false><<<d.units() * nwg, kEncThreads, 0, s>>>(Kp, nullptr, t0, n, mu, codes, nullptr,
+                                                                           d.Hkv, d.Lmax, nwg);
     return hipGetLastError();
 }
 
