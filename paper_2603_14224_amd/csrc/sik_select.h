@@ -118,6 +118,7 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
     for (int pass = 3; pass >= 0; --pass) {
         h256[tid] = 0u;
         __syncthreads();
+#pragma unroll 8
         for (int i = tid; i < L; i += kBlock) {
             const float v = s[i];
             const uint32_t key = float_to_key(v);
@@ -154,19 +155,20 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
         sh[3] = 0u;  // running count of equal members seen
     }
     __syncthreads();
-    for (int base = 0; base < L; base += kBlock) {
+    // larger members: any order, one barrier-free sweep
+#pragma unroll 8
+    for (int i = tid; i < L; i += kBlock) {
+        const float v = s[i];
+        if (score_bin(v, lo, scale) == bstar && float_to_key(v) > tau) out[atomicAdd(&sh[2], 1u)] = i;
+    }
+    // equal members: the first need_eq of them in index order; tiles of 256 tokens, stop when served
+    for (int base = 0; base < L && need_eq > 0u; base += kBlock) {
         const int i = base + tid;
-        bool gt = false, eq = false;
+        bool eq = false;
         if (i < L) {
             const float v = s[i];
-            const uint32_t key = float_to_key(v);
-            if (score_bin(v, lo, scale) == bstar) {
-                gt = key > tau;
-                eq = key == tau;
-            }
+            eq = score_bin(v, lo, scale) == bstar && float_to_key(v) == tau;
         }
-        if (gt) out[atomicAdd(&sh[2], 1u)] = i;
-        // ordered rank of the equal members of this tile
         const uint64_t bal = __ballot(eq);
         const int lane = tid & 63, wv = tid >> 6;
         if (lane == 0) h256[wv] = static_cast<uint32_t>(__popcll(bal));
@@ -175,10 +177,12 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
         for (int w = 0; w < wv; ++w) before += h256[w];
         const uint32_t ord = before + static_cast<uint32_t>(__popcll(bal & ((1ull << lane) - 1ull)));
         if (eq && ord < need_eq) out[n_gt + ord] = i;
+        const uint32_t total = sh[3] + h256[0] + h256[1] + h256[2] + h256[3];
         __syncthreads();
-        if (tid == 0) sh[3] += h256[0] + h256[1] + h256[2] + h256[3];
-        __syncthreads();
+        if (tid == 0) sh[3] = total;
+        if (total >= need_eq) break;  // uniform: every thread computed the same total
     }
+    __syncthreads();
 }
 
 }  // namespace sik

@@ -354,6 +354,59 @@ def test_decode_step_zero_query_all_scores_equal(oracle):
     check_attention(out.cpu().numpy().astype(np.float64), ref, True)
 
 
+def test_decode_step_duplicate_keys_at_threshold(oracle):
+    # 40 identical keys in a row have identical scores; with k chosen so that the cut falls inside
+    # that plateau, one wavefront's share of the threshold bin overflows its candidate slots and the
+    # exact radix fallback must take the smallest indices of the plateau
+    cfg = cfg_small("C2", n_kv_heads=1, n_q_heads=4, context=12000, top_k=64)
+    K, V = W.make_cache(cfg)
+    K[0, 0, 5000:5040] = K[0, 0, 5000]
+    sl = np.array([12000], np.int32)
+    mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    s_ref = oracle.score(q, cfg.dtype, cb, codes, sl)
+    order = np.lexsort((np.arange(12000), -s_ref[0, 0]))
+    r0 = int(np.where(order == 5000)[0][0])      # rank of the first duplicate for query head 0
+    k = r0 + 20
+    assert 20 < k < 11000
+    lay = sik.make_layout(1, 1, 4, 128, 12000, torch.bfloat16, torch.float32)
+    ws = sik.alloc_workspace(lay, k)
+    out = torch.empty(1, 4, 128, device="cuda")
+    idx = torch.empty(1, 4, k, dtype=torch.int32, device="cuda")
+    dsl = torch.from_numpy(sl.copy()).cuda()
+    sik.sik_decode_step(lay, dev(q, cfg.dtype), None, None, dev(K, cfg.dtype), dev(V, cfg.dtype), dsl,
+                        torch.from_numpy(mu).cuda(), torch.from_numpy(cb).cuda(), torch.from_numpy(codes).cuda(), k,
+                        0.0, out, idx, ws)
+    sync()
+    g = idx.cpu().numpy()
+    ref_idx = oracle.topk(s_ref, sl, k)
+    assert sorted(g[0, 0].tolist()) == sorted(ref_idx[0, 0].tolist())   # exact, smallest indices of the plateau
+    assert set(range(5000, 5020)) <= set(g[0, 0].tolist()) and 5020 not in set(g[0, 0].tolist())
+    for hq in range(1, 4):
+        topk_sets_agree(g[0, hq], ref_idx[0, hq], s_ref[0, hq], 12000, k)
+    check_attention(out.cpu().numpy().astype(np.float64), oracle.sparse_attn(q, K, V, cfg.dtype, g), True)
+
+
+def test_decode_step_output_is_bit_reproducible(oracle):
+    # fixed-order merges and rank-ordered candidates: the same inputs give the same output bits and the
+    # same index set on every run, whatever the arrival order of the workgroups
+    cfg = cfg_small("C2", context=20000, top_k=700)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 3)
+    dq = dev(q, cfg.dtype)
+    outs, sets = [], []
+    for _ in range(4):
+        o = torch.empty(1, 32, 128, device="cuda")
+        idx = torch.empty(1, 32, 700, dtype=torch.int32, device="cuda")
+        sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 700, 0.0, o,
+                            idx, st.ws)
+        sync()
+        outs.append(o.clone())
+        sets.append(torch.sort(idx, dim=-1).values.clone())
+    for o, s_ in zip(outs[1:], sets[1:]):
+        assert torch.equal(o, outs[0]) and torch.equal(s_, sets[0])
+
+
 def test_decode_step_without_idx_out_matches(oracle):
     cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=5000, top_k=200)
     st = GpuState(cfg, oracle, out_dtype=torch.float32)
