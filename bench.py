@@ -21,7 +21,9 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0
-KERNELS = ("prep_kernel", "score_kernel", "select_kernel", "attn_kernel")
+# event intervals of sik_decode_step_profiled, in launch order; the third one is empty when selection and
+# attention run fused in one launch (every benchmark workload)
+KERNELS = ("prep_kernel", "score_kernel", "select_kernel_unfused_only", "select_attend_kernel")
 
 
 def parse():
@@ -186,7 +188,8 @@ def main():
 
     ab = W.algorithmic_bytes(cfg)
     alg_by_kernel = {"prep_kernel": (B * Hkv * (2 * D * 2 + D // 8)) if cfg.append else 0,
-                     "score_kernel": ab["codes"], "select_kernel": 0, "attn_kernel": ab["gathered"]}
+                     "score_kernel": ab["codes"], "select_kernel_unfused_only": 0,
+                     "select_attend_kernel": ab["gathered"]}
     dom = max((1, 3), key=lambda i: kus[i])  # the two kernels that move the algorithmic bytes
     dom_name = KERNELS[dom]
     dom_bytes = alg_by_kernel[dom_name]

@@ -90,13 +90,6 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
     const bool ranked = nb <= kCandCap;
     SIK_TL(25);
-#ifdef SIK_TIMELINE
-    if (tid == 0 && c == 0 && sik_tl_buf) {  // debug: candidate count and selected-above count of 4 rows
-        sik_tl_buf[4 * 40 + (row & 3)] = static_cast<unsigned long long>(nb);
-        sik_tl_buf[4 * 41 + (row & 3)] = static_cast<unsigned long long>(cgt);
-        sik_tl_buf[4 * 42 + (row & 3)] = static_cast<unsigned long long>(bstar);
-    }
-#endif
 
     // ---- 3. wave-private compaction of the selected tokens, candidates aside -------------------
     const uint4* Kp = reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
