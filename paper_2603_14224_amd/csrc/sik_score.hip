@@ -224,10 +224,15 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     SIK_TL(4);
 }
 
+// float4 tables per workgroup (4 query heads each).  One: a GQA group wider than 4 is served by several
+// head blocks that re-read the codes from L2; two tables in one workgroup were measured slower (256 VGPRs,
+// two wavefronts per SIMD: 65 us against 2 x 18 us on the 8:1 workload).
+static int score_tables(const Dims&) { return 1; }
+
 // Tokens per workgroup: about two workgroups per compute unit, at least 1024 tokens each (so that
 // the table build and the 2 KB histogram per head are amortised), at most kMaxChunks per head.
 void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
-    const int NT = d.R > 4 ? 2 : 1;
+    const int NT = score_tables(d);
     const int HB = 4 * NT;
     const int nhb = (d.R + HB - 1) / HB;
     const int units = d.units() * nhb;
@@ -253,7 +258,7 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
                                  float* scores, hipStream_t s) {
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
-    const int NT = d.R > 4 ? 2 : 1;
+    const int NT = score_tables(d);
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
 #define SIK_SCORE(NTV, HV)                                                                                   \
