@@ -387,6 +387,39 @@ def test_decode_step_duplicate_keys_at_threshold(oracle):
     check_attention(out.cpu().numpy().astype(np.float64), oracle.sparse_attn(q, K, V, cfg.dtype, g), True)
 
 
+def test_decode_step_very_long_context_takes_the_unfused_path(oracle):
+    # above 512K tokens the fused select + attention kernel would need more than 64 chunks of 8192:
+    # the decode step then runs select_kernel + attn_kernel (also the 64-chunk limit of the histograms)
+    cfg = cfg_small("C2", n_kv_heads=1, n_q_heads=2, context=530000, top_k=3000)
+    run_decode_and_check(oracle, cfg, capacity=530004, steps=1, append=True)
+
+
+def test_decode_step_long_context_fused_many_chunks(oracle):
+    # 300K tokens: 37 chunks of 8192 in the fused kernel, more than the 32 whose partials the last
+    # arriver prefetches; 64 scoring chunks
+    cfg = cfg_small("C2", n_kv_heads=1, n_q_heads=4, context=300000, top_k=2048)
+    run_decode_and_check(oracle, cfg, capacity=300000, steps=1, append=False)
+
+
+def test_decode_step_empty_and_single_token_sequences(oracle):
+    cfg = cfg_small("C2", batch=3, n_kv_heads=2, n_q_heads=4, context=1500, top_k=8)
+    st = GpuState(cfg, oracle, capacity=1504, seq_len=[0, 1, 1500], out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    out = torch.full((3, 4, 128), 7.0, device="cuda")
+    idx = torch.full((3, 4, 8), -5, dtype=torch.int32, device="cuda")
+    sik.sik_decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes,
+                        8, 0.0, out, idx, st.ws)
+    sync()
+    g, o = idx.cpu().numpy(), out.cpu().numpy().astype(np.float64)
+    assert np.all(g[0] == -1) and np.all(o[0] == 0)                      # empty sequence: zero rows
+    assert np.all(np.sort(g[1], axis=-1)[:, -1] == 0) and np.all(np.sort(g[1], axis=-1)[:, :-1] == -1)
+    Vd = W.from_bits(st.V, cfg.dtype).astype(np.float64)
+    for hq in range(4):
+        assert np.allclose(o[1, hq], Vd[1, hq // 2, 0], rtol=1e-6, atol=1e-7)  # one token: its V row
+    ref = oracle.sparse_attn(q, st.K, st.V, cfg.dtype, g)
+    check_attention(o[2:3], ref[2:3], True)
+
+
 def test_decode_step_output_is_bit_reproducible(oracle):
     # fixed-order merges and rank-ordered candidates: the same inputs give the same output bits and the
     # same index set on every run, whatever the arrival order of the workgroups
