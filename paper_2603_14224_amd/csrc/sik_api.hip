@@ -124,7 +124,7 @@ int sik_score(const sik_layout* layout, const void* q, const float* codebook, co
     int rc = check_layout(layout, &d);
     if (rc) return rc;
     if (!q || !codebook || !codes || !seq_len || !scores) return SIK_ERR_NULL;
-    return launched(launch_score(d, nullptr, false, q, codebook, codes, seq_len, scores,
+    return launched(launch_score(d, nullptr, false, Append{}, q, codebook, codes, seq_len, scores,
                                  static_cast<hipStream_t>(stream)));
 }
 
@@ -180,18 +180,25 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     int32_t* idx = idx_out ? idx_out : w.idx;
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
     hipError_t e = mark(0);
-    // The prep launch (append one row per head, clear the per-call counters) is only needed when a
-    // row is appended; otherwise the scoring kernel clears the counters itself.
-    if (e == hipSuccess && k_new) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
-    if (e == hipSuccess) e = mark(1);
-    if (e == hipSuccess) e = launch_score(d, &w, k_new == nullptr, q, codebook, codes, seq_len, w.scores, s);
-    if (e == hipSuccess) e = mark(2);
     int fchunks, fchunk;
     if (fused_plan(d, &fchunks, &fchunk)) {
-        // selection and attention in one launch (the event between them collapses to an empty interval)
+        // Two launches: scoring (which also stores, encodes and scores an appended row and clears the
+        // per-call counters), then selection + attention (which publishes the new length).  The first
+        // and third event intervals are empty.
+        const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+                        static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes};
+        if (e == hipSuccess) e = mark(1);
+        if (e == hipSuccess) e = launch_score(d, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, s);
+        if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = mark(3);
-        if (e == hipSuccess) e = launch_fused(d, w, q, K, V, seq_len, k, softmax_scale, idx_out, out, s);
+        if (e == hipSuccess)
+            e = launch_fused(d, w, q, K, V, seq_len, k_new != nullptr, k, softmax_scale, idx_out, out, s);
     } else {
+        // contexts beyond 512K tokens: prep (append + clear counters), score, select, attention
+        if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
+        if (e == hipSuccess) e = mark(1);
+        if (e == hipSuccess) e = launch_score(d, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, s);
+        if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
         if (e == hipSuccess) e = mark(3);
         if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);

@@ -34,7 +34,7 @@ constexpr uint32_t kCandOverflow = 0xffffffffu;
 template <int DT, int ODT, int NQ>  // NQ float4 of scores per lane: chunk = 1024 * NQ tokens
 __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const float* __restrict__ scores, int sstride, const int32_t* __restrict__ seq_len,
+    const float* __restrict__ scores, int sstride, int32_t* __restrict__ seq_len, int appended,
     const uint32_t* __restrict__ parthist, const float* __restrict__ binp, uint32_t* __restrict__ counters,
     uint32_t* __restrict__ cand, float* __restrict__ partial, int32_t* __restrict__ idx_ws,
     int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
@@ -74,6 +74,8 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     widen8<DT>(qraw, qf);
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
+    const bool grew = appended && L < Lmax;  // the scoring launch stored and scored one more token
+    if (grew) L += 1;
     const int nact = L > 0 ? (L + kChunk - 1) / kChunk : 1;
     if (c >= nact) return;  // no token of this chunk is valid; the ticket below counts nact workgroups
     const int end = min(L, start + kChunk);
@@ -352,6 +354,12 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     }
     if (idx_out)
         for (int j = kk + tid; j < k; j += kBlock) olist[j] = -1;
+    // the last query head of the sequence to finish publishes the new length: by then every workgroup of
+    // every head of this sequence has read the old one
+    if (grew && tid == 0) {
+        if (atomic_add_u32(&counters[static_cast<size_t>(b) * Hq * 8 + 7], 1u) == static_cast<uint32_t>(Hq) - 1u)
+            seq_len[b] = L;
+    }
     SIK_TL_ANY(30);
 }
 
@@ -375,7 +383,7 @@ size_t fused_cand_words(const Dims& d) {
 
 template <int DT, int ODT>
 static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                                 const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out,
+                                 int32_t* seq_len, bool appended, int k, float scale, int32_t* idx_out, void* out,
                                  hipStream_t s) {
     int nhb, hchunks, hchunk, nchunk, chunk;
     score_plan(d, &nhb, &hchunks, &hchunk);
@@ -387,6 +395,7 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_FUSED(NQV)                                                                                      \
     select_attend_kernel<DT, ODT, NQV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, w.scores, w.sstride, seq_len,    \
+                                                               appended ? 1 : 0,                            \
                                                                w.parthist, w.binp, w.counters, w.cand,      \
                                                                w.partial, w.idx, idx_out, out, sl2, k,      \
                                                                d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks)
@@ -402,12 +411,12 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
 }
 
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out, hipStream_t s) {
-    if (d.kv_dtype == kBF16)
-        return d.out_dtype == kF32 ? launch_fused_t<kBF16, kF32>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s)
-                                   : launch_fused_t<kBF16, kBF16>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s);
-    return d.out_dtype == kF32 ? launch_fused_t<kF16, kF32>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s)
-                               : launch_fused_t<kF16, kF16>(d, w, q, K, V, seq_len, k, scale, idx_out, out, s);
+                        int32_t* seq_len, bool appended, int k, float scale, int32_t* idx_out, void* out,
+                        hipStream_t s) {
+#define SIK_F(DTV, ODTV) launch_fused_t<DTV, ODTV>(d, w, q, K, V, seq_len, appended, k, scale, idx_out, out, s)
+    if (d.kv_dtype == kBF16) return d.out_dtype == kF32 ? SIK_F(kBF16, kF32) : SIK_F(kBF16, kBF16);
+    return d.out_dtype == kF32 ? SIK_F(kF16, kF32) : SIK_F(kF16, kF16);
+#undef SIK_F
 }
 
 }  // namespace sik

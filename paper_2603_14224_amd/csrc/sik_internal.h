@@ -45,9 +45,21 @@ Workspace carve(const Dims& d, int k, void* base);
 // launchers (return hipError_t of the launch)
 hipError_t launch_prep(const Dims& d, const Workspace& w, const void* k_new, const void* v_new, void* K,
                        void* V, int32_t* seq_len, const float* mu, uint8_t* codes, hipStream_t s);
+// Decode-time append folded into the scoring launch (all null: nothing is appended).
+struct Append {
+    const uint16_t* k_new;
+    const uint16_t* v_new;
+    uint16_t* K;
+    uint16_t* V;
+    const float* mu;
+    uint8_t* codes;
+};
+
 // w == nullptr: scores only; otherwise also the per-chunk selection histograms, and with
-// zero_counters the per-head counters are cleared (decode step without a preceding prep launch)
-hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const void* q,
+// zero_counters the per-head counters are cleared (decode step without a preceding prep launch).
+// With ap.k_new the new row of every (b, h) is encoded, stored and scored as token seq_len[b]; the
+// length itself is left for launch_fused to increment.
+hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const Append& ap, const void* q,
                         const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
                         hipStream_t s);
 hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
@@ -62,8 +74,10 @@ hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score
 hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                        const int32_t* idx, int k, float scale, void* out, hipStream_t s);
 // select + attention in one launch; reads w.scores / w.parthist / w.binp written by launch_score
+// `appended`: launch_score counted one more token than seq_len says; the last workgroup increments it
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        const int32_t* seq_len, int k, float scale, int32_t* idx_out, void* out, hipStream_t s);
+                        int32_t* seq_len, bool appended, int k, float scale, int32_t* idx_out, void* out,
+                        hipStream_t s);
 bool fused_plan(const Dims& d, int* nchunk, int* chunk);
 size_t fused_cand_words(const Dims& d);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,

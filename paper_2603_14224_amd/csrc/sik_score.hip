@@ -66,13 +66,19 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
                                                        float* __restrict__ scores, int sstride,
                                                        uint32_t* __restrict__ parthist,
                                                        float* __restrict__ binp,
-                                                       uint32_t* __restrict__ zero_counters, int Hkv, int Hq,
-                                                       int R, int Lmax, int nchunk, int chunk, int nhb) {
+                                                       uint32_t* __restrict__ zero_counters,
+                                                       const uint16_t* __restrict__ k_new,
+                                                       const uint16_t* __restrict__ v_new,
+                                                       uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc,
+                                                       const float* __restrict__ mu,
+                                                       uint8_t* __restrict__ codes_w, int Hkv, int Hq, int R,
+                                                       int Lmax, int nchunk, int chunk, int nhb) {
     constexpr int HB = 4 * NT;
     __shared__ float4 lut[NT][kG * 16];
     __shared__ float qs[HB][kD];
     __shared__ float bp[HB][2];
     __shared__ uint32_t lhist[HIST ? HB * kBins : 1];
+    __shared__ __align__(16) uint8_t newcode[kCodeBytes];
 
     SIK_TL(0);
     const int tid = threadIdx.x;
@@ -112,8 +118,41 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         // chunk 0 of each head block clears those of its heads
         if (zero_counters && c == 0 && tid < nh * 8) zero_counters[row0 * 8 + tid] = 0u;
     }
+    // decode-time append (k_new != nullptr): the new key/value row of this KV head goes to row t =
+    // seq_len[b]; every workgroup counts it in (L = t + 1), the one whose chunk holds t encodes it
+    // against the frozen mu and scores it from LDS, and head block 0 of that chunk also stores the row and
+    // its code.  seq_len itself is incremented by the last workgroup of the kernel that follows.
+    uint4 knew = make_uint4(0u, 0u, 0u, 0u), vnew = make_uint4(0u, 0u, 0u, 0u);
+    float4 m0 = make_float4(0.f, 0.f, 0.f, 0.f), m1 = m0;
+    if (k_new && tid < 16) {
+        knew = reinterpret_cast<const uint4*>(k_new + static_cast<size_t>(unit) * kD)[tid];
+        vnew = reinterpret_cast<const uint4*>(v_new + static_cast<size_t>(unit) * kD)[tid];
+        m0 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * tid];
+        m1 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * tid + 1];
+    }
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
+    int t_new = -1;
+    if (k_new && L < Lmax) {
+        t_new = L;
+        L += 1;
+    }
+    const bool holds_new = t_new >= start && t_new < start + chunk;
+    if (holds_new && tid < 16) {
+        float f[8];
+        widen8<DT>(knew, f);
+        const float m[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+        uint32_t byte = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) byte |= (f[e] >= m[e] ? 1u : 0u) << (7 - e);
+        newcode[tid] = static_cast<uint8_t>(byte);
+        if (hb == 0) {
+            const size_t rowi = static_cast<size_t>(unit) * Lmax + t_new;
+            reinterpret_cast<uint4*>(Kc + rowi * kD)[tid] = knew;
+            reinterpret_cast<uint4*>(Vc + rowi * kD)[tid] = vnew;
+            codes_w[rowi * kCodeBytes + tid] = static_cast<uint8_t>(byte);
+        }
+    }
     if (start >= L && c != 0) {  // no valid token here (chunk 0 always runs: it owns the per-head outputs)
         if constexpr (HIST)      // consumers read every chunk's histogram: publish an empty one
             for (int s = 0; s < nh; ++s) parthist[((row0 + s) * nchunk + c) * kHistWords + tid] = 0u;
@@ -200,6 +239,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         for (int j = 0; j < kTokPerIter; ++j) {
             const int tok = base + j * kBlock + tid;
             float acc[HB];
+            if (tok == t_new) code[j] = *reinterpret_cast<const uint4*>(newcode);  // written before the barriers above
             score_token<NT>(code[j], lut, acc);
             if (tok < end) {
 #pragma unroll
@@ -253,7 +293,7 @@ bool score_plan_ok(const Dims& d) {
 }
 
 template <int DT>
-static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, const void* q,
+static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, const Append& ap, const void* q,
                                  const float* codebook, const uint8_t* codes, const int32_t* seq_len,
                                  float* scores, hipStream_t s) {
     int nhb, nchunk, chunk;
@@ -262,10 +302,10 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
 #define SIK_SCORE(NTV, HV)                                                                                   \
-    score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(qp, codebook, codes, seq_len, scores,                \
-                                                      w ? w->sstride : d.Lmax, w ? w->parthist : nullptr, \
-                                                      w ? w->binp : nullptr, zero ? w->counters : nullptr, \
-                                                      d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
+    score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(                                                     \
+        qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
+        w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
+        d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
     if (w) {
         if (NT == 1) SIK_SCORE(1, true); else SIK_SCORE(2, true);
     } else {
@@ -275,11 +315,12 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     return hipGetLastError();
 }
 
-hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const void* q,
+hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const Append& ap, const void* q,
                         const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
                         hipStream_t s) {
-    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, zero_counters, q, codebook, codes, seq_len, scores, s)
-                               : launch_score_t<kF16>(d, w, zero_counters, q, codebook, codes, seq_len, scores, s);
+    return d.kv_dtype == kBF16
+               ? launch_score_t<kBF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores, s)
+               : launch_score_t<kF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores, s);
 }
 
 }  // namespace sik
