@@ -440,6 +440,61 @@ def test_decode_step_output_is_bit_reproducible(oracle):
         assert torch.equal(o, outs[0]) and torch.equal(s_, sets[0])
 
 
+def test_decode_step_graph_replay_matches_eager(oracle):
+    # the step is captured into a HIP graph (kernels only, no memset nodes) and replayed several times with
+    # eager work and synchronisations in between; every replay must reproduce the eager result, including the
+    # device-side append (the graph resets the length first, as bench.py does)
+    cfg = cfg_small("C3", context=20000, top_k=600)
+    st = GpuState(cfg, oracle, capacity=20008, out_dtype=torch.float32)
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    dq, dkn, dvn = dev(q, cfg.dtype), dev(kn, cfg.dtype), dev(vn, cfg.dtype)
+    out = torch.empty(1, 32, 128, device="cuda")
+    idx = torch.empty(1, 32, 600, dtype=torch.int32, device="cuda")
+
+    def body():
+        st.dsl.fill_(20000)
+        sik.sik_decode_step(st.layout, dq, dkn, dvn, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 600, 0.0, out,
+                            idx, st.ws)
+
+    body()
+    sync()
+    eager_out, eager_idx = out.clone(), torch.sort(idx, dim=-1).values.clone()
+    assert int(st.dsl[0]) == 20001
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        body()
+        sync()
+        with torch.cuda.graph(g, stream=side):
+            body()
+    sync()
+    for r in range(4):
+        out.zero_()
+        idx.fill_(-3)
+        st.dsl.fill_(123)                      # eager work between replays
+        torch.randn(1 << 20, device="cuda").sum().item()
+        g.replay()
+        sync()
+        assert int(st.dsl[0]) == 20001
+        assert torch.equal(out, eager_out), r
+        assert torch.equal(torch.sort(idx, dim=-1).values, eager_idx), r
+
+
+def test_profiled_decode_step_same_result_and_five_intervals(oracle):
+    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=6000, top_k=128)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    dq = dev(q, cfg.dtype)
+    a = torch.empty(1, 8, 128, device="cuda")
+    b = torch.empty(1, 8, 128, device="cuda")
+    sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128, 0.0, a, None, st.ws)
+    us = sik.sik_decode_step_profiled(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128,
+                                      0.0, b, None, st.ws)
+    sync()
+    assert len(us) == 5 and all(u >= 0 for u in us) and us[1] > 0 and us[3] > 0
+    assert torch.equal(a, b)
+
+
 def test_decode_step_without_idx_out_matches(oracle):
     cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=5000, top_k=200)
     st = GpuState(cfg, oracle, out_dtype=torch.float32)
