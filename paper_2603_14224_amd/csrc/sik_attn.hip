@@ -29,7 +29,7 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
 
     SIK_TL(16);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int slot = lane >> 4, p = lane & 15;
+    const int p = lane & 15;
     const int row = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
     const int b = row / Hq, hq = row % Hq;
     const size_t unit = static_cast<size_t>(b) * Hkv + hq / R;

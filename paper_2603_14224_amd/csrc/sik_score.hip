@@ -1,8 +1,10 @@
 // LUT-GEMV retrieval over the packed sign codes for gfx950 (section "Compressed-Domain
 // Top-k Retrieval"): Table^(g)[j] = q^(g) . c_j^(g), score_i = sum_g Table^(g)[Code_g(k_i)].
 //
-// One workgroup serves one (batch, kv head) for a block of up to 4*NT query heads of its GQA
-// group and a contiguous chunk of tokens.  The tables live in LDS as float4 entries holding the
+// One workgroup serves one (batch, kv head) for a block of up to 4 query heads of its GQA group
+// (a wider group is served by several head blocks that re-read the codes from L2: two float4
+// tables in one workgroup were measured slower, 65 us against 2 x 18 us on the 8:1 workload)
+// and a contiguous chunk of tokens.  The tables live in LDS as float4 entries holding the
 // same (g, j) entry of four query heads: the 16 entries of a group span 256 B = all 64 LDS
 // banks once, so the data-dependent ds_read_b128 of a wavefront (all lanes are at the same g)
 // is bank-conflict free whatever the codes are.  Each lane owns one token per load: a single
@@ -21,11 +23,11 @@ SIK_TL_DEFINE(sik_dbg_tl_score)
 
 constexpr int kTokPerIter = 4;  // tokens per lane per loop iteration
 
-template <int NT>
-__device__ __forceinline__ void score_token(const uint4 code, const float4 (*lut)[kG * 16], float* acc) {
-    constexpr int HB = 4 * NT;
+constexpr int kHB = 4;  // query heads per workgroup = components of one float4 table entry
+
+__device__ __forceinline__ void score_token(const uint4 code, const float4* lut, float* acc) {
 #pragma unroll
-    for (int s = 0; s < HB; ++s) acc[s] = 0.0f;
+    for (int s = 0; s < kHB; ++s) acc[s] = 0.0f;
     const uint32_t w[4] = {code.x, code.y, code.z, code.w};
 #pragma unroll
     for (int dw = 0; dw < 4; ++dw) {
@@ -36,29 +38,22 @@ __device__ __forceinline__ void score_token(const uint4 code, const float4 (*lut
             const uint32_t bits = w[dw] >> (8 * by);
             const uint32_t off_hi = bits & 0xf0u;  // Code * 16 B
             const uint32_t off_lo = (bits & 0x0fu) << 4;
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float4 v =
-                    *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(&lut[t][g * 16]) + off_hi);
-                acc[4 * t + 0] += v.x;
-                acc[4 * t + 1] += v.y;
-                acc[4 * t + 2] += v.z;
-                acc[4 * t + 3] += v.w;
-            }
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float4 v = *reinterpret_cast<const float4*>(
-                    reinterpret_cast<const char*>(&lut[t][(g + 1) * 16]) + off_lo);
-                acc[4 * t + 0] += v.x;
-                acc[4 * t + 1] += v.y;
-                acc[4 * t + 2] += v.z;
-                acc[4 * t + 3] += v.w;
-            }
+            const float4 v0 = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(&lut[g * 16]) + off_hi);
+            acc[0] += v0.x;
+            acc[1] += v0.y;
+            acc[2] += v0.z;
+            acc[3] += v0.w;
+            const float4 v1 =
+                *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(&lut[(g + 1) * 16]) + off_lo);
+            acc[0] += v1.x;
+            acc[1] += v1.y;
+            acc[2] += v1.z;
+            acc[3] += v1.w;
         }
     }
 }
 
-template <int DT, int NT, bool HIST>
+template <int DT, bool HIST>
 __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restrict__ q,
                                                        const float* __restrict__ codebook,
                                                        const uint8_t* __restrict__ codes,
@@ -73,8 +68,8 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
                                                        const float* __restrict__ mu,
                                                        uint8_t* __restrict__ codes_w, int Hkv, int Hq, int R,
                                                        int Lmax, int nchunk, int chunk, int nhb) {
-    constexpr int HB = 4 * NT;
-    __shared__ float4 lut[NT][kG * 16];
+    constexpr int HB = kHB;
+    __shared__ float4 lut[kG * 16];
     __shared__ float qs[HB][kD];
     __shared__ float bp[HB][2];
     __shared__ uint32_t lhist[HIST ? HB * kBins : 1];
@@ -168,20 +163,17 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         const int e = tid + half * kBlock;
         const int g = e >> 4;
         const float4 cj = half ? cj1 : cj0;
+        float o[4];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            float o[4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float* qq = &qs[4 * t + s][4 * g];
-                float a = qq[0] * cj.x;
-                a = fmaf(qq[1], cj.y, a);
-                a = fmaf(qq[2], cj.z, a);
-                a = fmaf(qq[3], cj.w, a);
-                o[s] = a;
-            }
-            lut[t][e] = make_float4(o[0], o[1], o[2], o[3]);
+        for (int s = 0; s < 4; ++s) {
+            const float* qq = &qs[s][4 * g];
+            float a = qq[0] * cj.x;
+            a = fmaf(qq[1], cj.y, a);
+            a = fmaf(qq[2], cj.z, a);
+            a = fmaf(qq[3], cj.w, a);
+            o[s] = a;
         }
+        lut[e] = make_float4(o[0], o[1], o[2], o[3]);
     }
     __syncthreads();
 
@@ -192,7 +184,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         if (tid < HB * 32) {
             const int s = tid >> 5, g = tid & 31;
             // entry j of group g, head s: lanes start at different j so that they hit different banks
-            const float* lf = reinterpret_cast<const float*>(&lut[s >> 2][g * 16]) + (s & 3);
+            const float* lf = reinterpret_cast<const float*>(&lut[g * 16]) + s;
             float sum = 0.0f, sq = 0.0f;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -240,7 +232,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
             const int tok = base + j * kBlock + tid;
             float acc[HB];
             if (tok == t_new) code[j] = *reinterpret_cast<const uint4*>(newcode);  // written before the barriers above
-            score_token<NT>(code[j], lut, acc);
+            score_token(code[j], lut, acc);
             if (tok < end) {
 #pragma unroll
                 for (int s = 0; s < HB; ++s) {
@@ -264,17 +256,10 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     SIK_TL(4);
 }
 
-// float4 tables per workgroup (4 query heads each).  One: a GQA group wider than 4 is served by several
-// head blocks that re-read the codes from L2; two tables in one workgroup were measured slower (256 VGPRs,
-// two wavefronts per SIMD: 65 us against 2 x 18 us on the 8:1 workload).
-static int score_tables(const Dims&) { return 1; }
-
 // Tokens per workgroup: about two workgroups per compute unit, at least 1024 tokens each (so that
 // the table build and the 2 KB histogram per head are amortised), at most kMaxChunks per head.
 void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
-    const int NT = score_tables(d);
-    const int HB = 4 * NT;
-    const int nhb = (d.R + HB - 1) / HB;
+    const int nhb = (d.R + kHB - 1) / kHB;
     const int units = d.units() * nhb;
     int want = (512 + units - 1) / units;
     if (want > kMaxChunks) want = kMaxChunks;
@@ -298,19 +283,14 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
                                  float* scores, hipStream_t s) {
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
-    const int NT = score_tables(d);
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
-#define SIK_SCORE(NTV, HV)                                                                                   \
-    score_kernel<DT, NTV, HV><<<grid, kBlock, 0, s>>>(                                                     \
+#define SIK_SCORE(HV)                                                                                        \
+    score_kernel<DT, HV><<<grid, kBlock, 0, s>>>(                                                     \
         qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
         w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
         d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
-    if (w) {
-        if (NT == 1) SIK_SCORE(1, true); else SIK_SCORE(2, true);
-    } else {
-        if (NT == 1) SIK_SCORE(1, false); else SIK_SCORE(2, false);
-    }
+    if (w) SIK_SCORE(true); else SIK_SCORE(false);
 #undef SIK_SCORE
     return hipGetLastError();
 }
