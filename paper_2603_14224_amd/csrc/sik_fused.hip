@@ -263,8 +263,10 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
 #pragma unroll
                     for (int e = 0; e < kWaveCand; ++e) {
                         if (static_cast<uint32_t>(e) < cn && base + e < static_cast<uint32_t>(kCandCap)) {
-                            l_cand[2 * (base + e)] = ent[2 * e];
-                            l_cand[2 * (base + e) + 1] = ent[2 * e + 1];
+                            // one 64-bit sort key per candidate: score key above, inverted index below, so
+                            // that "larger" means better score, then smaller index
+                            l_cand[2 * (base + e)] = ~ent[2 * e + 1];
+                            l_cand[2 * (base + e) + 1] = ent[2 * e];
                         }
                     }
                 }
@@ -283,23 +285,23 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
             const int P = n <= 64 ? 4 : (n <= 128 ? 2 : 1);
             const int slice = ((n + P - 1) / P + 7) & ~7;
             for (int j = tid; j < P * slice - n; j += kBlock) {
-                l_cand[2 * (n + j)] = 0u;
-                l_cand[2 * (n + j) + 1] = 0xffffffffu;
+                l_cand[2 * (n + j)] = 0u;  // padding: the smallest 64-bit key, outranks nothing
+                l_cand[2 * (n + j) + 1] = 0u;
             }
             for (int j = tid; j < n; j += kBlock) rank_of[j] = 0u;
             __syncthreads();
-            const uint2* lc2 = reinterpret_cast<const uint2*>(l_cand);
+            const unsigned long long* lc2 = reinterpret_cast<const unsigned long long*>(l_cand);
             const int per = kBlock / P;  // candidates handled per pass
             const int part = tid / per;
             for (int a = tid % per; a < n; a += per) {
-                const uint2 me = lc2[a];
+                const unsigned long long me = lc2[a];
                 uint32_t rank = 0;
                 for (int x = part * slice; x < (part + 1) * slice; x += 8) {
-                    uint2 o8[8];
+                    unsigned long long o8[8];
 #pragma unroll
                     for (int y = 0; y < 8; ++y) o8[y] = lc2[x + y];
 #pragma unroll
-                    for (int y = 0; y < 8; ++y) rank += (o8[y].x > me.x || (o8[y].x == me.x && o8[y].y < me.y)) ? 1u : 0u;
+                    for (int y = 0; y < 8; ++y) rank += o8[y] > me ? 1u : 0u;
                 }
                 if (P > 1) atomicAdd(&rank_of[a], rank); else rank_of[a] = rank;
             }
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
             for (int a = tid; a < n; a += kBlock) {
                 const int rank = static_cast<int>(rank_of[a]);
                 if (rank < need) {
-                    const int32_t ia = static_cast<int32_t>(lc2[a].y);
+                    const int32_t ia = static_cast<int32_t>(~static_cast<uint32_t>(lc2[a]));
                     chosen[rank] = ia;
                     if (idx_out) olist[cgt + rank] = ia;
                 }
