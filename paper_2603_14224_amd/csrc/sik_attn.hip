@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
 #pragma unroll 8
         for (int s2 = 0; s2 < nsplit; ++s2) {  // fixed order: the result does not depend on arrival order
             const float* pp = prow + static_cast<size_t>(s2) * kPartStride;
-            const float a = exp2f(ld_agent(&pp[0]) - Mg);
+            const float a = fast_exp2(ld_agent(&pp[0]) - Mg);
             lt += ld_agent(&pp[1]) * a;
             ot += ld_agent(&pp[2 + tid]) * a;
         }

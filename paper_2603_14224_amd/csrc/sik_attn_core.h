@@ -17,7 +17,7 @@ __device__ __forceinline__ void merge_from_lane(SoftmaxState& st, int xor_mask) 
     const float mo = __shfl_xor(st.m, xor_mask, 64);
     const float lo = __shfl_xor(st.l, xor_mask, 64);
     const float M = fmaxf(st.m, mo);
-    const float a = exp2f(st.m - M), b = exp2f(mo - M);
+    const float a = fast_exp2(st.m - M), b = fast_exp2(mo - M);
     st.l = st.l * a + lo * b;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -72,13 +72,13 @@ __device__ __forceinline__ void attend_list(Fetch fetch, int n, int first, int s
             z[u] = id[u] >= 0 ? dot : kNegBig;
         }
         const float mnew = fmaxf(fmaxf(st.m, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));
-        const float corr = exp2f(st.m - mnew);
+        const float corr = fast_exp2(st.m - mnew);
         st.l *= corr;
 #pragma unroll
         for (int e = 0; e < 8; ++e) st.acc[e] *= corr;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float pu = id[u] >= 0 ? exp2f(z[u] - mnew) : 0.0f;
+            const float pu = id[u] >= 0 ? fast_exp2(z[u] - mnew) : 0.0f;
             float vf[8];
             widen8<DT>(vv[u], vf);
             st.l += pu;
@@ -114,7 +114,7 @@ __device__ __forceinline__ void workgroup_merge(SoftmaxState& st, float* sm, flo
     for (int w = 0; w < kBlock / kWave; ++w) M = fmaxf(M, sm[w]);
 #pragma unroll
     for (int w = 0; w < kBlock / kWave; ++w) {
-        const float a = exp2f(sm[w] - M);
+        const float a = fast_exp2(sm[w] - M);
         Lsum += sl[w] * a;
         if (tid < kD) o += sacc[w][tid] * a;
     }

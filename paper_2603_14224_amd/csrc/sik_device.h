@@ -147,6 +147,11 @@ __device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, i
     } while (0)
 #endif
 
+// 2^x as the bare hardware instruction (1 ulp; results below the normal range flush to zero, which
+// is what a softmax weight that small should be; the library routine adds ~6 instructions of range
+// handling per call).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // Sum over the 16 lanes of a DPP row (lanes 16r .. 16r+15); every lane gets the total.  Four
 // rotate-within-row DPP moves feeding adds: no LDS traffic, unlike ds_bpermute-based shuffles.
 template <int N>

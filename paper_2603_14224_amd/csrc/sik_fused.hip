@@ -336,19 +336,19 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
         float Mg = M2;
 #pragma unroll 8
         for (int s2 = 0; s2 < nact; ++s2) Mg = fmaxf(Mg, pml[s2]);
-        const float a2 = exp2f(M2 - Mg);
+        const float a2 = fast_exp2(M2 - Mg);
         float lt = L2 * a2, ot = o2 * a2;
 #pragma unroll
         for (int s2 = 0; s2 < kOPre; ++s2) {  // fixed order: the result does not depend on arrival order
             if (s2 < nact) {
-                const float a = exp2f(pml[s2] - Mg);
+                const float a = fast_exp2(pml[s2] - Mg);
                 lt += pml[kMaxChunks + s2] * a;
                 ot += o_pre[s2] * a;
             }
         }
 #pragma unroll 8
         for (int s2 = kOPre; s2 < nact; ++s2) {
-            const float a = exp2f(pml[s2] - Mg);
+            const float a = fast_exp2(pml[s2] - Mg);
             lt += pml[kMaxChunks + s2] * a;
             ot += ld_agent(&prow[static_cast<size_t>(s2) * kPartStride + 2 + tid]) * a;
         }
