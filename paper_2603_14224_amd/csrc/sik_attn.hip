@@ -37,15 +37,12 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
     const uint4* Vp = reinterpret_cast<const uint4*>(V + unit * Lmax * kD);
     const int32_t* ip = idx + static_cast<size_t>(row) * k;
 
-    float qf[8];
-    widen8<DT>(reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p], qf);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) qf[e] *= scale_log2e;
+    const uint4 qraw = reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p];
 
     SoftmaxState st;
     init_state(st);
     const int j0 = sp * per, j1 = min(k, j0 + per);
-    attend_list<DT>([&](int j) { return ip[j0 + j]; }, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qf, Lmax, st);
+    attend_list<DT>([&](int j) { return ip[j0 + j]; }, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
     SIK_TL(17);
     float M, Lsum, o;
     workgroup_merge(st, sm, sl, sacc, M, Lsum, o);

@@ -147,6 +147,19 @@ __device__ __forceinline__ bool last_arriver(uint32_t* ticket, uint32_t total, i
     } while (0)
 #endif
 
+// c + a.lo * b.lo + a.hi * b.hi on two packed 16-bit values per register, fp32 accumulate: one
+// instruction (v_dot2c_f32_bf16 / v_dot2c_f32_f16) instead of two widenings and two FMAs.
+typedef __bf16 sik_bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 sik_f16x2 __attribute__((ext_vector_type(2)));
+template <int DT>
+__device__ __forceinline__ float dot2_acc(uint32_t a, uint32_t b, float c) {
+    if constexpr (DT == kBF16)
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(sik_bf16x2, a), __builtin_bit_cast(sik_bf16x2, b), c,
+                                               false);
+    else
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(sik_f16x2, a), __builtin_bit_cast(sik_f16x2, b), c, false);
+}
+
 // 2^x as the bare hardware instruction (1 ulp; results below the normal range flush to zero, which
 // is what a softmax weight that small should be; the library routine adds ~6 instructions of range
 // handling per call).

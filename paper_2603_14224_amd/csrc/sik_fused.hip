@@ -70,8 +70,6 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const uint4 qraw = reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p];
     const float lo = binp[row * 2], scale = binp[row * 2 + 1];
     const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hchunks);
-    float qf[8];
-    widen8<DT>(qraw, qf);
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const bool grew = appended && L < Lmax;  // the scoring launch stored and scored one more token
@@ -80,8 +78,6 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     if (c >= nact) return;  // no token of this chunk is valid; the ticket below counts nact workgroups
     const int end = min(L, start + kChunk);
     const int kk = min(k, L);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) qf[e] *= scale_log2e;
     if (tid == 0) {
         s_over = 0;
         s_ncand = 0u;
@@ -178,7 +174,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
                 for (int t = lane; t < n16; t += 64)
                     if (base + t < static_cast<uint32_t>(k)) idx_out[static_cast<size_t>(row) * k + base + t] = mylist[t];
             }
-            attend_list<DT>([&](int t) { return mylist[t]; }, n16, 0, 16, Kp, Vp, qf, Lmax, st);
+            attend_list<DT>([&](int t) { return mylist[t]; }, n16, 0, 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
             const int rem = n_sel - n16;
             const int keep = lane < rem ? mylist[n16 + lane] : 0;
             if (lane < rem) mylist[lane] = keep;
@@ -200,7 +196,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     SIK_TL(26);
 
     // ---- 4. attend over this wavefront's own tokens, publish the chunk's partial ---------------
-    attend_list<DT>([&](int j) { return mylist[j]; }, n_sel, 0, 16, Kp, Vp, qf, Lmax, st);
+    attend_list<DT>([&](int j) { return mylist[j]; }, n_sel, 0, 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
     SIK_TL(27);
     if (idx_out && n_sel > 0) {
         out_base = static_cast<uint32_t>(__shfl(static_cast<int>(out_base), 0, 64));
@@ -317,7 +313,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
             __syncthreads();
             SIK_TL_ANY(34);
             attend_list<DT>([&](int j) { return chosen[j]; }, min(need, n), wv * 16, (kBlock / kWave) * 16, Kp, Vp,
-                            qf, Lmax, st);
+                            qraw, scale_log2e, Lmax, st);
         } else {
             // exact fallback: radix select over the members of b* in the whole row of scores
             radix_select_in_bin(scores + static_cast<size_t>(row) * sstride, L, lo, scale, bstar, need,
@@ -325,7 +321,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
             __threadfence_block();
             __syncthreads();
             const int32_t* gl = olist + cgt;
-            attend_list<DT>([&](int j) { return gl[j]; }, need, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qf, Lmax,
+            attend_list<DT>([&](int j) { return gl[j]; }, need, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e, Lmax,
                             st);
         }
     }
