@@ -21,6 +21,10 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the dominant kernel, from the FETCH_SIZE and WRITE_SIZE counter runs whose summary is
+# profiles/decode_step_C2_32k.md (counter units x the factor a 256 MiB plain copy calibrates: 2 KiB and 1 KiB).
+# Counters cannot be read from inside this process, so workloads without such a committed run report null.
+MEASURED_TRAFFIC_BYTES = {("C2", "select_attend_kernel"): int(14234.9 * 2048 + 301.2 * 1024)}
 # event intervals of sik_decode_step_profiled, in launch order; the third one is empty when selection and
 # attention run fused in one launch (every benchmark workload)
 KERNELS = ("prep_kernel", "score_kernel", "select_kernel_unfused_only", "select_attend_kernel")
@@ -220,7 +224,8 @@ def main():
         "kernel_us_hip_events": {KERNELS[i]: round(float(kus[i]), 3) for i in range(4)},
         "hip_event_pair_overhead_us": round(float(raw[4]), 3),
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom_name)),
                      "algorithmic_bytes_per_launch": dom_bytes},
         "setup_seconds": round(gen_s, 1),
     }
