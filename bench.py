@@ -179,6 +179,35 @@ def main():
             sec_step, launch = sec_graph, "hipgraph"
     reset_lengths()
 
+    # ---- spread of the step time: events on the launch stream around groups of `grp` consecutive steps (a
+    # single step is shorter than the cost of an event pair); percentiles of the group means
+    grp = 2 * n_layers
+    n_grp = max(1, min(40, total_steps // grp))
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_grp)]
+    for gi, (e0, e1) in enumerate(ev):
+        e0.record()
+        for i in range(grp):
+            step(gi * grp + i)
+        e1.record()
+    torch.cuda.synchronize()
+    grp_us = np.sort(np.array([e0.elapsed_time(e1) for e0, e1 in ev]) * 1e3 / grp)
+    pct = {f"p{p}": round(float(np.percentile(grp_us, p)), 3) for p in (10, 50, 90)}
+    reset_lengths()
+
+    # ---- rows the gather really touches: query heads of one GQA group may select the same token
+    idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
+    st0 = layers[0]
+    sik.sik_decode_step(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None, st0["K"],
+                        st0["V"], st0["sl"], st0["mu"], st0["cb"], st0["codes"], k, 0.0, out, idx, ws)
+    torch.cuda.synchronize()
+    srt = idx.view(B * Hkv, -1).sort(dim=1).values
+    fresh = torch.ones_like(srt, dtype=torch.bool)
+    fresh[:, 1:] = srt[:, 1:] != srt[:, :-1]
+    rows_unique = int((fresh & (srt >= 0)).sum())
+    rows_nominal = int((idx >= 0).sum())
+    del idx, srt, fresh
+    reset_lengths()
+
     # ---- per-kernel durations, HIP events on the launch stream, same steps as the timed region
     # (each interval includes the cost of the event pair; an empty interval measured in the same call
     # is subtracted)
@@ -221,6 +250,8 @@ def main():
         "algorithmic_bytes_per_step": ab["total"],
         "us_per_step_stream_launch": round(sec_stream * 1e6, 3),
         "us_per_step_hipgraph": None if sec_graph is None else round(sec_graph * 1e6, 3),
+        "us_per_step_percentiles": dict(pct, groups=n_grp, steps_per_group=grp, launch="stream"),
+        "gathered_rows": {"nominal": rows_nominal, "unique_per_kv_head": rows_unique},
         "kernel_us_hip_events": {KERNELS[i]: round(float(kus[i]), 3) for i in range(4)},
         "hip_event_pair_overhead_us": round(float(raw[4]), 3),
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
@@ -263,8 +294,14 @@ def cpu_baseline(cfg, host0, budget_s):
         if t_total >= budget_s or n >= 64:
             break
     oracle.set_threads(1)
-    return {"value": round(t_total / n * 1e6, 1), "unit": "us/step", "cores": used, "kind": "oracle",
-            "sample": f"{n} whole decode step(s) of layer 0 of the same workload (fp64 oracle, OpenMP over batch x head)"}
+    res = {"value": round(t_total / n * 1e6, 1), "unit": "us/step", "cores": used, "kind": "oracle",
+           "sample": f"{n} whole decode step(s) of layer 0 of the same workload (fp64 oracle, OpenMP over batch x head)"}
+    if t_total / n * used <= budget_s:  # one more step on a single thread, when that fits the budget too
+        q, _, _ = W.make_step_inputs(cfg, n)
+        t = time.perf_counter()
+        oracle.decode_step(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+        res["single_thread_us_per_step"] = round((time.perf_counter() - t) * 1e6, 1)
+    return res
 
 
 if __name__ == "__main__":

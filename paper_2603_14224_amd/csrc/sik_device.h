@@ -67,10 +67,9 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
 // Histogram bin of a score: a non-decreasing function of s for fixed (lo, scale >= 0), so that
 // "bin above the threshold bin" implies "score above every score of the threshold bin".
 __device__ __forceinline__ int score_bin(float s, float lo, float scale) {
+    // clamp, then truncate: equal to floor-then-clamp for every x (negative x ends in bin 0 either way)
     const float x = (s - lo) * scale;
-    int b = static_cast<int>(floorf(x));
-    b = b < 0 ? 0 : b;
-    return b > kBins - 1 ? kBins - 1 : b;
+    return static_cast<int>(fminf(fmaxf(x, 0.0f), static_cast<float>(kBins - 1)));
 }
 
 // Agent-scope relaxed atomics on global memory.

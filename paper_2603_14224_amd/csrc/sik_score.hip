@@ -21,7 +21,7 @@ namespace sik {
 
 SIK_TL_DEFINE(sik_dbg_tl_score)
 
-constexpr int kTokPerIter = 4;  // tokens per lane per loop iteration
+constexpr int kIterTokens = 1024;  // tokens a workgroup scores per loop iteration: BLK threads x 1024 / BLK each
 
 constexpr int kHB = 4;  // query heads per workgroup = components of one float4 table entry
 
@@ -53,8 +53,8 @@ __device__ __forceinline__ void score_token(const uint4 code, const float4* lut,
     }
 }
 
-template <int DT, bool HIST>
-__global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restrict__ q,
+template <int DT, bool HIST, int BLK>
+__global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__ q,
                                                        const float* __restrict__ codebook,
                                                        const uint8_t* __restrict__ codes,
                                                        const int32_t* __restrict__ seq_len,
@@ -69,6 +69,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
                                                        uint8_t* __restrict__ codes_w, int Hkv, int Hq, int R,
                                                        int Lmax, int nchunk, int chunk, int nhb) {
     constexpr int HB = kHB;
+    constexpr int kTokPerIter = kIterTokens / BLK;
     __shared__ float4 lut[kG * 16];
     __shared__ float qs[HB][kD];
     __shared__ float bp[HB][2];
@@ -94,12 +95,17 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     uint4 cur[kTokPerIter];
 #pragma unroll
     for (int j = 0; j < kTokPerIter; ++j) {
-        const int i = start + j * kBlock + tid;
+        const int i = start + j * BLK + tid;
         cur[j] = i < cap_end ? cp[i] : make_uint4(0u, 0u, 0u, 0u);
     }
-    const float4 cj0 = reinterpret_cast<const float4*>(codebook)[static_cast<size_t>(unit) * kG * 16 + tid];
-    const float4 cj1 =
-        reinterpret_cast<const float4*>(codebook)[static_cast<size_t>(unit) * kG * 16 + tid + kBlock];
+    constexpr int kEntPerThread = kG * 16 / BLK < 1 ? 1 : kG * 16 / BLK;  // table entries (g, j) per thread
+    float4 cj[kEntPerThread];
+#pragma unroll
+    for (int x = 0; x < kEntPerThread; ++x) {
+        const int e = tid + x * BLK;
+        cj[x] = e < kG * 16 ? reinterpret_cast<const float4*>(codebook)[static_cast<size_t>(unit) * kG * 16 + e]
+                            : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     if (tid < HB * 16) {  // 16 lanes x 16 B per query row
         const int s = tid >> 4, p = tid & 15;
         float f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -108,7 +114,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
         for (int e = 0; e < 8; ++e) qs[s][8 * p + e] = f[e];
     }
     if constexpr (HIST) {
-        for (int e = tid; e < HB * kBins; e += kBlock) lhist[e] = 0u;
+        for (int e = tid; e < HB * kBins; e += BLK) lhist[e] = 0u;
         // the kernels that follow count on zeroed per-head counters; when no prep launch precedes,
         // chunk 0 of each head block clears those of its heads
         if (zero_counters && c == 0 && tid < nh * 8) zero_counters[row0 * 8 + tid] = 0u;
@@ -150,7 +156,8 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     }
     if (start >= L && c != 0) {  // no valid token here (chunk 0 always runs: it owns the per-head outputs)
         if constexpr (HIST)      // consumers read every chunk's histogram: publish an empty one
-            for (int s = 0; s < nh; ++s) parthist[((row0 + s) * nchunk + c) * kHistWords + tid] = 0u;
+            if (tid < kHistWords)
+                for (int s = 0; s < nh; ++s) parthist[((row0 + s) * nchunk + c) * kHistWords + tid] = 0u;
         return;
     }
     const int end = min(L, start + chunk);
@@ -159,21 +166,22 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
 
     // Table^(g)[j] for the HB query heads, fp32
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        const int e = tid + half * kBlock;
-        const int g = e >> 4;
-        const float4 cj = half ? cj1 : cj0;
-        float o[4];
+    for (int x = 0; x < kEntPerThread; ++x) {
+        const int e = tid + x * BLK;
+        if (e < kG * 16) {
+            const int g = e >> 4;
+            float o[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const float* qq = &qs[s][4 * g];
-            float a = qq[0] * cj.x;
-            a = fmaf(qq[1], cj.y, a);
-            a = fmaf(qq[2], cj.z, a);
-            a = fmaf(qq[3], cj.w, a);
-            o[s] = a;
+            for (int s = 0; s < 4; ++s) {
+                const float* qq = &qs[s][4 * g];
+                float a = qq[0] * cj[x].x;
+                a = fmaf(qq[1], cj[x].y, a);
+                a = fmaf(qq[2], cj[x].z, a);
+                a = fmaf(qq[3], cj[x].w, a);
+                o[s] = a;
+            }
+            lut[e] = make_float4(o[0], o[1], o[2], o[3]);
         }
-        lut[e] = make_float4(o[0], o[1], o[2], o[3]);
     }
     __syncthreads();
 
@@ -215,21 +223,21 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     }
 
     SIK_TL(2);
-    for (int base = start; base < end; base += kTokPerIter * kBlock) {
+    for (int base = start; base < end; base += kIterTokens) {
         uint4 code[kTokPerIter];
 #pragma unroll
         for (int j = 0; j < kTokPerIter; ++j) code[j] = cur[j];
-        const int nbase = base + kTokPerIter * kBlock;
+        const int nbase = base + kIterTokens;
         if (nbase < end) {
 #pragma unroll
             for (int j = 0; j < kTokPerIter; ++j) {
-                const int i = nbase + j * kBlock + tid;
+                const int i = nbase + j * BLK + tid;
                 if (i < end) cur[j] = cp[i];
             }
         }
 #pragma unroll
         for (int j = 0; j < kTokPerIter; ++j) {
-            const int tok = base + j * kBlock + tid;
+            const int tok = base + j * BLK + tid;
             float acc[HB];
             if (tok == t_new) code[j] = *reinterpret_cast<const uint4*>(newcode);  // written before the barriers above
             score_token(code[j], lut, acc);
@@ -250,22 +258,32 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const uint16_t* __restric
     SIK_TL(3);
     if constexpr (HIST) {
         __syncthreads();
-        for (int s = 0; s < nh; ++s)
-            publish_hist(&lhist[s * kBins], parthist + ((row0 + s) * nchunk + c) * kHistWords);
+        if (tid < kHistWords)
+            for (int s = 0; s < nh; ++s)
+                publish_hist(&lhist[s * kBins], parthist + ((row0 + s) * nchunk + c) * kHistWords);
     }
     SIK_TL(4);
 }
 
-// Tokens per workgroup: about two workgroups per compute unit, at least 1024 tokens each (so that
-// the table build and the 2 KB histogram per head are amortised), at most kMaxChunks per head.
+// Workgroup size.  Small launches (one sequence) are latency-bound: 512 threads = two wavefronts per SIMD share one
+// table build and interleave their LDS reads and adds (measured on 1 x 8 KV heads: 5.6 against 6.5 us at 32K,
+// 13.4 against 14.6 us at 128K).  Large launches are bound by LDS bandwidth either way and run a little faster
+// as twice as many 256-thread workgroups (38 against 41 us on 32 x 8 heads x 16K).
+static int score_block(const Dims& d, int nhb) {
+    return static_cast<int64_t>(d.units()) * nhb * d.Lmax <= (2 << 20) ? 512 : 256;
+}
+
+// Tokens per workgroup: about 2 x 256 or 1 x 512 threads per compute unit, whole loop iterations of 1024
+// tokens (so that the table build and the 2 KB histogram per head are amortised), at most kMaxChunks per head.
 void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
     const int nhb = (d.R + kHB - 1) / kHB;
     const int units = d.units() * nhb;
-    int want = (512 + units - 1) / units;
+    const int target = score_block(d, nhb) == 512 ? 256 : 512;
+    int want = (target + units - 1) / units;
     if (want > kMaxChunks) want = kMaxChunks;
     int ch = (d.Lmax + want - 1) / want;
-    ch = (ch + 1023) / 1024 * 1024;  // whole loop iterations of 4 tokens per lane
-    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += 1024;
+    ch = (ch + kIterTokens - 1) / kIterTokens * kIterTokens;
+    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += kIterTokens;
     *nhb_out = nhb;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
@@ -285,12 +303,14 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     score_plan(d, &nhb, &nchunk, &chunk);
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
-#define SIK_SCORE(HV)                                                                                        \
-    score_kernel<DT, HV><<<grid, kBlock, 0, s>>>(                                                     \
+#define SIK_SCORE(HV, BLKV)                                                                                  \
+    score_kernel<DT, HV, BLKV><<<grid, BLKV, 0, s>>>(                                                        \
         qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
         w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
         d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
-    if (w) SIK_SCORE(true); else SIK_SCORE(false);
+    const bool wide = score_block(d, nhb) == 512;
+    if (!w) { if (wide) SIK_SCORE(false, 512); else SIK_SCORE(false, 256); }
+    else { if (wide) SIK_SCORE(true, 512); else SIK_SCORE(true, 256); }
 #undef SIK_SCORE
     return hipGetLastError();
 }
