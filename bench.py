@@ -12,6 +12,7 @@ Prints ONE JSON line (see README / DESIGN for the fields).  One GPU only.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -145,7 +146,9 @@ def main():
         # one graph = `rounds` decode steps on every layer in turn.  With append, the graph first resets
         # the lengths (one small fill per layer, inside the timed region) so that every replay appends
         # the same `rounds` distinct rows at the same positions instead of piling up copies.
-        rounds = min(8, n_new - 1) if cfg.append else 1
+        # A graph covers every one of the n_q queries (each selects its own rows), so that replays do not
+        # find the rows they gather still in the Infinity Cache from the previous replay.
+        rounds = min(n_q, n_new - 1) if cfg.append else math.lcm(n_layers, n_q) // n_layers
         per_graph = n_layers * rounds
         reps = max(1, args.steps // per_graph)
 

@@ -13,8 +13,9 @@
 //      score keys; the partial softmax (m, l, o[D]) of the chunk is published;
 //   5. the last workgroup of the head to arrive ranks the candidates exactly by (score desc, index
 //      asc), attends over the k - c_gt best of them, merges all partials and writes the output row.
-// Degenerate score distributions (more than kCandCap tokens in b*, or more than kWaveCand candidates
-// in one wavefront's share) take an exact radix-select fallback in step 5.
+// A wavefront that finds more than kWaveCand candidates in its share puts the surplus into an overflow pool
+// of the head (one atomic reservation per round), which the last workgroup reads in a second round trip.
+// More than kCandCap tokens in b* (e.g. all scores equal) take an exact radix-select fallback in step 5.
 #include "sik_attn_core.h"
 #include "sik_device.h"
 #include "sik_internal.h"
@@ -26,13 +27,14 @@ SIK_TL_DEFINE(sik_dbg_tl_fused)
 
 // Candidate exchange area of one query head: regions = 4 * nchunk (one per chunk and wavefront);
 // word w of region r lives at cand_row[w * regions + r], so that the last workgroup, which reads one
-// region per lane, issues coalesced loads.  Word 0 = count, then (key, index) pairs.
+// region per lane, issues coalesced loads.  Word 0 = count (may exceed kWaveCand: the surplus is in the pool),
+// then (key, index) pairs.  The pool of a head follows the regions of all heads: kCandCap (key, index) pairs,
+// filled in the order of reservations on counter 4 of the head.
 constexpr int kWaveCand = 16;                      // candidate slots per wavefront and chunk
 constexpr int kCandWaveWords = 1 + 2 * kWaveCand;  // words per region
-constexpr uint32_t kCandOverflow = 0xffffffffu;
 
 template <int DT, int ODT, int NQ>  // NQ float4 of scores per lane: chunk = 1024 * NQ tokens
-__global__ __launch_bounds__(kBlock) void select_attend_kernel(
+__global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const float* __restrict__ scores, int sstride, int32_t* __restrict__ seq_len, int appended,
     const uint32_t* __restrict__ parthist, const float* __restrict__ binp, uint32_t* __restrict__ counters,
@@ -96,6 +98,8 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     const int regions = nchunk * (kBlock / kWave);
     uint32_t* crow = cand + static_cast<size_t>(row) * regions * kCandWaveWords;
     uint32_t* cw = crow + c * (kBlock / kWave) + wv;  // word w of this wavefront's region: cw[w * regions]
+    uint32_t* pool = cand + static_cast<size_t>(gridDim.x / nchunk) * regions * kCandWaveWords +
+                     static_cast<size_t>(row) * kCandCap * 2;
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     // bin(s) > b*  <=>  x >= b* + 1 and bin(s) == b*  <=>  b* <= x < b* + 1 with x = (s - lo) * scale,
     // the clamped end bins taking everything beyond them (score_bin is floor + clamp of the same x)
@@ -151,12 +155,25 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
             for (int e = 0; e < 4; ++e) v = bit == 4 * j + e ? v4[e] : v;
         }
         const int pos = n_cand + __popcll(bc & lt_mask);
+        const uint32_t tok = static_cast<uint32_t>(start + (((bit >> 2) * kBlock + tid) * 4 + (bit & 3)));
         if (has && pos < kWaveCand) {
             st_agent(&cw[(1 + 2 * pos) * regions], float_to_key(v));
-            st_agent(&cw[(2 + 2 * pos) * regions],
-                     static_cast<uint32_t>(start + (((bit >> 2) * kBlock + tid) * 4 + (bit & 3))));
+            st_agent(&cw[(2 + 2 * pos) * regions], tok);
         }
         n_cand += __popcll(bc);
+        if (n_cand > kWaveCand) {  // rare: the surplus of this round goes to the head's pool
+            const bool over = has && pos >= kWaveCand;
+            const uint64_t bo = __ballot(over);
+            const int leader = __ffsll(static_cast<unsigned long long>(bo)) - 1;
+            uint32_t base = 0u;
+            if (lane == leader) base = atomic_add_u32(&counters[row * 8 + 4], static_cast<uint32_t>(__popcll(bo)));
+            base = static_cast<uint32_t>(__shfl(static_cast<int>(base), leader, 64));
+            const uint32_t slot = base + static_cast<uint32_t>(__popcll(bo & lt_mask));
+            if (over && slot < static_cast<uint32_t>(kCandCap)) {
+                st_agent(&pool[2 * slot], float_to_key(v));
+                st_agent(&pool[2 * slot + 1], tok);
+            }
+        }
     }
     // Stage B: compaction of the marked scores into the wavefront's list, one mask bit per lane and
     // round (as many rounds as the busiest lane has selected scores); the list is gathered whenever
@@ -187,7 +204,7 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
         }
         n_sel += __popcll(bal);
     }
-    if (lane == 0) st_agent(&cw[0], n_cand > kWaveCand ? kCandOverflow : static_cast<uint32_t>(n_cand));
+    if (lane == 0) st_agent(&cw[0], static_cast<uint32_t>(n_cand));
     // optional index output: reserve this wave's slots now, write them after the gather
     uint32_t out_base = 0u;
     if (idx_out && n_sel > 0) {
@@ -219,11 +236,11 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     SIK_TL_ANY(29);
 
     // ---- 5. last workgroup of the head: candidates, merge, output ------------------------------
-    // All exchange loads go out together: the (m, l) pair of every chunk (thread c), the first 32
+    // All exchange loads go out together: the (m, l) pair of every chunk (thread c), the first 16
     // chunks' o[d] (thread d), and one candidate region per thread.
     const int need = kk - min(cgt, kk);
     int32_t* olist = (idx_out ? idx_out : idx_ws) + static_cast<size_t>(row) * k;
-    constexpr int kOPre = 32;
+    constexpr int kOPre = 16;
     float o_pre[kOPre];
     float pm = kNegBig, pl = 0.0f;
     if (tid < nact) {
@@ -251,25 +268,36 @@ __global__ __launch_bounds__(kBlock) void select_attend_kernel(
     if (need > 0) {
         bool use_radix = !ranked;
         if (ranked) {
-            if (tid < nact * 4) {
-                if (cn == kCandOverflow) {
-                    s_over = 1;
-                } else if (cn > 0u) {
-                    const uint32_t base = atomicAdd(&s_ncand, cn);
+            if (tid < nact * 4 && cn > 0u) {
+                if (cn > static_cast<uint32_t>(kWaveCand)) {
+                    s_over = 1;  // the rest of this wavefront's candidates is in the pool
+                    cn = kWaveCand;
+                }
+                const uint32_t base = atomicAdd(&s_ncand, cn);
 #pragma unroll
-                    for (int e = 0; e < kWaveCand; ++e) {
-                        if (static_cast<uint32_t>(e) < cn && base + e < static_cast<uint32_t>(kCandCap)) {
-                            // one 64-bit sort key per candidate: score key above, inverted index below, so
-                            // that "larger" means better score, then smaller index
-                            l_cand[2 * (base + e)] = ~ent[2 * e + 1];
-                            l_cand[2 * (base + e) + 1] = ent[2 * e];
-                        }
+                for (int e = 0; e < kWaveCand; ++e) {
+                    if (static_cast<uint32_t>(e) < cn && base + e < static_cast<uint32_t>(kCandCap)) {
+                        // one 64-bit sort key per candidate: score key above, inverted index below, so
+                        // that "larger" means better score, then smaller index
+                        l_cand[2 * (base + e)] = ~ent[2 * e + 1];
+                        l_cand[2 * (base + e) + 1] = ent[2 * e];
                     }
                 }
             }
             __syncthreads();
+            if (s_over != 0) {
+                const uint32_t np = min(ld_agent(&counters[row * 8 + 4]), static_cast<uint32_t>(kCandCap));
+                for (uint32_t j = tid; j < np; j += kBlock) {
+                    const uint32_t key = ld_agent(&pool[2 * j]), tok = ld_agent(&pool[2 * j + 1]);
+                    const uint32_t at = atomicAdd(&s_ncand, 1u);
+                    if (at < static_cast<uint32_t>(kCandCap)) {
+                        l_cand[2 * at] = ~tok;
+                        l_cand[2 * at + 1] = key;
+                    }
+                }
+                __syncthreads();
+            }
             SIK_TL_ANY(33);
-            use_radix = s_over != 0;
         }
         if (!use_radix) {
             const int n = min(static_cast<int>(s_ncand), kCandCap);
@@ -376,7 +404,8 @@ bool fused_plan(const Dims& d, int* nchunk, int* chunk) {
 size_t fused_cand_words(const Dims& d) {
     int nchunk, chunk;
     if (!fused_plan(d, &nchunk, &chunk)) return 0;
-    return static_cast<size_t>(d.rows()) * nchunk * (kBlock / kWave) * kCandWaveWords;
+    return static_cast<size_t>(d.rows()) * nchunk * (kBlock / kWave) * kCandWaveWords +
+           static_cast<size_t>(d.rows()) * kCandCap * 2;  // regions of every head, then the overflow pools
 }
 
 template <int DT, int ODT>

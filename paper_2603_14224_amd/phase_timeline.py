@@ -54,7 +54,9 @@ def main():
     cnt = torch.empty(B, Hkv, D // 4, 16, dtype=torch.int32, device="cuda")
     codes = torch.zeros(B, Hkv, L, D // 8, dtype=torch.uint8, device="cuda")
     sik.sik_quantize_keys(lay, K, sl, 0, 0, sik.SIK_Q_FIT, mu, cb, cnt, codes, ws)
-    q = torch.randn(B, Hq, D, device="cuda", generator=g).to(tdt)
+    # a different query every step: each selects its own rows, so a step does not find its rows in the caches
+    # because the previous step gathered the same ones
+    qs = [torch.randn(B, Hq, D, device="cuda", generator=g).to(tdt) for _ in range(8)]
     out = torch.empty(B, Hq, D, dtype=tdt, device="cuda")
     tl = torch.zeros(4 * SLOTS, dtype=torch.int64, device="cuda")
     lib = sik.lib()
@@ -64,7 +66,7 @@ def main():
     for r in range(reps + 3):
         tl.zero_()
         torch.cuda.synchronize()
-        sik.sik_decode_step(lay, q, None, None, K, V, sl, mu, cb, codes, k, 0.0, out, None, ws)
+        sik.sik_decode_step(lay, qs[r % len(qs)], None, None, K, V, sl, mu, cb, codes, k, 0.0, out, None, ws)
         torch.cuda.synchronize()
         t = tl.cpu().numpy().astype(np.int64).reshape(SLOTS, 4)
         if r < 3:
