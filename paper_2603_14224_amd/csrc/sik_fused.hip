@@ -236,11 +236,11 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     SIK_TL_ANY(29);
 
     // ---- 5. last workgroup of the head: candidates, merge, output ------------------------------
-    // All exchange loads go out together: the (m, l) pair of every chunk (thread c), the first 16
+    // All exchange loads go out together: the (m, l) pair of every chunk (thread c), the first 8
     // chunks' o[d] (thread d), and one candidate region per thread.
     const int need = kk - min(cgt, kk);
     int32_t* olist = (idx_out ? idx_out : idx_ws) + static_cast<size_t>(row) * k;
-    constexpr int kOPre = 16;
+    constexpr int kOPre = 8;
     float o_pre[kOPre];
     float pm = kNegBig, pl = 0.0f;
     if (tid < nact) {
