@@ -345,3 +345,222 @@ int sik_oracle_append_rows(uint16_t *K, uint16_t *V, const uint16_t *k_new, cons
     }
     return 0;
 }
+
+/* ==========================================================================
+ * 2-bit token-wise magnitude quantisation (section "Token-Wise Quantization
+ * Format") -- the compressed K/V form that sparse attention reads instead of
+ * the 16-bit rows.
+ *
+ * The integer codes are decided by floating-point arithmetic, so this part is
+ * written in binary32 with one fixed order of operations (the library must
+ * take the same decisions bit for bit); everything downstream of the codes
+ * (dequantisation, attention) is fp64 again.
+ *
+ * Per token, each run of 32 consecutive channels is one quantisation group
+ * with B = 2 bits:
+ *     zp = fp16(min x),  qs = fp16((max x - min x) / 3)       (stored, 16 bit)
+ *     Q(x) = clamp(round((x - zp) / qs), 0, 3), round = nearest, ties to even;
+ *            qs = 0 (constant group) gives Q = 0
+ *     D(x) = qs * Q(x) + zp
+ * with the STORED (fp16-rounded) qs and zp used on both sides of the format.
+ * For V, x is the value itself.  For K, x = |K'| / alpha with K' = K - mu
+ * (binary32 subtraction of the exactly widened key and the fp32 mean),
+ * alpha_d = max over the fitted tokens of |K'_d|, and alpha_d = 0 gives x = 0;
+ * the sign of K' is not quantised: it is the sign bit of the 1-bit code.
+ * The dequantised key is  s * alpha * D(x),  s = +1 where the code bit is 1.
+ * ========================================================================== */
+
+/* binary32 -> IEEE binary16 bits, round to nearest even, with subnormals and
+ * overflow to infinity. */
+static uint16_t float_to_fp16_bits(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t mag = u & 0x7fffffffu;
+    if (mag >= 0x7f800000u) return (uint16_t)(sign | (mag > 0x7f800000u ? 0x7e00u : 0x7c00u));
+    double a = fabs((double)f);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                  /* a = m * 2^e, 0.5 <= m < 1: a in [2^(e-1), 2^e) */
+    int ulp_exp = (e - 1 < -14 ? -14 : e - 1) - 10;  /* spacing of fp16 numbers around a */
+    double steps = nearbyint(ldexp(a, -ulp_exp));    /* default rounding mode: ties to even */
+    double r = ldexp(steps, ulp_exp);
+    if (r >= 65520.0) return (uint16_t)(sign | 0x7c00u);
+    if (r < ldexp(1.0, -14)) return (uint16_t)(sign | (uint16_t)steps); /* subnormal or zero */
+    int re;
+    double rm = frexp(r, &re);                       /* r = rm * 2^re */
+    uint16_t frac = (uint16_t)((rm * 2.0 - 1.0) * 1024.0);
+    return (uint16_t)(sign | ((uint16_t)(re - 1 + 15) << 10) | frac);
+}
+
+int sik_oracle_to_fp16(const float *x, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = float_to_fp16_bits(x[i]);
+    return 0;
+}
+
+/* ---- alpha_d = max_i |K'_{i,d}| over the tokens i < seq_len[b] ----------- */
+int sik_oracle_alpha(const uint16_t *K, int dtype, int B, int Hkv, int Lmax, int D,
+                     const int32_t *seq_len, const float *mu, float *alpha)
+{
+    if (bad_shape(B, Hkv, Lmax, D) || (dtype != 0 && dtype != 1)) return -1;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h) {
+            int64_t bh = (int64_t)b * Hkv + h;
+            const uint16_t *Kh = K + bh * Lmax * D;
+            for (int d = 0; d < D; ++d) {
+                float a = 0.0f;
+                for (int i = 0; i < seq_len[b]; ++i) {
+                    float kp = (float)widen(Kh[(int64_t)i * D + d], dtype) - mu[bh * D + d];
+                    if (fabsf(kp) > a) a = fabsf(kp);
+                }
+                alpha[bh * D + d] = a;
+            }
+        }
+    return 0;
+}
+
+/* One group of 32 values: stored parameters and 2-bit codes. */
+static void quantize_group(const float *x, uint16_t *param /* qs, zp */, uint8_t *code)
+{
+    float lo = x[0], hi = x[0];
+    for (int e = 1; e < 32; ++e) {
+        if (x[e] < lo) lo = x[e];
+        if (x[e] > hi) hi = x[e];
+    }
+    float span = hi - lo;
+    volatile float third = span / 3.0f;   /* one rounded binary32 division */
+    param[0] = float_to_fp16_bits(third);
+    param[1] = float_to_fp16_bits(lo);
+    float qs = (float)fp16_to_double(param[0]);
+    float zp = (float)fp16_to_double(param[1]);
+    for (int e = 0; e < 32; ++e) {
+        if (!(qs > 0.0f)) { code[e] = 0; continue; }
+        volatile float diff = x[e] - zp;
+        volatile float t = diff / qs;
+        float r = nearbyintf(t);
+        code[e] = (uint8_t)(r < 0.0f ? 0 : (r > 3.0f ? 3 : (int)r));
+    }
+}
+
+/* ---- quantise tokens [t0, t0+n) of every (b, h) --------------------------
+ * kq, vq   : [B, Hkv, Lmax, D] uint8, values 0..3
+ * kpar,vpar: [B, Hkv, Lmax, D/32, 2] uint16 = fp16 bits of (qs, zp)          */
+int sik_oracle_quantize_kv(const uint16_t *K, const uint16_t *V, int dtype, int B, int Hkv,
+                           int Lmax, int D, int t0, int n, const float *mu, const float *alpha,
+                           uint8_t *kq, uint16_t *kpar, uint8_t *vq, uint16_t *vpar)
+{
+    if (bad_shape(B, Hkv, Lmax, D) || D % 32 || (dtype != 0 && dtype != 1)) return -1;
+    if (t0 < 0 || n < 0 || t0 + n > Lmax) return -1;
+    int NG = D / 32;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < Hkv; ++h) {
+            int64_t bh = (int64_t)b * Hkv + h;
+            for (int i = t0; i < t0 + n; ++i) {
+                int64_t row = bh * Lmax + i;
+                for (int g = 0; g < NG; ++g) {
+                    float xk[32], xv[32];
+                    for (int e = 0; e < 32; ++e) {
+                        int d = 32 * g + e;
+                        volatile float kp = (float)widen(K[row * D + d], dtype) - mu[bh * D + d];
+                        float a = alpha[bh * D + d];
+                        volatile float khat = a > 0.0f ? fabsf(kp) / a : 0.0f;
+                        xk[e] = khat;
+                        xv[e] = (float)widen(V[row * D + d], dtype);
+                    }
+                    quantize_group(xk, kpar + (row * NG + g) * 2, kq + row * D + 32 * g);
+                    quantize_group(xv, vpar + (row * NG + g) * 2, vq + row * D + 32 * g);
+                }
+            }
+        }
+    return 0;
+}
+
+/* One token of one (b, h): Kd = s * alpha * (qs Q + zp), Vd = qs Q + zp, in fp64.
+ * code16: the token's 16 sign bytes; kq/vq: its D 2-bit codes; kpar/vpar: its D/32 (qs, zp) pairs. */
+static void dequant_row(const uint8_t *code16, const uint8_t *kq, const uint16_t *kpar,
+                        const uint8_t *vq, const uint16_t *vpar, const float *alpha, int D,
+                        double *Kd, double *Vd)
+{
+    for (int d = 0; d < D; ++d) {
+        int g = d / 32;
+        double kqs = fp16_to_double(kpar[2 * g]), kzp = fp16_to_double(kpar[2 * g + 1]);
+        double vqs = fp16_to_double(vpar[2 * g]), vzp = fp16_to_double(vpar[2 * g + 1]);
+        int bit = (code16[d / 8] >> (7 - d % 8)) & 1;
+        double mag = (double)alpha[d] * (kqs * (double)kq[d] + kzp);
+        Kd[d] = bit ? mag : -mag;
+        Vd[d] = vqs * (double)vq[d] + vzp;
+    }
+}
+
+/* ---- dequantise tokens [t0, t0+n) of every (b, h) (for tests) ------------ */
+int sik_oracle_dequant_kv(const uint8_t *codes, const uint8_t *kq, const uint16_t *kpar,
+                          const uint8_t *vq, const uint16_t *vpar, const float *alpha, int B,
+                          int Hkv, int Lmax, int D, int t0, int n, double *Kd, double *Vd)
+{
+    if (bad_shape(B, Hkv, Lmax, D) || D % 32) return -1;
+    if (t0 < 0 || n < 0 || t0 + n > Lmax) return -1;
+    int NG = D / 32;
+    for (int64_t bh = 0; bh < (int64_t)B * Hkv; ++bh)
+        for (int i = t0; i < t0 + n; ++i) {
+            int64_t row = bh * Lmax + i;
+            dequant_row(codes + row * (D / 8), kq + row * D, kpar + row * NG * 2, vq + row * D,
+                        vpar + row * NG * 2, alpha + bh * D, D, Kd + row * D, Vd + row * D);
+        }
+    return 0;
+}
+
+/* ---- sparse attention over the dequantised rows --------------------------
+ * Same softmax as sik_oracle_sparse_attn; the key is the centred K' (the
+ * dropped q . mu is one constant per query and cancels in the softmax). */
+int sik_oracle_sparse_attn_q2(const uint16_t *q, int dtype, const uint8_t *codes, const uint8_t *kq,
+                              const uint16_t *kpar, const uint8_t *vq, const uint16_t *vpar,
+                              const float *alpha, int B, int Hkv, int Hq, int Lmax, int D,
+                              const int32_t *idx, int k, double scale, double *out)
+{
+    if (bad_shape(B, Hkv, Lmax, D) || D % 32 || Hq < 1 || Hq % Hkv || k < 1) return -1;
+    if (dtype != 0 && dtype != 1) return -1;
+    int R = Hq / Hkv, NG = D / 32;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)D);
+    int fail = 0;
+#pragma omp parallel for collapse(2) num_threads(g_threads)
+    for (int b = 0; b < B; ++b)
+        for (int hq = 0; hq < Hq; ++hq) {
+            int64_t bh = (int64_t)b * Hkv + hq / R;
+            const uint16_t *qh = q + ((int64_t)b * Hq + hq) * D;
+            const int32_t *S = idx + ((int64_t)b * Hq + hq) * k;
+            double *o = out + ((int64_t)b * Hq + hq) * D;
+            double *z = (double *)malloc(sizeof(double) * (size_t)k);
+            double *kd = (double *)malloc(sizeof(double) * (size_t)D * 2);
+            if (!z || !kd) { fail = 1; free(z); free(kd); continue; }
+            double *vd = kd + D;
+            double zmax = -INFINITY;
+            for (int pass = 0; pass < 2; ++pass) {   /* pass 0: logits and their maximum; pass 1: weighted sum */
+                double denom = 0.0;
+                if (pass == 1)
+                    for (int d = 0; d < D; ++d) o[d] = 0.0;
+                for (int r = 0; r < k; ++r) {
+                    if (S[r] < 0 || S[r] >= Lmax) { z[r] = -INFINITY; continue; }
+                    int64_t row = bh * Lmax + S[r];
+                    dequant_row(codes + row * (D / 8), kq + row * D, kpar + row * NG * 2, vq + row * D,
+                                vpar + row * NG * 2, alpha + bh * D, D, kd, vd);
+                    if (pass == 0) {
+                        double dot = 0.0;
+                        for (int d = 0; d < D; ++d) dot += widen(qh[d], dtype) * kd[d];
+                        z[r] = dot * scale;
+                        if (z[r] > zmax) zmax = z[r];
+                    } else {
+                        double p = exp(z[r] - zmax);
+                        denom += p;
+                        for (int d = 0; d < D; ++d) o[d] += p * vd[d];
+                    }
+                }
+                if (pass == 1 && denom > 0.0)
+                    for (int d = 0; d < D; ++d) o[d] /= denom;
+            }
+            free(z);
+            free(kd);
+        }
+    return fail ? -1 : 0;
+}

@@ -166,3 +166,154 @@ def decode_step(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, k, scale=0
     idx = topk(s, seq_len, k)
     out = sparse_attn(q, K, V, dtype, idx, scale)
     return out, idx
+
+
+# --------------------------------------------------------------------------- 2-bit token-wise K/V format
+def to_fp16(x):
+    """binary32 -> IEEE binary16 bit patterns (round to nearest even), the oracle's own conversion."""
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, np.uint16)
+    rc = lib().sik_oracle_to_fp16(_p(x), ctypes.c_int64(x.size), _p(out))
+    assert rc == 0
+    return out
+
+
+def alpha(K, dtype, seq_len, mu):
+    """Per-channel max |K - mu| over the tokens below seq_len: [B, Hkv, D] fp32."""
+    K = _c(K, np.uint16)
+    B, Hkv, Lmax, D = K.shape
+    sl = _c(seq_len, np.int32)
+    mu = _c(mu, np.float32)
+    a = np.empty((B, Hkv, D), np.float32)
+    rc = lib().sik_oracle_alpha(_p(K), _DT[dtype], B, Hkv, Lmax, D, _p(sl), _p(mu), _p(a))
+    assert rc == 0
+    return a
+
+
+class QuantKV:
+    """Logical fields of the 2-bit format: kq, vq [B,Hkv,Lmax,D] uint8 in 0..3; kpar, vpar
+    [B,Hkv,Lmax,D/32,2] uint16 = fp16 bits of (qs, zp)."""
+
+    def __init__(self, B, Hkv, Lmax, D):
+        self.kq = np.zeros((B, Hkv, Lmax, D), np.uint8)
+        self.vq = np.zeros((B, Hkv, Lmax, D), np.uint8)
+        self.kpar = np.zeros((B, Hkv, Lmax, D // 32, 2), np.uint16)
+        self.vpar = np.zeros((B, Hkv, Lmax, D // 32, 2), np.uint16)
+
+
+def quantize_kv(K, V, dtype, mu, alpha_, t0, n, qkv=None):
+    """Quantise tokens [t0, t0+n) of every (b, h) in place in qkv (created when None)."""
+    K = _c(K, np.uint16)
+    V = _c(V, np.uint16)
+    B, Hkv, Lmax, D = K.shape
+    if qkv is None:
+        qkv = QuantKV(B, Hkv, Lmax, D)
+    mu = _c(mu, np.float32)
+    al = _c(alpha_, np.float32)
+    rc = lib().sik_oracle_quantize_kv(_p(K), _p(V), _DT[dtype], B, Hkv, Lmax, D, int(t0), int(n), _p(mu), _p(al),
+                                      _p(qkv.kq), _p(qkv.kpar), _p(qkv.vq), _p(qkv.vpar))
+    assert rc == 0
+    return qkv
+
+
+def dequant_kv(codes, qkv, alpha_, t0, n):
+    """fp64 (K', V) reconstructed from the fields for tokens [t0, t0+n); other rows are zero."""
+    codes = _c(codes, np.uint8)
+    B, Hkv, Lmax, D = qkv.kq.shape
+    al = _c(alpha_, np.float32)
+    Kd = np.zeros((B, Hkv, Lmax, D), np.float64)
+    Vd = np.zeros((B, Hkv, Lmax, D), np.float64)
+    rc = lib().sik_oracle_dequant_kv(_p(codes), _p(qkv.kq), _p(qkv.kpar), _p(qkv.vq), _p(qkv.vpar), _p(al), B, Hkv,
+                                     Lmax, D, int(t0), int(n), _p(Kd), _p(Vd))
+    assert rc == 0
+    return Kd, Vd
+
+
+def sparse_attn_q2(q, dtype, codes, qkv, alpha_, idx, scale=0.0):
+    q = _c(q, np.uint16)
+    codes = _c(codes, np.uint8)
+    idx = _c(idx, np.int32)
+    B, Hkv, Lmax, D = qkv.kq.shape
+    Hq, k = q.shape[1], idx.shape[2]
+    al = _c(alpha_, np.float32)
+    out = np.empty((B, Hq, D), np.float64)
+    rc = lib().sik_oracle_sparse_attn_q2(_p(q), _DT[dtype], _p(codes), _p(qkv.kq), _p(qkv.kpar), _p(qkv.vq),
+                                         _p(qkv.vpar), _p(al), B, Hkv, Hq, Lmax, D, _p(idx), k,
+                                         ctypes.c_double(float(scale)), _p(out))
+    assert rc == 0
+    return out
+
+
+def pack_records(codes, qkv):
+    """The 128-byte per-token record of the library's 2-bit format, built from the fields: 16 slots of 8
+    bytes, slot p covering channels 8p..8p+7: byte 0 = sign byte p of the 1-bit code, byte 1 = 0, bytes 2-3 =
+    K codes (little-endian, code of channel 8p+e in bits 2e+1:2e), bytes 4-5 = V codes likewise, bytes 6-7 =
+    one fp16 parameter of 32-channel group p/4: K qs, K zp, V qs, V zp for p mod 4 = 0, 1, 2, 3."""
+    B, Hkv, Lmax, D = qkv.kq.shape
+    assert D == 128
+    rec = np.zeros((B, Hkv, Lmax, 16, 8), np.uint8)
+    rec[..., 0] = codes
+    sh = (2 * np.arange(8)).astype(np.uint16)
+    kw = (qkv.kq.reshape(B, Hkv, Lmax, 16, 8).astype(np.uint16) << sh).sum(axis=-1).astype(np.uint16)
+    vw = (qkv.vq.reshape(B, Hkv, Lmax, 16, 8).astype(np.uint16) << sh).sum(axis=-1).astype(np.uint16)
+    par = np.concatenate([qkv.kpar, qkv.vpar], axis=-1).reshape(B, Hkv, Lmax, 16)  # group-major: Kqs Kzp Vqs Vzp
+    for word, at in ((kw, 2), (vw, 4), (par, 6)):
+        rec[..., at] = (word & 0xff).astype(np.uint8)
+        rec[..., at + 1] = (word >> 8).astype(np.uint8)
+    return rec.reshape(B, Hkv, Lmax, 128)
+
+
+def unpack_records(rec):
+    """Inverse of pack_records: (codes, QuantKV) from [B,Hkv,Lmax,128] uint8 records."""
+    rec = np.ascontiguousarray(rec, np.uint8)
+    B, Hkv, Lmax, _ = rec.shape
+    r = rec.reshape(B, Hkv, Lmax, 16, 8)
+    codes = r[..., 0].copy()
+    out = QuantKV(B, Hkv, Lmax, 128)
+    sh = (2 * np.arange(8)).astype(np.uint16)
+    kw = r[..., 2].astype(np.uint16) | (r[..., 3].astype(np.uint16) << 8)
+    vw = r[..., 4].astype(np.uint16) | (r[..., 5].astype(np.uint16) << 8)
+    out.kq = ((kw[..., None] >> sh) & 3).astype(np.uint8).reshape(B, Hkv, Lmax, 128)
+    out.vq = ((vw[..., None] >> sh) & 3).astype(np.uint8).reshape(B, Hkv, Lmax, 128)
+    par = (r[..., 6].astype(np.uint16) | (r[..., 7].astype(np.uint16) << 8)).reshape(B, Hkv, Lmax, 4, 4)
+    out.kpar = np.ascontiguousarray(par[..., 0:2])
+    out.vpar = np.ascontiguousarray(par[..., 2:4])
+    return codes, out
+
+
+def fit_q2(K, V, dtype, seq_len, mu):
+    """Prefill-side 2-bit quantiser: alpha from the fitted tokens, then their fields."""
+    K = _c(K, np.uint16)
+    B = K.shape[0]
+    sl = _c(seq_len, np.int32)
+    al = alpha(K, dtype, sl, mu)
+    qkv = None
+    for b in range(B):
+        part = quantize_kv(K[b:b + 1], V[b:b + 1], dtype, mu[b:b + 1], al[b:b + 1], 0, int(sl[b]))
+        if qkv is None:
+            qkv = QuantKV(*K.shape)
+        for f in ("kq", "vq", "kpar", "vpar"):
+            getattr(qkv, f)[b] = getattr(part, f)[0]
+    return al, qkv
+
+
+def decode_step_q2(q, k_new, v_new, dtype, seq_len, mu, alpha_, cb, codes, qkv, k, scale=0.0):
+    """One decode step on the 2-bit cache.  With k_new/v_new [B,Hkv,D] given, the new token is encoded
+    (sign code against the frozen mu, magnitudes against the frozen alpha) into row seq_len[b] in place and
+    seq_len grows by one.  Returns (out fp64, idx)."""
+    B, Hkv, Lmax, D = qkv.kq.shape
+    if k_new is not None:
+        kn = _c(k_new, np.uint16).reshape(B, Hkv, 1, D)
+        vn = _c(v_new, np.uint16).reshape(B, Hkv, 1, D)
+        for b in range(B):
+            t = int(seq_len[b])
+            assert t < Lmax
+            codes[b, :, t] = encode(kn[b:b + 1], dtype, mu[b:b + 1], 0, 1)[0, :, 0]
+            one = quantize_kv(kn[b:b + 1], vn[b:b + 1], dtype, mu[b:b + 1], alpha_[b:b + 1], 0, 1)
+            for f in ("kq", "vq", "kpar", "vpar"):
+                getattr(qkv, f)[b, :, t] = getattr(one, f)[0, :, 0]
+        seq_len += 1
+    s = score(q, dtype, cb, codes, seq_len)
+    idx = topk(s, seq_len, k)
+    out = sparse_attn_q2(q, dtype, codes, qkv, alpha_, idx, scale)
+    return out, idx

@@ -372,3 +372,177 @@ def test_retrieval_quality_sanity(oracle):
         exact = set(np.argsort(-(Kd[0, hq // 4] @ qd[0, hq]))[:128])
         rec.append(len(exact & set(idx[0, hq])) / 128)
     assert np.mean(rec) > 10 * 128 / 4096
+
+
+# =========================================================================== 2-bit token-wise K/V format
+def q2_cfg(**kw):
+    base = dict(batch=2, n_kv_heads=2, n_q_heads=4, head_dim=128, context=150, top_k=20, dtype="bf16",
+                sigma="lognormal", outlier_frac=0.05, outlier_scale=8.0, seed=21)
+    base.update(kw)
+    return W.scaled(W.CONFIGS["C2"], **base)
+
+
+def test_fp16_conversion_matches_numpy(oracle):
+    rng = np.random.default_rng(3)
+    x = np.concatenate([
+        rng.normal(0, 1, 4000), rng.normal(0, 1e-5, 2000), rng.normal(0, 3e4, 2000),
+        np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e6, -1e6, 6.103515625e-05, 6.0975552e-05,
+                  5.9604645e-08, 2.9802322e-08, 2.98023224e-08 * 1.0001, 8.940697e-08, 1.0009765625,
+                  1.00048828125, 1.00146484375, np.inf, -np.inf])]).astype(np.float32)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    assert np.array_equal(oracle.to_fp16(x), want)
+
+
+def test_two_bit_groups_worked_by_hand(oracle):
+    rows = [l for l in open(os.path.join(GOLDEN, "eq9_two_bit_groups.txt")) if l[0] not in "#\n"]
+    assert len(rows) == 6
+    for line in rows:
+        vals, par, codes = [np.array(p.split(), np.float64) for p in line.split("|")]
+        V = np.tile(vals, 16).astype(np.float32).reshape(1, 1, 1, 128)     # 4 groups of 32, all alike
+        Kz = np.zeros((1, 1, 1, 128), np.uint16)
+        qkv = oracle.quantize_kv(Kz, bits_of(V, "fp16"), "fp16", np.zeros((1, 1, 128), np.float32),
+                                 np.ones((1, 1, 128), np.float32), 0, 1)
+        assert np.array_equal(qkv.vq[0, 0, 0], np.tile(codes, 16).astype(np.uint8)), line
+        got = oracle.widen(qkv.vpar[0, 0, 0], "fp16")
+        assert np.array_equal(got, np.tile(par, (4, 1))), line
+        # an all-zero key: zero magnitudes, zero parameters
+        assert not qkv.kq.any() and not qkv.kpar.any()
+
+
+def test_two_bit_memory_model_matches_overhead_analysis(oracle):
+    row = [l.split() for l in open(os.path.join(GOLDEN, "memory_model.txt")) if l.startswith("q2")][0]
+    sign, val, par, fp16_bits, saving = map(int, row[1:])
+    cfg = q2_cfg(batch=1, n_kv_heads=1, context=10)
+    qkv = oracle.QuantKV(1, 1, 10, 128)
+    # the fields hold exactly the paper's bit counts per token: 2 bits per code, 16 bits per parameter
+    assert 2 * (qkv.kq[0, 0, 0].size + qkv.vq[0, 0, 0].size) == val
+    assert 16 * (qkv.kpar[0, 0, 0].size + qkv.vpar[0, 0, 0].size) == par
+    assert sign == cfg.head_dim and fp16_bits == 2 * 16 * cfg.head_dim
+    assert round(100 * (1 - (sign + val + par) / fp16_bits)) == saving
+    # the library's record keeps one token in one 128-byte line: the 896 bits plus 16 spare bytes
+    rec = oracle.pack_records(np.zeros((1, 1, 10, 16), np.uint8), qkv)
+    assert rec.shape[-1] == 128 and (sign + val + par) // 8 + 16 == 128
+
+
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_alpha_and_two_bit_quantiser_against_numpy(oracle, dtype):
+    cfg = q2_cfg(dtype=dtype)
+    K, V = W.make_cache(cfg, channel_offset_std=1.5)
+    sl = np.array([150, 97], np.int32)
+    mu, codes, _, _ = oracle.fit(K, dtype, sl)
+    al, qkv = oracle.fit_q2(K, V, dtype, sl, mu)
+    K32, V32 = W.from_bits(K, dtype).astype(np.float32), W.from_bits(V, dtype).astype(np.float32)
+    for b in range(2):
+        L = int(sl[b])
+        Kp = K32[b, :, :L] - mu[b, :, None, :]                      # binary32 subtraction
+        assert np.array_equal(al[b], np.abs(Kp).max(axis=1))
+        khat = np.abs(Kp) / al[b, :, None, :]
+        for x, q, par in ((khat, qkv.kq, qkv.kpar), (V32[b, :, :L], qkv.vq, qkv.vpar)):
+            g = x.reshape(x.shape[0], L, 4, 32)
+            lo, hi = g.min(-1), g.max(-1)
+            zp16 = lo.astype(np.float16)
+            qs16 = ((hi - lo) / np.float32(3)).astype(np.float16)
+            assert np.array_equal(par[b, :, :L, :, 0], qs16.view(np.uint16))
+            assert np.array_equal(par[b, :, :L, :, 1], zp16.view(np.uint16))
+            qs, zp = qs16.astype(np.float32)[..., None], zp16.astype(np.float32)[..., None]
+            with np.errstate(divide="ignore", invalid="ignore"):
+                want = np.where(qs > 0, np.clip(np.rint((g - zp) / qs), 0, 3), 0).astype(np.uint8)
+            assert np.array_equal(q[b, :, :L].reshape(g.shape), want)
+        assert not qkv.kq[b, :, L:].any() and not qkv.vpar[b, :, L:].any()   # untouched beyond seq_len
+
+
+def test_two_bit_reconstruction_error_bound_and_signs(oracle):
+    cfg = q2_cfg(batch=1, context=300)
+    K, V = W.make_cache(cfg, channel_offset_std=1.0)
+    sl = np.array([300], np.int32)
+    mu, codes, _, _ = oracle.fit(K, cfg.dtype, sl)
+    al, qkv = oracle.fit_q2(K, V, cfg.dtype, sl, mu)
+    Kd, Vd = oracle.dequant_kv(codes, qkv, al, 0, 300)
+    Kp = (W.from_bits(K, cfg.dtype).astype(np.float32) - mu[:, :, None, :]).astype(np.float64)
+    Vf = f64(V, cfg.dtype)
+    # codes reach both ends of every non-constant group
+    vg = qkv.vq.reshape(1, 2, 300, 4, 32)
+    nonconst = oracle.widen(qkv.vpar[..., 0], "fp16") > 0
+    assert np.all(vg.min(-1)[nonconst] == 0) and np.all(vg.max(-1)[nonconst] == 3)
+    # |x - D(Q(x))| <= qs / 2 plus what rounding qs and zp to 16 bits can add (3 |dqs| + |dzp|)
+    vqs = oracle.widen(qkv.vpar[..., 0], "fp16")[..., None]
+    span = Vf.reshape(1, 2, 300, 4, 32)
+    slack = 4 * 2.0 ** -11 * np.abs(span).max(-1, keepdims=True) + 3 * 2.0 ** -11 * vqs
+    assert np.all(np.abs(span - Vd.reshape(span.shape)) <= vqs / 2 + slack)
+    kqs = oracle.widen(qkv.kpar[..., 0], "fp16")[..., None]
+    a = al.astype(np.float64)[:, :, None, :].reshape(1, 2, 1, 4, 32)
+    kerr = np.abs(np.abs(Kp) - np.abs(Kd)).reshape(1, 2, 300, 4, 32)
+    assert np.all(kerr <= a * (kqs / 2 + 8 * 2.0 ** -11))
+    # the sign of the reconstruction is the code bit, and the code bit is the sign of K - mu
+    bits = np.unpackbits(codes, axis=-1, bitorder="big").astype(bool)
+    assert np.all((Kd >= 0) | ~bits) and np.all((Kd <= 0) | bits)
+    assert np.all(np.abs(Kd) <= a.reshape(1, 2, 1, 128) * (1 + 2.0 ** -9))
+
+
+def test_two_bit_record_round_trip_and_layout(oracle):
+    rng = np.random.default_rng(8)
+    qkv = oracle.QuantKV(1, 2, 5, 128)
+    qkv.kq[:] = rng.integers(0, 4, qkv.kq.shape)
+    qkv.vq[:] = rng.integers(0, 4, qkv.vq.shape)
+    qkv.kpar[:] = rng.integers(0, 2 ** 16, qkv.kpar.shape)
+    qkv.vpar[:] = rng.integers(0, 2 ** 16, qkv.vpar.shape)
+    codes = rng.integers(0, 256, (1, 2, 5, 16)).astype(np.uint8)
+    rec = oracle.pack_records(codes, qkv)
+    c2, back = oracle.unpack_records(rec)
+    assert np.array_equal(c2, codes)
+    for f in ("kq", "vq", "kpar", "vpar"):
+        assert np.array_equal(getattr(back, f), getattr(qkv, f))
+    # spot-check the layout by hand: slot 5 of token 3 of head 1 covers channels 40..47, group 1
+    slot = rec[0, 1, 3, 40:48]
+    assert slot[0] == codes[0, 1, 3, 5] and slot[1] == 0
+    assert (int(slot[2]) | int(slot[3]) << 8) == sum(int(qkv.kq[0, 1, 3, 40 + e]) << (2 * e) for e in range(8))
+    assert (int(slot[4]) | int(slot[5]) << 8) == sum(int(qkv.vq[0, 1, 3, 40 + e]) << (2 * e) for e in range(8))
+    assert (int(slot[6]) | int(slot[7]) << 8) == int(qkv.kpar[0, 1, 3, 1, 1])       # slot 5 = group 1, K zp
+
+
+def test_two_bit_attention_all_tokens_equals_dense_on_reconstruction(oracle):
+    cfg = q2_cfg(batch=1, n_kv_heads=2, n_q_heads=4, context=90)
+    K, V = W.make_cache(cfg, channel_offset_std=0.5)
+    sl = np.array([90], np.int32)
+    mu, codes, _, _ = oracle.fit(K, cfg.dtype, sl)
+    al, qkv = oracle.fit_q2(K, V, cfg.dtype, sl, mu)
+    Kd, Vd = oracle.dequant_kv(codes, qkv, al, 0, 90)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    qf = f64(q, cfg.dtype)
+    idx = np.tile(np.arange(90, dtype=np.int32), (1, 4, 1))
+    out = oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, al, idx)
+    for hq in range(4):
+        want = dense_attention(qf[0, hq], Kd[0, hq // 2], Vd[0, hq // 2], 1 / np.sqrt(128))
+        assert np.allclose(out[0, hq], want, rtol=1e-12, atol=1e-13)
+    # one selected token: the output is that token's reconstructed value row; -1 entries are skipped
+    one = np.full((1, 4, 3), -1, np.int32)
+    one[:, :, 1] = 17
+    out1 = oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, al, one)
+    for hq in range(4):
+        assert np.array_equal(out1[0, hq], Vd[0, hq // 2, 17])
+    # a permutation of the selection changes nothing beyond rounding
+    perm = np.random.default_rng(2).permutation(90).astype(np.int32)
+    outp = oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, al, np.tile(perm, (1, 4, 1)))
+    assert np.allclose(outp, out, rtol=1e-12, atol=1e-13)
+
+
+def test_two_bit_decode_step_appends_against_frozen_parameters(oracle):
+    cfg = q2_cfg(batch=2, context=64, top_k=12)
+    K, V = W.make_cache(cfg, capacity=70, channel_offset_std=1.0)
+    sl = np.array([64, 40], np.int32)
+    mu, codes, cb, _ = oracle.fit(K, cfg.dtype, sl)
+    al, qkv = oracle.fit_q2(K, V, cfg.dtype, sl, mu)
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    al0 = al.copy()
+    out, idx = oracle.decode_step_q2(q, kn, vn, cfg.dtype, sl, mu, al, cb, codes, qkv, 12)
+    assert sl.tolist() == [65, 41] and np.array_equal(al, al0)
+    for b, t in ((0, 64), (1, 40)):
+        want_bits = f64(kn[b], cfg.dtype) >= mu[b].astype(np.float64)
+        assert np.array_equal(np.unpackbits(codes[b, :, t], axis=-1, bitorder="big").astype(bool), want_bits)
+        # the new value row obeys the same group rule as a fitted one
+        v32 = W.from_bits(vn[b], cfg.dtype).astype(np.float32).reshape(2, 4, 32)
+        assert np.array_equal(qkv.vpar[b, :, t, :, 1], v32.min(-1).astype(np.float16).view(np.uint16))
+    assert out.shape == (2, 4, 128) and np.all(idx[1] < 41) and np.all(idx[0] < 65)
+    ref = oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, al, idx)
+    assert np.array_equal(ref, out)
