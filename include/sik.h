@@ -154,6 +154,49 @@ int sik_decode_step_profiled(const sik_layout *layout, const void *q, const void
                              void *out, int32_t *idx_out, void *workspace, size_t workspace_bytes,
                              void *stream, float *kernel_us);
 
+/* ---- 2-bit token-wise K/V cache (section "Token-Wise Quantization Format") -------------------
+ * The compressed form sparse attention can read instead of the 16-bit rows.  Per (b, h, token)
+ * one record of SIK_KVQ_RECORD_BYTES = 128 bytes, kvq [B, Hkv, max_len, 128] uint8 (device,
+ * caller-owned, 16-byte aligned), made of 16 slots of 8 bytes; slot p covers channels
+ * 8p .. 8p+7:
+ *   byte 0     sign byte p of the token's 1-bit code (bit 7-e = [K >= mu] of channel 8p+e)
+ *   byte 1     0
+ *   bytes 2-3  K magnitude codes, little-endian, code of channel 8p+e in bits 2e+1:2e
+ *   bytes 4-5  V codes, same packing
+ *   bytes 6-7  one fp16 parameter of the 32-channel group p/4: K qs, K zp, V qs, V zp for
+ *              p mod 4 = 0, 1, 2, 3
+ * i.e. the paper's 896 bits per token (128 sign bits, 2 x 256 code bits, 2 x 4 x 2 sixteen-bit
+ * parameters) laid out so that a selected token is one aligned 128-byte line; 16 bytes are spare.
+ * Quantisation function with B = 2, per token and per group x of 32 consecutive channels:
+ *   zp = fp16(min x), qs = fp16((max x - min x) / 3), Q = clamp(round((x - zp) / qs), 0, 3)
+ *   with the stored qs and zp, round = nearest, ties to even, qs = 0 -> Q = 0; D = qs Q + zp.
+ * V: x = the value.  K: x = |K - mu| / alpha with alpha[b,h,d] = max over the fitted tokens of
+ * |K - mu| (alpha = 0 -> x = 0); the reconstructed centred key is s * alpha * D, s = +1 where the
+ * sign bit is set.  Codes are decided in binary32 in this operation order.  Values must be
+ * finite and within the fp16 range. */
+#define SIK_KVQ_RECORD_BYTES 128
+
+/* Bytes of the record plane of a layout: B * Hkv * max_len * 128 (0 if the layout is invalid). */
+size_t sik_kvq_bytes(const sik_layout *layout);
+
+/* Writes records from 16-bit K and V ([B,Hkv,max_len,D] kv_dtype).
+ *   SIK_Q_FIT    alpha (out, [B,Hkv,D] fp32) from tokens i < seq_len[b] against the given mu
+ *                (as fitted by sik_quantize_keys), then the records of those tokens
+ *   SIK_Q_ENCODE records of tokens t0 <= i < t0 + n of every (b, h) against the given mu and
+ *                alpha (both inputs); seq_len is not read and may be NULL
+ * Other records are left untouched.  Needs no workspace. */
+int sik_quantize_kv(const sik_layout *layout, const void *K, const void *V, const int32_t *seq_len,
+                    int32_t t0, int32_t n, int mode, const float *mu, float *alpha, void *kvq,
+                    void *stream);
+
+/* Sparse attention as sik_sparse_attn, on records: the logit of token j is
+ * softmax_scale * sum_d q_d * s_d alpha_d D(K)_jd (the centred key: the dropped q . mu is one
+ * constant per query head and cancels in the softmax, normalisation section), the value row is
+ * D(V)_j; both are rebuilt in registers from the gathered record, never written to memory. */
+int sik_sparse_attn_q2(const sik_layout *layout, const void *q, const void *kvq, const float *alpha,
+                       const int32_t *idx, int32_t k, float softmax_scale, void *out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -430,6 +430,7 @@ static void quantize_group(const float *x, uint16_t *param /* qs, zp */, uint8_t
         if (x[e] > hi) hi = x[e];
     }
     float span = hi - lo;
+    lo = lo + 0.0f;                       /* a zero minimum is stored as +0 whatever the signs of the zeros */
     volatile float third = span / 3.0f;   /* one rounded binary32 division */
     param[0] = float_to_fp16_bits(third);
     param[1] = float_to_fp16_bits(lo);

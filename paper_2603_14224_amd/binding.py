@@ -18,7 +18,8 @@ SIK_Q_FIT, SIK_Q_ENCODE = 1, 2
 _TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: SIK_F32}
 
 EXPORTS = ("sik_strerror", "sik_version", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
-           "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_profiled")
+           "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_profiled", "sik_kvq_bytes",
+           "sik_quantize_kv", "sik_sparse_attn_q2")
 
 
 class SikError(RuntimeError):
@@ -63,6 +64,12 @@ def lib():
         L.sik_decode_step.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
         L.sik_decode_step_profiled.restype = ctypes.c_int
         L.sik_decode_step_profiled.argtypes = L.sik_decode_step.argtypes + [ctypes.POINTER(ctypes.c_float)]
+        L.sik_kvq_bytes.restype = sz
+        L.sik_kvq_bytes.argtypes = [lp]
+        L.sik_quantize_kv.restype = ctypes.c_int
+        L.sik_quantize_kv.argtypes = [lp, vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, vp, vp]
+        L.sik_sparse_attn_q2.restype = ctypes.c_int
+        L.sik_sparse_attn_q2.argtypes = [lp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -127,6 +134,29 @@ def sik_sparse_attn(layout, q, K, V, idx, k, softmax_scale, out, workspace):
     _check(lib().sik_sparse_attn(ctypes.byref(layout), _ptr(q), _ptr(K), _ptr(V), _ptr(idx), int(k),
                                  float(softmax_scale), _ptr(out), _ptr(workspace),
                                  workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def sik_kvq_bytes(layout: Layout) -> int:
+    return int(lib().sik_kvq_bytes(ctypes.byref(layout)))
+
+
+def alloc_kvq(layout: Layout, device="cuda") -> torch.Tensor:
+    """Zeroed record plane [B, Hkv, max_len, 128] uint8 of the 2-bit K/V format."""
+    n = sik_kvq_bytes(layout)
+    if n == 0:
+        raise SikError(-2, "sik_kvq_bytes rejected the layout")
+    return torch.zeros(layout.batch, layout.n_kv_heads, layout.max_len, 128, dtype=torch.uint8, device=device)
+
+
+def sik_quantize_kv(layout, K, V, seq_len, t0, n, mode, mu, alpha, kvq):
+    _check(lib().sik_quantize_kv(ctypes.byref(layout), _ptr(K), _ptr(V), _ptr(seq_len), int(t0), int(n), int(mode),
+                                 _ptr(mu), _ptr(alpha), _ptr(kvq), _stream()))
+
+
+def sik_sparse_attn_q2(layout, q, kvq, alpha, idx, k, softmax_scale, out, workspace):
+    _check(lib().sik_sparse_attn_q2(ctypes.byref(layout), _ptr(q), _ptr(kvq), _ptr(alpha), _ptr(idx), int(k),
+                                    float(softmax_scale), _ptr(out), _ptr(workspace),
+                                    workspace.numel() if workspace is not None else 0, _stream()))
 
 
 def sik_decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out, idx_out,

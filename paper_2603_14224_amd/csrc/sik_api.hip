@@ -162,6 +162,47 @@ int sik_sparse_attn(const sik_layout* layout, const void* q, const void* K, cons
     return launched(e);
 }
 
+size_t sik_kvq_bytes(const sik_layout* layout) {
+    Dims d;
+    if (check_layout(layout, &d) != SIK_OK) return 0;
+    return static_cast<size_t>(d.units()) * d.Lmax * SIK_KVQ_RECORD_BYTES;
+}
+
+int sik_quantize_kv(const sik_layout* layout, const void* K, const void* V, const int32_t* seq_len, int32_t t0,
+                    int32_t n, int mode, const float* mu, float* alpha, void* kvq, void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (mode != SIK_Q_FIT && mode != SIK_Q_ENCODE) return SIK_ERR_FLAGS;
+    if (!K || !V || !mu || !alpha || !kvq) return SIK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (mode == SIK_Q_ENCODE) {
+        if (t0 < 0 || n < 0 || static_cast<int64_t>(t0) + n > d.Lmax) return SIK_ERR_CAPACITY;
+        return launched(launch_quantize_kv(d, K, V, nullptr, t0, n, mu, alpha, kvq, s));
+    }
+    if (!seq_len) return SIK_ERR_NULL;
+    hipError_t e = launch_alpha(d, K, seq_len, mu, alpha, s);
+    if (e == hipSuccess) e = launch_quantize_kv(d, K, V, seq_len, 0, 0, mu, alpha, kvq, s);
+    return launched(e);
+}
+
+int sik_sparse_attn_q2(const sik_layout* layout, const void* q, const void* kvq, const float* alpha,
+                       const int32_t* idx, int32_t k, float softmax_scale, void* out, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (!q || !kvq || !alpha || !idx || !out) return SIK_ERR_NULL;
+    if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    Workspace w;
+    rc = check_ws(d, k, workspace, workspace_bytes, &w);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_prep(d, w, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    if (e == hipSuccess) e = launch_attn_q2(d, w, q, kvq, alpha, idx, k, softmax_scale, out, s);
+    return launched(e);
+}
+
 static int decode_step_impl(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
                             void* K, void* V, int32_t* seq_len, const float* mu, const float* codebook,
                             uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,

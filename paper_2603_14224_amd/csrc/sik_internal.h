@@ -85,4 +85,13 @@ hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const in
 hipError_t launch_encode(const Dims& d, const void* K, int t0, int n, const float* mu, uint8_t* codes,
                          hipStream_t s);
 
+// 2-bit token-wise K/V format
+hipError_t launch_alpha(const Dims& d, const void* K, const int32_t* seq_len, const float* mu, float* alpha,
+                        hipStream_t s);
+// seq_len != nullptr: tokens [0, seq_len[b]); else tokens [t0, t0 + n)
+hipError_t launch_quantize_kv(const Dims& d, const void* K, const void* V, const int32_t* seq_len, int t0, int n,
+                              const float* mu, const float* alpha, void* kvq, hipStream_t s);
+hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, const void* kvq, const float* alpha,
+                          const int32_t* idx, int k, float scale, void* out, hipStream_t s);
+
 }  // namespace sik

@@ -1,0 +1,196 @@
+// 2-bit token-wise K/V format (section "Token-Wise Quantization Format"): building one token's record
+// and attending over gathered records, at wavefront level.
+//
+// Record = 128 B per (sequence, KV head, token) = 16 slots of 8 B; slot p covers channels 8p .. 8p+7, the
+// channels one lane of a 16-lane row owns everywhere in this library:
+//   byte 0    sign byte p of the token's 1-bit code (bit 7-e = [K >= mu] of channel 8p+e)
+//   byte 1    0
+//   bytes 2-3 K magnitude codes, little-endian: code of channel 8p+e in bits 2e+1:2e
+//   bytes 4-5 V codes, same packing
+//   bytes 6-7 one fp16 parameter of the 32-channel group p/4: K qs, K zp, V qs, V zp for p mod 4 = 0, 1, 2, 3
+// so the four lanes of a quad hold the four parameters of their common group, one quad-permute away, and a
+// selected token costs one 128 B line instead of 2 x 256 B of 16-bit rows.
+//
+// Quantisation of a group x[0..31] (B = 2): zp = fp16(min x), qs = fp16((max x - min x) / 3),
+// Q = clamp(rint((x - zp) / qs), 0, 3) with the stored qs, zp (qs = 0 gives Q = 0), D = qs Q + zp.
+// V: x = the value.  K: x = |K - mu| / alpha (alpha = per-channel max of |K - mu| over the fitted
+// tokens; alpha = 0 gives x = 0), the sign travels as the code bit: K' ~ s alpha D.
+// The codes are decided in binary32 in exactly this operation order.
+#pragma once
+
+#include "sik_attn_core.h"
+#include "sik_device.h"
+
+namespace sik {
+
+constexpr int kRecBytes = 128;  // bytes per token record
+constexpr int kRecSlots = 16;   // uint2 slots per record
+
+// Value of lane (quad base + J) for every lane of the quad (DPP quad_perm broadcast).
+template <int J>
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {
+    return static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(0, static_cast<int>(v), J * 0x55, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float quad_min(float v) {
+    v = fminf(v, __uint_as_float(static_cast<uint32_t>(
+                     __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xb1, 0xf, 0xf, false))));  // lanes 1,0,3,2
+    return fminf(v, __uint_as_float(static_cast<uint32_t>(
+                        __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4e, 0xf, 0xf, false))));  // lanes 2,3,0,1
+}
+__device__ __forceinline__ float quad_max(float v) {
+    v = fmaxf(v, __uint_as_float(static_cast<uint32_t>(
+                     __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xb1, 0xf, 0xf, false))));
+    return fmaxf(v, __uint_as_float(static_cast<uint32_t>(
+                        __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4e, 0xf, 0xf, false))));
+}
+
+__device__ __forceinline__ uint32_t fp16_bits(float f) {
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));  // round to nearest even
+}
+__device__ __forceinline__ float fp16_value(uint32_t h) {
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+}
+
+// Parameters and 2-bit codes of this lane's 8 values of one 32-value group; the 4 lanes of the quad hold the
+// group and must all be active.  Returns the 16 code bits; qs_h, zp_h = the stored fp16 bits.
+__device__ __forceinline__ uint32_t quantize_octet(const float (&x)[8], uint32_t& qs_h, uint32_t& zp_h) {
+    float lo = x[0], hi = x[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) {
+        lo = fminf(lo, x[e]);
+        hi = fmaxf(hi, x[e]);
+    }
+    lo = quad_min(lo) + 0.0f;  // a zero minimum is stored as +0 whatever the signs of the zeros
+    hi = quad_max(hi);
+    qs_h = fp16_bits((hi - lo) / 3.0f);
+    zp_h = fp16_bits(lo);
+    const float qs = fp16_value(qs_h), zp = fp16_value(zp_h);
+    uint32_t bits = 0u;
+    if (qs > 0.0f) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float r = rintf((x[e] - zp) / qs);
+            const int c = static_cast<int>(fminf(fmaxf(r, 0.0f), 3.0f));
+            bits |= static_cast<uint32_t>(c) << (2 * e);
+        }
+    }
+    return bits;
+}
+
+// One 8-byte slot of a token's record from this lane's 8 key and 8 value elements (16-bit storage form),
+// the channel means and alphas of the same 8 channels, and p = slot index (lane within the 16-lane row).
+template <int DT>
+__device__ __forceinline__ uint2 kvq_make_slot(const uint4 kraw, const uint4 vraw, const float (&mu)[8],
+                                               const float (&alpha)[8], int p) {
+    float kf[8], vf[8], kh[8];
+    widen8<DT>(kraw, kf);
+    widen8<DT>(vraw, vf);
+    uint32_t sign = 0u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        sign |= (kf[e] >= mu[e] ? 1u : 0u) << (7 - e);
+        const float kp = kf[e] - mu[e];
+        kh[e] = alpha[e] > 0.0f ? fabsf(kp) / alpha[e] : 0.0f;
+    }
+    uint32_t kqs, kzp, vqs, vzp;
+    const uint32_t kbits = quantize_octet(kh, kqs, kzp);
+    const uint32_t vbits = quantize_octet(vf, vqs, vzp);
+    const int which = p & 3;
+    const uint32_t par = which == 0 ? kqs : (which == 1 ? kzp : (which == 2 ? vqs : vzp));
+    return make_uint2(sign | (kbits << 16), vbits | (par << 16));
+}
+
+// What a lane keeps of the query for logits against records: |q_e alpha_e| and, packed like a sign byte
+// (bit 7-e), the sign of q_e alpha_e, for its 8 channels.  q . K' = sum_e q_e s_e alpha_e D_e.
+struct Q2Query {
+    float absqa[8];
+    uint32_t neg;  // bit 7-e set: q_e alpha_e < 0
+};
+
+template <int DT>
+__device__ __forceinline__ Q2Query q2_prepare(const uint4 qraw, const float (&alpha)[8]) {
+    Q2Query r;
+    float qf[8];
+    widen8<DT>(qraw, qf);
+    r.neg = 0u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float qa = qf[e] * alpha[e];
+        r.absqa[e] = fabsf(qa);
+        r.neg |= (qa < 0.0f ? 1u : 0u) << (7 - e);
+    }
+    return r;
+}
+
+// attend_list over records: same contract as attend_list (entries first + it * step + 0..31 per wavefront
+// iteration, 8 rows per 16-lane group so that 8 x 8 B loads are in flight per lane).  rec = the (sequence,
+// KV head)'s records as uint2 slots.
+template <class Fetch>
+__device__ __forceinline__ void attend_list_q2(Fetch fetch, int n, int first, int step,
+                                               const uint2* __restrict__ rec, const Q2Query& qq,
+                                               float scale_log2e, int Lmax, SoftmaxState& st) {
+    constexpr int U = 8;
+    const int lane = threadIdx.x & 63;
+    const int slot = lane >> 4, p = lane & 15;
+    float zsum = 0.0f;  // sum of weight * V zero point: the same for this lane's 8 channels
+    for (int base = first; base < n; base += step) {
+        const int jj = base + (lane & 31);
+        const int mine = jj < n ? fetch(jj) : -1;
+        int id[U];
+        uint2 r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            id[u] = __shfl(mine, 4 * u + slot, 64);
+            const bool ok = id[u] >= 0 && id[u] < Lmax;
+            const size_t t = ok ? static_cast<size_t>(id[u]) : 0;
+            id[u] = ok ? id[u] : -1;
+            r[u] = rec[t * kRecSlots + p];
+        }
+        float z[U], vqs[U], vzp[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t par = r[u].y >> 16;
+            const float kqs = fp16_value(quad_bcast<0>(par)), kzp = fp16_value(quad_bcast<1>(par));
+            vqs[u] = fp16_value(quad_bcast<2>(par));
+            vzp[u] = fp16_value(quad_bcast<3>(par));
+            // sign of the product q_e alpha_e K'_e: minus where exactly one of (code bit clear, q alpha < 0)
+            const uint32_t flip = ((~r[u].x) ^ qq.neg) << 24;  // bit 31-e = flip channel e
+            const uint32_t kb = r[u].x >> 16;
+            float a = 0.0f, bsum = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float t = __uint_as_float(__float_as_uint(qq.absqa[e]) | ((flip << e) & 0x80000000u));
+                const float c = static_cast<float>((kb >> (2 * e)) & 3u);
+                a = fmaf(t, c, a);
+                bsum += t;
+            }
+            const float dot = row16_sum(fmaf(kqs, a, kzp * bsum)) * scale_log2e;
+            z[u] = id[u] >= 0 ? dot : kNegBig;
+        }
+        float mnew = st.m;
+#pragma unroll
+        for (int u = 0; u < U; ++u) mnew = fmaxf(mnew, z[u]);
+        const float corr = fast_exp2(st.m - mnew);
+        st.l *= corr;
+        zsum *= corr;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.acc[e] *= corr;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float pu = id[u] >= 0 ? fast_exp2(z[u] - mnew) : 0.0f;
+            st.l += pu;
+            const float ps = pu * vqs[u];
+            zsum = fmaf(pu, vzp[u], zsum);
+            const uint32_t vb = r[u].y;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                st.acc[e] = fmaf(ps, static_cast<float>((vb >> (2 * e)) & 3u), st.acc[e]);
+        }
+        st.m = mnew;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[e] += zsum;
+}
+
+}  // namespace sik
