@@ -197,6 +197,19 @@ int sik_sparse_attn_q2(const sik_layout *layout, const void *q, const void *kvq,
                        const int32_t *idx, int32_t k, float softmax_scale, void *out,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* One decode step on the 2-bit cache: as sik_decode_step, with the records in place of K and V.
+ * With k_new / v_new ([B,Hkv,D] kv_dtype, both or neither) the new token of every (b, h) is
+ * quantised against the frozen mu and alpha into record seq_len[b] of kvq, its sign code is
+ * written to codes, and seq_len[b] is incremented on the device; the 16-bit row is not kept.
+ * kernel_us: NULL, or a host pointer to SIK_N_KERNELS + 1 floats that receives the event
+ * intervals exactly as sik_decode_step_profiled does (and makes the call wait for the stream).
+ * max_len above 524288 is not supported on this path (SIK_ERR_SHAPE). */
+int sik_decode_step_q2(const sik_layout *layout, const void *q, const void *k_new, const void *v_new,
+                       void *kvq, int32_t *seq_len, const float *mu, const float *alpha,
+                       const float *codebook, uint8_t *codes, int32_t k, float softmax_scale,
+                       void *out, int32_t *idx_out, void *workspace, size_t workspace_bytes,
+                       void *stream, float *kernel_us);
+
 #ifdef __cplusplus
 }
 #endif

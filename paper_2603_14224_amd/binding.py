@@ -19,7 +19,7 @@ _TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: S
 
 EXPORTS = ("sik_strerror", "sik_version", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
            "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_profiled", "sik_kvq_bytes",
-           "sik_quantize_kv", "sik_sparse_attn_q2")
+           "sik_quantize_kv", "sik_sparse_attn_q2", "sik_decode_step_q2")
 
 
 class SikError(RuntimeError):
@@ -70,6 +70,9 @@ def lib():
         L.sik_quantize_kv.argtypes = [lp, vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, vp, vp]
         L.sik_sparse_attn_q2.restype = ctypes.c_int
         L.sik_sparse_attn_q2.argtypes = [lp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+        L.sik_decode_step_q2.restype = ctypes.c_int
+        L.sik_decode_step_q2.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp,
+                                         ctypes.POINTER(ctypes.c_float)]
         _lib = L
     return _lib
 
@@ -157,6 +160,17 @@ def sik_sparse_attn_q2(layout, q, kvq, alpha, idx, k, softmax_scale, out, worksp
     _check(lib().sik_sparse_attn_q2(ctypes.byref(layout), _ptr(q), _ptr(kvq), _ptr(alpha), _ptr(idx), int(k),
                                     float(softmax_scale), _ptr(out), _ptr(workspace),
                                     workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def sik_decode_step_q2(layout, q, k_new, v_new, kvq, seq_len, mu, alpha, codebook, codes, k, softmax_scale, out,
+                       idx_out, workspace, profiled=False):
+    """Decode step on the 2-bit cache; with profiled=True returns the SIK_N_KERNELS + 1 event intervals (us)."""
+    us = (ctypes.c_float * 5)() if profiled else None
+    _check(lib().sik_decode_step_q2(ctypes.byref(layout), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(kvq),
+                                    _ptr(seq_len), _ptr(mu), _ptr(alpha), _ptr(codebook), _ptr(codes), int(k),
+                                    float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(workspace),
+                                    workspace.numel() if workspace is not None else 0, _stream(), us))
+    return [float(x) for x in us] if profiled else None
 
 
 def sik_decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out, idx_out,

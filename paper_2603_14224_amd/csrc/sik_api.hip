@@ -203,14 +203,17 @@ int sik_sparse_attn_q2(const sik_layout* layout, const void* q, const void* kvq,
     return launched(e);
 }
 
+// kvq == nullptr: 16-bit cache (K, V); else the 2-bit cache (kvq, alpha), K and V unused.
 static int decode_step_impl(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
-                            void* K, void* V, int32_t* seq_len, const float* mu, const float* codebook,
-                            uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
-                            void* workspace, size_t workspace_bytes, void* stream, hipEvent_t* ev) {
+                            void* K, void* V, void* kvq, const float* alpha, int32_t* seq_len, const float* mu,
+                            const float* codebook, uint8_t* codes, int32_t k, float softmax_scale, void* out,
+                            int32_t* idx_out, void* workspace, size_t workspace_bytes, void* stream,
+                            hipEvent_t* ev) {
     Dims d;
     int rc = check_layout(layout, &d);
     if (rc) return rc;
-    if (!q || !K || !V || !seq_len || !codebook || !codes || !out) return SIK_ERR_NULL;
+    if (!q || !seq_len || !codebook || !codes || !out) return SIK_ERR_NULL;
+    if (kvq ? !alpha : (!K || !V)) return SIK_ERR_NULL;
     if ((k_new == nullptr) != (v_new == nullptr)) return SIK_ERR_NULL;
     if (k_new && !mu) return SIK_ERR_NULL;
     if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
@@ -220,20 +223,22 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t* idx = idx_out ? idx_out : w.idx;
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
-    hipError_t e = mark(0);
     int fchunks, fchunk;
-    if (fused_plan(d, &fchunks, &fchunk)) {
+    const bool fused = fused_plan(d, &fchunks, &fchunk);
+    if (kvq && !fused) return SIK_ERR_SHAPE;  // the 2-bit cache has no unfused path: max_len <= 524288
+    hipError_t e = mark(0);
+    if (fused) {
         // Two launches: scoring (which also stores, encodes and scores an appended row and clears the
         // per-call counters), then selection + attention (which publishes the new length).  The first
         // and third event intervals are empty.
         const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
-                        static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes};
+                        static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
         if (e == hipSuccess) e = mark(1);
         if (e == hipSuccess) e = launch_score(d, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = mark(3);
         if (e == hipSuccess)
-            e = launch_fused(d, w, q, K, V, seq_len, k_new != nullptr, k, softmax_scale, idx_out, out, s);
+            e = launch_fused(d, w, q, K, V, kvq, alpha, seq_len, k_new != nullptr, k, softmax_scale, idx_out, out, s);
     } else {
         // contexts beyond 512K tokens: prep (append + clear counters), score, select, attention
         if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
@@ -249,18 +254,9 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     return launched(e);
 }
 
-int sik_decode_step(const sik_layout* layout, const void* q, const void* k_new, const void* v_new, void* K,
-                    void* V, int32_t* seq_len, const float* mu, const float* codebook, uint8_t* codes, int32_t k,
-                    float softmax_scale, void* out, int32_t* idx_out, void* workspace, size_t workspace_bytes,
-                    void* stream) {
-    return decode_step_impl(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,
-                            idx_out, workspace, workspace_bytes, stream, nullptr);
-}
-
-int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
-                             void* K, void* V, int32_t* seq_len, const float* mu, const float* codebook,
-                             uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
-                             void* workspace, size_t workspace_bytes, void* stream, float* kernel_us) {
+// Runs decode_step_impl between HIP events and converts them to intervals (see sik_decode_step_profiled).
+extern "C++" template <class Run>
+static int profiled(void* stream, float* kernel_us, Run run) {
     if (!kernel_us) return SIK_ERR_NULL;
     constexpr int kEvents = SIK_N_KERNELS + 2;
     hipEvent_t ev[kEvents];
@@ -268,9 +264,7 @@ int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void
     for (; made < kEvents; ++made)
         if (hipEventCreate(&ev[made]) != hipSuccess) break;
     int rc = made == kEvents ? SIK_OK : SIK_ERR_LAUNCH;
-    if (rc == SIK_OK)
-        rc = decode_step_impl(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,
-                              idx_out, workspace, workspace_bytes, stream, ev);
+    if (rc == SIK_OK) rc = run(ev);
     if (rc == SIK_OK && hipEventSynchronize(ev[SIK_N_KERNELS + 1]) != hipSuccess) rc = SIK_ERR_LAUNCH;
     for (int i = 0; rc == SIK_OK && i <= SIK_N_KERNELS; ++i) {
         float ms = 0.0f;
@@ -278,7 +272,40 @@ int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void
         kernel_us[i] = ms * 1000.0f;
     }
     for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
+    (void)stream;
     return rc;
+}
+
+int sik_decode_step(const sik_layout* layout, const void* q, const void* k_new, const void* v_new, void* K,
+                    void* V, int32_t* seq_len, const float* mu, const float* codebook, uint8_t* codes, int32_t k,
+                    float softmax_scale, void* out, int32_t* idx_out, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+    return decode_step_impl(layout, q, k_new, v_new, K, V, nullptr, nullptr, seq_len, mu, codebook, codes, k,
+                            softmax_scale, out, idx_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
+                             void* K, void* V, int32_t* seq_len, const float* mu, const float* codebook,
+                             uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
+                             void* workspace, size_t workspace_bytes, void* stream, float* kernel_us) {
+    return profiled(stream, kernel_us, [&](hipEvent_t* ev) {
+        return decode_step_impl(layout, q, k_new, v_new, K, V, nullptr, nullptr, seq_len, mu, codebook, codes, k,
+                                softmax_scale, out, idx_out, workspace, workspace_bytes, stream, ev);
+    });
+}
+
+int sik_decode_step_q2(const sik_layout* layout, const void* q, const void* k_new, const void* v_new, void* kvq,
+                       int32_t* seq_len, const float* mu, const float* alpha, const float* codebook,
+                       uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
+                       void* workspace, size_t workspace_bytes, void* stream, float* kernel_us) {
+    if (!kvq) return SIK_ERR_NULL;
+    if (!kernel_us)
+        return decode_step_impl(layout, q, k_new, v_new, nullptr, nullptr, kvq, alpha, seq_len, mu, codebook, codes,
+                                k, softmax_scale, out, idx_out, workspace, workspace_bytes, stream, nullptr);
+    return profiled(stream, kernel_us, [&](hipEvent_t* ev) {
+        return decode_step_impl(layout, q, k_new, v_new, nullptr, nullptr, kvq, alpha, seq_len, mu, codebook, codes,
+                                k, softmax_scale, out, idx_out, workspace, workspace_bytes, stream, ev);
+    });
 }
 
 }  // extern "C"

@@ -19,6 +19,7 @@
 #include "sik_attn_core.h"
 #include "sik_device.h"
 #include "sik_internal.h"
+#include "sik_kvq.h"
 #include "sik_select.h"
 
 namespace sik {
@@ -33,10 +34,12 @@ SIK_TL_DEFINE(sik_dbg_tl_fused)
 constexpr int kWaveCand = 16;                      // candidate slots per wavefront and chunk
 constexpr int kCandWaveWords = 1 + 2 * kWaveCand;  // words per region
 
-template <int DT, int ODT, int NQ>  // NQ float4 of scores per lane: chunk = 1024 * NQ tokens
+// NQ float4 of scores per lane: chunk = 1024 * NQ tokens.  KVQ: the selected tokens are gathered as 128-byte
+// records of the 2-bit cache (kvq, alpha) and dequantised in registers, instead of as 16-bit K and V rows.
+template <int DT, int ODT, int NQ, bool KVQ>
 __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const float* __restrict__ scores, int sstride, int32_t* __restrict__ seq_len, int appended,
+    const uint2* __restrict__ kvq, const float* __restrict__ alpha, const float* __restrict__ scores, int sstride, int32_t* __restrict__ seq_len, int appended,
     const uint32_t* __restrict__ parthist, const float* __restrict__ binp, uint32_t* __restrict__ counters,
     uint32_t* __restrict__ cand, float* __restrict__ partial, int32_t* __restrict__ idx_ws,
     int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
@@ -70,6 +73,11 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         sv[j] = i < sstride ? s4[j * kBlock + tid] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     const uint4 qraw = reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p];
+    float4 al0 = make_float4(0.f, 0.f, 0.f, 0.f), al1 = al0;
+    if constexpr (KVQ) {
+        al0 = reinterpret_cast<const float4*>(alpha + unit * kD)[2 * p];
+        al1 = reinterpret_cast<const float4*>(alpha + unit * kD)[2 * p + 1];
+    }
     const float lo = binp[row * 2], scale = binp[row * 2 + 1];
     const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hchunks);
     int L = seq_len[b];
@@ -92,8 +100,23 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     SIK_TL(25);
 
     // ---- 3. wave-private compaction of the selected tokens, candidates aside -------------------
-    const uint4* Kp = reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
-    const uint4* Vp = reinterpret_cast<const uint4*>(V + unit * Lmax * kD);
+    const uint4* Kp = KVQ ? nullptr : reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
+    const uint4* Vp = KVQ ? nullptr : reinterpret_cast<const uint4*>(V + unit * Lmax * kD);
+    const uint2* Rp = KVQ ? kvq + unit * Lmax * kRecSlots : nullptr;
+    Q2Query qq;
+    if constexpr (KVQ) {
+        const float a8[8] = {al0.x, al0.y, al0.z, al0.w, al1.x, al1.y, al1.z, al1.w};
+        qq = q2_prepare<DT>(qraw, a8);
+    }
+    // Gather + online softmax over a list: wavefront-private lists go in steps of kStep entries, lists shared by
+    // the workgroup's four wavefronts in interleaved steps.
+    constexpr int kStep = KVQ ? 32 : 16;
+    auto attend = [&](auto fetch, int n, int first, int step, SoftmaxState& s_) {
+        if constexpr (KVQ)
+            attend_list_q2(fetch, n, first, step, Rp, qq, scale_log2e, Lmax, s_);
+        else
+            attend_list<DT>(fetch, n, first, step, Kp, Vp, qraw, scale_log2e, Lmax, s_);
+    };
     int n_sel = 0, n_cand = 0;  // wave-uniform
     const int regions = nchunk * (kBlock / kWave);
     uint32_t* crow = cand + static_cast<size_t>(row) * regions * kCandWaveWords;
@@ -183,7 +206,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         const uint64_t bal = __ballot(has);
         if (bal == 0ull) break;
         if (n_sel > kListCap - 64) {
-            const int n16 = n_sel & ~15;  // complete groups of 16 now, the rest moves to the front
+            const int n16 = n_sel & ~(kStep - 1);  // complete gather steps now, the rest moves to the front
             if (idx_out) {
                 uint32_t base = 0u;
                 if (lane == 0) base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(n16));
@@ -191,7 +214,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
                 for (int t = lane; t < n16; t += 64)
                     if (base + t < static_cast<uint32_t>(k)) idx_out[static_cast<size_t>(row) * k + base + t] = mylist[t];
             }
-            attend_list<DT>([&](int t) { return mylist[t]; }, n16, 0, 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
+            attend([&](int t) { return mylist[t]; }, n16, 0, kStep, st);
             const int rem = n_sel - n16;
             const int keep = lane < rem ? mylist[n16 + lane] : 0;
             if (lane < rem) mylist[lane] = keep;
@@ -213,7 +236,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     SIK_TL(26);
 
     // ---- 4. attend over this wavefront's own tokens, publish the chunk's partial ---------------
-    attend_list<DT>([&](int j) { return mylist[j]; }, n_sel, 0, 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
+    attend([&](int j) { return mylist[j]; }, n_sel, 0, kStep, st);
     SIK_TL(27);
     if (idx_out && n_sel > 0) {
         out_base = static_cast<uint32_t>(__shfl(static_cast<int>(out_base), 0, 64));
@@ -340,8 +363,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
             }
             __syncthreads();
             SIK_TL_ANY(34);
-            attend_list<DT>([&](int j) { return chosen[j]; }, min(need, n), wv * 16, (kBlock / kWave) * 16, Kp, Vp,
-                            qraw, scale_log2e, Lmax, st);
+            attend([&](int j) { return chosen[j]; }, min(need, n), wv * kStep, (kBlock / kWave) * kStep, st);
         } else {
             // exact fallback: radix select over the members of b* in the whole row of scores
             radix_select_in_bin(scores + static_cast<size_t>(row) * sstride, L, lo, scale, bstar, need,
@@ -349,8 +371,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
             __threadfence_block();
             __syncthreads();
             const int32_t* gl = olist + cgt;
-            attend_list<DT>([&](int j) { return gl[j]; }, need, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e, Lmax,
-                            st);
+            attend([&](int j) { return gl[j]; }, need, wv * kStep, (kBlock / kWave) * kStep, st);
         }
     }
     SIK_TL_ANY(31);
@@ -410,8 +431,8 @@ size_t fused_cand_words(const Dims& d) {
 
 template <int DT, int ODT>
 static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                                 int32_t* seq_len, bool appended, int k, float scale, int32_t* idx_out, void* out,
-                                 hipStream_t s) {
+                                 const void* kvq, const float* alpha, int32_t* seq_len, bool appended, int k,
+                                 float scale, int32_t* idx_out, void* out, hipStream_t s) {
     int nhb, hchunks, hchunk, nchunk, chunk;
     score_plan(d, &nhb, &hchunks, &hchunk);
     if (!fused_plan(d, &nchunk, &chunk)) return hipErrorInvalidValue;
@@ -420,12 +441,15 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     auto qp = static_cast<const uint16_t*>(q);
     auto Kp = static_cast<const uint16_t*>(K);
     auto Vp = static_cast<const uint16_t*>(V);
+    auto Rp = static_cast<const uint2*>(kvq);
+#define SIK_FUSED_Q(NQV, KVQV)                                                                              \
+    select_attend_kernel<DT, ODT, NQV, KVQV><<<grid, kBlock, 0, s>>>(                                       \
+        qp, Kp, Vp, Rp, alpha, w.scores, w.sstride, seq_len, appended ? 1 : 0, w.parthist, w.binp, w.counters, \
+        w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks)
 #define SIK_FUSED(NQV)                                                                                      \
-    select_attend_kernel<DT, ODT, NQV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, w.scores, w.sstride, seq_len,    \
-                                                               appended ? 1 : 0,                            \
-                                                               w.parthist, w.binp, w.counters, w.cand,      \
-                                                               w.partial, w.idx, idx_out, out, sl2, k,      \
-                                                               d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks)
+    do {                                                                                                    \
+        if (kvq) SIK_FUSED_Q(NQV, true); else SIK_FUSED_Q(NQV, false);                                      \
+    } while (0)
     switch (chunk) {
         case 1024: SIK_FUSED(1); break;
         case 2048: SIK_FUSED(2); break;
@@ -434,13 +458,15 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
         default: return hipErrorInvalidValue;
     }
 #undef SIK_FUSED
+#undef SIK_FUSED_Q
     return hipGetLastError();
 }
 
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        int32_t* seq_len, bool appended, int k, float scale, int32_t* idx_out, void* out,
-                        hipStream_t s) {
-#define SIK_F(DTV, ODTV) launch_fused_t<DTV, ODTV>(d, w, q, K, V, seq_len, appended, k, scale, idx_out, out, s)
+                        const void* kvq, const float* alpha, int32_t* seq_len, bool appended, int k, float scale,
+                        int32_t* idx_out, void* out, hipStream_t s) {
+#define SIK_F(DTV, ODTV) \
+    launch_fused_t<DTV, ODTV>(d, w, q, K, V, kvq, alpha, seq_len, appended, k, scale, idx_out, out, s)
     if (d.kv_dtype == kBF16) return d.out_dtype == kF32 ? SIK_F(kBF16, kF32) : SIK_F(kBF16, kBF16);
     return d.out_dtype == kF32 ? SIK_F(kF16, kF32) : SIK_F(kF16, kF16);
 #undef SIK_F

@@ -53,6 +53,8 @@ struct Append {
     uint16_t* V;
     const float* mu;
     uint8_t* codes;
+    const float* alpha;  // with kvq: the row is stored as one record of the 2-bit cache instead of into K and V
+    void* kvq;
 };
 
 // w == nullptr: scores only; otherwise also the per-chunk selection histograms, and with
@@ -75,9 +77,10 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
                        const int32_t* idx, int k, float scale, void* out, hipStream_t s);
 // select + attention in one launch; reads w.scores / w.parthist / w.binp written by launch_score
 // `appended`: launch_score counted one more token than seq_len says; the last workgroup increments it
+// kvq != nullptr: gather records of the 2-bit cache (K, V unused) with the per-channel alpha
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        int32_t* seq_len, bool appended, int k, float scale, int32_t* idx_out, void* out,
-                        hipStream_t s);
+                        const void* kvq, const float* alpha, int32_t* seq_len, bool appended, int k, float scale,
+                        int32_t* idx_out, void* out, hipStream_t s);
 bool fused_plan(const Dims& d, int* nchunk, int* chunk);
 size_t fused_cand_words(const Dims& d);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,

@@ -15,6 +15,7 @@
 // map of each query head's scores, published per chunk for the select kernel.
 #include "sik_device.h"
 #include "sik_internal.h"
+#include "sik_kvq.h"
 #include "sik_select.h"
 
 namespace sik {
@@ -66,7 +67,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
                                                        const uint16_t* __restrict__ v_new,
                                                        uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc,
                                                        const float* __restrict__ mu,
-                                                       uint8_t* __restrict__ codes_w, int Hkv, int Hq, int R,
+                                                       uint8_t* __restrict__ codes_w,
+                                                       const float* __restrict__ alpha, uint2* __restrict__ kvq,
+                                                       int Hkv, int Hq, int R,
                                                        int Lmax, int nchunk, int chunk, int nhb) {
     constexpr int HB = kHB;
     constexpr int kTokPerIter = kIterTokens / BLK;
@@ -124,12 +127,20 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     // against the frozen mu and scores it from LDS, and head block 0 of that chunk also stores the row and
     // its code.  seq_len itself is incremented by the last workgroup of the kernel that follows.
     uint4 knew = make_uint4(0u, 0u, 0u, 0u), vnew = make_uint4(0u, 0u, 0u, 0u);
-    float4 m0 = make_float4(0.f, 0.f, 0.f, 0.f), m1 = m0;
+    float m8[8] = {0, 0, 0, 0, 0, 0, 0, 0}, a8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (k_new && tid < 16) {
         knew = reinterpret_cast<const uint4*>(k_new + static_cast<size_t>(unit) * kD)[tid];
         vnew = reinterpret_cast<const uint4*>(v_new + static_cast<size_t>(unit) * kD)[tid];
-        m0 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * tid];
-        m1 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * tid + 1];
+        const float4 m0 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * tid];
+        const float4 m1 = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[2 * tid + 1];
+        m8[0] = m0.x, m8[1] = m0.y, m8[2] = m0.z, m8[3] = m0.w;
+        m8[4] = m1.x, m8[5] = m1.y, m8[6] = m1.z, m8[7] = m1.w;
+        if (kvq) {  // 2-bit cache: the row is stored as a record, which also needs the frozen alpha
+            const float4 a0 = reinterpret_cast<const float4*>(alpha + static_cast<size_t>(unit) * kD)[2 * tid];
+            const float4 a1 = reinterpret_cast<const float4*>(alpha + static_cast<size_t>(unit) * kD)[2 * tid + 1];
+            a8[0] = a0.x, a8[1] = a0.y, a8[2] = a0.z, a8[3] = a0.w;
+            a8[4] = a1.x, a8[5] = a1.y, a8[6] = a1.z, a8[7] = a1.w;
+        }
     }
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
@@ -142,15 +153,18 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     if (holds_new && tid < 16) {
         float f[8];
         widen8<DT>(knew, f);
-        const float m[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
         uint32_t byte = 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) byte |= (f[e] >= m[e] ? 1u : 0u) << (7 - e);
+        for (int e = 0; e < 8; ++e) byte |= (f[e] >= m8[e] ? 1u : 0u) << (7 - e);
         newcode[tid] = static_cast<uint8_t>(byte);
         if (hb == 0) {
             const size_t rowi = static_cast<size_t>(unit) * Lmax + t_new;
-            reinterpret_cast<uint4*>(Kc + rowi * kD)[tid] = knew;
-            reinterpret_cast<uint4*>(Vc + rowi * kD)[tid] = vnew;
+            if (kvq) {
+                kvq[rowi * kRecSlots + tid] = kvq_make_slot<DT>(knew, vnew, m8, a8, tid);
+            } else {
+                reinterpret_cast<uint4*>(Kc + rowi * kD)[tid] = knew;
+                reinterpret_cast<uint4*>(Vc + rowi * kD)[tid] = vnew;
+            }
             codes_w[rowi * kCodeBytes + tid] = static_cast<uint8_t>(byte);
         }
     }
@@ -307,7 +321,7 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     score_kernel<DT, HV, BLKV><<<grid, BLKV, 0, s>>>(                                                        \
         qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
         w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
-        d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
+        ap.alpha, static_cast<uint2*>(ap.kvq), d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
     const bool wide = score_block(d, nhb) == 512;
     if (!w) { if (wide) SIK_SCORE(false, 512); else SIK_SCORE(false, 256); }
     else { if (wide) SIK_SCORE(true, 512); else SIK_SCORE(true, 256); }

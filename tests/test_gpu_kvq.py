@@ -141,3 +141,130 @@ def test_attention_on_records_all_tokens_and_small_selections(oracle):
         sync()
         ref = oracle.sparse_attn_q2(q, cfg.dtype, st.codes, st.qkv, st.alpha, idx, scale=0.09)
         check_attention(out.cpu().numpy().astype(np.float64), ref, True)
+
+
+# --------------------------------------------------------------------------- decode step on records
+def run_decode_q2_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0, seq_len=None, out_f32=True):
+    st = Q2State(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=offset_std,
+                 out_dtype=torch.float32 if out_f32 else None)
+    B, Hq, k = cfg.batch, cfg.n_q_heads, min(cfg.top_k, capacity)
+    kvq = torch.from_numpy(st.records()).cuda()
+    dal = torch.from_numpy(st.alpha).cuda()
+    sl, codes, qkv = st.sl.copy(), st.codes, st.qkv
+    out = torch.empty(B, Hq, 128, dtype=torch.float32 if out_f32 else TDT[cfg.dtype], device="cuda")
+    idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
+    total_diff = 0
+    for step in range(steps):
+        q, kn, vn = W.make_step_inputs(cfg, step)
+        dkn = dev(kn, cfg.dtype) if append else None
+        dvn = dev(vn, cfg.dtype) if append else None
+        sik.sik_decode_step_q2(st.layout, dev(q, cfg.dtype), dkn, dvn, kvq, st.dsl, st.dmu, dal, st.dcb, st.dcodes, k,
+                               0.0, out, idx, st.ws)
+        sync()
+        ref_out, ref_idx = oracle.decode_step_q2(q, kn if append else None, vn if append else None, cfg.dtype, sl,
+                                                 st.mu, st.alpha, st.cb, codes, qkv, k)
+        assert np.array_equal(st.dsl.cpu().numpy(), sl)
+        if append:
+            want = oracle.pack_records(codes, qkv)
+            got = kvq.cpu().numpy()
+            for b in range(B):
+                t = sl[b] - 1
+                assert np.array_equal(got[b, :, t], want[b, :, t]), (step, b)
+                assert np.array_equal(st.dcodes[b, :, t].cpu().numpy(), codes[b, :, t])
+        g_idx = idx.cpu().numpy()
+        s_ref = oracle.score(q, cfg.dtype, st.cb, codes, sl)
+        for b in range(B):
+            for hq in range(Hq):
+                total_diff += topk_sets_agree(g_idx[b, hq], ref_idx[b, hq], s_ref[b, hq], int(sl[b]), k)
+        ref_on_gpu_set = oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, st.alpha, g_idx)
+        check_attention(out.float().cpu().numpy().astype(np.float64), ref_on_gpu_set, out_f32, cfg.dtype)
+    return total_diff
+
+
+def test_decode_q2_c1_full(oracle):
+    run_decode_q2_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=2, append=False)
+
+
+def test_decode_q2_c1_16bit_out(oracle):
+    run_decode_q2_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=1, append=False, out_f32=False)
+
+
+def test_decode_q2_c2_shape_reduced(oracle):
+    run_decode_q2_and_check(oracle, cfg_small("C2", context=8192, top_k=256), capacity=8192, steps=2, append=False,
+                            offset_std=1.0)
+
+
+def test_decode_q2_c3_shape_reduced_with_append(oracle):
+    run_decode_q2_and_check(oracle, cfg_small("C3", context=9000, top_k=300), capacity=9004, steps=3, append=True,
+                            offset_std=1.0)
+
+
+def test_decode_q2_c4_shape_reduced_ragged_batch(oracle):
+    run_decode_q2_and_check(oracle, cfg_small("C4", batch=4, context=2048, top_k=512), capacity=2050, steps=1,
+                            append=True, seq_len=[2048, 1, 511, 700])
+
+
+def test_decode_q2_c5_shape_reduced_gqa8_fp16(oracle):
+    cfg = cfg_small("C5", batch=2, n_kv_heads=2, n_q_heads=16, context=6000, top_k=1536, dtype="fp16")
+    run_decode_q2_and_check(oracle, cfg, capacity=6016, steps=3, append=True)
+
+
+def test_decode_q2_dense_selection_and_k_above_context(oracle):
+    run_decode_q2_and_check(oracle, cfg_small("C2", context=20000, top_k=20000), capacity=20000, steps=1, append=False)
+    run_decode_q2_and_check(oracle, cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=700, top_k=1024),
+                            capacity=1100, steps=1, append=True)
+
+
+def test_decode_q2_empty_and_single_token_sequences(oracle):
+    cfg = cfg_small("C2", batch=3, n_kv_heads=2, n_q_heads=4, context=300, top_k=16)
+    run_decode_q2_and_check(oracle, cfg, capacity=320, steps=2, append=True, seq_len=[0, 1, 300])
+
+
+def test_decode_q2_graph_replay_and_profiled(oracle):
+    cfg = cfg_small("C2", context=20000, top_k=600)
+    st = Q2State(cfg, oracle, capacity=20008, out_dtype=torch.float32)
+    kvq = torch.from_numpy(st.records()).cuda()
+    dal = torch.from_numpy(st.alpha).cuda()
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    dq, dkn, dvn = dev(q, cfg.dtype), dev(kn, cfg.dtype), dev(vn, cfg.dtype)
+    out = torch.empty(1, 32, 128, device="cuda")
+    idx = torch.empty(1, 32, 600, dtype=torch.int32, device="cuda")
+
+    def body(prof=False):
+        st.dsl.fill_(20000)
+        return sik.sik_decode_step_q2(st.layout, dq, dkn, dvn, kvq, st.dsl, st.dmu, dal, st.dcb, st.dcodes, 600, 0.0,
+                                      out, idx, st.ws, profiled=prof)
+
+    body()
+    sync()
+    eager_out, eager_idx = out.clone(), torch.sort(idx, dim=-1).values.clone()
+    assert int(st.dsl[0]) == 20001
+    us = body(prof=True)
+    assert len(us) == 5 and us[1] > 0 and us[3] > 0 and torch.equal(out, eager_out)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        body()
+        sync()
+        with torch.cuda.graph(g, stream=side):
+            body()
+    sync()
+    for r in range(3):
+        out.zero_()
+        idx.fill_(-3)
+        st.dsl.fill_(123)
+        torch.randn(1 << 20, device="cuda").sum().item()
+        g.replay()
+        sync()
+        assert int(st.dsl[0]) == 20001
+        assert torch.equal(out, eager_out), r
+        assert torch.equal(torch.sort(idx, dim=-1).values, eager_idx), r
+
+
+def test_decode_q2_rejects_contexts_without_a_fused_plan(oracle):
+    lay = sik.make_layout(1, 1, 1, 128, 600000, torch.bfloat16, torch.float32)
+    ws = sik.alloc_workspace(lay, 16)
+    t = torch.zeros(16, device="cuda")
+    with pytest.raises(sik.SikError) as e:
+        sik.sik_decode_step_q2(lay, t, None, None, t, t, t, t, t, t, 16, 0.0, t, None, ws)
+    assert e.value.status == -2
