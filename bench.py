@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of HIP-graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--kv", default="rows", choices=["rows", "q2"],
+                    help="rows: 16-bit K/V rows (the headline metric); q2: the 2-bit token-wise cache, one 128-byte "
+                         "record per token, dequantised inside the attention kernel")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB): under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counters' scale factor")
@@ -73,7 +76,8 @@ def main():
     cfg = W.CONFIGS[args.config]
     B, Hkv, Hq, D, L, k = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.context, cfg.top_k
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float16
-    per_layer = 2 * B * Hkv * L * D * 2 + B * Hkv * L * (D // 8)
+    q2 = args.kv == "q2"
+    per_layer = (B * Hkv * L * 128 if q2 else 2 * B * Hkv * L * D * 2) + B * Hkv * L * (D // 8)
     n_layers = args.layers or max(2, min(16, -(-2 * 256 * 2 ** 20 // per_layer)))
     total_steps = args.warmup + args.steps
     # capacity: room for the appended rows of every step that lands on a layer
@@ -95,6 +99,13 @@ def main():
                   codes=torch.zeros(B, Hkv, cap, D // 8, dtype=torch.uint8, device="cuda"))
         sik.sik_quantize_keys(lay, st["K"], st["sl"], 0, 0, sik.SIK_Q_FIT, st["mu"], st["cb"], st["cnt"],
                               st["codes"], ws)
+        if q2:  # the records replace the 16-bit rows, which are dropped
+            st["alpha"] = torch.empty(B, Hkv, D, device="cuda")
+            st["kvq"] = sik.alloc_kvq(lay)
+            sik.sik_quantize_kv(lay, st["K"], st["V"], st["sl"], 0, 0, sik.SIK_Q_FIT, st["mu"], st["alpha"],
+                                st["kvq"])
+            torch.cuda.synchronize()
+            st["K"] = st["V"] = None
         if li == 0:
             host0 = (Kb, Vb)
         layers.append(st)
@@ -117,9 +128,13 @@ def main():
         st = layers[i % n_layers]
         j = i % n_q
         a = ((i - base) // n_layers) % n_new  # how many rows this layer has been given since its reset
+        kn, vn = (kns[a], vns[a]) if cfg.append else (None, None)
+        if q2:
+            return sik.sik_decode_step_q2(lay, qs[j], kn, vn, st["kvq"], st["sl"], st["mu"], st["alpha"], st["cb"],
+                                          st["codes"], k, 0.0, out, None, ws, profiled=profiled)
         fn = sik.sik_decode_step_profiled if profiled else sik.sik_decode_step
-        return fn(lay, qs[j], kns[a] if cfg.append else None, vns[a] if cfg.append else None, st["K"], st["V"],
-                  st["sl"], st["mu"], st["cb"], st["codes"], k, 0.0, out, None, ws)
+        return fn(lay, qs[j], kn, vn, st["K"], st["V"], st["sl"], st["mu"], st["cb"], st["codes"], k, 0.0, out, None,
+                  ws)
 
     def reset_lengths():
         for st in layers:
@@ -200,8 +215,13 @@ def main():
     # ---- rows the gather really touches: query heads of one GQA group may select the same token
     idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
     st0 = layers[0]
-    sik.sik_decode_step(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None, st0["K"],
-                        st0["V"], st0["sl"], st0["mu"], st0["cb"], st0["codes"], k, 0.0, out, idx, ws)
+    if q2:
+        sik.sik_decode_step_q2(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None,
+                               st0["kvq"], st0["sl"], st0["mu"], st0["alpha"], st0["cb"], st0["codes"], k, 0.0, out,
+                               idx, ws)
+    else:
+        sik.sik_decode_step(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None, st0["K"],
+                            st0["V"], st0["sl"], st0["mu"], st0["cb"], st0["codes"], k, 0.0, out, idx, ws)
     torch.cuda.synchronize()
     srt = idx.view(B * Hkv, -1).sort(dim=1).values
     fresh = torch.ones_like(srt, dtype=torch.bool)
@@ -223,6 +243,9 @@ def main():
     reset_lengths()
 
     ab = W.algorithmic_bytes(cfg)
+    if q2:  # a selected (query head, token) costs one 128-byte record instead of 2 x 256 bytes of rows
+        ab = dict(ab, gathered=ab["gathered"] // 4)
+        ab["total"] = ab["codes"] + ab["gathered"]
     alg_by_kernel = {"prep_kernel": (B * Hkv * (2 * D * 2 + D // 8)) if cfg.append else 0,
                      "score_kernel": ab["codes"], "select_kernel_unfused_only": 0,
                      "select_attend_kernel": ab["gathered"]}
@@ -246,7 +269,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "head_dim": D,
-                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "append": cfg.append,
+                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv, "append": cfg.append,
                    "layers_rotated": n_layers, "launch": launch},
         "effective_hbm_GBps": round(ab["total"] / sec_step / 1e9, 1),
         "effective_hbm_frac_of_8TBps": round(ab["total"] / sec_step / 1e9 / HBM_PEAK_GBPS, 4),
@@ -259,17 +282,17 @@ def main():
         "hip_event_pair_overhead_us": round(float(raw[4]), 3),
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, dom_name)),
+                     "traffic": None if q2 else MEASURED_TRAFFIC_BYTES.get((args.config, dom_name)),
                      "algorithmic_bytes_per_launch": dom_bytes},
         "setup_seconds": round(gen_s, 1),
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, host0, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(cfg, host0, args.cpu_seconds, q2)
     print(json.dumps(result))
 
 
-def cpu_baseline(cfg, host0, budget_s):
+def cpu_baseline(cfg, host0, budget_s, q2=False):
     """The CPU oracle, as it stands, on the same workload's layer 0: whole decode steps on the host
     cores of this machine (OpenMP over batch x head), as many as fit the time budget."""
     import numpy as np
@@ -284,14 +307,23 @@ def cpu_baseline(cfg, host0, budget_s):
     B, cap = K.shape[0], K.shape[2]
     sl = np.full(B, cfg.context, np.int32)
     mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    if q2:
+        al, qkv = oracle.fit_q2(K, V, cfg.dtype, sl, mu)
+
+    def one(q, kn, vn):
+        if q2:
+            oracle.decode_step_q2(q, kn, vn, cfg.dtype, sl, mu, al, cb, codes, qkv, cfg.top_k)
+        else:
+            oracle.decode_step(q, kn, vn, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+
     n, t_total = 0, 0.0
     while True:
         q, kn, vn = W.make_step_inputs(cfg, n)
         t = time.perf_counter()
         if cfg.append and sl.max() < cap:
-            oracle.decode_step(q, kn, vn, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+            one(q, kn, vn)
         else:
-            oracle.decode_step(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+            one(q, None, None)
         t_total += time.perf_counter() - t
         n += 1
         if t_total >= budget_s or n >= 64:
@@ -302,7 +334,7 @@ def cpu_baseline(cfg, host0, budget_s):
     if t_total / n * used <= budget_s:  # one more step on a single thread, when that fits the budget too
         q, _, _ = W.make_step_inputs(cfg, n)
         t = time.perf_counter()
-        oracle.decode_step(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+        one(q, None, None)
         res["single_thread_us_per_step"] = round((time.perf_counter() - t) * 1e6, 1)
     return res
 

@@ -168,12 +168,12 @@ int sik_decode_step_profiled(const sik_layout *layout, const void *q, const void
  * i.e. the paper's 896 bits per token (128 sign bits, 2 x 256 code bits, 2 x 4 x 2 sixteen-bit
  * parameters) laid out so that a selected token is one aligned 128-byte line; 16 bytes are spare.
  * Quantisation function with B = 2, per token and per group x of 32 consecutive channels:
- *   zp = fp16(min x), qs = fp16((max x - min x) / 3), Q = clamp(round((x - zp) / qs), 0, 3)
+ *   zp = fp16(min x), qs = fp16((max x - min x) / 3), Q = clamp(round((x - zp) * (1 / qs)), 0, 3)
  *   with the stored qs and zp, round = nearest, ties to even, qs = 0 -> Q = 0; D = qs Q + zp.
- * V: x = the value.  K: x = |K - mu| / alpha with alpha[b,h,d] = max over the fitted tokens of
- * |K - mu| (alpha = 0 -> x = 0); the reconstructed centred key is s * alpha * D, s = +1 where the
- * sign bit is set.  Codes are decided in binary32 in this operation order.  Values must be
- * finite and within the fp16 range. */
+ * V: x = the value.  K: x = |K - mu| * (1 / alpha) with alpha[b,h,d] = max over the fitted tokens
+ * of |K - mu| (alpha = 0 -> x = 0); the reconstructed centred key is s * alpha * D, s = +1 where
+ * the sign bit is set.  Codes are decided in binary32 in this operation order (each reciprocal is
+ * one correctly rounded division).  Values must be finite and within the fp16 range. */
 #define SIK_KVQ_RECORD_BYTES 128
 
 /* Bytes of the record plane of a layout: B * Hkv * max_len * 128 (0 if the layout is invalid). */

@@ -359,13 +359,16 @@ int sik_oracle_append_rows(uint16_t *K, uint16_t *V, const uint16_t *k_new, cons
  * Per token, each run of 32 consecutive channels is one quantisation group
  * with B = 2 bits:
  *     zp = fp16(min x),  qs = fp16((max x - min x) / 3)       (stored, 16 bit)
- *     Q(x) = clamp(round((x - zp) / qs), 0, 3), round = nearest, ties to even;
- *            qs = 0 (constant group) gives Q = 0
+ *     Q(x) = clamp(round((x - zp) * (1 / qs)), 0, 3), round = nearest, ties to
+ *            even; qs = 0 (constant group) gives Q = 0
  *     D(x) = qs * Q(x) + zp
  * with the STORED (fp16-rounded) qs and zp used on both sides of the format.
- * For V, x is the value itself.  For K, x = |K'| / alpha with K' = K - mu
+ * For V, x is the value itself.  For K, x = |K'| * (1 / alpha) with K' = K - mu
  * (binary32 subtraction of the exactly widened key and the fp32 mean),
- * alpha_d = max over the fitted tokens of |K'_d|, and alpha_d = 0 gives x = 0;
+ * alpha_d = max over the fitted tokens of |K'_d|, and alpha_d = 0 gives x = 0.
+ * Both divisions of the paper's formulas are taken as multiplications by a
+ * binary32 reciprocal (one per channel, one per group): the paper fixes no
+ * precision or operation order, and this is the order the library uses;
  * the sign of K' is not quantised: it is the sign bit of the 1-bit code.
  * The dequantised key is  s * alpha * D(x),  s = +1 where the code bit is 1.
  * ========================================================================== */
@@ -436,10 +439,11 @@ static void quantize_group(const float *x, uint16_t *param /* qs, zp */, uint8_t
     param[1] = float_to_fp16_bits(lo);
     float qs = (float)fp16_to_double(param[0]);
     float zp = (float)fp16_to_double(param[1]);
+    volatile float rqs = qs > 0.0f ? 1.0f / qs : 0.0f;
     for (int e = 0; e < 32; ++e) {
         if (!(qs > 0.0f)) { code[e] = 0; continue; }
         volatile float diff = x[e] - zp;
-        volatile float t = diff / qs;
+        volatile float t = diff * rqs;
         float r = nearbyintf(t);
         code[e] = (uint8_t)(r < 0.0f ? 0 : (r > 3.0f ? 3 : (int)r));
     }
@@ -466,7 +470,8 @@ int sik_oracle_quantize_kv(const uint16_t *K, const uint16_t *V, int dtype, int 
                         int d = 32 * g + e;
                         volatile float kp = (float)widen(K[row * D + d], dtype) - mu[bh * D + d];
                         float a = alpha[bh * D + d];
-                        volatile float khat = a > 0.0f ? fabsf(kp) / a : 0.0f;
+                        volatile float ra = a > 0.0f ? 1.0f / a : 0.0f;
+                        volatile float khat = fabsf(kp) * ra;
                         xk[e] = khat;
                         xv[e] = (float)widen(V[row * D + d], dtype);
                     }

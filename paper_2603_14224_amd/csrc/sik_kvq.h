@@ -12,10 +12,12 @@
 // selected token costs one 128 B line instead of 2 x 256 B of 16-bit rows.
 //
 // Quantisation of a group x[0..31] (B = 2): zp = fp16(min x), qs = fp16((max x - min x) / 3),
-// Q = clamp(rint((x - zp) / qs), 0, 3) with the stored qs, zp (qs = 0 gives Q = 0), D = qs Q + zp.
-// V: x = the value.  K: x = |K - mu| / alpha (alpha = per-channel max of |K - mu| over the fitted
+// Q = clamp(rint((x - zp) * (1 / qs)), 0, 3) with the stored qs, zp (qs = 0 gives Q = 0), D = qs Q + zp.
+// V: x = the value.  K: x = |K - mu| * (1 / alpha) (alpha = per-channel max of |K - mu| over the fitted
 // tokens; alpha = 0 gives x = 0), the sign travels as the code bit: K' ~ s alpha D.
-// The codes are decided in binary32 in exactly this operation order.
+// The codes are decided in binary32 in exactly this operation order: the two divisions of the paper's
+// formulas are multiplications by a correctly rounded reciprocal (one per channel, one per group), which keeps
+// the quantiser bound by memory instead of by per-element divisions.
 #pragma once
 
 #include "sik_attn_core.h"
@@ -68,9 +70,10 @@ __device__ __forceinline__ uint32_t quantize_octet(const float (&x)[8], uint32_t
     const float qs = fp16_value(qs_h), zp = fp16_value(zp_h);
     uint32_t bits = 0u;
     if (qs > 0.0f) {
+        const float rqs = 1.0f / qs;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float r = rintf((x[e] - zp) / qs);
+            const float r = rintf((x[e] - zp) * rqs);
             const int c = static_cast<int>(fminf(fmaxf(r, 0.0f), 3.0f));
             bits |= static_cast<uint32_t>(c) << (2 * e);
         }
@@ -78,11 +81,15 @@ __device__ __forceinline__ uint32_t quantize_octet(const float (&x)[8], uint32_t
     return bits;
 }
 
+// 1 / alpha, and 0 for a channel that never leaves its mean.
+__device__ __forceinline__ float alpha_reciprocal(float alpha) { return alpha > 0.0f ? 1.0f / alpha : 0.0f; }
+
 // One 8-byte slot of a token's record from this lane's 8 key and 8 value elements (16-bit storage form),
-// the channel means and alphas of the same 8 channels, and p = slot index (lane within the 16-lane row).
+// the channel means and alpha reciprocals of the same 8 channels, and p = slot index (lane within the
+// 16-lane row).
 template <int DT>
 __device__ __forceinline__ uint2 kvq_make_slot(const uint4 kraw, const uint4 vraw, const float (&mu)[8],
-                                               const float (&alpha)[8], int p) {
+                                               const float (&ralpha)[8], int p) {
     float kf[8], vf[8], kh[8];
     widen8<DT>(kraw, kf);
     widen8<DT>(vraw, vf);
@@ -91,7 +98,7 @@ __device__ __forceinline__ uint2 kvq_make_slot(const uint4 kraw, const uint4 vra
     for (int e = 0; e < 8; ++e) {
         sign |= (kf[e] >= mu[e] ? 1u : 0u) << (7 - e);
         const float kp = kf[e] - mu[e];
-        kh[e] = alpha[e] > 0.0f ? fabsf(kp) / alpha[e] : 0.0f;
+        kh[e] = fabsf(kp) * ralpha[e];
     }
     uint32_t kqs, kzp, vqs, vzp;
     const uint32_t kbits = quantize_octet(kh, kqs, kzp);

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kBlock) void quantize_kv_kernel(const uint16_t* __r
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         m[e] = mu[static_cast<size_t>(unit) * kD + 8 * p + e];
-        a[e] = alpha[static_cast<size_t>(unit) * kD + 8 * p + e];
+        a[e] = alpha_reciprocal(alpha[static_cast<size_t>(unit) * kD + 8 * p + e]);
     }
     int i = start + r;
     for (; i + 16 < end; i += 32) {  // two rows (K and V of each) in flight per lane

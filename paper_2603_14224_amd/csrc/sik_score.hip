@@ -127,7 +127,7 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     // against the frozen mu and scores it from LDS, and head block 0 of that chunk also stores the row and
     // its code.  seq_len itself is incremented by the last workgroup of the kernel that follows.
     uint4 knew = make_uint4(0u, 0u, 0u, 0u), vnew = make_uint4(0u, 0u, 0u, 0u);
-    float m8[8] = {0, 0, 0, 0, 0, 0, 0, 0}, a8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float m8[8] = {0, 0, 0, 0, 0, 0, 0, 0}, a8[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // mu, 1 / alpha
     if (k_new && tid < 16) {
         knew = reinterpret_cast<const uint4*>(k_new + static_cast<size_t>(unit) * kD)[tid];
         vnew = reinterpret_cast<const uint4*>(v_new + static_cast<size_t>(unit) * kD)[tid];
@@ -138,8 +138,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
         if (kvq) {  // 2-bit cache: the row is stored as a record, which also needs the frozen alpha
             const float4 a0 = reinterpret_cast<const float4*>(alpha + static_cast<size_t>(unit) * kD)[2 * tid];
             const float4 a1 = reinterpret_cast<const float4*>(alpha + static_cast<size_t>(unit) * kD)[2 * tid + 1];
-            a8[0] = a0.x, a8[1] = a0.y, a8[2] = a0.z, a8[3] = a0.w;
-            a8[4] = a1.x, a8[5] = a1.y, a8[6] = a1.z, a8[7] = a1.w;
+            const float av[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a8[e] = alpha_reciprocal(av[e]);
         }
     }
     int L = seq_len[b];

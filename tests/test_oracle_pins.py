@@ -437,7 +437,9 @@ def test_alpha_and_two_bit_quantiser_against_numpy(oracle, dtype):
         L = int(sl[b])
         Kp = K32[b, :, :L] - mu[b, :, None, :]                      # binary32 subtraction
         assert np.array_equal(al[b], np.abs(Kp).max(axis=1))
-        khat = np.abs(Kp) / al[b, :, None, :]
+        with np.errstate(divide="ignore"):
+            ral = np.where(al[b] > 0, np.float32(1) / al[b], np.float32(0)).astype(np.float32)
+        khat = np.abs(Kp) * ral[:, None, :]
         for x, q, par in ((khat, qkv.kq, qkv.kpar), (V32[b, :, :L], qkv.vq, qkv.vpar)):
             g = x.reshape(x.shape[0], L, 4, 32)
             lo, hi = g.min(-1), g.max(-1)
@@ -447,7 +449,8 @@ def test_alpha_and_two_bit_quantiser_against_numpy(oracle, dtype):
             assert np.array_equal(par[b, :, :L, :, 1], zp16.view(np.uint16))
             qs, zp = qs16.astype(np.float32)[..., None], zp16.astype(np.float32)[..., None]
             with np.errstate(divide="ignore", invalid="ignore"):
-                want = np.where(qs > 0, np.clip(np.rint((g - zp) / qs), 0, 3), 0).astype(np.uint8)
+                rqs = (np.float32(1) / qs).astype(np.float32)
+                want = np.where(qs > 0, np.clip(np.rint((g - zp) * rqs), 0, 3), 0).astype(np.uint8)
             assert np.array_equal(q[b, :, :L].reshape(g.shape), want)
         assert not qkv.kq[b, :, L:].any() and not qkv.vpar[b, :, L:].any()   # untouched beyond seq_len
 
