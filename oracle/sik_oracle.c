@@ -570,3 +570,73 @@ int sik_oracle_sparse_attn_q2(const uint16_t *q, int dtype, const uint8_t *codes
         }
     return fail ? -1 : 0;
 }
+
+/* ---- sparse attention with full-precision forced rows next to records ----
+ * ("Full Precision Sink Tokens": a fixed set of tokens kept in 16 bits that always takes part
+ * in the sparse attention computation.)  The softmax runs over the union of
+ *   - the selected tokens idx[b,hq,:] (entries < 0 skipped), read from the 2-bit fields, and
+ *   - the forced rows fK, fV [B,Hkv,nf,D] (16-bit), row j counted when fvalid[b,h,j] != 0.
+ * The records hold the centred key K' = K - mu, so a forced key is centred the same way,
+ * K_f - mu, before its dot product (one softmax needs one common shift). */
+int sik_oracle_sparse_attn_q2_forced(const uint16_t *q, int dtype, const uint8_t *codes,
+                                     const uint8_t *kq, const uint16_t *kpar, const uint8_t *vq,
+                                     const uint16_t *vpar, const float *alpha, const float *mu,
+                                     const uint16_t *fK, const uint16_t *fV, const uint8_t *fvalid,
+                                     int nf, int B, int Hkv, int Hq, int Lmax, int D,
+                                     const int32_t *idx, int k, double scale, double *out)
+{
+    if (bad_shape(B, Hkv, Lmax, D) || D % 32 || Hq < 1 || Hq % Hkv || k < 1 || nf < 0) return -1;
+    if (dtype != 0 && dtype != 1) return -1;
+    int R = Hq / Hkv, NG = D / 32;
+    if (!(scale > 0.0)) scale = 1.0 / sqrt((double)D);
+    int fail = 0;
+#pragma omp parallel for collapse(2) num_threads(g_threads)
+    for (int b = 0; b < B; ++b)
+        for (int hq = 0; hq < Hq; ++hq) {
+            int64_t bh = (int64_t)b * Hkv + hq / R;
+            const uint16_t *qh = q + ((int64_t)b * Hq + hq) * D;
+            const int32_t *S = idx + ((int64_t)b * Hq + hq) * k;
+            double *o = out + ((int64_t)b * Hq + hq) * D;
+            int n = k + nf;
+            double *z = (double *)malloc(sizeof(double) * (size_t)n);
+            double *kd = (double *)malloc(sizeof(double) * (size_t)D * 2);
+            if (!z || !kd) { fail = 1; free(z); free(kd); continue; }
+            double *vd = kd + D;
+            double zmax = -INFINITY;
+            for (int pass = 0; pass < 2; ++pass) {
+                double denom = 0.0;
+                if (pass == 1)
+                    for (int d = 0; d < D; ++d) o[d] = 0.0;
+                for (int r = 0; r < n; ++r) {
+                    if (r < k) {                         /* a selected token, from its record */
+                        if (S[r] < 0 || S[r] >= Lmax) { z[r] = -INFINITY; continue; }
+                        int64_t row = bh * Lmax + S[r];
+                        dequant_row(codes + row * (D / 8), kq + row * D, kpar + row * NG * 2, vq + row * D,
+                                    vpar + row * NG * 2, alpha + bh * D, D, kd, vd);
+                    } else {                             /* a forced row, 16-bit, centred */
+                        int j = r - k;
+                        if (!fvalid[bh * nf + j]) { z[r] = -INFINITY; continue; }
+                        for (int d = 0; d < D; ++d) {
+                            kd[d] = widen(fK[(bh * nf + j) * D + d], dtype) - (double)mu[bh * D + d];
+                            vd[d] = widen(fV[(bh * nf + j) * D + d], dtype);
+                        }
+                    }
+                    if (pass == 0) {
+                        double dot = 0.0;
+                        for (int d = 0; d < D; ++d) dot += widen(qh[d], dtype) * kd[d];
+                        z[r] = dot * scale;
+                        if (z[r] > zmax) zmax = z[r];
+                    } else {
+                        double p = exp(z[r] - zmax);
+                        denom += p;
+                        for (int d = 0; d < D; ++d) o[d] += p * vd[d];
+                    }
+                }
+                if (pass == 1 && denom > 0.0)
+                    for (int d = 0; d < D; ++d) o[d] /= denom;
+            }
+            free(z);
+            free(kd);
+        }
+    return fail ? -1 : 0;
+}

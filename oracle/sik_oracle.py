@@ -317,3 +317,86 @@ def decode_step_q2(q, k_new, v_new, dtype, seq_len, mu, alpha_, cb, codes, qkv, 
     idx = topk(s, seq_len, k)
     out = sparse_attn_q2(q, dtype, codes, qkv, alpha_, idx, scale)
     return out, idx
+
+
+# --------------------------------------------------------------------------- forced-inclusion sets (sink tokens)
+def forced_valid(forced_idx, seq_len):
+    """Which entries of forced_idx [B,Hkv,nf] name a token: 0 <= idx < seq_len[b]."""
+    f = np.asarray(forced_idx, np.int32)
+    sl = np.asarray(seq_len, np.int32).reshape(-1, 1, 1)
+    return (f >= 0) & (f < sl)
+
+
+def topk_with_forced(scores, seq_len, k, forced_idx, R):
+    """Selection with a forced set: per (b, KV head) the valid forced tokens always take part and never
+    compete; every query head of the group then takes the k - (number of valid forced tokens) best of the
+    others.  Returns idx [B,Hq,k]: forced tokens first, then the dynamic picks, then -1."""
+    s = np.array(scores, np.float64, copy=True)
+    B, Hq, Lmax = s.shape
+    valid = forced_valid(forced_idx, seq_len)
+    idx = np.full((B, Hq, int(k)), -1, np.int32)
+    for b in range(B):
+        for h in range(Hq // R):
+            f = np.asarray(forced_idx)[b, h][valid[b, h]].astype(np.int32)
+            assert len(set(f.tolist())) == len(f), "forced tokens must be distinct"
+            assert len(f) < k, "the budget k must exceed the forced set"
+            rows = slice(h * R, (h + 1) * R)
+            s[b, rows][:, f] = -np.inf
+            kd = int(k) - len(f)
+            dyn = topk(s[b:b + 1, rows], np.asarray(seq_len, np.int32)[b:b + 1], kd)[0]
+            # a dynamic pick can never be a forced token: there are seq_len - len(f) others and kd of them exist
+            kd_eff = min(kd, int(seq_len[b]) - len(f))
+            dyn[:, kd_eff:] = -1
+            idx[b, rows, :len(f)] = f
+            idx[b, rows, len(f):len(f) + kd] = dyn
+    return idx
+
+
+def sparse_attn_q2_forced(q, dtype, codes, qkv, alpha_, mu, fK, fV, fvalid, idx, scale=0.0):
+    """Attention over records (idx) plus full-precision forced rows fK, fV [B,Hkv,nf,D] (valid where fvalid)."""
+    q = _c(q, np.uint16)
+    codes = _c(codes, np.uint8)
+    idx = _c(idx, np.int32)
+    fK, fV = _c(fK, np.uint16), _c(fV, np.uint16)
+    fv = _c(fvalid, np.uint8)
+    B, Hkv, Lmax, D = qkv.kq.shape
+    Hq, k, nf = q.shape[1], idx.shape[2], fK.shape[2]
+    out = np.empty((B, Hq, D), np.float64)
+    rc = lib().sik_oracle_sparse_attn_q2_forced(_p(q), _DT[dtype], _p(codes), _p(qkv.kq), _p(qkv.kpar), _p(qkv.vq),
+                                                _p(qkv.vpar), _p(_c(alpha_, np.float32)), _p(_c(mu, np.float32)),
+                                                _p(fK), _p(fV), _p(fv), nf, B, Hkv, Hq, Lmax, D, _p(idx), k,
+                                                ctypes.c_double(float(scale)), _p(out))
+    assert rc == 0
+    return out
+
+
+def decode_step_forced(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, k, forced_idx, scale=0.0):
+    """decode_step with a forced set on the 16-bit cache: forced tokens are read from the cache like the others."""
+    B, Hkv, Lmax, D = K.shape
+    if k_new is not None:
+        decode_step(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, 1, scale)  # append only; result unused
+    s = score(q, dtype, cb, codes, seq_len)
+    idx = topk_with_forced(s, seq_len, k, forced_idx, q.shape[1] // Hkv)
+    return sparse_attn(q, K, V, dtype, idx, scale), idx
+
+
+def decode_step_q2_forced(q, k_new, v_new, dtype, seq_len, mu, alpha_, cb, codes, qkv, k, forced_idx, fK=None,
+                          fV=None, scale=0.0):
+    """decode_step_q2 with a forced set.  With fK, fV (16-bit rows of the forced tokens, slot by slot) the forced
+    tokens are attended in full precision and only the dynamic picks come from records; otherwise all from
+    records.  Returns (out, idx) with idx = forced tokens, dynamic picks, -1."""
+    Hkv = qkv.kq.shape[1]
+    if k_new is not None:
+        decode_step_q2(q, k_new, v_new, dtype, seq_len, mu, alpha_, cb, codes, qkv, 1, scale)  # append only
+    s = score(q, dtype, cb, codes, seq_len)
+    idx = topk_with_forced(s, seq_len, k, forced_idx, q.shape[1] // Hkv)
+    if fK is None:
+        return sparse_attn_q2(q, dtype, codes, qkv, alpha_, idx, scale), idx
+    valid = forced_valid(forced_idx, seq_len)
+    R = q.shape[1] // Hkv
+    dyn = idx.copy()
+    for b in range(idx.shape[0]):
+        for h in range(Hkv):
+            dyn[b, h * R:(h + 1) * R, :int(valid[b, h].sum())] = -1   # the forced ones come from fK, fV instead
+    out = sparse_attn_q2_forced(q, dtype, codes, qkv, alpha_, mu, fK, fV, valid.astype(np.uint8), dyn, scale)
+    return out, idx

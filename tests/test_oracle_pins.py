@@ -549,3 +549,83 @@ def test_two_bit_decode_step_appends_against_frozen_parameters(oracle):
     assert out.shape == (2, 4, 128) and np.all(idx[1] < 41) and np.all(idx[0] < 65)
     ref = oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, al, idx)
     assert np.array_equal(ref, out)
+
+
+# =========================================================================== forced-inclusion sets (sink tokens)
+def forced_setup(oracle, seed=31, L=400, cap=None, shorter=123):
+    cfg = q2_cfg(batch=2, n_kv_heads=2, n_q_heads=8, context=L, top_k=40, seed=seed)
+    K, V = W.make_cache(cfg, capacity=cap or L, channel_offset_std=0.7)
+    sl = np.array([L, L - shorter], np.int32)
+    mu, codes, cb, _ = oracle.fit(K, cfg.dtype, sl)
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    rng = np.random.default_rng(seed)
+    forced = np.stack([np.stack([rng.choice(int(sl[b]), 12, replace=False) for _ in range(2)]) for b in range(2)])
+    forced = forced.astype(np.int32)
+    return cfg, K, V, sl, mu, codes, cb, q, kn, vn, forced
+
+
+def test_forced_set_selection_against_brute_force(oracle):
+    cfg, K, V, sl, mu, codes, cb, q, _, _, forced = forced_setup(oracle)
+    forced[0, 1, 3] = -1                 # unused slot
+    forced[1, 0, 5] = 399                # beyond seq_len[1] = 277: ignored
+    out, idx = oracle.decode_step_forced(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, 40, forced)
+    s = oracle.score(q, cfg.dtype, cb, codes, sl)
+    for b in range(2):
+        for hq in range(8):
+            h = hq // 4
+            f = [int(i) for i in forced[b, h] if 0 <= i < sl[b]]
+            got = [int(i) for i in idx[b, hq] if i >= 0]
+            assert len(got) == len(set(got)) == 40 and set(f) <= set(got)
+            others = np.array([i for i in range(int(sl[b])) if i not in f])
+            order = others[np.lexsort((others, -s[b, hq, others]))]
+            assert set(got) - set(f) == set(order[:40 - len(f)].tolist())
+    # the result is ordinary sparse attention over that set
+    assert np.array_equal(out, oracle.sparse_attn(q, K, V, cfg.dtype, idx))
+    # an empty forced set is the plain decode step
+    none = np.full((2, 2, 4), -1, np.int32)
+    out0, idx0 = oracle.decode_step_forced(q, None, None, K, V, cfg.dtype, sl.copy(), mu, cb, codes, 40, none)
+    ref0, ridx0 = oracle.decode_step(q, None, None, K, V, cfg.dtype, sl.copy(), mu, cb, codes, 40)
+    assert np.array_equal(np.sort(idx0, -1), np.sort(ridx0, -1)) and np.allclose(out0, ref0, rtol=1e-12, atol=1e-14)
+
+
+def test_forced_set_with_full_budget_is_dense_attention(oracle):
+    cfg, K, V, sl, mu, codes, cb, q, _, _, forced = forced_setup(oracle, seed=32, L=90, shorter=0)
+    out, idx = oracle.decode_step_forced(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, 90, forced)
+    Kf, Vf, qf = f64(K, cfg.dtype), f64(V, cfg.dtype), f64(q, cfg.dtype)
+    for b in range(2):
+        for hq in range(8):
+            assert sorted(idx[b, hq].tolist()) == list(range(90))
+            want = dense_attention(qf[b, hq], Kf[b, hq // 4, :90], Vf[b, hq // 4, :90], 1 / np.sqrt(128))
+            assert np.allclose(out[b, hq], want, rtol=1e-12, atol=1e-13)
+
+
+def test_forced_rows_in_full_precision_next_to_records(oracle):
+    cfg, K, V, sl, mu, codes, cb, q, kn, vn, forced = forced_setup(oracle, seed=33, L=300, cap=304)
+    al, qkv = oracle.fit_q2(K, V, cfg.dtype, sl, mu)
+    forced[0, 0, 0] = -1
+    fK = np.zeros((2, 2, 12, 128), np.uint16)
+    fV = np.zeros((2, 2, 12, 128), np.uint16)
+    for b in range(2):
+        for h in range(2):
+            for j in range(12):
+                if forced[b, h, j] >= 0:
+                    fK[b, h, j], fV[b, h, j] = K[b, h, forced[b, h, j]], V[b, h, forced[b, h, j]]
+    out, idx = oracle.decode_step_q2_forced(q, kn, vn, cfg.dtype, sl, mu, al, cb, codes, qkv, 40, forced, fK, fV)
+    assert sl.tolist() == [301, 178]
+    Kd, Vd = oracle.dequant_kv(codes, qkv, al, 0, 301)
+    qf = f64(q, cfg.dtype)
+    for b in range(2):
+        for hq in range(8):
+            h = hq // 4
+            f = [int(i) for i in forced[b, h] if i >= 0]
+            dyn = [int(i) for i in idx[b, hq] if i >= 0 and i not in f]
+            assert len(dyn) == 40 - len(f)
+            Kc = np.concatenate([Kd[b, h, dyn], f64(K[b, h, f], cfg.dtype) - mu[b, h].astype(np.float64)])
+            Vc = np.concatenate([Vd[b, h, dyn], f64(V[b, h, f], cfg.dtype)])
+            want = dense_attention(qf[b, hq], Kc, Vc, 1 / np.sqrt(128))
+            assert np.allclose(out[b, hq], want, rtol=1e-12, atol=1e-13)
+    # without the side rows everything comes from records
+    out_r, idx_r = oracle.decode_step_q2_forced(q, None, None, cfg.dtype, sl, mu, al, cb, codes, qkv, 40, forced)
+    assert np.array_equal(idx_r, idx)
+    assert np.array_equal(out_r, oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, al, idx))
+    assert not np.allclose(out_r, out, rtol=1e-6, atol=0)      # 2-bit and 16-bit forced rows do differ
