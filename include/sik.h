@@ -210,6 +210,46 @@ int sik_decode_step_q2(const sik_layout *layout, const void *q, const void *k_ne
                        void *out, int32_t *idx_out, void *workspace, size_t workspace_bytes,
                        void *stream, float *kernel_us);
 
+/* ---- forced-inclusion sets (section "Full Precision Sink Tokens"; decode-time tokens that are
+ * "always included", "Experimental Setup") ---------------------------------------------------
+ * The general decode step: everything sik_decode_step and sik_decode_step_q2 take, as one
+ * argument block, plus a set of tokens per (sequence, KV head) that always takes part in the
+ * attention of the R query heads of that KV head and never competes in the top-k:
+ *   forced_idx [B,Hkv,n_forced] int32 (device), n_forced <= 128; entries outside
+ *   [0, seq_len[b]) name no token (use -1 for unused slots; after an append the new token's
+ *   index is valid); the valid entries of one (b, h) must be distinct.
+ * The budget k counts the forced tokens: each query head attends its forced tokens and the
+ * k - (number of valid forced tokens of its KV head) best of the remaining ones (k > n_forced
+ * is required).  idx_out lists both kinds, order unspecified, -1 padded.
+ * forced_K / forced_V (2-bit cache only, both or neither): [B,Hkv,n_forced,D] kv_dtype rows of
+ * the forced tokens, slot by slot, kept in 16 bits by the caller; when given, the forced tokens
+ * are attended from these rows, each key centred by mu (the records hold the centred key),
+ * instead of from their records.
+ * Cache: K and V (16-bit rows) with kvq = NULL, or kvq and alpha (2-bit records) with K = V =
+ * NULL.  kernel_us as in sik_decode_step_q2.  Zero-initialise the block and set what applies. */
+typedef struct {
+    const void *q, *k_new, *v_new;
+    void *K, *V;
+    void *kvq;
+    const float *alpha;
+    int32_t *seq_len;
+    const float *mu, *codebook;
+    uint8_t *codes;
+    int32_t k;
+    float softmax_scale;
+    const int32_t *forced_idx;
+    int32_t n_forced;
+    const void *forced_K, *forced_V;
+    void *out;
+    int32_t *idx_out;
+    void *workspace;
+    size_t workspace_bytes;
+    void *stream;
+    float *kernel_us;
+} sik_decode_args;
+
+int sik_decode_step_ex(const sik_layout *layout, const sik_decode_args *args);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,13 +19,25 @@ _TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: S
 
 EXPORTS = ("sik_strerror", "sik_version", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
            "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_profiled", "sik_kvq_bytes",
-           "sik_quantize_kv", "sik_sparse_attn_q2", "sik_decode_step_q2")
+           "sik_quantize_kv", "sik_sparse_attn_q2", "sik_decode_step_q2", "sik_decode_step_ex")
 
 
 class SikError(RuntimeError):
     def __init__(self, status, text):
         super().__init__(f"sik status {status}: {text}")
         self.status = status
+
+
+class DecodeArgs(ctypes.Structure):
+    """sik_decode_args of include/sik.h."""
+    _fields_ = [("q", ctypes.c_void_p), ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p),
+                ("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("kvq", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+                ("seq_len", ctypes.c_void_p), ("mu", ctypes.c_void_p), ("codebook", ctypes.c_void_p),
+                ("codes", ctypes.c_void_p), ("k", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("forced_idx", ctypes.c_void_p), ("n_forced", ctypes.c_int32), ("forced_K", ctypes.c_void_p),
+                ("forced_V", ctypes.c_void_p), ("out", ctypes.c_void_p), ("idx_out", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p),
+                ("kernel_us", ctypes.POINTER(ctypes.c_float))]
 
 
 class Layout(ctypes.Structure):
@@ -70,6 +82,8 @@ def lib():
         L.sik_quantize_kv.argtypes = [lp, vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, vp, vp]
         L.sik_sparse_attn_q2.restype = ctypes.c_int
         L.sik_sparse_attn_q2.argtypes = [lp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
+        L.sik_decode_step_ex.restype = ctypes.c_int
+        L.sik_decode_step_ex.argtypes = [lp, ctypes.POINTER(DecodeArgs)]
         L.sik_decode_step_q2.restype = ctypes.c_int
         L.sik_decode_step_q2.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp,
                                          ctypes.POINTER(ctypes.c_float)]
@@ -170,6 +184,28 @@ def sik_decode_step_q2(layout, q, k_new, v_new, kvq, seq_len, mu, alpha, codeboo
                                     _ptr(seq_len), _ptr(mu), _ptr(alpha), _ptr(codebook), _ptr(codes), int(k),
                                     float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(workspace),
                                     workspace.numel() if workspace is not None else 0, _stream(), us))
+    return [float(x) for x in us] if profiled else None
+
+
+def sik_decode_step_ex(layout, *, q, seq_len, codebook, codes, k, out, workspace, k_new=None, v_new=None, K=None,
+                       V=None, kvq=None, alpha=None, mu=None, softmax_scale=0.0, forced_idx=None, forced_K=None,
+                       forced_V=None, idx_out=None, profiled=False):
+    """General decode step (argument block of include/sik.h): either cache format, optional forced set."""
+    us = (ctypes.c_float * 5)() if profiled else None
+
+    def vp(t):
+        return None if t is None else _ptr(t).value
+
+    st = _stream()
+
+    a = DecodeArgs(q=vp(q), k_new=vp(k_new), v_new=vp(v_new), K=vp(K), V=vp(V), kvq=vp(kvq), alpha=vp(alpha),
+                   seq_len=vp(seq_len), mu=vp(mu), codebook=vp(codebook), codes=vp(codes), k=int(k),
+                   softmax_scale=float(softmax_scale), forced_idx=vp(forced_idx),
+                   n_forced=0 if forced_idx is None else int(forced_idx.shape[-1]), forced_K=vp(forced_K),
+                   forced_V=vp(forced_V), out=vp(out), idx_out=vp(idx_out), workspace=vp(workspace),
+                   workspace_bytes=workspace.numel() if workspace is not None else 0,
+                   stream=None if st is None else st.value, kernel_us=us)
+    _check(lib().sik_decode_step_ex(ctypes.byref(layout), ctypes.byref(a)))
     return [float(x) for x in us] if profiled else None
 
 

@@ -124,7 +124,7 @@ int sik_score(const sik_layout* layout, const void* q, const float* codebook, co
     int rc = check_layout(layout, &d);
     if (rc) return rc;
     if (!q || !codebook || !codes || !seq_len || !scores) return SIK_ERR_NULL;
-    return launched(launch_score(d, nullptr, false, Append{}, q, codebook, codes, seq_len, scores,
+    return launched(launch_score(d, nullptr, false, Append{}, q, codebook, codes, seq_len, scores, nullptr, 0,
                                  static_cast<hipStream_t>(stream)));
 }
 
@@ -208,7 +208,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
                             void* K, void* V, void* kvq, const float* alpha, int32_t* seq_len, const float* mu,
                             const float* codebook, uint8_t* codes, int32_t k, float softmax_scale, void* out,
                             int32_t* idx_out, void* workspace, size_t workspace_bytes, void* stream,
-                            hipEvent_t* ev) {
+                            hipEvent_t* ev, const Forced& forced = Forced{}) {
     Dims d;
     int rc = check_layout(layout, &d);
     if (rc) return rc;
@@ -217,6 +217,12 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if ((k_new == nullptr) != (v_new == nullptr)) return SIK_ERR_NULL;
     if (k_new && !mu) return SIK_ERR_NULL;
     if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    if (forced.n < 0 || forced.n > kMaxForced) return SIK_ERR_SHAPE;
+    if (forced.n > 0 && !forced.idx) return SIK_ERR_NULL;
+    if (forced.n > 0 && k <= forced.n) return SIK_ERR_K_RANGE;  // the budget k counts the forced tokens too
+    if ((forced.fK == nullptr) != (forced.fV == nullptr)) return SIK_ERR_NULL;
+    if (forced.fK && (!kvq || forced.n == 0)) return SIK_ERR_FLAGS;  // side rows go with the 2-bit cache only
+    if (forced.fK && !mu) return SIK_ERR_NULL;
     Workspace w;
     rc = check_ws(d, k, workspace, workspace_bytes, &w);
     if (rc) return rc;
@@ -225,7 +231,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
     int fchunks, fchunk;
     const bool fused = fused_plan(d, &fchunks, &fchunk);
-    if (kvq && !fused) return SIK_ERR_SHAPE;  // the 2-bit cache has no unfused path: max_len <= 524288
+    if ((kvq || forced.n > 0) && !fused) return SIK_ERR_SHAPE;  // only the fused path: max_len <= 524288
     hipError_t e = mark(0);
     if (fused) {
         // Two launches: scoring (which also stores, encodes and scores an appended row and clears the
@@ -234,16 +240,20 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
         const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
                         static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
         if (e == hipSuccess) e = mark(1);
-        if (e == hipSuccess) e = launch_score(d, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, s);
+        if (e == hipSuccess)
+            e = launch_score(d, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, forced.idx,
+                             forced.n, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = mark(3);
         if (e == hipSuccess)
-            e = launch_fused(d, w, q, K, V, kvq, alpha, seq_len, k_new != nullptr, k, softmax_scale, idx_out, out, s);
+            e = launch_fused(d, w, q, K, V, kvq, alpha, Forced{forced.idx, forced.n, forced.fK, forced.fV, mu}, seq_len,
+                             k_new != nullptr, k, softmax_scale, idx_out, out, s);
     } else {
         // contexts beyond 512K tokens: prep (append + clear counters), score, select, attention
         if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
         if (e == hipSuccess) e = mark(1);
-        if (e == hipSuccess) e = launch_score(d, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, s);
+        if (e == hipSuccess)
+            e = launch_score(d, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
         if (e == hipSuccess) e = mark(3);
@@ -306,6 +316,18 @@ int sik_decode_step_q2(const sik_layout* layout, const void* q, const void* k_ne
         return decode_step_impl(layout, q, k_new, v_new, nullptr, nullptr, kvq, alpha, seq_len, mu, codebook, codes,
                                 k, softmax_scale, out, idx_out, workspace, workspace_bytes, stream, ev);
     });
+}
+
+int sik_decode_step_ex(const sik_layout* layout, const sik_decode_args* a) {
+    if (!a) return SIK_ERR_NULL;
+    const Forced forced{a->forced_idx, a->n_forced, static_cast<const uint16_t*>(a->forced_K),
+                        static_cast<const uint16_t*>(a->forced_V), a->mu};
+    auto run = [&](hipEvent_t* ev) {
+        return decode_step_impl(layout, a->q, a->k_new, a->v_new, a->K, a->V, a->kvq, a->alpha, a->seq_len, a->mu,
+                                a->codebook, a->codes, a->k, a->softmax_scale, a->out, a->idx_out, a->workspace,
+                                a->workspace_bytes, a->stream, ev, forced);
+    };
+    return a->kernel_us ? profiled(a->stream, a->kernel_us, run) : run(nullptr);
 }
 
 }  // extern "C"

@@ -39,11 +39,13 @@ __device__ __forceinline__ void store_out(void* out, size_t pos, float v) {
 // (0..15), it = 0, 1, ... while below n (a workgroup sharing one list uses first = 16 * wave,
 // step = 64; a wavefront with a private list first = 0, step = 16).  Negative or out-of-range
 // entries are skipped.  qraw holds this lane's 8 query components in their 16-bit storage form; the
-// logit is (q . k) * scale_log2e with scale_log2e = softmax_scale * log2(e).
+// logit is (q . k) * scale_log2e + zbias with scale_log2e = softmax_scale * log2(e); zbias (one constant per
+// query) lets rows of an uncentred key share a softmax with logits taken against the centred key.
 template <int DT, class Fetch>
 __device__ __forceinline__ void attend_list(Fetch fetch, int n, int first, int step,
                                             const uint4* __restrict__ Kp, const uint4* __restrict__ Vp,
-                                            const uint4 qraw, float scale_log2e, int Lmax, SoftmaxState& st) {
+                                            const uint4 qraw, float scale_log2e, int Lmax, SoftmaxState& st,
+                                            float zbias = 0.0f) {
     const int lane = threadIdx.x & 63;
     const int slot = lane >> 4, p = lane & 15;
     for (int base = first; base < n; base += step) {
@@ -67,7 +69,7 @@ __device__ __forceinline__ void attend_list(Fetch fetch, int n, int first, int s
             dot = dot2_acc<DT>(qraw.y, kv[u].y, dot);
             dot = dot2_acc<DT>(qraw.z, kv[u].z, dot);
             dot = dot2_acc<DT>(qraw.w, kv[u].w, dot);
-            dot = row16_sum(dot) * scale_log2e;
+            dot = fmaf(row16_sum(dot), scale_log2e, zbias);
             z[u] = id[u] >= 0 ? dot : kNegBig;
         }
         const float mnew = fmaxf(fmaxf(st.m, fmaxf(z[0], z[1])), fmaxf(z[2], z[3]));

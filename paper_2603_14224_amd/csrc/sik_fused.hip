@@ -43,7 +43,8 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const uint32_t* __restrict__ parthist, const float* __restrict__ binp, uint32_t* __restrict__ counters,
     uint32_t* __restrict__ cand, float* __restrict__ partial, int32_t* __restrict__ idx_ws,
     int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
-    int Lmax, int nchunk, int hchunks) {
+    int Lmax, int nchunk, int hchunks, const int32_t* __restrict__ forced_idx, int n_forced,
+    const uint16_t* __restrict__ fK, const uint16_t* __restrict__ fV, const float* __restrict__ mu) {
     constexpr int kChunk = 1024 * NQ;
     constexpr int kListCap = 512;  // selected-token slots per wavefront; flushed to the gather when half full
     __shared__ int32_t l_sel[kBlock / kWave][kListCap];
@@ -54,6 +55,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     __shared__ uint32_t lds4[4], sh[4];
     __shared__ int sthr[3], s_flag, s_over;
     __shared__ uint32_t s_ncand;
+    __shared__ int32_t s_fidx[kMaxForced];  // forced tokens of the KV head, -1 where the slot names no token
 
     SIK_TL(24);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, p = lane & 15;
@@ -79,6 +81,19 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         al1 = reinterpret_cast<const float4*>(alpha + unit * kD)[2 * p + 1];
     }
     const float lo = binp[row * 2], scale = binp[row * 2 + 1];
+    // Forced set (n_forced > 0): thread t < n_forced looks after entry t.  The scoring launch gave these tokens
+    // -infinity, so they are never selected below; workgroup 0 of the head attends them on top of its own.
+    int fi = -1;
+    if (tid < n_forced) fi = forced_idx[unit * n_forced + tid];
+    float mu_dot = 0.0f;  // q . mu over this lane's channels: centres the full-precision forced keys
+    if (KVQ && fK != nullptr && c == 0) {
+        float qf[8];
+        widen8<DT>(qraw, qf);
+        const float4 m0 = reinterpret_cast<const float4*>(mu + unit * kD)[2 * p];
+        const float4 m1 = reinterpret_cast<const float4*>(mu + unit * kD)[2 * p + 1];
+        mu_dot = qf[0] * m0.x + qf[1] * m0.y + qf[2] * m0.z + qf[3] * m0.w + qf[4] * m1.x + qf[5] * m1.y +
+                 qf[6] * m1.z + qf[7] * m1.w;
+    }
     const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hchunks);
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
@@ -87,14 +102,22 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const int nact = L > 0 ? (L + kChunk - 1) / kChunk : 1;
     if (c >= nact) return;  // no token of this chunk is valid; the ticket below counts nact workgroups
     const int end = min(L, start + kChunk);
-    const int kk = min(k, L);
+    int nfv = 0;  // forced tokens that exist: the dynamic budget and the competing population shrink by them
+    if (n_forced > 0) {
+        const bool fv = fi >= 0 && fi < L;
+        if (tid < kMaxForced) s_fidx[tid] = fv ? fi : -1;
+        nfv = __syncthreads_count(fv ? 1 : 0);
+        fi = fv ? fi : -1;
+    }
+    const int Lc = L - nfv;           // tokens that compete
+    const int kk = min(k - nfv, Lc);  // dynamic picks (the host guarantees k > n_forced)
     if (tid == 0) {
         s_over = 0;
         s_ncand = 0u;
     }
 
     // ---- 2. threshold bin ---------------------------------------------------------------------
-    const Threshold th = find_threshold(hl, kk, L, red, lds4, sthr);
+    const Threshold th = find_threshold(hl, kk, Lc, red, lds4, sthr);
     const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
     const bool ranked = nb <= kCandCap;
     SIK_TL(25);
@@ -126,8 +149,9 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     // bin(s) > b*  <=>  x >= b* + 1 and bin(s) == b*  <=>  b* <= x < b* + 1 with x = (s - lo) * scale,
     // the clamped end bins taking everything beyond them (score_bin is floor + clamp of the same x)
-    const float hi_f = bstar < 0 ? -INFINITY : (bstar == kBins - 1 ? INFINITY : static_cast<float>(bstar + 1));
-    const float lo_f = bstar <= 0 ? -INFINITY : static_cast<float>(bstar);
+    // (open ends are -FLT_MAX, not -infinity: a forced token's score is -infinity and must fail every test)
+    const float hi_f = bstar < 0 ? -3.4028235e38f : (bstar == kBins - 1 ? INFINITY : static_cast<float>(bstar + 1));
+    const float lo_f = bstar <= 0 ? -3.4028235e38f : static_cast<float>(bstar);
     const bool has_cand = bstar >= 0 && ranked;
     SoftmaxState st;
     init_state(st);
@@ -196,6 +220,31 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
                 st_agent(&pool[2 * slot], float_to_key(v));
                 st_agent(&pool[2 * slot + 1], tok);
             }
+        }
+    }
+    // Forced tokens: workgroup 0 of the head takes them on.  Read like every other token (16-bit cache, or
+    // 2-bit cache without side rows) they simply start the lists of the wavefronts that hold their entries;
+    // given as 16-bit side rows they are attended here, each logit shifted by -q . mu because the records
+    // they share the softmax with hold the centred key.
+    if (n_forced > 0 && c == 0) {
+        const bool fv = fi >= 0;
+        const uint64_t bf = __ballot(fv);
+        const bool side = KVQ && fK != nullptr;
+        if (!side) {
+            if (fv) mylist[__popcll(bf & lt_mask)] = fi;
+            n_sel = __popcll(bf);
+        } else {
+            if (idx_out && bf != 0ull) {
+                uint32_t base = 0u;
+                if (lane == 0) base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(__popcll(bf)));
+                base = static_cast<uint32_t>(__shfl(static_cast<int>(base), 0, 64));
+                if (fv) idx_out[static_cast<size_t>(row) * k + base + __popcll(bf & lt_mask)] = fi;
+            }
+            const float zbias = -row16_sum(mu_dot) * scale_log2e;
+            attend_list<DT>([&](int j) { return s_fidx[j] >= 0 ? j : -1; }, n_forced, wv * 16, (kBlock / kWave) * 16,
+                            reinterpret_cast<const uint4*>(fK + unit * n_forced * kD),
+                            reinterpret_cast<const uint4*>(fV + unit * n_forced * kD), qraw, scale_log2e, n_forced,
+                            st, zbias);
         }
     }
     // Stage B: compaction of the marked scores into the wavefront's list, one mask bit per lane and
@@ -358,7 +407,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
                 if (rank < need) {
                     const int32_t ia = static_cast<int32_t>(~static_cast<uint32_t>(lc2[a]));
                     chosen[rank] = ia;
-                    if (idx_out) olist[cgt + rank] = ia;
+                    if (idx_out) olist[nfv + cgt + rank] = ia;
                 }
             }
             __syncthreads();
@@ -367,10 +416,10 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         } else {
             // exact fallback: radix select over the members of b* in the whole row of scores
             radix_select_in_bin(scores + static_cast<size_t>(row) * sstride, L, lo, scale, bstar, need,
-                                olist + cgt, red, sh);
+                                olist + nfv + cgt, red, sh);
             __threadfence_block();
             __syncthreads();
-            const int32_t* gl = olist + cgt;
+            const int32_t* gl = olist + nfv + cgt;
             attend([&](int j) { return gl[j]; }, need, wv * kStep, (kBlock / kWave) * kStep, st);
         }
     }
@@ -400,7 +449,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, lt > 0.0f ? ot / lt : 0.0f);
     }
     if (idx_out)
-        for (int j = kk + tid; j < k; j += kBlock) olist[j] = -1;
+        for (int j = nfv + kk + tid; j < k; j += kBlock) olist[j] = -1;
     // the last query head of the sequence to finish publishes the new length: by then every workgroup of
     // every head of this sequence has read the old one
     if (grew && tid == 0) {
@@ -431,8 +480,8 @@ size_t fused_cand_words(const Dims& d) {
 
 template <int DT, int ODT>
 static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                                 const void* kvq, const float* alpha, int32_t* seq_len, bool appended, int k,
-                                 float scale, int32_t* idx_out, void* out, hipStream_t s) {
+                                 const void* kvq, const float* alpha, const Forced& fo, int32_t* seq_len,
+                                 bool appended, int k, float scale, int32_t* idx_out, void* out, hipStream_t s) {
     int nhb, hchunks, hchunk, nchunk, chunk;
     score_plan(d, &nhb, &hchunks, &hchunk);
     if (!fused_plan(d, &nchunk, &chunk)) return hipErrorInvalidValue;
@@ -445,7 +494,8 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
 #define SIK_FUSED_Q(NQV, KVQV)                                                                              \
     select_attend_kernel<DT, ODT, NQV, KVQV><<<grid, kBlock, 0, s>>>(                                       \
         qp, Kp, Vp, Rp, alpha, w.scores, w.sstride, seq_len, appended ? 1 : 0, w.parthist, w.binp, w.counters, \
-        w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks)
+        w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks, fo.idx, fo.n,    \
+        fo.fK, fo.fV, fo.mu)
 #define SIK_FUSED(NQV)                                                                                      \
     do {                                                                                                    \
         if (kvq) SIK_FUSED_Q(NQV, true); else SIK_FUSED_Q(NQV, false);                                      \
@@ -463,10 +513,10 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
 }
 
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        const void* kvq, const float* alpha, int32_t* seq_len, bool appended, int k, float scale,
-                        int32_t* idx_out, void* out, hipStream_t s) {
+                        const void* kvq, const float* alpha, const Forced& forced, int32_t* seq_len, bool appended,
+                        int k, float scale, int32_t* idx_out, void* out, hipStream_t s) {
 #define SIK_F(DTV, ODTV) \
-    launch_fused_t<DTV, ODTV>(d, w, q, K, V, kvq, alpha, seq_len, appended, k, scale, idx_out, out, s)
+    launch_fused_t<DTV, ODTV>(d, w, q, K, V, kvq, alpha, forced, seq_len, appended, k, scale, idx_out, out, s)
     if (d.kv_dtype == kBF16) return d.out_dtype == kF32 ? SIK_F(kBF16, kF32) : SIK_F(kBF16, kBF16);
     return d.out_dtype == kF32 ? SIK_F(kF16, kF32) : SIK_F(kF16, kF16);
 #undef SIK_F

@@ -61,9 +61,11 @@ struct Append {
 // zero_counters the per-head counters are cleared (decode step without a preceding prep launch).
 // With ap.k_new the new row of every (b, h) is encoded, stored and scored as token seq_len[b]; the
 // length itself is left for launch_fused to increment.
+// n_forced > 0 (with w): tokens of forced_idx [B, Hkv, n_forced] get score -infinity and no histogram count.
+constexpr int kMaxForced = 128;
 hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const Append& ap, const void* q,
                         const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
-                        hipStream_t s);
+                        const int32_t* forced_idx, int n_forced, hipStream_t s);
 hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
                             hipStream_t s);
 void score_plan(const Dims& d, int* nhb, int* nchunk, int* chunk);
@@ -78,9 +80,19 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
 // select + attention in one launch; reads w.scores / w.parthist / w.binp written by launch_score
 // `appended`: launch_score counted one more token than seq_len says; the last workgroup increments it
 // kvq != nullptr: gather records of the 2-bit cache (K, V unused) with the per-channel alpha
+// Forced set: n_forced entries per (b, KV head), always attended and outside the top-k (launch_score gave them
+// -infinity); with fK, fV (2-bit cache only) they are attended from those 16-bit rows [B, Hkv, n_forced, D],
+// centred by mu, instead of from their records.
+struct Forced {
+    const int32_t* idx;
+    int n;
+    const uint16_t* fK;
+    const uint16_t* fV;
+    const float* mu;
+};
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        const void* kvq, const float* alpha, int32_t* seq_len, bool appended, int k, float scale,
-                        int32_t* idx_out, void* out, hipStream_t s);
+                        const void* kvq, const float* alpha, const Forced& forced, int32_t* seq_len, bool appended,
+                        int k, float scale, int32_t* idx_out, void* out, hipStream_t s);
 bool fused_plan(const Dims& d, int* nchunk, int* chunk);
 size_t fused_cand_words(const Dims& d);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,

@@ -54,7 +54,10 @@ __device__ __forceinline__ void score_token(const uint4 code, const float4* lut,
     }
 }
 
-template <int DT, bool HIST, int BLK>
+// FORCED: tokens named in forced_idx [B, Hkv, n_forced] (entries outside [0, L) ignored) always take part in
+// the attention that follows and must not compete in the selection: their score is stored as -infinity and
+// they are left out of the histogram ("Full Precision Sink Tokens": a fixed set that is always attended).
+template <int DT, bool HIST, int BLK, bool FORCED>
 __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__ q,
                                                        const float* __restrict__ codebook,
                                                        const uint8_t* __restrict__ codes,
@@ -69,6 +72,7 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
                                                        const float* __restrict__ mu,
                                                        uint8_t* __restrict__ codes_w,
                                                        const float* __restrict__ alpha, uint2* __restrict__ kvq,
+                                                       const int32_t* __restrict__ forced_idx, int n_forced,
                                                        int Hkv, int Hq, int R,
                                                        int Lmax, int nchunk, int chunk, int nhb) {
     constexpr int HB = kHB;
@@ -78,6 +82,7 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     __shared__ float bp[HB][2];
     __shared__ uint32_t lhist[HIST ? HB * kBins : 1];
     __shared__ __align__(16) uint8_t newcode[kCodeBytes];
+    __shared__ uint32_t fbits[FORCED ? (kMaxChunkTokens + 32) / 32 : 1];  // one bit per token of the chunk
 
     SIK_TL(0);
     const int tid = threadIdx.x;
@@ -101,6 +106,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
         const int i = start + j * BLK + tid;
         cur[j] = i < cap_end ? cp[i] : make_uint4(0u, 0u, 0u, 0u);
     }
+    int fi = -1;  // forced token of this KV head that thread tid looks after
+    if constexpr (FORCED)
+        if (tid < n_forced) fi = forced_idx[static_cast<size_t>(unit) * n_forced + tid];
     constexpr int kEntPerThread = kG * 16 / BLK < 1 ? 1 : kG * 16 / BLK;  // table entries (g, j) per thread
     float4 cj[kEntPerThread];
 #pragma unroll
@@ -118,6 +126,8 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     }
     if constexpr (HIST) {
         for (int e = tid; e < HB * kBins; e += BLK) lhist[e] = 0u;
+        if constexpr (FORCED)
+            for (int e = tid; e < (chunk + 31) / 32; e += BLK) fbits[e] = 0u;
         // the kernels that follow count on zeroed per-head counters; when no prep launch precedes,
         // chunk 0 of each head block clears those of its heads
         if (zero_counters && c == 0 && tid < nh * 8) zero_counters[row0 * 8 + tid] = 0u;
@@ -177,6 +187,8 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     }
     const int end = min(L, start + chunk);
     __syncthreads();
+    if constexpr (FORCED)  // the barriers below order these bits before the scoring loop reads them
+        if (fi >= start && fi < end) atomicOr(&fbits[(fi - start) >> 5], 1u << ((fi - start) & 31));
     SIK_TL(1);
 
     // Table^(g)[j] for the HB query heads, fp32
@@ -257,13 +269,15 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
             if (tok == t_new) code[j] = *reinterpret_cast<const uint4*>(newcode);  // written before the barriers above
             score_token(code[j], lut, acc);
             if (tok < end) {
+                bool forced = false;
+                if constexpr (FORCED) forced = (fbits[(tok - start) >> 5] >> ((tok - start) & 31)) & 1u;
 #pragma unroll
                 for (int s = 0; s < HB; ++s) {
                     if (s < nh) {
                         // streamed once, read by the next kernel: keep it out of the way of the end-of-kernel write-back
-                        __builtin_nontemporal_store(acc[s], &scores[(row0 + s) * sstride + tok]);
+                        __builtin_nontemporal_store(forced ? -INFINITY : acc[s], &scores[(row0 + s) * sstride + tok]);
                         if constexpr (HIST)
-                            atomicAdd(&lhist[s * kBins + score_bin(acc[s], bp[s][0], bp[s][1])], 1u);
+                            if (!forced) atomicAdd(&lhist[s * kBins + score_bin(acc[s], bp[s][0], bp[s][1])], 1u);
                     }
                 }
             }
@@ -313,29 +327,32 @@ bool score_plan_ok(const Dims& d) {
 template <int DT>
 static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, const Append& ap, const void* q,
                                  const float* codebook, const uint8_t* codes, const int32_t* seq_len,
-                                 float* scores, hipStream_t s) {
+                                 float* scores, const int32_t* forced_idx, int n_forced, hipStream_t s) {
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
-#define SIK_SCORE(HV, BLKV)                                                                                  \
-    score_kernel<DT, HV, BLKV><<<grid, BLKV, 0, s>>>(                                                        \
+#define SIK_SCORE(HV, BLKV, FV)                                                                              \
+    score_kernel<DT, HV, BLKV, FV><<<grid, BLKV, 0, s>>>(                                                    \
         qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
         w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
-        ap.alpha, static_cast<uint2*>(ap.kvq), d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
+        ap.alpha, static_cast<uint2*>(ap.kvq), forced_idx, n_forced, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
     const bool wide = score_block(d, nhb) == 512;
-    if (!w) { if (wide) SIK_SCORE(false, 512); else SIK_SCORE(false, 256); }
-    else { if (wide) SIK_SCORE(true, 512); else SIK_SCORE(true, 256); }
+    if (!w) { if (wide) SIK_SCORE(false, 512, false); else SIK_SCORE(false, 256, false); }
+    else if (n_forced > 0) { if (wide) SIK_SCORE(true, 512, true); else SIK_SCORE(true, 256, true); }
+    else { if (wide) SIK_SCORE(true, 512, false); else SIK_SCORE(true, 256, false); }
 #undef SIK_SCORE
     return hipGetLastError();
 }
 
 hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const Append& ap, const void* q,
                         const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
-                        hipStream_t s) {
-    return d.kv_dtype == kBF16
-               ? launch_score_t<kBF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores, s)
-               : launch_score_t<kF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores, s);
+                        const int32_t* forced_idx, int n_forced, hipStream_t s) {
+    if (!w) n_forced = 0;  // forced sets belong to the decode step (histogram-producing launches)
+    return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores,
+                                                       forced_idx, n_forced, s)
+                               : launch_score_t<kF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores,
+                                                      forced_idx, n_forced, s);
 }
 
 }  // namespace sik

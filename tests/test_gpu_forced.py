@@ -1,0 +1,190 @@
+"""Parity of the decode step with forced-inclusion sets (always-attended tokens that stay out of the top-k)
+against the CPU oracle, on both cache formats, through sik_decode_step_ex.
+
+Bars as in the plain decode step: every valid forced token is in the index set exactly once; the dynamic part is
+the oracle's top-(k - forced) of the remaining tokens up to score ties within 1e-5 relative of its last pick;
+attention within 1e-5 relative (fp32 output) of the oracle's on the GPU's own index set.
+"""
+import numpy as np
+import pytest
+import torch
+
+import sik_workloads as W
+from helpers import dev
+from test_gpu_kvq import Q2State
+from test_gpu_parity import GpuState, TDT, cfg_small, check_attention, sync
+
+pytestmark = pytest.mark.gpu
+
+import paper_2603_14224_amd as sik  # noqa: E402
+
+
+def draw_forced(cfg, sl, n_forced, seed, spoil=True):
+    rng = np.random.default_rng(seed)
+    B, H = cfg.batch, cfg.n_kv_heads
+    f = np.full((B, H, n_forced), -1, np.int32)
+    for b in range(B):
+        for h in range(H):
+            m = min(n_forced, int(sl[b]))
+            f[b, h, :m] = rng.choice(int(sl[b]), m, replace=False) if m else []
+    if spoil and n_forced >= 4:
+        f[0, 0, 1] = -1                       # an unused slot
+        f[-1, -1, 2] = int(sl[-1]) + 5        # beyond the sequence: names no token
+    return f
+
+
+def check_sets(g_idx, ref_idx, s_ref, forced, sl, k, R):
+    """Forced tokens present once; the dynamic part agrees with the oracle's up to ties at its cut."""
+    B, Hq = g_idx.shape[:2]
+    n_diff = 0
+    for b in range(B):
+        for hq in range(Hq):
+            f = {int(i) for i in forced[b, hq // R] if 0 <= i < sl[b]}
+            g = [int(i) for i in g_idx[b, hq] if i >= 0]
+            r = [int(i) for i in ref_idx[b, hq] if i >= 0]
+            assert len(g) == len(set(g)) == len(r), (b, hq, len(g), len(r))
+            assert f <= set(g) and all(0 <= i < sl[b] for i in g)
+            diff = (set(g) ^ set(r))
+            if diff:
+                assert not (diff & f)
+                dyn_ref = [i for i in r if i not in f]
+                cut = min(s_ref[b, hq, i] for i in dyn_ref)
+                for i in diff:
+                    assert abs(s_ref[b, hq, i] - cut) <= 1e-5 * abs(cut), (b, hq, i)
+                n_diff += len(diff)
+    return n_diff
+
+
+def run_rows(oracle, cfg, capacity, steps, append, n_forced, seq_len=None, seed=1):
+    st = GpuState(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=0.8, out_dtype=torch.float32)
+    B, Hq, k = cfg.batch, cfg.n_q_heads, cfg.top_k
+    R = Hq // cfg.n_kv_heads
+    K, V, codes, sl = st.K, st.V, st.codes, st.sl.copy()
+    out = torch.empty(B, Hq, 128, device="cuda")
+    idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
+    for step in range(steps):
+        q, kn, vn = W.make_step_inputs(cfg, step)
+        forced = draw_forced(cfg, sl + (1 if append else 0), n_forced, seed + step)
+        if append:
+            forced[0, 0, 0] = sl[0]           # the token being appended may be forced too ("always included")
+        sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), k_new=dev(kn, cfg.dtype) if append else None,
+                               v_new=dev(vn, cfg.dtype) if append else None, K=st.dK, V=st.dV, seq_len=st.dsl,
+                               mu=st.dmu, codebook=st.dcb, codes=st.dcodes, k=k, out=out, idx_out=idx,
+                               forced_idx=torch.from_numpy(forced).cuda(), workspace=st.ws)
+        sync()
+        ref_out, ref_idx = oracle.decode_step_forced(q, kn if append else None, vn if append else None, K, V,
+                                                     cfg.dtype, sl, st.mu, st.cb, codes, k, forced)
+        assert np.array_equal(st.dsl.cpu().numpy(), sl)
+        g_idx = idx.cpu().numpy()
+        check_sets(g_idx, ref_idx, oracle.score(q, cfg.dtype, st.cb, codes, sl), forced, sl, k, R)
+        check_attention(out.cpu().numpy().astype(np.float64), oracle.sparse_attn(q, K, V, cfg.dtype, g_idx), True)
+
+
+def test_forced_rows_c1(oracle):
+    run_rows(oracle, W.CONFIGS["C1"], 4096, steps=2, append=False, n_forced=64)
+
+
+def test_forced_rows_c2_shape_with_append(oracle):
+    run_rows(oracle, cfg_small("C2", context=9000, top_k=160), 9004, steps=3, append=True, n_forced=64)
+
+
+def test_forced_rows_ragged_batch_gqa8_max_set(oracle):
+    cfg = cfg_small("C5", batch=3, n_kv_heads=2, n_q_heads=16, context=5000, top_k=300)
+    run_rows(oracle, cfg, 5008, steps=2, append=True, n_forced=128, seq_len=[5000, 40, 777])
+
+
+def test_forced_rows_everything_selected_and_tiny_sequences(oracle):
+    # k above the context: forced plus all the others; sequences shorter than the forced set
+    cfg = cfg_small("C2", batch=3, n_kv_heads=2, n_q_heads=4, context=600, top_k=700)
+    run_rows(oracle, cfg, 704, steps=1, append=False, n_forced=16, seq_len=[600, 5, 0])
+
+
+def test_forced_empty_set_equals_plain_step(oracle):
+    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=6000, top_k=128)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    a, b_ = torch.empty(1, 8, 128, device="cuda"), torch.empty(1, 8, 128, device="cuda")
+    none = torch.full((1, 2, 8), -1, dtype=torch.int32, device="cuda")
+    sik.sik_decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128,
+                        0.0, a, None, st.ws)
+    sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
+                           codebook=st.dcb, codes=st.dcodes, k=128, out=b_, forced_idx=none, workspace=st.ws)
+    sync()
+    assert torch.equal(a, b_)
+
+
+def run_q2(oracle, cfg, capacity, steps, append, n_forced, side_rows, seq_len=None, seed=5):
+    st = Q2State(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=0.8, out_dtype=torch.float32)
+    B, Hkv, Hq, k = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.top_k
+    R = Hq // Hkv
+    kvq = torch.from_numpy(st.records()).cuda()
+    dal = torch.from_numpy(st.alpha).cuda()
+    sl, codes, qkv = st.sl.copy(), st.codes, st.qkv
+    out = torch.empty(B, Hq, 128, device="cuda")
+    idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
+    for step in range(steps):
+        q, kn, vn = W.make_step_inputs(cfg, step)
+        forced = draw_forced(cfg, sl, n_forced, seed + step)      # sinks are prefill tokens
+        fK = np.zeros((B, Hkv, n_forced, 128), np.uint16)
+        fV = np.zeros((B, Hkv, n_forced, 128), np.uint16)
+        for b in range(B):
+            for h in range(Hkv):
+                for j, t in enumerate(forced[b, h]):
+                    if 0 <= t < sl[b]:
+                        fK[b, h, j], fV[b, h, j] = st.K[b, h, t], st.V[b, h, t]
+        sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), k_new=dev(kn, cfg.dtype) if append else None,
+                               v_new=dev(vn, cfg.dtype) if append else None, kvq=kvq, alpha=dal, seq_len=st.dsl,
+                               mu=st.dmu, codebook=st.dcb, codes=st.dcodes, k=k, out=out, idx_out=idx,
+                               forced_idx=torch.from_numpy(forced).cuda(),
+                               forced_K=dev(fK, cfg.dtype) if side_rows else None,
+                               forced_V=dev(fV, cfg.dtype) if side_rows else None, workspace=st.ws)
+        sync()
+        ref_out, ref_idx = oracle.decode_step_q2_forced(q, kn if append else None, vn if append else None, cfg.dtype,
+                                                        sl, st.mu, st.alpha, st.cb, codes, qkv, k, forced,
+                                                        fK if side_rows else None, fV if side_rows else None)
+        assert np.array_equal(st.dsl.cpu().numpy(), sl)
+        g_idx = idx.cpu().numpy()
+        check_sets(g_idx, ref_idx, oracle.score(q, cfg.dtype, st.cb, codes, sl), forced, sl, k, R)
+        if side_rows:
+            valid = oracle.forced_valid(forced, sl)
+            dyn = g_idx.copy()
+            for b in range(B):
+                for hq in range(Hq):
+                    f = {int(t) for t in forced[b, hq // R][valid[b, hq // R]]}
+                    dyn[b, hq] = [-1 if int(t) in f else t for t in g_idx[b, hq]]
+            ref = oracle.sparse_attn_q2_forced(q, cfg.dtype, codes, qkv, st.alpha, st.mu, fK, fV,
+                                               valid.astype(np.uint8), dyn)
+        else:
+            ref = oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, st.alpha, g_idx)
+        check_attention(out.cpu().numpy().astype(np.float64), ref, True)
+
+
+@pytest.mark.parametrize("side_rows", [False, True])
+def test_forced_q2_c2_shape_with_append(oracle, side_rows):
+    run_q2(oracle, cfg_small("C2", context=9000, top_k=160), 9004, steps=3, append=True, n_forced=64,
+           side_rows=side_rows)
+
+
+@pytest.mark.parametrize("side_rows", [False, True])
+def test_forced_q2_ragged_batch_fp16(oracle, side_rows):
+    cfg = cfg_small("C4", batch=4, n_kv_heads=2, n_q_heads=8, context=2048, top_k=200, dtype="fp16")
+    run_q2(oracle, cfg, 2052, steps=2, append=True, n_forced=100, side_rows=side_rows, seq_len=[2048, 3, 511, 0])
+
+
+def test_forced_argument_errors(oracle):
+    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=1000, top_k=64)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    out = torch.empty(1, 8, 128, device="cuda")
+    base = dict(q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu, codebook=st.dcb, codes=st.dcodes,
+                out=out, workspace=st.ws)
+    f64_ = torch.full((1, 2, 64), -1, dtype=torch.int32, device="cuda")
+    f200 = torch.full((1, 2, 200), -1, dtype=torch.int32, device="cuda")
+    rows = torch.zeros(1, 2, 64, 128, dtype=torch.bfloat16, device="cuda")
+    for kw, status in ((dict(k=64, forced_idx=f64_), -4),             # the budget must exceed the forced set
+                       (dict(k=64, forced_idx=f200), -2),             # more than 128 forced slots
+                       (dict(k=100, forced_idx=f64_, forced_K=rows, forced_V=rows), -8),   # side rows need the 2-bit cache
+                       (dict(k=100, forced_idx=f64_, forced_K=rows), -1)):
+        with pytest.raises(sik.SikError) as e:
+            sik.sik_decode_step_ex(st.layout, **base, **kw)
+        assert e.value.status == status, (kw.keys(), e.value.status)
