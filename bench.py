@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--kv", default="rows", choices=["rows", "q2"],
                     help="rows: 16-bit K/V rows (the headline metric); q2: the 2-bit token-wise cache, one 128-byte "
                          "record per token, dequantised inside the attention kernel")
+    ap.add_argument("--forced", type=int, default=0,
+                    help="forced-inclusion set of this many tokens per KV head (the paper's 64 sink tokens; with "
+                         "--kv q2 kept as 16-bit side rows); the budget top_k then counts them")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB): under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counters' scale factor")
@@ -106,6 +109,11 @@ def main():
                                 st["kvq"])
             torch.cuda.synchronize()
             st["K"] = st["V"] = None
+        if args.forced:  # the first tokens of the context, as attention sinks usually are
+            st["fidx"] = torch.arange(args.forced, dtype=torch.int32, device="cuda").repeat(B, Hkv, 1).contiguous()
+            if q2:
+                st["fK"] = dev(Kb[:, :, :args.forced], cfg.dtype).contiguous()
+                st["fV"] = dev(Vb[:, :, :args.forced], cfg.dtype).contiguous()
         if li == 0:
             host0 = (Kb, Vb)
         layers.append(st)
@@ -129,6 +137,11 @@ def main():
         j = i % n_q
         a = ((i - base) // n_layers) % n_new  # how many rows this layer has been given since its reset
         kn, vn = (kns[a], vns[a]) if cfg.append else (None, None)
+        if args.forced:
+            return sik.sik_decode_step_ex(lay, q=qs[j], k_new=kn, v_new=vn, K=st["K"], V=st["V"], kvq=st.get("kvq"),
+                                          alpha=st.get("alpha"), seq_len=st["sl"], mu=st["mu"], codebook=st["cb"],
+                                          codes=st["codes"], k=k, out=out, workspace=ws, forced_idx=st["fidx"],
+                                          forced_K=st.get("fK"), forced_V=st.get("fV"), profiled=profiled)
         if q2:
             return sik.sik_decode_step_q2(lay, qs[j], kn, vn, st["kvq"], st["sl"], st["mu"], st["alpha"], st["cb"],
                                           st["codes"], k, 0.0, out, None, ws, profiled=profiled)
@@ -215,7 +228,13 @@ def main():
     # ---- rows the gather really touches: query heads of one GQA group may select the same token
     idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
     st0 = layers[0]
-    if q2:
+    if args.forced:
+        sik.sik_decode_step_ex(lay, q=qs[0], k_new=kns[0] if cfg.append else None,
+                               v_new=vns[0] if cfg.append else None, K=st0["K"], V=st0["V"], kvq=st0.get("kvq"),
+                               alpha=st0.get("alpha"), seq_len=st0["sl"], mu=st0["mu"], codebook=st0["cb"],
+                               codes=st0["codes"], k=k, out=out, idx_out=idx, workspace=ws, forced_idx=st0["fidx"],
+                               forced_K=st0.get("fK"), forced_V=st0.get("fV"))
+    elif q2:
         sik.sik_decode_step_q2(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None,
                                st0["kvq"], st0["sl"], st0["mu"], st0["alpha"], st0["cb"], st0["codes"], k, 0.0, out,
                                idx, ws)
@@ -269,7 +288,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "head_dim": D,
-                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv, "append": cfg.append,
+                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv, "forced_tokens": args.forced, "append": cfg.append,
                    "layers_rotated": n_layers, "launch": launch},
         "effective_hbm_GBps": round(ab["total"] / sec_step / 1e9, 1),
         "effective_hbm_frac_of_8TBps": round(ab["total"] / sec_step / 1e9 / HBM_PEAK_GBPS, 4),
@@ -287,7 +306,7 @@ def main():
         "setup_seconds": round(gen_s, 1),
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.forced:
         result["cpu_baseline"] = cpu_baseline(cfg, host0, args.cpu_seconds, q2)
     print(json.dumps(result))
 
