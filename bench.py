@@ -8,7 +8,7 @@ Llama-3-8B-shaped 32K-context layer decode (batch 1, 8 KV heads, 32 query heads,
 top-k 1024, bf16).  Inputs are resident in HBM before the timed region; steps rotate over several
 distinct layer states so that the working set exceeds the 256 MB Infinity Cache.
 
-Prints ONE JSON line (see README / DESIGN for the fields).  One GPU only.
+Prints ONE JSON line.  One GPU only.
 """
 import argparse
 import json
@@ -25,7 +25,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel, from the FETCH_SIZE and WRITE_SIZE counter runs whose summary is
 # profiles/decode_step_C2_32k.md (counter units x the factor a 256 MiB plain copy calibrates: 2 KiB and 1 KiB).
 # Counters cannot be read from inside this process, so workloads without such a committed run report null.
-MEASURED_TRAFFIC_BYTES = {("C2", "select_attend_kernel"): int(14234.9 * 2048 + 301.2 * 1024)}
+MEASURED_TRAFFIC_BYTES = {("C2", "select_attend_kernel"): int(14253.3 * 2048 + 301.5 * 1024)}
 # event intervals of sik_decode_step_profiled, in launch order; the third one is empty when selection and
 # attention run fused in one launch (every benchmark workload)
 KERNELS = ("prep_kernel", "score_kernel", "select_kernel_unfused_only", "select_attend_kernel")
@@ -56,7 +56,7 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures ONE GPU (the path has no cross-GPU exchange; see DESIGN.md); "
+        print("bench.py: this build measures ONE GPU (batch and KV heads shard without any exchange); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         sys.exit(2)
 
