@@ -225,6 +225,10 @@ int sik_decode_step_q2(const sik_layout *layout, const void *q, const void *k_ne
  * the forced tokens, slot by slot, kept in 16 bits by the caller; when given, the forced tokens
  * are attended from these rows, each key centred by mu (the records hold the centred key),
  * instead of from their records.
+ * k_per_mille (0 = off, else 1..1000): a budget that follows the context length, as in the
+ * paper's "retains only 7.5 % of the tokens" setting (75): sequence b attends
+ * min(k, max(1, ceil(seq_len[b] * k_per_mille / 1000))) tokens (integer arithmetic; forced
+ * tokens counted, they may use the budget up); k stays the row length of idx_out.
  * Cache: K and V (16-bit rows) with kvq = NULL, or kvq and alpha (2-bit records) with K = V =
  * NULL.  kernel_us as in sik_decode_step_q2.  Zero-initialise the block and set what applies. */
 typedef struct {
@@ -236,6 +240,7 @@ typedef struct {
     const float *mu, *codebook;
     uint8_t *codes;
     int32_t k;
+    int32_t k_per_mille;
     float softmax_scale;
     const int32_t *forced_idx;
     int32_t n_forced;

@@ -327,10 +327,19 @@ def forced_valid(forced_idx, seq_len):
     return (f >= 0) & (f < sl)
 
 
-def topk_with_forced(scores, seq_len, k, forced_idx, R):
+def budget(k, seq_len_b, k_per_mille):
+    """Tokens sequence b attends: k, or with k_per_mille > 0 the smaller of k and ceil(L * k_per_mille / 1000)
+    (a fraction of the context such as the paper's 7.5 %), at least 1."""
+    if k_per_mille <= 0:
+        return int(k)
+    return min(int(k), max(1, (int(seq_len_b) * int(k_per_mille) + 999) // 1000))
+
+
+def topk_with_forced(scores, seq_len, k, forced_idx, R, k_per_mille=0):
     """Selection with a forced set: per (b, KV head) the valid forced tokens always take part and never
-    compete; every query head of the group then takes the k - (number of valid forced tokens) best of the
-    others.  Returns idx [B,Hq,k]: forced tokens first, then the dynamic picks, then -1."""
+    compete; every query head of the group then takes the budget - (number of valid forced tokens) best of
+    the others (none if the forced tokens fill the budget).  Returns idx [B,Hq,k]: forced tokens first, then
+    the dynamic picks, then -1."""
     s = np.array(scores, np.float64, copy=True)
     B, Hq, Lmax = s.shape
     valid = forced_valid(forced_idx, seq_len)
@@ -342,12 +351,14 @@ def topk_with_forced(scores, seq_len, k, forced_idx, R):
             assert len(f) < k, "the budget k must exceed the forced set"
             rows = slice(h * R, (h + 1) * R)
             s[b, rows][:, f] = -np.inf
-            kd = int(k) - len(f)
+            idx[b, rows, :len(f)] = f
+            kd = budget(k, seq_len[b], k_per_mille) - len(f)
+            if kd <= 0:
+                continue
             dyn = topk(s[b:b + 1, rows], np.asarray(seq_len, np.int32)[b:b + 1], kd)[0]
             # a dynamic pick can never be a forced token: there are seq_len - len(f) others and kd of them exist
             kd_eff = min(kd, int(seq_len[b]) - len(f))
             dyn[:, kd_eff:] = -1
-            idx[b, rows, :len(f)] = f
             idx[b, rows, len(f):len(f) + kd] = dyn
     return idx
 
@@ -370,13 +381,15 @@ def sparse_attn_q2_forced(q, dtype, codes, qkv, alpha_, mu, fK, fV, fvalid, idx,
     return out
 
 
-def decode_step_forced(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, k, forced_idx, scale=0.0):
-    """decode_step with a forced set on the 16-bit cache: forced tokens are read from the cache like the others."""
+def decode_step_forced(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, k, forced_idx, scale=0.0,
+                       k_per_mille=0):
+    """decode_step with a forced set (and optionally a budget that follows the context length) on the 16-bit
+    cache: forced tokens are read from the cache like the others."""
     B, Hkv, Lmax, D = K.shape
     if k_new is not None:
         decode_step(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, 1, scale)  # append only; result unused
     s = score(q, dtype, cb, codes, seq_len)
-    idx = topk_with_forced(s, seq_len, k, forced_idx, q.shape[1] // Hkv)
+    idx = topk_with_forced(s, seq_len, k, forced_idx, q.shape[1] // Hkv, k_per_mille)
     return sparse_attn(q, K, V, dtype, idx, scale), idx
 
 

@@ -217,6 +217,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if ((k_new == nullptr) != (v_new == nullptr)) return SIK_ERR_NULL;
     if (k_new && !mu) return SIK_ERR_NULL;
     if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    if (forced.k_per_mille < 0 || forced.k_per_mille > 1000) return SIK_ERR_K_RANGE;
     if (forced.n < 0 || forced.n > kMaxForced) return SIK_ERR_SHAPE;
     if (forced.n > 0 && !forced.idx) return SIK_ERR_NULL;
     if (forced.n > 0 && k <= forced.n) return SIK_ERR_K_RANGE;  // the budget k counts the forced tokens too
@@ -231,7 +232,8 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
     int fchunks, fchunk;
     const bool fused = fused_plan(d, &fchunks, &fchunk);
-    if ((kvq || forced.n > 0) && !fused) return SIK_ERR_SHAPE;  // only the fused path: max_len <= 524288
+    if ((kvq || forced.n > 0 || forced.k_per_mille > 0) && !fused)
+        return SIK_ERR_SHAPE;  // these run on the fused path only: max_len <= 524288
     hipError_t e = mark(0);
     if (fused) {
         // Two launches: scoring (which also stores, encodes and scores an appended row and clears the
@@ -246,7 +248,8 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = mark(3);
         if (e == hipSuccess)
-            e = launch_fused(d, w, q, K, V, kvq, alpha, Forced{forced.idx, forced.n, forced.fK, forced.fV, mu}, seq_len,
+            e = launch_fused(d, w, q, K, V, kvq, alpha,
+                             Forced{forced.idx, forced.n, forced.fK, forced.fV, mu, forced.k_per_mille}, seq_len,
                              k_new != nullptr, k, softmax_scale, idx_out, out, s);
     } else {
         // contexts beyond 512K tokens: prep (append + clear counters), score, select, attention
@@ -321,7 +324,7 @@ int sik_decode_step_q2(const sik_layout* layout, const void* q, const void* k_ne
 int sik_decode_step_ex(const sik_layout* layout, const sik_decode_args* a) {
     if (!a) return SIK_ERR_NULL;
     const Forced forced{a->forced_idx, a->n_forced, static_cast<const uint16_t*>(a->forced_K),
-                        static_cast<const uint16_t*>(a->forced_V), a->mu};
+                        static_cast<const uint16_t*>(a->forced_V), a->mu, a->k_per_mille};
     auto run = [&](hipEvent_t* ev) {
         return decode_step_impl(layout, a->q, a->k_new, a->v_new, a->K, a->V, a->kvq, a->alpha, a->seq_len, a->mu,
                                 a->codebook, a->codes, a->k, a->softmax_scale, a->out, a->idx_out, a->workspace,

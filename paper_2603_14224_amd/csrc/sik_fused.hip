@@ -44,7 +44,8 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     uint32_t* __restrict__ cand, float* __restrict__ partial, int32_t* __restrict__ idx_ws,
     int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
     int Lmax, int nchunk, int hchunks, const int32_t* __restrict__ forced_idx, int n_forced,
-    const uint16_t* __restrict__ fK, const uint16_t* __restrict__ fV, const float* __restrict__ mu) {
+    const uint16_t* __restrict__ fK, const uint16_t* __restrict__ fV, const float* __restrict__ mu,
+    int k_per_mille) {
     constexpr int kChunk = 1024 * NQ;
     constexpr int kListCap = 512;  // selected-token slots per wavefront; flushed to the gather when half full
     __shared__ int32_t l_sel[kBlock / kWave][kListCap];
@@ -109,15 +110,25 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         nfv = __syncthreads_count(fv ? 1 : 0);
         fi = fv ? fi : -1;
     }
-    const int Lc = L - nfv;           // tokens that compete
-    const int kk = min(k - nfv, Lc);  // dynamic picks (the host guarantees k > n_forced)
+    // Budget of this sequence: k, or with k_per_mille > 0 the smaller of k and ceil(L * k_per_mille / 1000) (a
+    // fraction of the context, in integer arithmetic), but at least one token.
+    const int kb = k_per_mille > 0 ? min(k, max(1, static_cast<int>((static_cast<int64_t>(L) * k_per_mille + 999) / 1000))) : k;
+    const int Lc = L - nfv;                     // tokens that compete
+    const int kk = max(0, min(kb - nfv, Lc));   // dynamic picks (the forced tokens may use up the budget)
     if (tid == 0) {
         s_over = 0;
         s_ncand = 0u;
     }
 
     // ---- 2. threshold bin ---------------------------------------------------------------------
-    const Threshold th = find_threshold(hl, kk, Lc, red, lds4, sthr);
+    Threshold th;
+    if (kk > 0) {
+        th = find_threshold(hl, kk, Lc, red, lds4, sthr);
+    } else {  // nothing to pick (empty sequence, or a budget the forced tokens fill): every test below fails
+        th.bstar = kBins;
+        th.cgt = 0;
+        th.nb = 0;
+    }
     const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
     const bool ranked = nb <= kCandCap;
     SIK_TL(25);
@@ -150,9 +161,9 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     // bin(s) > b*  <=>  x >= b* + 1 and bin(s) == b*  <=>  b* <= x < b* + 1 with x = (s - lo) * scale,
     // the clamped end bins taking everything beyond them (score_bin is floor + clamp of the same x)
     // (open ends are -FLT_MAX, not -infinity: a forced token's score is -infinity and must fail every test)
-    const float hi_f = bstar < 0 ? -3.4028235e38f : (bstar == kBins - 1 ? INFINITY : static_cast<float>(bstar + 1));
-    const float lo_f = bstar <= 0 ? -3.4028235e38f : static_cast<float>(bstar);
-    const bool has_cand = bstar >= 0 && ranked;
+    const float hi_f = bstar < 0 ? -3.4028235e38f : (bstar >= kBins - 1 ? INFINITY : static_cast<float>(bstar + 1));
+    const float lo_f = bstar <= 0 ? -3.4028235e38f : (bstar >= kBins ? INFINITY : static_cast<float>(bstar));
+    const bool has_cand = bstar >= 0 && bstar < kBins && ranked;
     SoftmaxState st;
     init_state(st);
     int32_t* mylist = l_sel[wv];
@@ -495,7 +506,7 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     select_attend_kernel<DT, ODT, NQV, KVQV><<<grid, kBlock, 0, s>>>(                                       \
         qp, Kp, Vp, Rp, alpha, w.scores, w.sstride, seq_len, appended ? 1 : 0, w.parthist, w.binp, w.counters, \
         w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks, fo.idx, fo.n,    \
-        fo.fK, fo.fV, fo.mu)
+        fo.fK, fo.fV, fo.mu, fo.k_per_mille)
 #define SIK_FUSED(NQV)                                                                                      \
     do {                                                                                                    \
         if (kvq) SIK_FUSED_Q(NQV, true); else SIK_FUSED_Q(NQV, false);                                      \

@@ -89,6 +89,7 @@ struct Forced {
     const uint16_t* fK;
     const uint16_t* fV;
     const float* mu;
+    int k_per_mille;  // > 0: per-sequence budget min(k, ceil(L * k_per_mille / 1000)) (rides along in this block)
 };
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                         const void* kvq, const float* alpha, const Forced& forced, int32_t* seq_len, bool appended,

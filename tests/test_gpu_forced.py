@@ -188,3 +188,48 @@ def test_forced_argument_errors(oracle):
         with pytest.raises(sik.SikError) as e:
             sik.sik_decode_step_ex(st.layout, **base, **kw)
         assert e.value.status == status, (kw.keys(), e.value.status)
+
+
+# --------------------------------------------------------------------------- budgets that follow the context
+@pytest.mark.parametrize("per_mille,n_forced", [(75, 0), (75, 16), (4, 16), (1000, 0)])
+def test_budget_per_mille_ragged_batch(oracle, per_mille, n_forced):
+    # 7.5 % of each sequence's own length; 0.4 %: the forced tokens fill (or exceed) the budget; 100 %: capped by k
+    cfg = cfg_small("C2", batch=4, n_kv_heads=2, n_q_heads=8, context=6000, top_k=500)
+    st = GpuState(cfg, oracle, capacity=6000, seq_len=[6000, 2500, 40, 0], offset_std=0.5, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    forced = draw_forced(cfg, st.sl, max(n_forced, 1), 3, spoil=False)
+    if n_forced == 0:
+        forced[:] = -1
+    out = torch.empty(4, 8, 128, device="cuda")
+    idx = torch.empty(4, 8, 500, dtype=torch.int32, device="cuda")
+    sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
+                           codebook=st.dcb, codes=st.dcodes, k=500, k_per_mille=per_mille, out=out, idx_out=idx,
+                           forced_idx=torch.from_numpy(forced).cuda(), workspace=st.ws)
+    sync()
+    sl = st.sl.copy()
+    ref_out, ref_idx = oracle.decode_step_forced(q, None, None, st.K, st.V, cfg.dtype, sl, st.mu, st.cb, st.codes, 500,
+                                                 forced, k_per_mille=per_mille)
+    g_idx = idx.cpu().numpy()
+    for b in range(4):
+        want = max(oracle.budget(500, sl[b], per_mille), int(((forced[b, 0] >= 0) & (forced[b, 0] < sl[b])).sum()))
+        assert int((g_idx[b, 0] >= 0).sum()) == min(want, int(sl[b]))
+    check_sets(g_idx, ref_idx, oracle.score(q, cfg.dtype, st.cb, st.codes, sl), forced, sl, 500, 4)
+    check_attention(out.cpu().numpy().astype(np.float64), oracle.sparse_attn(q, st.K, st.V, cfg.dtype, g_idx), True)
+
+
+def test_sign_only_retrieval_is_a_codebook_of_signs(oracle):
+    # the ablation's "sign-only retrieval" (similarity from the sign bits alone) needs no kernel of its own: with
+    # the centroid of Code j set to its sign pattern, the table lookup sums q_d * sign_d
+    cfg = cfg_small("C2", batch=1, n_kv_heads=2, n_q_heads=8, context=3000, top_k=64)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    j = np.arange(16)
+    pattern = np.stack([2.0 * ((j >> (3 - e)) & 1) - 1.0 for e in range(4)], axis=-1).astype(np.float32)   # [16, 4]
+    cb = np.broadcast_to(pattern, (1, 2, 32, 16, 4)).copy()
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    scores = torch.empty(1, 8, 3000, device="cuda")
+    sik.sik_score(st.layout, dev(q, cfg.dtype), torch.from_numpy(cb).cuda(), st.dcodes, st.dsl, scores)
+    sync()
+    signs = 2.0 * np.unpackbits(st.codes, axis=-1, bitorder="big").astype(np.float64) - 1.0     # [1, 2, 3000, 128]
+    qf = W.from_bits(q, cfg.dtype).astype(np.float64)
+    want = np.einsum("hd,hld->hl", qf[0], np.repeat(signs[0], 4, axis=0))
+    assert np.abs(scores.cpu().numpy()[0] - want).max() <= 1e-5 * np.abs(want).max()

@@ -629,3 +629,23 @@ def test_forced_rows_in_full_precision_next_to_records(oracle):
     assert np.array_equal(idx_r, idx)
     assert np.array_equal(out_r, oracle.sparse_attn_q2(q, cfg.dtype, codes, qkv, al, idx))
     assert not np.allclose(out_r, out, rtol=1e-6, atol=0)      # 2-bit and 16-bit forced rows do differ
+
+
+def test_budget_that_follows_the_context_length(oracle):
+    # 7.5 % of the context ("retains only 7.5 % of the tokens"), integer ceiling, capped by k, at least 1
+    assert [oracle.budget(4000, L, 75) for L in (32768, 1000, 13, 1, 0, 100000)] == [2458, 75, 1, 1, 1, 4000]
+    assert oracle.budget(64, 999, 0) == 64
+    cfg, K, V, sl, mu, codes, cb, q, _, _, forced = forced_setup(oracle, seed=34)
+    none = np.full((2, 2, 1), -1, np.int32)
+    out, idx = oracle.decode_step_forced(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, 60, none, k_per_mille=75)
+    s = oracle.score(q, cfg.dtype, cb, codes, sl)
+    for b, kb in ((0, 30), (1, 21)):            # ceil(400 * 0.075), ceil(277 * 0.075)
+        for hq in range(8):
+            got = [int(i) for i in idx[b, hq] if i >= 0]
+            order = np.lexsort((np.arange(int(sl[b])), -s[b, hq, :sl[b]]))
+            assert len(got) == kb and set(got) == set(order[:kb].tolist())
+    # forced tokens count towards the budget and may use it up: 12 forced of a budget of 10 leave no pick
+    out2, idx2 = oracle.decode_step_forced(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, 60, forced, k_per_mille=25)
+    for b in range(2):
+        for hq in range(8):
+            assert sorted(i for i in idx2[b, hq] if i >= 0) == sorted(forced[b, hq // 4].tolist())
