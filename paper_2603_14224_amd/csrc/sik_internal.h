@@ -21,13 +21,16 @@ struct Workspace {
     // zeroed by the prep kernel at the start of every call that selects or attends
     uint32_t* zero_begin;   // start of the zero-initialised region
     size_t zero_words;      // its length in 32-bit words
-    uint32_t* counters;     // [rows][8]          0 sel_cnt, 1 cand_cnt, 2 select ticket, 3 attn ticket,
-                            //                    4 ~min key, 5 max key (stand-alone top-k), 
+    uint32_t* counters;     // [rows][8]  0 index-output reservation, 1 candidate count (stand-alone selector),
+                            //            2 select ticket, 3 attention / fused ticket, 4 ~min key (stand-alone
+                            //            top-k) or candidate-pool reservation (fused kernel), 5 max key
+                            //            (stand-alone top-k), 7 of a sequence's first head: heads finished
     // plain scratch
     uint32_t* parthist;     // [rows][nchunk][kBins/2]  per-chunk histograms, two 16-bit counts per word
     float* binp;            // [rows][2]          histogram origin, scale
-    uint32_t* cand;         // per row: (key, index) of threshold-bin members; [kCandCap][2] words for the
-                            // stand-alone selector, [nchunk][136] words for the fused kernel
+    uint32_t* cand;         // (key, index) of threshold-bin members: per row [kCandCap][2] words for the
+                            // stand-alone selector; for the fused kernel per row [33][4 * nchunk] words of
+                            // wavefront regions, then per row an overflow pool of [kCandCap][2] words
     int32_t* idx;           // [rows][k]          selection when the caller passes no idx_out
     float* partial;         // [rows][kMaxSplit][D + 2]  split softmax partials (m, l, o[D])
     float* scores;          // [rows][sstride]    decode step only
