@@ -413,3 +413,23 @@ def decode_step_q2_forced(q, k_new, v_new, dtype, seq_len, mu, alpha_, cb, codes
             dyn[b, h * R:(h + 1) * R, :int(valid[b, h].sum())] = -1   # the forced ones come from fK, fV instead
     out = sparse_attn_q2_forced(q, dtype, codes, qkv, alpha_, mu, fK, fV, valid.astype(np.uint8), dyn, scale)
     return out, idx
+
+
+# --------------------------------------------------------------------------- group-shared selection
+def shared_scores(q, dtype, cb, codes, seq_len):
+    """Scores of a KV head = sum of the scores of its R query heads: [B, Hkv, Lmax] fp64 (-inf beyond seq_len)."""
+    s = score(q, dtype, cb, codes, seq_len)
+    B, Hq, Lmax = s.shape
+    Hkv = codes.shape[1]
+    return s.reshape(B, Hkv, Hq // Hkv, Lmax).sum(axis=2)
+
+
+def decode_step_shared(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, k, scale=0.0):
+    """Decode step with ONE index set per KV head, shared by the R query heads of its group: the k tokens with
+    the largest summed score (ties to the smaller index).  Each query head then attends over that set with its
+    own query.  Returns (out [B,Hq,D] fp64, idx [B,Hkv,k])."""
+    if k_new is not None:
+        decode_step(q, k_new, v_new, K, V, dtype, seq_len, mu, cb, codes, 1, scale)   # append only
+    idx_kv = topk(shared_scores(q, dtype, cb, codes, seq_len), seq_len, k)
+    R = q.shape[1] // K.shape[1]
+    return sparse_attn(q, K, V, dtype, np.repeat(idx_kv, R, axis=1), scale), idx_kv

@@ -649,3 +649,38 @@ def test_budget_that_follows_the_context_length(oracle):
     for b in range(2):
         for hq in range(8):
             assert sorted(i for i in idx2[b, hq] if i >= 0) == sorted(forced[b, hq // 4].tolist())
+
+
+def test_group_shared_selection_is_the_summed_query(oracle):
+    cfg = q2_cfg(batch=2, n_kv_heads=2, n_q_heads=8, context=500, top_k=30, seed=51)
+    K, V = W.make_cache(cfg, channel_offset_std=0.8)
+    sl = np.array([500, 211], np.int32)
+    mu, codes, cb, _ = oracle.fit(K, cfg.dtype, sl)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    s_kv = oracle.shared_scores(q, cfg.dtype, cb, codes, sl)
+    # the lookup table is linear in the query: summed scores = (sum of the group's queries) . reconstructed key
+    qsum = f64(q, cfg.dtype).reshape(2, 2, 4, 128).sum(axis=2)
+    for b in range(2):
+        for h in range(2):
+            L = int(sl[b])
+            nib = np.stack([codes[b, h, :L] >> 4, codes[b, h, :L] & 15], axis=-1).reshape(L, 32)
+            Khat = cb[b, h][np.arange(32)[None, :], nib].reshape(L, 128).astype(np.float64)
+            assert np.allclose(s_kv[b, h, :L], Khat @ qsum[b, h], rtol=1e-12, atol=1e-12)
+            assert np.all(np.isneginf(s_kv[b, h, L:]))
+    out, idx = oracle.decode_step_shared(q, None, None, K, V, cfg.dtype, sl, mu, cb, codes, 30)
+    assert idx.shape == (2, 2, 30)
+    for b in range(2):
+        for h in range(2):
+            L = int(sl[b])
+            order = np.lexsort((np.arange(L), -s_kv[b, h, :L]))
+            assert idx[b, h].tolist() == order[:30].tolist()
+    assert np.array_equal(out, oracle.sparse_attn(q, K, V, cfg.dtype, np.repeat(idx, 4, axis=1)))
+    # one query head per KV head: nothing to share, the plain decode step
+    cfg1 = q2_cfg(batch=1, n_kv_heads=2, n_q_heads=2, context=300, top_k=20, seed=52)
+    K1, V1 = W.make_cache(cfg1)
+    sl1 = np.array([300], np.int32)
+    mu1, codes1, cb1, _ = oracle.fit(K1, cfg1.dtype, sl1)
+    q1, _, _ = W.make_step_inputs(cfg1, 0)
+    o_s, i_s = oracle.decode_step_shared(q1, None, None, K1, V1, cfg1.dtype, sl1, mu1, cb1, codes1, 20)
+    o_p, i_p = oracle.decode_step(q1, None, None, K1, V1, cfg1.dtype, sl1, mu1, cb1, codes1, 20)
+    assert np.array_equal(i_s, i_p) and np.array_equal(o_s, o_p)
