@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--forced", type=int, default=0,
                     help="forced-inclusion set of this many tokens per KV head (the paper's 64 sink tokens; with "
                          "--kv q2 kept as 16-bit side rows); the budget top_k then counts them")
+    ap.add_argument("--shared", action="store_true",
+                    help="group-shared selection: one index set per KV head from the summed scores of its query heads")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB): under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counters' scale factor")
@@ -137,11 +139,12 @@ def main():
         j = i % n_q
         a = ((i - base) // n_layers) % n_new  # how many rows this layer has been given since its reset
         kn, vn = (kns[a], vns[a]) if cfg.append else (None, None)
-        if args.forced:
+        if args.forced or args.shared:
             return sik.sik_decode_step_ex(lay, q=qs[j], k_new=kn, v_new=vn, K=st["K"], V=st["V"], kvq=st.get("kvq"),
                                           alpha=st.get("alpha"), seq_len=st["sl"], mu=st["mu"], codebook=st["cb"],
-                                          codes=st["codes"], k=k, out=out, workspace=ws, forced_idx=st["fidx"],
-                                          forced_K=st.get("fK"), forced_V=st.get("fV"), profiled=profiled)
+                                          codes=st["codes"], k=k, out=out, workspace=ws, forced_idx=st.get("fidx"),
+                                          forced_K=st.get("fK"), forced_V=st.get("fV"), group_shared=args.shared,
+                                          profiled=profiled)
         if q2:
             return sik.sik_decode_step_q2(lay, qs[j], kn, vn, st["kvq"], st["sl"], st["mu"], st["alpha"], st["cb"],
                                           st["codes"], k, 0.0, out, None, ws, profiled=profiled)
@@ -228,12 +231,15 @@ def main():
     # ---- rows the gather really touches: query heads of one GQA group may select the same token
     idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
     st0 = layers[0]
-    if args.forced:
+    if args.shared:
+        idx = torch.empty(B, Hkv, k, dtype=torch.int32, device="cuda")
+    if args.forced or args.shared:
         sik.sik_decode_step_ex(lay, q=qs[0], k_new=kns[0] if cfg.append else None,
                                v_new=vns[0] if cfg.append else None, K=st0["K"], V=st0["V"], kvq=st0.get("kvq"),
                                alpha=st0.get("alpha"), seq_len=st0["sl"], mu=st0["mu"], codebook=st0["cb"],
-                               codes=st0["codes"], k=k, out=out, idx_out=idx, workspace=ws, forced_idx=st0["fidx"],
-                               forced_K=st0.get("fK"), forced_V=st0.get("fV"))
+                               codes=st0["codes"], k=k, out=out, idx_out=idx, workspace=ws,
+                               forced_idx=st0.get("fidx"), forced_K=st0.get("fK"), forced_V=st0.get("fV"),
+                               group_shared=args.shared)
     elif q2:
         sik.sik_decode_step_q2(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None,
                                st0["kvq"], st0["sl"], st0["mu"], st0["alpha"], st0["cb"], st0["codes"], k, 0.0, out,
@@ -265,6 +271,9 @@ def main():
     if q2:  # a selected (query head, token) costs one 128-byte record instead of 2 x 256 bytes of rows
         ab = dict(ab, gathered=ab["gathered"] // 4)
         ab["total"] = ab["codes"] + ab["gathered"]
+    if args.shared:  # the R query heads of a KV head attend over one set of rows
+        ab = dict(ab, gathered=ab["gathered"] // (Hq // Hkv))
+        ab["total"] = ab["codes"] + ab["gathered"]
     alg_by_kernel = {"prep_kernel": (B * Hkv * (2 * D * 2 + D // 8)) if cfg.append else 0,
                      "score_kernel": ab["codes"], "select_kernel_unfused_only": 0,
                      "select_attend_kernel": ab["gathered"]}
@@ -288,7 +297,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "head_dim": D,
-                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv, "forced_tokens": args.forced, "append": cfg.append,
+                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv, "forced_tokens": args.forced, "group_shared": args.shared, "append": cfg.append,
                    "layers_rotated": n_layers, "launch": launch},
         "effective_hbm_GBps": round(ab["total"] / sec_step / 1e9, 1),
         "effective_hbm_frac_of_8TBps": round(ab["total"] / sec_step / 1e9 / HBM_PEAK_GBPS, 4),
@@ -306,7 +315,7 @@ def main():
         "setup_seconds": round(gen_s, 1),
     }
 
-    if not args.no_cpu_baseline and not args.forced:
+    if not args.no_cpu_baseline and not args.forced and not args.shared:
         result["cpu_baseline"] = cpu_baseline(cfg, host0, args.cpu_seconds, q2)
     print(json.dumps(result))
 

@@ -229,6 +229,12 @@ int sik_decode_step_q2(const sik_layout *layout, const void *q, const void *k_ne
  * paper's "retains only 7.5 % of the tokens" setting (75): sequence b attends
  * min(k, max(1, ceil(seq_len[b] * k_per_mille / 1000))) tokens (integer arithmetic; forced
  * tokens counted, they may use the budget up); k stays the row length of idx_out.
+ * group_shared (0 / 1): one index set per KV head, shared by its R query heads (a selector
+ * variant that cuts the gathered bytes by R): the k tokens with the largest SUM over the group's
+ * query heads of the compressed-domain scores (the table is linear in the query, so this is the
+ * score of the summed query); each query head attends over that set with its own query.
+ * idx_out is then [B,Hkv,k].  Runs as separate score / select / attention launches; not
+ * combinable with forced_idx or k_per_mille, nor with k_new on the 2-bit cache (SIK_ERR_FLAGS).
  * Cache: K and V (16-bit rows) with kvq = NULL, or kvq and alpha (2-bit records) with K = V =
  * NULL.  kernel_us as in sik_decode_step_q2.  Zero-initialise the block and set what applies. */
 typedef struct {
@@ -241,6 +247,7 @@ typedef struct {
     uint8_t *codes;
     int32_t k;
     int32_t k_per_mille;
+    int32_t group_shared;
     float softmax_scale;
     const int32_t *forced_idx;
     int32_t n_forced;

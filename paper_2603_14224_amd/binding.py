@@ -34,7 +34,7 @@ class DecodeArgs(ctypes.Structure):
                 ("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("kvq", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
                 ("seq_len", ctypes.c_void_p), ("mu", ctypes.c_void_p), ("codebook", ctypes.c_void_p),
                 ("codes", ctypes.c_void_p), ("k", ctypes.c_int32), ("k_per_mille", ctypes.c_int32),
-                ("softmax_scale", ctypes.c_float),
+                ("group_shared", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("forced_idx", ctypes.c_void_p), ("n_forced", ctypes.c_int32), ("forced_K", ctypes.c_void_p),
                 ("forced_V", ctypes.c_void_p), ("out", ctypes.c_void_p), ("idx_out", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p),
@@ -190,7 +190,7 @@ def sik_decode_step_q2(layout, q, k_new, v_new, kvq, seq_len, mu, alpha, codeboo
 
 def sik_decode_step_ex(layout, *, q, seq_len, codebook, codes, k, out, workspace, k_new=None, v_new=None, K=None,
                        V=None, kvq=None, alpha=None, mu=None, softmax_scale=0.0, forced_idx=None, forced_K=None,
-                       forced_V=None, idx_out=None, k_per_mille=0, profiled=False):
+                       forced_V=None, idx_out=None, k_per_mille=0, group_shared=False, profiled=False):
     """General decode step (argument block of include/sik.h): either cache format, optional forced set."""
     us = (ctypes.c_float * 5)() if profiled else None
 
@@ -201,7 +201,7 @@ def sik_decode_step_ex(layout, *, q, seq_len, codebook, codes, k, out, workspace
 
     a = DecodeArgs(q=vp(q), k_new=vp(k_new), v_new=vp(v_new), K=vp(K), V=vp(V), kvq=vp(kvq), alpha=vp(alpha),
                    seq_len=vp(seq_len), mu=vp(mu), codebook=vp(codebook), codes=vp(codes), k=int(k),
-                   k_per_mille=int(k_per_mille), softmax_scale=float(softmax_scale), forced_idx=vp(forced_idx),
+                   k_per_mille=int(k_per_mille), group_shared=1 if group_shared else 0, softmax_scale=float(softmax_scale), forced_idx=vp(forced_idx),
                    n_forced=0 if forced_idx is None else int(forced_idx.shape[-1]), forced_K=vp(forced_K),
                    forced_V=vp(forced_V), out=vp(out), idx_out=vp(idx_out), workspace=vp(workspace),
                    workspace_bytes=workspace.numel() if workspace is not None else 0,

@@ -124,7 +124,7 @@ int sik_score(const sik_layout* layout, const void* q, const float* codebook, co
     int rc = check_layout(layout, &d);
     if (rc) return rc;
     if (!q || !codebook || !codes || !seq_len || !scores) return SIK_ERR_NULL;
-    return launched(launch_score(d, nullptr, false, Append{}, q, codebook, codes, seq_len, scores, nullptr, 0,
+    return launched(launch_score(d, nullptr, false, Append{}, q, codebook, codes, seq_len, scores, nullptr, 0, 1,
                                  static_cast<hipStream_t>(stream)));
 }
 
@@ -158,7 +158,7 @@ int sik_sparse_attn(const sik_layout* layout, const void* q, const void* K, cons
     if (rc) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = launch_prep(d, w, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
-    if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
+    if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, false, k, softmax_scale, out, s);
     return launched(e);
 }
 
@@ -199,7 +199,7 @@ int sik_sparse_attn_q2(const sik_layout* layout, const void* q, const void* kvq,
     if (rc) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = launch_prep(d, w, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, s);
-    if (e == hipSuccess) e = launch_attn_q2(d, w, q, kvq, alpha, idx, k, softmax_scale, out, s);
+    if (e == hipSuccess) e = launch_attn_q2(d, w, q, kvq, alpha, idx, false, k, softmax_scale, out, s);
     return launched(e);
 }
 
@@ -208,7 +208,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
                             void* K, void* V, void* kvq, const float* alpha, int32_t* seq_len, const float* mu,
                             const float* codebook, uint8_t* codes, int32_t k, float softmax_scale, void* out,
                             int32_t* idx_out, void* workspace, size_t workspace_bytes, void* stream,
-                            hipEvent_t* ev, const Forced& forced = Forced{}) {
+                            hipEvent_t* ev, const StepOptions& opt = StepOptions{}) {
     Dims d;
     int rc = check_layout(layout, &d);
     if (rc) return rc;
@@ -217,13 +217,15 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if ((k_new == nullptr) != (v_new == nullptr)) return SIK_ERR_NULL;
     if (k_new && !mu) return SIK_ERR_NULL;
     if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
-    if (forced.k_per_mille < 0 || forced.k_per_mille > 1000) return SIK_ERR_K_RANGE;
-    if (forced.n < 0 || forced.n > kMaxForced) return SIK_ERR_SHAPE;
-    if (forced.n > 0 && !forced.idx) return SIK_ERR_NULL;
-    if (forced.n > 0 && k <= forced.n) return SIK_ERR_K_RANGE;  // the budget k counts the forced tokens too
-    if ((forced.fK == nullptr) != (forced.fV == nullptr)) return SIK_ERR_NULL;
-    if (forced.fK && (!kvq || forced.n == 0)) return SIK_ERR_FLAGS;  // side rows go with the 2-bit cache only
-    if (forced.fK && !mu) return SIK_ERR_NULL;
+    if (opt.k_per_mille < 0 || opt.k_per_mille > 1000) return SIK_ERR_K_RANGE;
+    if (opt.n < 0 || opt.n > kMaxForced) return SIK_ERR_SHAPE;
+    if (opt.n > 0 && !opt.idx) return SIK_ERR_NULL;
+    if (opt.n > 0 && k <= opt.n) return SIK_ERR_K_RANGE;  // the budget k counts the forced tokens too
+    if ((opt.fK == nullptr) != (opt.fV == nullptr)) return SIK_ERR_NULL;
+    if (opt.fK && (!kvq || opt.n == 0)) return SIK_ERR_FLAGS;  // side rows go with the 2-bit cache only
+    if (opt.fK && !mu) return SIK_ERR_NULL;
+    // group-shared selection runs unfused, without the extras of the fused kernel; the 2-bit cache cannot append there
+    if (opt.group_shared && (opt.n > 0 || opt.k_per_mille > 0 || (kvq && k_new))) return SIK_ERR_FLAGS;
     Workspace w;
     rc = check_ws(d, k, workspace, workspace_bytes, &w);
     if (rc) return rc;
@@ -231,11 +233,29 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     int32_t* idx = idx_out ? idx_out : w.idx;
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
     int fchunks, fchunk;
-    const bool fused = fused_plan(d, &fchunks, &fchunk);
-    if ((kvq || forced.n > 0 || forced.k_per_mille > 0) && !fused)
+    const bool fused = fused_plan(d, &fchunks, &fchunk) && !opt.group_shared;
+    if ((kvq || opt.n > 0 || opt.k_per_mille > 0) && !fused && !opt.group_shared)
         return SIK_ERR_SHAPE;  // these run on the fused path only: max_len <= 524288
     hipError_t e = mark(0);
-    if (fused) {
+    if (opt.group_shared) {
+        // One index set per KV head: the scoring launch sees one query head per KV head whose query is the sum
+        // of the group's R queries; the stand-alone selector picks k tokens per KV head; every query head
+        // attends over its KV head's list.  idx_out, if given, is [B, Hkv, k].
+        Dims ds = d;
+        ds.Hq = d.Hkv;
+        ds.R = 1;
+        if (carve(ds, k, nullptr).total_bytes > w.total_bytes || !score_plan_ok(ds)) return SIK_ERR_WORKSPACE;
+        if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
+        if (e == hipSuccess) e = mark(1);
+        if (e == hipSuccess)
+            e = launch_score(ds, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, d.R, s);
+        if (e == hipSuccess) e = mark(2);
+        if (e == hipSuccess) e = launch_select(ds, w, true, w.scores, seq_len, k, idx, s);
+        if (e == hipSuccess) e = mark(3);
+        if (e == hipSuccess)
+            e = kvq ? launch_attn_q2(d, w, q, kvq, alpha, idx, true, k, softmax_scale, out, s)
+                    : launch_attn(d, w, q, K, V, idx, true, k, softmax_scale, out, s);
+    } else if (fused) {
         // Two launches: scoring (which also stores, encodes and scores an appended row and clears the
         // per-call counters), then selection + attention (which publishes the new length).  The first
         // and third event intervals are empty.
@@ -243,24 +263,25 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
                         static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
         if (e == hipSuccess) e = mark(1);
         if (e == hipSuccess)
-            e = launch_score(d, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, forced.idx,
-                             forced.n, s);
+            e = launch_score(d, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, opt.idx,
+                             opt.n, 1, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = mark(3);
         if (e == hipSuccess)
             e = launch_fused(d, w, q, K, V, kvq, alpha,
-                             Forced{forced.idx, forced.n, forced.fK, forced.fV, mu, forced.k_per_mille}, seq_len,
+                             StepOptions{opt.idx, opt.n, opt.fK, opt.fV, mu, opt.k_per_mille, false},
+                             seq_len,
                              k_new != nullptr, k, softmax_scale, idx_out, out, s);
     } else {
         // contexts beyond 512K tokens: prep (append + clear counters), score, select, attention
         if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
         if (e == hipSuccess) e = mark(1);
         if (e == hipSuccess)
-            e = launch_score(d, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, s);
+            e = launch_score(d, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, 1, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
         if (e == hipSuccess) e = mark(3);
-        if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, k, softmax_scale, out, s);
+        if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, false, k, softmax_scale, out, s);
     }
     if (e == hipSuccess) e = mark(4);
     if (e == hipSuccess && ev) e = hipEventRecord(ev[5], s);  // empty interval: cost of an event pair
@@ -323,12 +344,12 @@ int sik_decode_step_q2(const sik_layout* layout, const void* q, const void* k_ne
 
 int sik_decode_step_ex(const sik_layout* layout, const sik_decode_args* a) {
     if (!a) return SIK_ERR_NULL;
-    const Forced forced{a->forced_idx, a->n_forced, static_cast<const uint16_t*>(a->forced_K),
-                        static_cast<const uint16_t*>(a->forced_V), a->mu, a->k_per_mille};
+    const StepOptions opt{a->forced_idx, a->n_forced, static_cast<const uint16_t*>(a->forced_K),
+                        static_cast<const uint16_t*>(a->forced_V), a->mu, a->k_per_mille, a->group_shared != 0};
     auto run = [&](hipEvent_t* ev) {
         return decode_step_impl(layout, a->q, a->k_new, a->v_new, a->K, a->V, a->kvq, a->alpha, a->seq_len, a->mu,
                                 a->codebook, a->codes, a->k, a->softmax_scale, a->out, a->idx_out, a->workspace,
-                                a->workspace_bytes, a->stream, ev, forced);
+                                a->workspace_bytes, a->stream, ev, opt);
     };
     return a->kernel_us ? profiled(a->stream, a->kernel_us, run) : run(nullptr);
 }

@@ -22,7 +22,8 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
                                                       const int32_t* __restrict__ idx, int k,
                                                       float scale_log2e, uint32_t* __restrict__ counters,
                                                       float* __restrict__ partial, void* __restrict__ out,
-                                                      int Hkv, int Hq, int R, int Lmax, int nsplit, int per) {
+                                                      int Hkv, int Hq, int R, int Lmax, int nsplit, int per,
+                                                      int idx_per_unit) {
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ int s_flag;
@@ -35,7 +36,7 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
     const size_t unit = static_cast<size_t>(b) * Hkv + hq / R;
     const uint4* Kp = reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
     const uint4* Vp = reinterpret_cast<const uint4*>(V + unit * Lmax * kD);
-    const int32_t* ip = idx + static_cast<size_t>(row) * k;
+    const int32_t* ip = idx + (idx_per_unit ? unit : static_cast<size_t>(row)) * k;
 
     const uint4 qraw = reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p];
 
@@ -93,7 +94,7 @@ static void attn_plan(const Dims& d, int k, int* nsplit, int* per) {
 }
 
 hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                       const int32_t* idx, int k, float scale, void* out, hipStream_t s) {
+                       const int32_t* idx, bool idx_per_unit, int k, float scale, void* out, hipStream_t s) {
     int nsplit, per;
     attn_plan(d, k, &nsplit, &per);
     const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
@@ -103,7 +104,7 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
     auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_ATTN(DTV, ODTV)                                                                                  \
     attn_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, k, sl2, w.counters, w.partial, out, d.Hkv, \
-                                                   d.Hq, d.R, d.Lmax, nsplit, per)
+                                                   d.Hq, d.R, d.Lmax, nsplit, per, idx_per_unit ? 1 : 0)
     if (d.kv_dtype == kBF16) {
         if (d.out_dtype == kF32) SIK_ATTN(kBF16, kF32); else SIK_ATTN(kBF16, kBF16);
     } else {

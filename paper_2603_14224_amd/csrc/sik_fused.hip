@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         al1 = reinterpret_cast<const float4*>(alpha + unit * kD)[2 * p + 1];
     }
     const float lo = binp[row * 2], scale = binp[row * 2 + 1];
-    // Forced set (n_forced > 0): thread t < n_forced looks after entry t.  The scoring launch gave these tokens
+    // StepOptions set (n_forced > 0): thread t < n_forced looks after entry t.  The scoring launch gave these tokens
     // -infinity, so they are never selected below; workgroup 0 of the head attends them on top of its own.
     int fi = -1;
     if (tid < n_forced) fi = forced_idx[unit * n_forced + tid];
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
             }
         }
     }
-    // Forced tokens: workgroup 0 of the head takes them on.  Read like every other token (16-bit cache, or
+    // StepOptions tokens: workgroup 0 of the head takes them on.  Read like every other token (16-bit cache, or
     // 2-bit cache without side rows) they simply start the lists of the wavefronts that hold their entries;
     // given as 16-bit side rows they are attended here, each logit shifted by -q . mu because the records
     // they share the softmax with hold the centred key.
@@ -491,7 +491,7 @@ size_t fused_cand_words(const Dims& d) {
 
 template <int DT, int ODT>
 static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                                 const void* kvq, const float* alpha, const Forced& fo, int32_t* seq_len,
+                                 const void* kvq, const float* alpha, const StepOptions& fo, int32_t* seq_len,
                                  bool appended, int k, float scale, int32_t* idx_out, void* out, hipStream_t s) {
     int nhb, hchunks, hchunk, nchunk, chunk;
     score_plan(d, &nhb, &hchunks, &hchunk);
@@ -524,7 +524,7 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
 }
 
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        const void* kvq, const float* alpha, const Forced& forced, int32_t* seq_len, bool appended,
+                        const void* kvq, const float* alpha, const StepOptions& forced, int32_t* seq_len, bool appended,
                         int k, float scale, int32_t* idx_out, void* out, hipStream_t s) {
 #define SIK_F(DTV, ODTV) \
     launch_fused_t<DTV, ODTV>(d, w, q, K, V, kvq, alpha, forced, seq_len, appended, k, scale, idx_out, out, s)

@@ -65,10 +65,12 @@ struct Append {
 // With ap.k_new the new row of every (b, h) is encoded, stored and scored as token seq_len[b]; the
 // length itself is left for launch_fused to increment.
 // n_forced > 0 (with w): tokens of forced_idx [B, Hkv, n_forced] get score -infinity and no histogram count.
+// q_sum > 1 (group-shared selection): d describes one query head per KV head (Hq = Hkv, R = 1) and the scores
+// are those of the sum of the q_sum consecutive real query rows of each KV head; else q_sum = 1.
 constexpr int kMaxForced = 128;
 hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const Append& ap, const void* q,
                         const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
-                        const int32_t* forced_idx, int n_forced, hipStream_t s);
+                        const int32_t* forced_idx, int n_forced, int q_sum, hipStream_t s);
 hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
                             hipStream_t s);
 void score_plan(const Dims& d, int* nhb, int* nchunk, int* chunk);
@@ -78,24 +80,26 @@ void select_plan(const Dims& d, int* nchunk, int* chunk);
 // hist_from_score: the chunk histograms come from the scoring kernel (else from launch_topk_hist)
 hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score, const float* scores,
                          const int32_t* seq_len, int k, int32_t* idx, hipStream_t s);
+// idx_per_unit: idx is [B, Hkv, k], one list shared by the query heads of a KV head; else [B, Hq, k]
 hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                       const int32_t* idx, int k, float scale, void* out, hipStream_t s);
+                       const int32_t* idx, bool idx_per_unit, int k, float scale, void* out, hipStream_t s);
 // select + attention in one launch; reads w.scores / w.parthist / w.binp written by launch_score
 // `appended`: launch_score counted one more token than seq_len says; the last workgroup increments it
 // kvq != nullptr: gather records of the 2-bit cache (K, V unused) with the per-channel alpha
-// Forced set: n_forced entries per (b, KV head), always attended and outside the top-k (launch_score gave them
+// StepOptions set: n_forced entries per (b, KV head), always attended and outside the top-k (launch_score gave them
 // -infinity); with fK, fV (2-bit cache only) they are attended from those 16-bit rows [B, Hkv, n_forced, D],
 // centred by mu, instead of from their records.
-struct Forced {
+struct StepOptions {  // what sik_decode_step_ex adds to the plain decode step
     const int32_t* idx;
     int n;
     const uint16_t* fK;
     const uint16_t* fV;
     const float* mu;
-    int k_per_mille;  // > 0: per-sequence budget min(k, ceil(L * k_per_mille / 1000)) (rides along in this block)
+    int k_per_mille;    // > 0: per-sequence budget min(k, ceil(L * k_per_mille / 1000))
+    bool group_shared;  // one index set per KV head from the summed scores of its query heads (unfused path)
 };
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
-                        const void* kvq, const float* alpha, const Forced& forced, int32_t* seq_len, bool appended,
+                        const void* kvq, const float* alpha, const StepOptions& forced, int32_t* seq_len, bool appended,
                         int k, float scale, int32_t* idx_out, void* out, hipStream_t s);
 bool fused_plan(const Dims& d, int* nchunk, int* chunk);
 size_t fused_cand_words(const Dims& d);
@@ -111,6 +115,6 @@ hipError_t launch_alpha(const Dims& d, const void* K, const int32_t* seq_len, co
 hipError_t launch_quantize_kv(const Dims& d, const void* K, const void* V, const int32_t* seq_len, int t0, int n,
                               const float* mu, const float* alpha, void* kvq, hipStream_t s);
 hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, const void* kvq, const float* alpha,
-                          const int32_t* idx, int k, float scale, void* out, hipStream_t s);
+                          const int32_t* idx, bool idx_per_unit, int k, float scale, void* out, hipStream_t s);
 
 }  // namespace sik

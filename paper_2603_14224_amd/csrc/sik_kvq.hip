@@ -117,7 +117,8 @@ __global__ __launch_bounds__(kBlock) void attn_q2_kernel(const uint16_t* __restr
                                                          const int32_t* __restrict__ idx, int k, float scale_log2e,
                                                          uint32_t* __restrict__ counters,
                                                          float* __restrict__ partial, void* __restrict__ out,
-                                                         int Hkv, int Hq, int R, int Lmax, int nsplit, int per) {
+                                                         int Hkv, int Hq, int R, int Lmax, int nsplit, int per,
+                                                         int idx_per_unit) {
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ int s_flag;
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(kBlock) void attn_q2_kernel(const uint16_t* __restr
     const int b = row / Hq, hq = row % Hq;
     const size_t unit = static_cast<size_t>(b) * Hkv + hq / R;
     const uint2* rp = rec + unit * Lmax * kRecSlots;
-    const int32_t* ip = idx + static_cast<size_t>(row) * k;
+    const int32_t* ip = idx + (idx_per_unit ? unit : static_cast<size_t>(row)) * k;
 
     const uint4 qraw = reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p];
     float a8[8];
@@ -211,7 +212,7 @@ hipError_t launch_quantize_kv(const Dims& d, const void* K, const void* V, const
 }
 
 hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, const void* kvq, const float* alpha,
-                          const int32_t* idx, int k, float scale, void* out, hipStream_t s) {
+                          const int32_t* idx, bool idx_per_unit, int k, float scale, void* out, hipStream_t s) {
     // splits of whole 128-entry steps (4 wavefronts x 32 entries), about 1024 workgroups
     const int rows = d.rows();
     int ns = (1024 + rows - 1) / rows;
@@ -228,7 +229,7 @@ hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, cons
     auto rp = static_cast<const uint2*>(kvq);
 #define SIK_ATTNQ(DTV, ODTV)                                                                                 \
     attn_q2_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, k, sl2, w.counters, w.partial, out, \
-                                                      d.Hkv, d.Hq, d.R, d.Lmax, nsplit, per)
+                                                      d.Hkv, d.Hq, d.R, d.Lmax, nsplit, per, idx_per_unit ? 1 : 0)
     if (d.kv_dtype == kBF16) {
         if (d.out_dtype == kF32) SIK_ATTNQ(kBF16, kF32); else SIK_ATTNQ(kBF16, kBF16);
     } else {

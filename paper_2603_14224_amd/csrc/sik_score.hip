@@ -73,7 +73,7 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
                                                        uint8_t* __restrict__ codes_w,
                                                        const float* __restrict__ alpha, uint2* __restrict__ kvq,
                                                        const int32_t* __restrict__ forced_idx, int n_forced,
-                                                       int Hkv, int Hq, int R,
+                                                       int q_sum, int Hkv, int Hq, int R,
                                                        int Lmax, int nchunk, int chunk, int nhb) {
     constexpr int HB = kHB;
     constexpr int kTokPerIter = kIterTokens / BLK;
@@ -120,7 +120,18 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     if (tid < HB * 16) {  // 16 lanes x 16 B per query row
         const int s = tid >> 4, p = tid & 15;
         float f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (s < nh) widen8<DT>(reinterpret_cast<const uint4*>(q + (row0 + s) * kD)[p], f);
+        if (q_sum <= 1) {
+            if (s < nh) widen8<DT>(reinterpret_cast<const uint4*>(q + (row0 + s) * kD)[p], f);
+        } else if (s == 0) {
+            // group-shared selection: the launch sees one "query head" per KV head whose query is the sum of the
+            // q_sum real ones (the table is linear in the query, so its scores are the summed scores)
+            for (int r = 0; r < q_sum; ++r) {
+                float g[8];
+                widen8<DT>(reinterpret_cast<const uint4*>(q + (row0 * q_sum + r) * kD)[p], g);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] += g[e];
+            }
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e) qs[s][8 * p + e] = f[e];
     }
@@ -327,7 +338,7 @@ bool score_plan_ok(const Dims& d) {
 template <int DT>
 static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, const Append& ap, const void* q,
                                  const float* codebook, const uint8_t* codes, const int32_t* seq_len,
-                                 float* scores, const int32_t* forced_idx, int n_forced, hipStream_t s) {
+                                 float* scores, const int32_t* forced_idx, int n_forced, int q_sum, hipStream_t s) {
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
     const int grid = nchunk * nhb * d.units();
@@ -336,7 +347,8 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     score_kernel<DT, HV, BLKV, FV><<<grid, BLKV, 0, s>>>(                                                    \
         qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
         w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
-        ap.alpha, static_cast<uint2*>(ap.kvq), forced_idx, n_forced, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb)
+        ap.alpha, static_cast<uint2*>(ap.kvq), forced_idx, n_forced, q_sum, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, \
+        nhb)
     const bool wide = score_block(d, nhb) == 512;
     if (!w) { if (wide) SIK_SCORE(false, 512, false); else SIK_SCORE(false, 256, false); }
     else if (n_forced > 0) { if (wide) SIK_SCORE(true, 512, true); else SIK_SCORE(true, 256, true); }
@@ -347,12 +359,12 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
 
 hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const Append& ap, const void* q,
                         const float* codebook, const uint8_t* codes, const int32_t* seq_len, float* scores,
-                        const int32_t* forced_idx, int n_forced, hipStream_t s) {
+                        const int32_t* forced_idx, int n_forced, int q_sum, hipStream_t s) {
     if (!w) n_forced = 0;  // forced sets belong to the decode step (histogram-producing launches)
     return d.kv_dtype == kBF16 ? launch_score_t<kBF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores,
-                                                       forced_idx, n_forced, s)
+                                                       forced_idx, n_forced, q_sum, s)
                                : launch_score_t<kF16>(d, w, zero_counters, ap, q, codebook, codes, seq_len, scores,
-                                                      forced_idx, n_forced, s);
+                                                      forced_idx, n_forced, q_sum, s);
 }
 
 }  // namespace sik

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import sik_workloads as W
-from helpers import dev
+from helpers import dev, topk_sets_agree
 from test_gpu_kvq import Q2State
 from test_gpu_parity import GpuState, TDT, cfg_small, check_attention, sync
 
@@ -233,3 +233,71 @@ def test_sign_only_retrieval_is_a_codebook_of_signs(oracle):
     qf = W.from_bits(q, cfg.dtype).astype(np.float64)
     want = np.einsum("hd,hld->hl", qf[0], np.repeat(signs[0], 4, axis=0))
     assert np.abs(scores.cpu().numpy()[0] - want).max() <= 1e-5 * np.abs(want).max()
+
+
+# --------------------------------------------------------------------------- group-shared selection
+def run_shared(oracle, cfg, capacity, steps, append, q2=False, seq_len=None):
+    B, Hkv, Hq, k = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.top_k
+    R = Hq // Hkv
+    if q2:
+        st = Q2State(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=0.7, out_dtype=torch.float32)
+        kvq, dal = torch.from_numpy(st.records()).cuda(), torch.from_numpy(st.alpha).cuda()
+    else:
+        st = GpuState(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=0.7, out_dtype=torch.float32)
+    sl = st.sl.copy()
+    out = torch.empty(B, Hq, 128, device="cuda")
+    idx = torch.empty(B, Hkv, k, dtype=torch.int32, device="cuda")
+    for step in range(steps):
+        q, kn, vn = W.make_step_inputs(cfg, step)
+        kw = dict(q=dev(q, cfg.dtype), k_new=dev(kn, cfg.dtype) if append else None,
+                  v_new=dev(vn, cfg.dtype) if append else None, seq_len=st.dsl, mu=st.dmu, codebook=st.dcb,
+                  codes=st.dcodes, k=k, out=out, idx_out=idx, workspace=st.ws, group_shared=True)
+        kw.update(dict(kvq=kvq, alpha=dal) if q2 else dict(K=st.dK, V=st.dV))
+        sik.sik_decode_step_ex(st.layout, **kw)
+        sync()
+        _, ref_idx = oracle.decode_step_shared(q, kn if append else None, vn if append else None, st.K, st.V,
+                                               cfg.dtype, sl, st.mu, st.cb, st.codes, k)
+        assert np.array_equal(st.dsl.cpu().numpy(), sl)
+        s_kv = oracle.shared_scores(q, cfg.dtype, st.cb, st.codes, sl)
+        g_idx = idx.cpu().numpy()
+        for b in range(B):
+            for h in range(Hkv):
+                topk_sets_agree(g_idx[b, h], ref_idx[b, h], s_kv[b, h], int(sl[b]), k)
+        full = np.repeat(g_idx, R, axis=1)
+        if q2:
+            ref = oracle.sparse_attn_q2(q, cfg.dtype, st.codes, st.qkv, st.alpha, full)
+        else:
+            ref = oracle.sparse_attn(q, st.K, st.V, cfg.dtype, full)
+        check_attention(out.cpu().numpy().astype(np.float64), ref, True)
+
+
+def test_shared_selection_c2_shape_with_append(oracle):
+    run_shared(oracle, cfg_small("C2", context=9000, top_k=300), 9004, steps=3, append=True)
+
+
+def test_shared_selection_gqa8_ragged_batch(oracle):
+    cfg = cfg_small("C5", batch=3, n_kv_heads=2, n_q_heads=16, context=5000, top_k=700)
+    run_shared(oracle, cfg, 5004, steps=2, append=True, seq_len=[5000, 300, 0])
+
+
+def test_shared_selection_gqa3_fp16_k_above_context(oracle):
+    cfg = cfg_small("C2", batch=2, n_kv_heads=2, n_q_heads=6, context=800, top_k=900, dtype="fp16")
+    run_shared(oracle, cfg, 904, steps=1, append=False, seq_len=[800, 5])
+
+
+def test_shared_selection_on_records(oracle):
+    run_shared(oracle, cfg_small("C2", context=7000, top_k=256), 7000, steps=2, append=False, q2=True)
+
+
+def test_shared_selection_rejects_what_it_cannot_combine(oracle):
+    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=1000, top_k=64)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    q, _, _ = W.make_step_inputs(cfg, 0)
+    out = torch.empty(1, 8, 128, device="cuda")
+    f = torch.full((1, 2, 8), -1, dtype=torch.int32, device="cuda")
+    base = dict(q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu, codebook=st.dcb, codes=st.dcodes,
+                out=out, workspace=st.ws, k=64, group_shared=True)
+    for kw in (dict(forced_idx=f), dict(k_per_mille=75)):
+        with pytest.raises(sik.SikError) as e:
+            sik.sik_decode_step_ex(st.layout, **base, **kw)
+        assert e.value.status == -8
