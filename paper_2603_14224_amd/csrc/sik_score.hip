@@ -11,6 +11,9 @@
 // 128-bit load brings its 32 codes, i.e. a wavefront streams 1 KB of the code plane per load;
 // four such loads per lane are in flight while the previous four tokens are scored.
 //
+// A launch with one query head per KV head (no GQA, or the summed query of a group-shared selection) uses
+// scalar table entries instead (HB = 1).
+//
 // With HIST the kernel also builds the first level of the selection: a histogram of a monotone
 // map of each query head's scores, published per chunk for the select kernel.
 #include "sik_device.h"
@@ -26,10 +29,15 @@ constexpr int kIterTokens = 1024;  // tokens a workgroup scores per loop iterati
 
 constexpr int kHB = 4;  // query heads per workgroup = components of one float4 table entry
 
-__device__ __forceinline__ void score_token(const uint4 code, const float4* lut, float* acc) {
+// Table lookups of one token.  HB = 4: float4 entries (four query heads at once), 256 B per group; HB = 1: scalar
+// entries, 64 B per group (one query head per KV head: multi-head attention, or the summed query of a
+// group-shared selection) - a quarter of the LDS traffic, the 16 entries of a group on 16 different banks.
+template <int HB>
+__device__ __forceinline__ void score_token(const uint4 code, const float* lut, float* acc) {
 #pragma unroll
-    for (int s = 0; s < kHB; ++s) acc[s] = 0.0f;
+    for (int s = 0; s < HB; ++s) acc[s] = 0.0f;
     const uint32_t w[4] = {code.x, code.y, code.z, code.w};
+    const char* base = reinterpret_cast<const char*>(lut);
 #pragma unroll
     for (int dw = 0; dw < 4; ++dw) {
 #pragma unroll
@@ -37,19 +45,25 @@ __device__ __forceinline__ void score_token(const uint4 code, const float4* lut,
             // byte (4 dw + by) of the token: high nibble = Code of group g, low nibble = group g+1
             const int g = 8 * dw + 2 * by;
             const uint32_t bits = w[dw] >> (8 * by);
-            const uint32_t off_hi = bits & 0xf0u;  // Code * 16 B
-            const uint32_t off_lo = (bits & 0x0fu) << 4;
-            const float4 v0 = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(&lut[g * 16]) + off_hi);
-            acc[0] += v0.x;
-            acc[1] += v0.y;
-            acc[2] += v0.z;
-            acc[3] += v0.w;
-            const float4 v1 =
-                *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(&lut[(g + 1) * 16]) + off_lo);
-            acc[0] += v1.x;
-            acc[1] += v1.y;
-            acc[2] += v1.z;
-            acc[3] += v1.w;
+            if constexpr (HB == 4) {
+                const uint32_t off_hi = bits & 0xf0u;  // Code * 16 B
+                const uint32_t off_lo = (bits & 0x0fu) << 4;
+                const float4 v0 = *reinterpret_cast<const float4*>(base + g * 256 + off_hi);
+                acc[0] += v0.x;
+                acc[1] += v0.y;
+                acc[2] += v0.z;
+                acc[3] += v0.w;
+                const float4 v1 = *reinterpret_cast<const float4*>(base + (g + 1) * 256 + off_lo);
+                acc[0] += v1.x;
+                acc[1] += v1.y;
+                acc[2] += v1.z;
+                acc[3] += v1.w;
+            } else {
+                const uint32_t off_hi = (bits & 0xf0u) >> 2;  // Code * 4 B
+                const uint32_t off_lo = (bits & 0x0fu) << 2;
+                acc[0] += *reinterpret_cast<const float*>(base + g * 64 + off_hi);
+                acc[0] += *reinterpret_cast<const float*>(base + (g + 1) * 64 + off_lo);
+            }
         }
     }
 }
@@ -57,7 +71,7 @@ __device__ __forceinline__ void score_token(const uint4 code, const float4* lut,
 // FORCED: tokens named in forced_idx [B, Hkv, n_forced] (entries outside [0, L) ignored) always take part in
 // the attention that follows and must not compete in the selection: their score is stored as -infinity and
 // they are left out of the histogram ("Full Precision Sink Tokens": a fixed set that is always attended).
-template <int DT, bool HIST, int BLK, bool FORCED>
+template <int DT, bool HIST, int BLK, bool FORCED, int HB>
 __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__ q,
                                                        const float* __restrict__ codebook,
                                                        const uint8_t* __restrict__ codes,
@@ -75,9 +89,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
                                                        const int32_t* __restrict__ forced_idx, int n_forced,
                                                        int q_sum, int Hkv, int Hq, int R,
                                                        int Lmax, int nchunk, int chunk, int nhb) {
-    constexpr int HB = kHB;
+    static_assert(HB == 1 || HB == kHB, "scalar or float4 table entries");
     constexpr int kTokPerIter = kIterTokens / BLK;
-    __shared__ float4 lut[kG * 16];
+    __shared__ __align__(16) float lut[kG * 16 * HB];  // entry (g, j): HB consecutive floats, one per query head
     __shared__ float qs[HB][kD];
     __shared__ float bp[HB][2];
     __shared__ uint32_t lhist[HIST ? HB * kBins : 1];
@@ -208,9 +222,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
         const int e = tid + x * BLK;
         if (e < kG * 16) {
             const int g = e >> 4;
-            float o[4];
+            float o[HB];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s < HB; ++s) {
                 const float* qq = &qs[s][4 * g];
                 float a = qq[0] * cj[x].x;
                 a = fmaf(qq[1], cj[x].y, a);
@@ -218,7 +232,10 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
                 a = fmaf(qq[3], cj[x].w, a);
                 o[s] = a;
             }
-            lut[e] = make_float4(o[0], o[1], o[2], o[3]);
+            if constexpr (HB == 4)
+                *reinterpret_cast<float4*>(&lut[e * 4]) = make_float4(o[0], o[1], o[2], o[3]);
+            else
+                lut[e] = o[0];
         }
     }
     __syncthreads();
@@ -230,11 +247,11 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
         if (tid < HB * 32) {
             const int s = tid >> 5, g = tid & 31;
             // entry j of group g, head s: lanes start at different j so that they hit different banks
-            const float* lf = reinterpret_cast<const float*>(&lut[g * 16]) + s;
+            const float* lf = &lut[g * 16 * HB + s];
             float sum = 0.0f, sq = 0.0f;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                const float x = lf[((j + g) & 15) * 4];
+                const float x = lf[((j + g) & 15) * HB];
                 sum += x;
                 sq = fmaf(x, x, sq);
             }
@@ -278,7 +295,7 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
             const int tok = base + j * BLK + tid;
             float acc[HB];
             if (tok == t_new) code[j] = *reinterpret_cast<const uint4*>(newcode);  // written before the barriers above
-            score_token(code[j], lut, acc);
+            score_token<HB>(code[j], lut, acc);
             if (tok < end) {
                 bool forced = false;
                 if constexpr (FORCED) forced = (fbits[(tok - start) >> 5] >> ((tok - start) & 31)) & 1u;
@@ -318,7 +335,8 @@ static int score_block(const Dims& d, int nhb) {
 void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
     const int nhb = (d.R + kHB - 1) / kHB;
     const int units = d.units() * nhb;
-    const int target = score_block(d, nhb) == 512 ? 256 : 512;
+    // (scalar tables, R = 1: 62 registers, 8 wavefronts per SIMD fit, and a table costs 512 entries to build)
+    const int target = score_block(d, nhb) == 512 ? 256 : (d.R == 1 ? 2048 : 512);
     int want = (target + units - 1) / units;
     if (want > kMaxChunks) want = kMaxChunks;
     int ch = (d.Lmax + want - 1) / want;
@@ -343,17 +361,22 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     score_plan(d, &nhb, &nchunk, &chunk);
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
-#define SIK_SCORE(HV, BLKV, FV)                                                                              \
-    score_kernel<DT, HV, BLKV, FV><<<grid, BLKV, 0, s>>>(                                                    \
+#define SIK_SCORE1(HV, BLKV, FV, HBV)                                                                        \
+    score_kernel<DT, HV, BLKV, FV, HBV><<<grid, BLKV, 0, s>>>(                                               \
         qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
         w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
         ap.alpha, static_cast<uint2*>(ap.kvq), forced_idx, n_forced, q_sum, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, \
         nhb)
+#define SIK_SCORE(HV, BLKV, FV)                                                                              \
+    do {                                                                                                     \
+        if (d.R == 1) SIK_SCORE1(HV, BLKV, FV, 1); else SIK_SCORE1(HV, BLKV, FV, kHB);                       \
+    } while (0)
     const bool wide = score_block(d, nhb) == 512;
     if (!w) { if (wide) SIK_SCORE(false, 512, false); else SIK_SCORE(false, 256, false); }
     else if (n_forced > 0) { if (wide) SIK_SCORE(true, 512, true); else SIK_SCORE(true, 256, true); }
     else { if (wide) SIK_SCORE(true, 512, false); else SIK_SCORE(true, 256, false); }
 #undef SIK_SCORE
+#undef SIK_SCORE1
     return hipGetLastError();
 }
 
