@@ -49,6 +49,10 @@ def parse():
                          "--kv q2 kept as 16-bit side rows); the budget top_k then counts them")
     ap.add_argument("--shared", action="store_true",
                     help="group-shared selection: one index set per KV head from the summed scores of its query heads")
+    ap.add_argument("--fit", action="store_true",
+                    help="measure the prefill-side quantiser instead of the decode step: sik_quantize_keys FIT "
+                         "(channel means, sign codes, codebook) and, with --kv q2, sik_quantize_kv FIT (alpha, records) "
+                         "of one layer of the workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB): under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counters' scale factor")
@@ -90,6 +94,8 @@ def main():
     cap = (cap + 7) // 8 * 8
     lay = sik.make_layout(B, Hkv, Hq, D, cap, tdt, tdt)
     ws = sik.alloc_workspace(lay, k)
+    if args.fit:
+        return bench_fit(args, cfg, lay, ws, cap, q2)
 
     # ---- resident state: n_layers independent draws of the recipe, quantised by the library itself
     layers = []
@@ -318,6 +324,61 @@ def main():
     if not args.no_cpu_baseline and not args.forced and not args.shared:
         result["cpu_baseline"] = cpu_baseline(cfg, host0, args.cpu_seconds, q2)
     print(json.dumps(result))
+
+
+def bench_fit(args, cfg, lay, ws, cap, q2):
+    """Prefill-compress of one layer ("one-pass sign-based clustering": means, codes, codebook; plus the 2-bit
+    records with --kv q2): two (q2: four) passes over K, one over V, all HBM-bound; rotates over enough layer
+    copies of K (and V) to stay out of the Infinity Cache."""
+    import torch
+
+    import paper_2603_14224_amd as sik
+    import sik_workloads as W
+    from helpers import dev
+
+    B, Hkv, D, L = cfg.batch, cfg.n_kv_heads, cfg.head_dim, cfg.context
+    kv_bytes = B * Hkv * L * D * 2
+    n_layers = args.layers or max(2, min(8, -(-2 * 256 * 2 ** 20 // kv_bytes)))
+    Ks, Vs = [], []
+    for li in range(n_layers):
+        Kb, Vb = W.make_cache(cfg, capacity=cap, layer=li)
+        Ks.append(dev(Kb, cfg.dtype))
+        Vs.append(dev(Vb, cfg.dtype) if q2 else None)
+    sl = torch.full((B,), L, dtype=torch.int32, device="cuda")
+    mu = torch.empty(B, Hkv, D, device="cuda")
+    cb = torch.empty(B, Hkv, D // 4, 16, 4, device="cuda")
+    cnt = torch.empty(B, Hkv, D // 4, 16, dtype=torch.int32, device="cuda")
+    codes = torch.zeros(B, Hkv, cap, D // 8, dtype=torch.uint8, device="cuda")
+    alpha = torch.empty(B, Hkv, D, device="cuda") if q2 else None
+    kvq = sik.alloc_kvq(lay) if q2 else None
+
+    def fit(i):
+        sik.sik_quantize_keys(lay, Ks[i % n_layers], sl, 0, 0, sik.SIK_Q_FIT, mu, cb, cnt, codes, ws)
+        if q2:
+            sik.sik_quantize_kv(lay, Ks[i % n_layers], Vs[i % n_layers], sl, 0, 0, sik.SIK_Q_FIT, mu, alpha, kvq)
+
+    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    for i in range(warmup):
+        fit(i)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for i in range(steps):
+        fit(warmup + i)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t) / steps
+    # K is read twice (means, then codes + clusters), with q2 twice more (alpha, records) and V once; codes and
+    # records are written
+    nbytes = kv_bytes * (5 if q2 else 2) + B * Hkv * L * (D // 8) + (B * Hkv * L * 128 if q2 else 0)
+    print(json.dumps({
+        "metric": "us per prefill-compress of one layer (quantiser FIT)", "value": round(sec * 1e6, 2),
+        "unit": "us/layer", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(sec * 1e3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name + " / prefill-compress", "batch": B, "n_kv_heads": Hkv, "head_dim": D,
+                   "context": L, "kv_dtype": cfg.dtype, "kv_format": args.kv, "layers_rotated": n_layers},
+        "roofline": {"bound": "hbm", "kernel": "colsum + encode" + (" + alpha + quantize_kv" if q2 else ""),
+                     "achieved": round(nbytes / sec / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(nbytes / sec / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": nbytes}}))
 
 
 def cpu_baseline(cfg, host0, budget_s, q2=False):
