@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "T4"])
     ap.add_argument("--layers", type=int, default=0, help="distinct layer states to rotate over (0 = auto)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of HIP-graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")

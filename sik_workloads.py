@@ -45,6 +45,10 @@ CONFIGS = {
                  "lognormal", 0.01, 0, 8.0, 3, False, 1),
     "C5": Config("C5 prefill-compress + 16 decode steps 4x64K GQA8", 4, 8, 64, 128, 65536, 1536, "bf16",
                  "lognormal", 0.02, 0, 10.0, 4, True, 16),
+    # the shape the paper's module-timing table is quoted on ("16K token input with batch size 10", 7.5 % of the
+    # tokens kept), on a Llama-3-8B-shaped layer: context for the paper's numbers, not one of the five workloads
+    "T4": Config("T4 module-timing shape 10x16K, 7.5 % kept", 10, 8, 32, 128, 16384, 1229, "bf16",
+                 "lognormal", 0.01, 0, 8.0, 5, False, 1),
 }
 
 
