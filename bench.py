@@ -395,7 +395,9 @@ def cpu_baseline(cfg, host0, budget_s, q2=False):
     K, V = host0
     B, cap = K.shape[0], K.shape[2]
     sl = np.full(B, cfg.context, np.int32)
+    t = time.perf_counter()
     mu, codes, cb, cnt = oracle.fit(K, cfg.dtype, sl)
+    stages = {"quantise_fit": time.perf_counter() - t}
     if q2:
         al, qkv = oracle.fit_q2(K, V, cfg.dtype, sl, mu)
 
@@ -404,6 +406,19 @@ def cpu_baseline(cfg, host0, budget_s, q2=False):
             oracle.decode_step_q2(q, kn, vn, cfg.dtype, sl, mu, al, cb, codes, qkv, cfg.top_k)
         else:
             oracle.decode_step(q, kn, vn, K, V, cfg.dtype, sl, mu, cb, codes, cfg.top_k)
+
+    # the stages of one step, timed apart (16-bit cache, no append)
+    q0 = W.make_step_inputs(cfg, 10 ** 6)[0]
+    t = time.perf_counter()
+    s0 = oracle.score(q0, cfg.dtype, cb, codes, sl)
+    stages["score"] = time.perf_counter() - t
+    t = time.perf_counter()
+    i0 = oracle.topk(s0, sl, cfg.top_k)
+    stages["topk"] = time.perf_counter() - t
+    t = time.perf_counter()
+    oracle.sparse_attn(q0, K, V, cfg.dtype, i0)
+    stages["attention"] = time.perf_counter() - t
+    del s0, i0
 
     n, t_total = 0, 0.0
     while True:
@@ -419,7 +434,8 @@ def cpu_baseline(cfg, host0, budget_s, q2=False):
             break
     oracle.set_threads(1)
     res = {"value": round(t_total / n * 1e6, 1), "unit": "us/step", "cores": used, "kind": "oracle",
-           "sample": f"{n} whole decode step(s) of layer 0 of the same workload (fp64 oracle, OpenMP over batch x head)"}
+           "sample": f"{n} whole decode step(s) of layer 0 of the same workload (fp64 oracle, OpenMP over batch x head)",
+           "stages_us": {k_: round(v * 1e6, 1) for k_, v in stages.items()}}
     if t_total / n * used <= budget_s:  # one more step on a single thread, when that fits the budget too
         q, _, _ = W.make_step_inputs(cfg, n)
         t = time.perf_counter()
