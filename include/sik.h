@@ -233,8 +233,8 @@ int sik_decode_step_q2(const sik_layout *layout, const void *q, const void *k_ne
  * variant that cuts the gathered bytes by R): the k tokens with the largest SUM over the group's
  * query heads of the compressed-domain scores (the table is linear in the query, so this is the
  * score of the summed query); each query head attends over that set with its own query.
- * idx_out is then [B,Hkv,k].  Runs as separate score / select / attention launches; not
- * combinable with forced_idx or k_per_mille, nor with k_new on the 2-bit cache (SIK_ERR_FLAGS).
+ * idx_out is then [B,Hkv,k].  Combines with forced_idx (forced tokens are per KV head anyway)
+ * and k_per_mille.
  * Cache: K and V (16-bit rows) with kvq = NULL, or kvq and alpha (2-bit records) with K = V =
  * NULL.  kernel_us as in sik_decode_step_q2.  Zero-initialise the block and set what applies. */
 typedef struct {

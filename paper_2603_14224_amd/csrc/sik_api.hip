@@ -224,8 +224,6 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if ((opt.fK == nullptr) != (opt.fV == nullptr)) return SIK_ERR_NULL;
     if (opt.fK && (!kvq || opt.n == 0)) return SIK_ERR_FLAGS;  // side rows go with the 2-bit cache only
     if (opt.fK && !mu) return SIK_ERR_NULL;
-    // group-shared selection runs unfused, without the extras of the fused kernel; the 2-bit cache cannot append there
-    if (opt.group_shared && (opt.n > 0 || opt.k_per_mille > 0 || (kvq && k_new))) return SIK_ERR_FLAGS;
     Workspace w;
     rc = check_ws(d, k, workspace, workspace_bytes, &w);
     if (rc) return rc;
@@ -233,22 +231,32 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     int32_t* idx = idx_out ? idx_out : w.idx;
     auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
     int fchunks, fchunk;
-    const bool fused = fused_plan(d, &fchunks, &fchunk) && !opt.group_shared;
-    if ((kvq || opt.n > 0 || opt.k_per_mille > 0) && !fused && !opt.group_shared)
+    const bool fused = fused_plan(d, &fchunks, &fchunk);
+    if ((kvq || opt.n > 0 || opt.k_per_mille > 0) && !fused)
         return SIK_ERR_SHAPE;  // these run on the fused path only: max_len <= 524288
-    hipError_t e = mark(0);
+    // Group-shared selection: the scoring launch sees one query head per KV head (the summed query).
+    Dims ds = d;
     if (opt.group_shared) {
-        // One index set per KV head: the scoring launch sees one query head per KV head whose query is the sum
-        // of the group's R queries; the stand-alone selector picks k tokens per KV head; every query head
-        // attends over its KV head's list.  idx_out, if given, is [B, Hkv, k].
-        Dims ds = d;
         ds.Hq = d.Hkv;
         ds.R = 1;
         if (carve(ds, k, nullptr).total_bytes > w.total_bytes || !score_plan_ok(ds)) return SIK_ERR_WORKSPACE;
+    }
+    const int q_sum = opt.group_shared ? d.R : 1;
+    // Large launches select once per KV head with the stand-alone selector and let the attention kernels read that
+    // list (measured on 32 x 8 KV heads x 16K: 83 against 86 us; on 4 x 8 x 64K with 8:1 GQA: 57 against 71 us);
+    // small ones, and everything that needs the fused kernel's extras, go through the fused kernel, where the R
+    // query heads of a group each classify the shared scores (32K context, one sequence: 20 against 26 us).
+    const bool plain = opt.n == 0 && opt.k_per_mille == 0 && !(kvq && k_new);
+    const bool shared_unfused =
+        opt.group_shared && (!fused || (plain && static_cast<int64_t>(d.units()) * d.Lmax > (2 << 20)));
+    hipError_t e = mark(0);
+    if (shared_unfused) {
+        // prep, score (summed query), stand-alone selector per KV head, attention reading one index list per KV
+        // head.  idx_out, if given, is [B, Hkv, k].
         if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
         if (e == hipSuccess) e = mark(1);
         if (e == hipSuccess)
-            e = launch_score(ds, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, d.R, s);
+            e = launch_score(ds, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, q_sum, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = launch_select(ds, w, true, w.scores, seq_len, k, idx, s);
         if (e == hipSuccess) e = mark(3);
@@ -263,13 +271,13 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
                         static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
         if (e == hipSuccess) e = mark(1);
         if (e == hipSuccess)
-            e = launch_score(d, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, opt.idx,
-                             opt.n, 1, s);
+            e = launch_score(ds, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, opt.idx,
+                             opt.n, q_sum, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = mark(3);
         if (e == hipSuccess)
             e = launch_fused(d, w, q, K, V, kvq, alpha,
-                             StepOptions{opt.idx, opt.n, opt.fK, opt.fV, mu, opt.k_per_mille, false},
+                             StepOptions{opt.idx, opt.n, opt.fK, opt.fV, mu, opt.k_per_mille, opt.group_shared},
                              seq_len,
                              k_new != nullptr, k, softmax_scale, idx_out, out, s);
     } else {

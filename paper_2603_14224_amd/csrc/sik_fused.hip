@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
     int Lmax, int nchunk, int hchunks, const int32_t* __restrict__ forced_idx, int n_forced,
     const uint16_t* __restrict__ fK, const uint16_t* __restrict__ fV, const float* __restrict__ mu,
-    int k_per_mille) {
+    int k_per_mille, int shared) {
     constexpr int kChunk = 1024 * NQ;
     constexpr int kListCap = 512;  // selected-token slots per wavefront; flushed to the gather when half full
     __shared__ int32_t l_sel[kBlock / kWave][kListCap];
@@ -64,11 +64,18 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const int b = row / Hq, hq = row % Hq;
     const size_t unit = static_cast<size_t>(b) * Hkv + hq / R;
     const int start = c * kChunk;
+    // Group-shared selection (shared != 0): scores, histograms and bin bounds exist once per KV head (the scoring
+    // launch ran on the summed query), so the R query heads of a group find the same threshold and select the
+    // same tokens, each attending with its own query; the group's first head writes the one index list.
+    const size_t srow = shared ? unit : static_cast<size_t>(row);
+    int32_t* const orow = !idx_out ? nullptr
+                          : !shared ? idx_out + static_cast<size_t>(row) * k
+                                    : (hq % R == 0 ? idx_out + unit * k : nullptr);
 
     // ---- 1. every load that does not depend on another goes out now ---------------------------
     // (the histogram loads come last in program order because their values are consumed as they
     // arrive: whatever is issued after them would wait for them)
-    const float4* s4 = reinterpret_cast<const float4*>(scores + static_cast<size_t>(row) * sstride + start);
+    const float4* s4 = reinterpret_cast<const float4*>(scores + srow * sstride + start);
     float4 sv[NQ];
 #pragma unroll
     for (int j = 0; j < NQ; ++j) {
@@ -81,7 +88,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         al0 = reinterpret_cast<const float4*>(alpha + unit * kD)[2 * p];
         al1 = reinterpret_cast<const float4*>(alpha + unit * kD)[2 * p + 1];
     }
-    const float lo = binp[row * 2], scale = binp[row * 2 + 1];
+    const float lo = binp[srow * 2], scale = binp[srow * 2 + 1];
     // StepOptions set (n_forced > 0): thread t < n_forced looks after entry t.  The scoring launch gave these tokens
     // -infinity, so they are never selected below; workgroup 0 of the head attends them on top of its own.
     int fi = -1;
@@ -95,7 +102,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         mu_dot = qf[0] * m0.x + qf[1] * m0.y + qf[2] * m0.z + qf[3] * m0.w + qf[4] * m1.x + qf[5] * m1.y +
                  qf[6] * m1.z + qf[7] * m1.w;
     }
-    const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hchunks);
+    const HistLoads hl = load_chunk_hists(parthist + srow * hchunks * kHistWords, hchunks);
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const bool grew = appended && L < Lmax;  // the scoring launch stored and scored one more token
@@ -245,11 +252,11 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
             if (fv) mylist[__popcll(bf & lt_mask)] = fi;
             n_sel = __popcll(bf);
         } else {
-            if (idx_out && bf != 0ull) {
+            if (orow && bf != 0ull) {
                 uint32_t base = 0u;
                 if (lane == 0) base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(__popcll(bf)));
                 base = static_cast<uint32_t>(__shfl(static_cast<int>(base), 0, 64));
-                if (fv) idx_out[static_cast<size_t>(row) * k + base + __popcll(bf & lt_mask)] = fi;
+                if (fv) orow[base + __popcll(bf & lt_mask)] = fi;
             }
             const float zbias = -row16_sum(mu_dot) * scale_log2e;
             attend_list<DT>([&](int j) { return s_fidx[j] >= 0 ? j : -1; }, n_forced, wv * 16, (kBlock / kWave) * 16,
@@ -267,12 +274,12 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         if (bal == 0ull) break;
         if (n_sel > kListCap - 64) {
             const int n16 = n_sel & ~(kStep - 1);  // complete gather steps now, the rest moves to the front
-            if (idx_out) {
+            if (orow) {
                 uint32_t base = 0u;
                 if (lane == 0) base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(n16));
                 base = static_cast<uint32_t>(__shfl(static_cast<int>(base), 0, 64));
                 for (int t = lane; t < n16; t += 64)
-                    if (base + t < static_cast<uint32_t>(k)) idx_out[static_cast<size_t>(row) * k + base + t] = mylist[t];
+                    if (base + t < static_cast<uint32_t>(k)) orow[base + t] = mylist[t];
             }
             attend([&](int t) { return mylist[t]; }, n16, 0, kStep, st);
             const int rem = n_sel - n16;
@@ -290,7 +297,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     if (lane == 0) st_agent(&cw[0], static_cast<uint32_t>(n_cand));
     // optional index output: reserve this wave's slots now, write them after the gather
     uint32_t out_base = 0u;
-    if (idx_out && n_sel > 0) {
+    if (orow && n_sel > 0) {
         if (lane == 0) out_base = atomic_add_u32(&counters[row * 8 + 0], static_cast<uint32_t>(n_sel));
     }
     SIK_TL(26);
@@ -298,10 +305,10 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     // ---- 4. attend over this wavefront's own tokens, publish the chunk's partial ---------------
     attend([&](int j) { return mylist[j]; }, n_sel, 0, kStep, st);
     SIK_TL(27);
-    if (idx_out && n_sel > 0) {
+    if (orow && n_sel > 0) {
         out_base = static_cast<uint32_t>(__shfl(static_cast<int>(out_base), 0, 64));
         for (int j = lane; j < n_sel; j += 64)
-            if (out_base + j < static_cast<uint32_t>(k)) idx_out[static_cast<size_t>(row) * k + out_base + j] = mylist[j];
+            if (out_base + j < static_cast<uint32_t>(k)) orow[out_base + j] = mylist[j];
     }
     float M, Lsum, o;
     workgroup_merge(st, sm, sl, sacc, M, Lsum, o);
@@ -322,7 +329,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     // All exchange loads go out together: the (m, l) pair of every chunk (thread c), the first 8
     // chunks' o[d] (thread d), and one candidate region per thread.
     const int need = kk - min(cgt, kk);
-    int32_t* olist = (idx_out ? idx_out : idx_ws) + static_cast<size_t>(row) * k;
+    int32_t* olist = orow ? orow : idx_ws + static_cast<size_t>(row) * k;
     constexpr int kOPre = 8;
     float o_pre[kOPre];
     float pm = kNegBig, pl = 0.0f;
@@ -418,7 +425,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
                 if (rank < need) {
                     const int32_t ia = static_cast<int32_t>(~static_cast<uint32_t>(lc2[a]));
                     chosen[rank] = ia;
-                    if (idx_out) olist[nfv + cgt + rank] = ia;
+                    if (orow) olist[nfv + cgt + rank] = ia;
                 }
             }
             __syncthreads();
@@ -426,7 +433,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
             attend([&](int j) { return chosen[j]; }, min(need, n), wv * kStep, (kBlock / kWave) * kStep, st);
         } else {
             // exact fallback: radix select over the members of b* in the whole row of scores
-            radix_select_in_bin(scores + static_cast<size_t>(row) * sstride, L, lo, scale, bstar, need,
+            radix_select_in_bin(scores + srow * sstride, L, lo, scale, bstar, need,
                                 olist + nfv + cgt, red, sh);
             __threadfence_block();
             __syncthreads();
@@ -459,7 +466,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         }
         store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, lt > 0.0f ? ot / lt : 0.0f);
     }
-    if (idx_out)
+    if (orow)
         for (int j = nfv + kk + tid; j < k; j += kBlock) olist[j] = -1;
     // the last query head of the sequence to finish publishes the new length: by then every workgroup of
     // every head of this sequence has read the old one
@@ -494,7 +501,12 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
                                  const void* kvq, const float* alpha, const StepOptions& fo, int32_t* seq_len,
                                  bool appended, int k, float scale, int32_t* idx_out, void* out, hipStream_t s) {
     int nhb, hchunks, hchunk, nchunk, chunk;
-    score_plan(d, &nhb, &hchunks, &hchunk);
+    Dims dscore = d;  // the launch that wrote the scores and histograms
+    if (fo.group_shared) {
+        dscore.Hq = d.Hkv;
+        dscore.R = 1;
+    }
+    score_plan(dscore, &nhb, &hchunks, &hchunk);
     if (!fused_plan(d, &nchunk, &chunk)) return hipErrorInvalidValue;
     const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
     const int grid = nchunk * d.rows();
@@ -506,7 +518,7 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     select_attend_kernel<DT, ODT, NQV, KVQV><<<grid, kBlock, 0, s>>>(                                       \
         qp, Kp, Vp, Rp, alpha, w.scores, w.sstride, seq_len, appended ? 1 : 0, w.parthist, w.binp, w.counters, \
         w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks, fo.idx, fo.n,    \
-        fo.fK, fo.fV, fo.mu, fo.k_per_mille)
+        fo.fK, fo.fV, fo.mu, fo.k_per_mille, fo.group_shared ? 1 : 0)
 #define SIK_FUSED(NQV)                                                                                      \
     do {                                                                                                    \
         if (kvq) SIK_FUSED_Q(NQV, true); else SIK_FUSED_Q(NQV, false);                                      \

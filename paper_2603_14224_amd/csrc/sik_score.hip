@@ -155,7 +155,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
             for (int e = tid; e < (chunk + 31) / 32; e += BLK) fbits[e] = 0u;
         // the kernels that follow count on zeroed per-head counters; when no prep launch precedes,
         // chunk 0 of each head block clears those of its heads
-        if (zero_counters && c == 0 && tid < nh * 8) zero_counters[row0 * 8 + tid] = 0u;
+        // (a launch on the summed query of q_sum heads stands for q_sum rows of the kernel that follows)
+        const int nrows = q_sum > 1 ? q_sum : nh;
+        if (zero_counters && c == 0 && tid < nrows * 8) zero_counters[row0 * (q_sum > 1 ? q_sum : 1) * 8 + tid] = 0u;
     }
     // decode-time append (k_new != nullptr): the new key/value row of this KV head goes to row t =
     // seq_len[b]; every workgroup counts it in (L = t + 1), the one whose chunk holds t encodes it

@@ -289,15 +289,62 @@ def test_shared_selection_on_records(oracle):
     run_shared(oracle, cfg_small("C2", context=7000, top_k=256), 7000, steps=2, append=False, q2=True)
 
 
-def test_shared_selection_rejects_what_it_cannot_combine(oracle):
-    cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=1000, top_k=64)
-    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+@pytest.mark.parametrize("q2", [False, True])
+def test_shared_selection_with_forced_set_budget_and_append(oracle, q2):
+    # everything at once: one index set per KV head, 20 forced tokens, a budget of 5 % of each sequence, append
+    cfg = cfg_small("C2", batch=3, n_kv_heads=2, n_q_heads=8, context=4000, top_k=400)
+    B, Hkv, Hq, k, R = 3, 2, 8, 400, 4
+    cls = Q2State if q2 else GpuState
+    st = cls(cfg, oracle, capacity=4004, seq_len=[4000, 900, 33], offset_std=0.6, out_dtype=torch.float32)
+    if q2:
+        kvq, dal = torch.from_numpy(st.records()).cuda(), torch.from_numpy(st.alpha).cuda()
+    sl = st.sl.copy()
+    out = torch.empty(B, Hq, 128, device="cuda")
+    idx = torch.empty(B, Hkv, k, dtype=torch.int32, device="cuda")
+    for step in range(2):
+        q, kn, vn = W.make_step_inputs(cfg, step)
+        forced = draw_forced(cfg, sl, 20, 9 + step)
+        kw = dict(q=dev(q, cfg.dtype), k_new=dev(kn, cfg.dtype), v_new=dev(vn, cfg.dtype), seq_len=st.dsl, mu=st.dmu,
+                  codebook=st.dcb, codes=st.dcodes, k=k, k_per_mille=50, out=out, idx_out=idx, workspace=st.ws,
+                  group_shared=True, forced_idx=torch.from_numpy(forced).cuda())
+        kw.update(dict(kvq=kvq, alpha=dal) if q2 else dict(K=st.dK, V=st.dV))
+        sik.sik_decode_step_ex(st.layout, **kw)
+        sync()
+        if q2:
+            oracle.decode_step_q2(q, kn, vn, cfg.dtype, sl, st.mu, st.alpha, st.cb, st.codes, st.qkv, 1)
+        else:
+            oracle.decode_step(q, kn, vn, st.K, st.V, cfg.dtype, sl, st.mu, st.cb, st.codes, 1)
+        assert np.array_equal(st.dsl.cpu().numpy(), sl)
+        s_kv = oracle.shared_scores(q, cfg.dtype, st.cb, st.codes, sl)
+        ref_idx = oracle.topk_with_forced(s_kv, sl, k, forced, 1, 50)        # KV heads as rows
+        g_idx = idx.cpu().numpy()
+        check_sets(g_idx, ref_idx, s_kv, forced, sl, k, 1)
+        for b in range(B):
+            want = max(oracle.budget(k, sl[b], 50), int(((forced[b, 0] >= 0) & (forced[b, 0] < sl[b])).sum()))
+            assert int((g_idx[b, 0] >= 0).sum()) == min(want, int(sl[b]))
+        full = np.repeat(g_idx, R, axis=1)
+        if q2:
+            ref = oracle.sparse_attn_q2(q, cfg.dtype, st.codes, st.qkv, st.alpha, full)
+        else:
+            ref = oracle.sparse_attn(q, st.K, st.V, cfg.dtype, full)
+        check_attention(out.cpu().numpy().astype(np.float64), ref, True)
+
+
+def test_shared_selection_beyond_the_fused_plan(oracle):
+    # contexts above 512K tokens take separate score / select / attention launches, also with one list per KV head
+    cfg = cfg_small("C2", batch=1, n_kv_heads=1, n_q_heads=4, context=3000, top_k=64)
+    st = GpuState(cfg, oracle, capacity=600000, out_dtype=torch.float32)
     q, _, _ = W.make_step_inputs(cfg, 0)
-    out = torch.empty(1, 8, 128, device="cuda")
-    f = torch.full((1, 2, 8), -1, dtype=torch.int32, device="cuda")
-    base = dict(q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu, codebook=st.dcb, codes=st.dcodes,
-                out=out, workspace=st.ws, k=64, group_shared=True)
-    for kw in (dict(forced_idx=f), dict(k_per_mille=75)):
-        with pytest.raises(sik.SikError) as e:
-            sik.sik_decode_step_ex(st.layout, **base, **kw)
-        assert e.value.status == -8
+    out = torch.empty(1, 4, 128, device="cuda")
+    idx = torch.empty(1, 1, 64, dtype=torch.int32, device="cuda")
+    sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
+                           codebook=st.dcb, codes=st.dcodes, k=64, out=out, idx_out=idx, workspace=st.ws,
+                           group_shared=True)
+    sync()
+    sl = st.sl.copy()
+    _, ref_idx = oracle.decode_step_shared(q, None, None, st.K, st.V, cfg.dtype, sl, st.mu, st.cb, st.codes, 64)
+    s_kv = oracle.shared_scores(q, cfg.dtype, st.cb, st.codes, sl)
+    g_idx = idx.cpu().numpy()
+    topk_sets_agree(g_idx[0, 0], ref_idx[0, 0], s_kv[0, 0], 3000, 64)
+    ref = oracle.sparse_attn(q, st.K, st.V, cfg.dtype, np.repeat(g_idx, 4, axis=1))
+    check_attention(out.cpu().numpy().astype(np.float64), ref, True)
