@@ -63,21 +63,81 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
     SIK_TL(18);
     if (!last_arriver(&counters[row * 8 + 3], static_cast<uint32_t>(nsplit), &s_flag)) return;
     SIK_TL_ANY(19);
-    if (tid < kD) {
-        float Mg = kNegBig;
-#pragma unroll 8
-        for (int s2 = 0; s2 < nsplit; ++s2) Mg = fmaxf(Mg, ld_agent(&prow[static_cast<size_t>(s2) * kPartStride]));
-        float lt = 0.0f, ot = 0.0f;
-#pragma unroll 8
-        for (int s2 = 0; s2 < nsplit; ++s2) {  // fixed order: the result does not depend on arrival order
-            const float* pp = prow + static_cast<size_t>(s2) * kPartStride;
-            const float a = fast_exp2(ld_agent(&pp[0]) - Mg);
-            lt += ld_agent(&pp[1]) * a;
-            ot += ld_agent(&pp[2 + tid]) * a;
-        }
-        store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, lt > 0.0f ? ot / lt : 0.0f);
-    }
+    if (tid < kD) store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, merge_partials(prow, nsplit, tid));
     SIK_TL_ANY(20);
+}
+
+// Group-shared selection: the query heads of a KV head attend over ONE index list (idx [B, Hkv, k]).  A workgroup
+// takes a block of up to kSharedHeads query heads of one KV head and a slice of the list, gathers every row
+// once and feeds it to all its heads: the gathered bytes are those of one head, not of R.
+constexpr int kSharedHeads = 4;
+
+template <int DT, int ODT>
+__global__ __launch_bounds__(kBlock) void attn_shared_kernel(const uint16_t* __restrict__ q,
+                                                             const uint16_t* __restrict__ K,
+                                                             const uint16_t* __restrict__ V,
+                                                             const int32_t* __restrict__ idx, int k,
+                                                             float scale_log2e, uint32_t* __restrict__ counters,
+                                                             float* __restrict__ partial, void* __restrict__ out,
+                                                             int Hkv, int Hq, int R, int Lmax, int nsplit, int per,
+                                                             int nblk) {
+    constexpr int NH = kSharedHeads;
+    __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
+    __shared__ float sacc[kBlock / kWave][kD];
+    __shared__ int s_flag;
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int p = lane & 15;
+    const int sp = blockIdx.x % nsplit, ub = blockIdx.x / nsplit;
+    const int blk = ub % nblk;
+    const size_t unit = ub / nblk;
+    const int b = static_cast<int>(unit / Hkv), h = static_cast<int>(unit % Hkv);
+    const int hq0 = h * R + blk * NH;          // first query head of this workgroup
+    const int nh = min(NH, R - blk * NH);      // real heads in the block
+    const size_t row0 = static_cast<size_t>(b) * Hq + hq0;
+    const uint4* Kp = reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
+    const uint4* Vp = reinterpret_cast<const uint4*>(V + unit * Lmax * kD);
+    const int32_t* ip = idx + unit * k;
+
+    uint4 qraw[NH];
+    SoftmaxState st[NH];
+#pragma unroll
+    for (int x = 0; x < NH; ++x) {
+        qraw[x] = x < nh ? reinterpret_cast<const uint4*>(q + (row0 + x) * kD)[p] : make_uint4(0u, 0u, 0u, 0u);
+        init_state(st[x]);
+    }
+    const int j0 = sp * per, j1 = min(k, j0 + per);
+    attend_list_multi<DT, NH>([&](int j) { return ip[j0 + j]; }, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw,
+                              scale_log2e, Lmax, st);
+    float M[NH], Lsum[NH], o[NH];
+#pragma unroll
+    for (int x = 0; x < NH; ++x) {
+        workgroup_merge(st[x], sm, sl, sacc, M[x], Lsum[x], o[x]);
+        __syncthreads();  // the LDS staging is reused by the next head
+    }
+    if (nsplit == 1) {
+#pragma unroll
+        for (int x = 0; x < NH; ++x)
+            if (x < nh && tid < kD)
+                store_out<ODT>(out, (row0 + x) * kD + tid, Lsum[x] > 0.0f ? o[x] / Lsum[x] : 0.0f);
+        return;
+    }
+#pragma unroll
+    for (int x = 0; x < NH; ++x) {
+        if (x < nh && tid < kD) {
+            float* pp = partial + ((row0 + x) * kMaxSplit + sp) * kPartStride;
+            st_agent(&pp[2 + tid], o[x]);
+            if (tid == 0) {
+                st_agent(&pp[0], M[x]);
+                st_agent(&pp[1], Lsum[x]);
+            }
+        }
+    }
+    if (!last_arriver(&counters[row0 * 8 + 3], static_cast<uint32_t>(nsplit), &s_flag)) return;
+    // two heads at a time: threads 0..127 and 128..255 each take a channel of one head
+    for (int x = tid >> 7; x < nh; x += kBlock / kD)
+        store_out<ODT>(out, (row0 + x) * kD + (tid & (kD - 1)),
+                       merge_partials(partial + (row0 + x) * kMaxSplit * kPartStride, nsplit, tid & (kD - 1)));
 }
 
 static void attn_plan(const Dims& d, int k, int* nsplit, int* per) {
@@ -95,6 +155,29 @@ static void attn_plan(const Dims& d, int k, int* nsplit, int* per) {
 
 hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                        const int32_t* idx, bool idx_per_unit, int k, float scale, void* out, hipStream_t s) {
+    if (idx_per_unit && d.R > 1) {
+        // one gather per block of up to 4 query heads; splits planned over those blocks
+        const int nblk = (d.R + kSharedHeads - 1) / kSharedHeads;
+        Dims db = d;
+        db.Hq = d.Hkv * nblk;
+        int nsplit, per;
+        attn_plan(db, k, &nsplit, &per);
+        const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
+        const int grid = nsplit * d.units() * nblk;
+        auto qp = static_cast<const uint16_t*>(q);
+        auto Kp = static_cast<const uint16_t*>(K);
+        auto Vp = static_cast<const uint16_t*>(V);
+#define SIK_ATTNS(DTV, ODTV)                                                                                  \
+    attn_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, k, sl2, w.counters, w.partial, out, \
+                                                          d.Hkv, d.Hq, d.R, d.Lmax, nsplit, per, nblk)
+        if (d.kv_dtype == kBF16) {
+            if (d.out_dtype == kF32) SIK_ATTNS(kBF16, kF32); else SIK_ATTNS(kBF16, kBF16);
+        } else {
+            if (d.out_dtype == kF32) SIK_ATTNS(kF16, kF32); else SIK_ATTNS(kF16, kF16);
+        }
+#undef SIK_ATTNS
+        return hipGetLastError();
+    }
     int nsplit, per;
     attn_plan(d, k, &nsplit, &per);
     const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;

@@ -90,6 +90,64 @@ __device__ __forceinline__ void attend_list(Fetch fetch, int n, int first, int s
     }
 }
 
+// attend_list for NH query heads that share one index list (group-shared selection): every row is gathered once
+// and used NH times.  qraw[h] / st[h]: query slice and softmax state of head h.
+template <int DT, int NH, class Fetch>
+__device__ __forceinline__ void attend_list_multi(Fetch fetch, int n, int first, int step,
+                                                  const uint4* __restrict__ Kp, const uint4* __restrict__ Vp,
+                                                  const uint4 (&qraw)[NH], float scale_log2e, int Lmax,
+                                                  SoftmaxState (&st)[NH]) {
+    const int lane = threadIdx.x & 63;
+    const int slot = lane >> 4, p = lane & 15;
+    for (int base = first; base < n; base += step) {
+        const int jj = base + p;
+        const int mine = jj < n ? fetch(jj) : -1;
+        int id[4];
+        uint4 kv[4], vv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            id[u] = __shfl(mine, (lane & 48) + 4 * u + slot, 64);
+            const bool ok = id[u] >= 0 && id[u] < Lmax;
+            const size_t r = ok ? static_cast<size_t>(id[u]) : 0;
+            id[u] = ok ? id[u] : -1;
+            kv[u] = Kp[r * 16 + p];
+            vv[u] = Vp[r * 16 + p];
+        }
+        float z[NH][4];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            float mnew = st[h].m;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float dot = dot2_acc<DT>(qraw[h].x, kv[u].x, 0.0f);
+                dot = dot2_acc<DT>(qraw[h].y, kv[u].y, dot);
+                dot = dot2_acc<DT>(qraw[h].z, kv[u].z, dot);
+                dot = dot2_acc<DT>(qraw[h].w, kv[u].w, dot);
+                dot = row16_sum(dot) * scale_log2e;
+                z[h][u] = id[u] >= 0 ? dot : kNegBig;
+                mnew = fmaxf(mnew, z[h][u]);
+            }
+            const float corr = fast_exp2(st[h].m - mnew);
+            st[h].l *= corr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st[h].acc[e] *= corr;
+            st[h].m = mnew;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float vf[8];
+            widen8<DT>(vv[u], vf);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const float pu = id[u] >= 0 ? fast_exp2(z[h][u] - st[h].m) : 0.0f;
+                st[h].l += pu;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) st[h].acc[e] = fmaf(pu, vf[e], st[h].acc[e]);
+            }
+        }
+    }
+}
+
 // Combine the wavefronts' states into one (M, l, o[d]) triple of the workgroup: after the call
 // thread d < kD holds o[d]; M and l are returned to every thread.  sm/sl: LDS [4], sacc: LDS [4][kD].
 __device__ __forceinline__ void workgroup_merge(SoftmaxState& st, float* sm, float* sl, float (*sacc)[kD],
@@ -119,6 +177,38 @@ __device__ __forceinline__ void workgroup_merge(SoftmaxState& st, float* sm, flo
         Lsum += sl[w] * a;
         if (tid < kD) o += sacc[w][tid] * a;
     }
+}
+
+// Final value of channel d of one output row from the nsplit (m, l, o[D]) partials that its workgroups published
+// (prow = the row's partial area): one pass in split order - the result does not depend on the arrival order -
+// with 8 splits' loads in flight at a time.
+__device__ __forceinline__ float merge_partials(const float* prow, int nsplit, int d) {
+    float Mg = kNegBig, lt = 0.0f, ot = 0.0f;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float m[8], l[8], o[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float* pp = prow + static_cast<size_t>(s0 + j) * kPartStride;
+            const bool on = s0 + j < nsplit;
+            m[j] = on ? ld_agent(&pp[0]) : kNegBig;
+            l[j] = on ? ld_agent(&pp[1]) : 0.0f;
+            o[j] = on ? ld_agent(&pp[2 + d]) : 0.0f;
+        }
+        float Mb = Mg;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) Mb = fmaxf(Mb, m[j]);
+        const float keep = fast_exp2(Mg - Mb);
+        lt *= keep;
+        ot *= keep;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float a = fast_exp2(m[j] - Mb);
+            lt += l[j] * a;
+            ot += o[j] * a;
+        }
+        Mg = Mb;
+    }
+    return lt > 0.0f ? ot / lt : 0.0f;
 }
 
 __device__ __forceinline__ void init_state(SoftmaxState& st) {

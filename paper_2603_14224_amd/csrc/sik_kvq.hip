@@ -158,20 +158,7 @@ __global__ __launch_bounds__(kBlock) void attn_q2_kernel(const uint16_t* __restr
         }
     }
     if (!last_arriver(&counters[row * 8 + 3], static_cast<uint32_t>(nsplit), &s_flag)) return;
-    if (tid < kD) {
-        float Mg = kNegBig;
-#pragma unroll 8
-        for (int s2 = 0; s2 < nsplit; ++s2) Mg = fmaxf(Mg, ld_agent(&prow[static_cast<size_t>(s2) * kPartStride]));
-        float lt = 0.0f, ot = 0.0f;
-#pragma unroll 8
-        for (int s2 = 0; s2 < nsplit; ++s2) {  // fixed order: the result does not depend on arrival order
-            const float* pp = prow + static_cast<size_t>(s2) * kPartStride;
-            const float a = fast_exp2(ld_agent(&pp[0]) - Mg);
-            lt += ld_agent(&pp[1]) * a;
-            ot += ld_agent(&pp[2 + tid]) * a;
-        }
-        store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, lt > 0.0f ? ot / lt : 0.0f);
-    }
+    if (tid < kD) store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, merge_partials(prow, nsplit, tid));
 }
 
 static int kvq_workgroups(const Dims& d, int tokens) {

@@ -348,3 +348,11 @@ def test_shared_selection_beyond_the_fused_plan(oracle):
     topk_sets_agree(g_idx[0, 0], ref_idx[0, 0], s_kv[0, 0], 3000, 64)
     ref = oracle.sparse_attn(q, st.K, st.V, cfg.dtype, np.repeat(g_idx, 4, axis=1))
     check_attention(out.cpu().numpy().astype(np.float64), ref, True)
+
+
+@pytest.mark.parametrize("R,q2", [(5, False), (4, True)])
+def test_shared_selection_large_launch_gathers_once(oracle, R, q2):
+    # above 2 M keys the plain shared step selects once per KV head and the attention kernel feeds each gathered
+    # row to the query heads of the group (blocks of 4: R = 5 leaves a block with a single head)
+    cfg = cfg_small("C2", batch=8, n_kv_heads=8, n_q_heads=8 * R, context=33000, top_k=300)
+    run_shared(oracle, cfg, 33000, steps=1, append=False, q2=q2, seq_len=[33000, 20000, 5, 33000, 1000, 0, 33000, 777])
