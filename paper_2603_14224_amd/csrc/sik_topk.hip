@@ -97,10 +97,15 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
                                                         uint32_t* __restrict__ cand,
                                                         int32_t* __restrict__ idx, int Hq, int Lmax, int k,
                                                         int nchunk, int chunk) {
+    // 17 KB of LDS per workgroup, so that eight of them fit a compute unit: the selected tokens are kept as 16-bit
+    // offsets into the chunk, and the candidate list shares its storage with the histogram staging of
+    // find_threshold (dead after the barrier that follows it).
+    static_assert(kSelChunkMax <= 65536, "16-bit chunk offsets");
+    static_assert((kBlock / kWave) * kBins <= 2 * kCandCap + 16, "the staging area fits the candidate list");
     __shared__ uint32_t h256[kBlock];
-    __shared__ int32_t l_sel[kSelChunkMax];
-    __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 16];
-    __shared__ uint32_t red[(kBlock / kWave) * kBins];
+    __shared__ uint16_t l_sel[kSelChunkMax];
+    __shared__ __align__(8) uint32_t red[2 * kCandCap + 16];
+    uint32_t* const l_cand = red;
     __shared__ int s_flag, sthr[3];
     __shared__ uint32_t s_nsel, s_ncand, s_base[2], sh[4];
 
@@ -121,6 +126,17 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
         s_ncand = 0u;
     }
     const int hact = L > 0 ? (L + hchunk - 1) / hchunk : 1;  // chunks the producer ran for this sequence
+    // the first 4096 scores of the chunk (all of them: chunks are at most kSelChunkMax long) are requested
+    // together with the histograms, one round trip for both
+    const bool vec = (sstride & 3) == 0;  // rows are 16-byte aligned: vector loads
+    const float4* s4 = reinterpret_cast<const float4*>(s);
+    const int q0 = start >> 2, q1 = (end + 3) >> 2;  // start is a multiple of 256
+    float4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int qi = q0 + j * kBlock + tid;
+        v[j] = (vec && qi < q1) ? s4[qi] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     const HistLoads hl = load_chunk_hists(parthist + static_cast<size_t>(row) * hchunks * kHistWords, hact);
     const Threshold th = find_threshold(hl, kk, L, red, sh, sthr);
     const int bstar = th.bstar, cgt = th.cgt, nb = th.nb;
@@ -128,27 +144,26 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     __syncthreads();
     SIK_TL(9);
 
-    auto classify = [&](float v, int i) {
-        const int bin = bstar < 0 ? 0 : score_bin(v, lo, scale);
+    auto classify = [&](float x, int i) {
+        const int bin = bstar < 0 ? 0 : score_bin(x, lo, scale);
         if (bin > bstar) {
-            l_sel[atomicAdd(&s_nsel, 1u)] = i;
+            l_sel[atomicAdd(&s_nsel, 1u)] = static_cast<uint16_t>(i - start);
         } else if (bin == bstar && ranked) {
             const uint32_t pos = atomicAdd(&s_ncand, 1u);
             if (pos < static_cast<uint32_t>(kCandCap)) {
-                l_cand[2 * pos] = float_to_key(v);
+                l_cand[2 * pos] = float_to_key(x);
                 l_cand[2 * pos + 1] = static_cast<uint32_t>(i);
             }
         }
     };
-    if ((sstride & 3) == 0) {  // rows are 16-byte aligned: vector loads
-        const float4* s4 = reinterpret_cast<const float4*>(s);
-        const int q0 = start >> 2, q1 = (end + 3) >> 2;  // start is a multiple of 256
+    if (vec) {
         for (int base = q0; base < q1; base += 4 * kBlock) {
-            float4 v[4];
+            if (base != q0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int qi = base + j * kBlock + tid;
-                v[j] = qi < q1 ? s4[qi] : make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int j = 0; j < 4; ++j) {
+                    const int qi = base + j * kBlock + tid;
+                    v[j] = qi < q1 ? s4[qi] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -172,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     __syncthreads();
     for (uint32_t j = tid; j < s_nsel; j += kBlock) {
         const uint32_t pos = s_base[0] + j;
-        if (pos < static_cast<uint32_t>(k)) out[pos] = l_sel[j];
+        if (pos < static_cast<uint32_t>(k)) out[pos] = start + static_cast<int32_t>(l_sel[j]);
     }
     const uint32_t ncand = min(s_ncand, static_cast<uint32_t>(kCandCap));
     uint32_t* crow = cand + static_cast<size_t>(row) * kCandCap * 2;
