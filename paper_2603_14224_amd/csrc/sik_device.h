@@ -64,12 +64,16 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
     return __uint_as_float(u);
 }
 
+// Bin coordinate of a score, x = (s - lo) * scale evaluated as one fused multiply-add (-lo * scale is invariant
+// wherever this is used in a loop): non-decreasing in s for scale >= 0.  Every kernel that bins or classifies
+// scores goes through this one function, so that they agree on every score.
+__device__ __forceinline__ float bin_coord(float s, float lo, float scale) { return fmaf(s, scale, -lo * scale); }
+
 // Histogram bin of a score: a non-decreasing function of s for fixed (lo, scale >= 0), so that
 // "bin above the threshold bin" implies "score above every score of the threshold bin".
 __device__ __forceinline__ int score_bin(float s, float lo, float scale) {
-    // clamp, then truncate: equal to floor-then-clamp for every x (negative x ends in bin 0 either way)
-    const float x = (s - lo) * scale;
-    return static_cast<int>(fminf(fmaxf(x, 0.0f), static_cast<float>(kBins - 1)));
+    // clamp (median of x, 0, kBins - 1; 0 for a NaN), then truncate: equal to floor-then-clamp for every x
+    return static_cast<int>(__builtin_amdgcn_fmed3f(bin_coord(s, lo, scale), 0.0f, static_cast<float>(kBins - 1)));
 }
 
 // Agent-scope relaxed atomics on global memory.

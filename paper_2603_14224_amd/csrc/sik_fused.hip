@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     uint32_t* pool = cand + static_cast<size_t>(gridDim.x / nchunk) * regions * kCandWaveWords +
                      static_cast<size_t>(row) * kCandCap * 2;
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    // bin(s) > b*  <=>  x >= b* + 1 and bin(s) == b*  <=>  b* <= x < b* + 1 with x = (s - lo) * scale,
+    // bin(s) > b*  <=>  x >= b* + 1 and bin(s) == b*  <=>  b* <= x < b* + 1 with x = bin_coord(s),
     // the clamped end bins taking everything beyond them (score_bin is floor + clamp of the same x)
     // (open ends are -FLT_MAX, not -infinity: a forced token's score is -infinity and must fail every test)
     const float hi_f = bstar < 0 ? -3.4028235e38f : (bstar >= kBins - 1 ? INFINITY : static_cast<float>(bstar + 1));
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
             const float v4[4] = {sv[j].x, sv[j].y, sv[j].z, sv[j].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float x = (v4[e] - lo) * scale;
+                const float x = bin_coord(v4[e], lo, scale);
                 smask |= (x >= hi_f ? 1u : 0u) << (4 * j + e);
                 gmask |= (x >= lo_f ? 1u : 0u) << (4 * j + e);
             }
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int i = start + (j * kBlock + tid) * 4 + e;
-                const float x = i < end ? (v4[e] - lo) * scale : __builtin_nanf("");
+                const float x = i < end ? bin_coord(v4[e], lo, scale) : __builtin_nanf("");
                 smask |= (x >= hi_f ? 1u : 0u) << (4 * j + e);
                 gmask |= (x >= lo_f ? 1u : 0u) << (4 * j + e);
             }

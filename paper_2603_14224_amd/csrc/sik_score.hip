@@ -1,15 +1,20 @@
 // LUT-GEMV retrieval over the packed sign codes for gfx950 (section "Compressed-Domain
 // Top-k Retrieval"): Table^(g)[j] = q^(g) . c_j^(g), score_i = sum_g Table^(g)[Code_g(k_i)].
 //
-// One workgroup serves one (batch, kv head) for a block of up to 4 query heads of its GQA group
-// (a wider group is served by several head blocks that re-read the codes from L2: two float4
+// One workgroup of 512 threads serves one (batch, kv head) for a block of up to 4 query heads of its GQA
+// group (a wider group is served by several head blocks that re-read the codes from L2: two float4
 // tables in one workgroup were measured slower, 65 us against 2 x 18 us on the 8:1 workload)
 // and a contiguous chunk of tokens.  The tables live in LDS as float4 entries holding the
 // same (g, j) entry of four query heads: the 16 entries of a group span 256 B = all 64 LDS
 // banks once, so the data-dependent ds_read_b128 of a wavefront (all lanes are at the same g)
 // is bank-conflict free whatever the codes are.  Each lane owns one token per load: a single
 // 128-bit load brings its 32 codes, i.e. a wavefront streams 1 KB of the code plane per load;
-// four such loads per lane are in flight while the previous four tokens are scored.
+// two such loads per lane are in flight while the previous two tokens are scored.
+//
+// What bounds the scan is vector-instruction issue: 4 x 32 adds per token for a block of four heads cannot be
+// avoided (no packed fp32 here), so everything around them is kept small - one instruction per table offset,
+// four per histogram count - and the kernel stays under 128 registers, i.e. four wavefronts per SIMD, which
+// hide the LDS latency (ds_read_b128 itself sustains over 200 B/clk per compute unit, twice what the scan asks).
 //
 // A launch with one query head per KV head (no GQA, or the summed query of a group-shared selection) uses
 // scalar table entries instead (HB = 1).
@@ -29,41 +34,82 @@ constexpr int kIterTokens = 1024;  // tokens a workgroup scores per loop iterati
 
 constexpr int kHB = 4;  // query heads per workgroup = components of one float4 table entry
 
-// Table lookups of one token.  HB = 4: float4 entries (four query heads at once), 256 B per group; HB = 1: scalar
-// entries, 64 B per group (one query head per KV head: multi-head attention, or the summed query of a
-// group-shared selection) - a quarter of the LDS traffic, the 16 entries of a group on 16 different banks.
+// (byte BY of w) & mask in one instruction (sub-dword operand select), for any BY; the compiler finds this form
+// for the upper byte and the upper half only.
+template <int BY>
+__device__ __forceinline__ uint32_t byte_and(uint32_t w, uint32_t mask) {
+    uint32_t r;
+    if constexpr (BY == 0)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD"
+            : "=v"(r) : "v"(w), "v"(mask));
+    else if constexpr (BY == 1)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD"
+            : "=v"(r) : "v"(w), "v"(mask));
+    else if constexpr (BY == 2)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD"
+            : "=v"(r) : "v"(w), "v"(mask));
+    else
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD"
+            : "=v"(r) : "v"(w), "v"(mask));
+    return r;
+}
+
+// Table lookups.  HB = 4: float4 entries (four query heads at once), 256 B per group; HB = 1: scalar entries,
+// 64 B per group (one query head per KV head: multi-head attention, or the summed query of a group-shared
+// selection) - a quarter of the LDS traffic, the 16 entries of a group on 16 different banks.
+// A batch = the 8 lookups of one 32-bit word of a token's code (groups 8 dw .. 8 dw + 7).  A table offset costs
+// one instruction: byte b of the code word, or of the word shifted by one nibble, under the mask that leaves
+// Code x entry size (9 instructions per batch instead of 16).
 template <int HB>
-__device__ __forceinline__ void score_token(const uint4 code, const float* lut, float* acc) {
+struct TableEntry {
+    using type = float;
+};
+template <>
+struct TableEntry<4> {
+    using type = float4;
+};
+
+template <int HB>
+__device__ __forceinline__ void lookup_batch(uint32_t word, int dw, const float* lut,
+                                             typename TableEntry<HB>::type (&v)[8]) {
+    using T = typename TableEntry<HB>::type;
+    constexpr int kEnt = 4 * HB;            // bytes per table entry
+    constexpr uint32_t kMask = 15u * kEnt;  // Code * kEnt
+    constexpr int kUp = HB == 4 ? 0 : 2;    // high nibble (Code * 16) -> Code * kEnt: shift right by kUp
+    constexpr int kDown = HB == 4 ? 4 : 2;  // low nibble -> Code * kEnt: shift left by kDown
+    // byte `by` of the word: high nibble = Code of group 8 dw + 2 by, low nibble = Code of the next group
+    const uint32_t whi = kUp ? word >> kUp : word;
+    const uint32_t wlo = word << kDown;
+    uint32_t off[8];
+    off[0] = byte_and<0>(whi, kMask);
+    off[1] = byte_and<0>(wlo, kMask);
+    off[2] = byte_and<1>(whi, kMask);
+    off[3] = byte_and<1>(wlo, kMask);
+    off[4] = byte_and<2>(whi, kMask);
+    off[5] = byte_and<2>(wlo, kMask);
+    off[6] = byte_and<3>(whi, kMask);
+    off[7] = byte_and<3>(wlo, kMask);
+    const char* base = reinterpret_cast<const char*>(lut) + dw * 8 * 16 * kEnt;
 #pragma unroll
-    for (int s = 0; s < HB; ++s) acc[s] = 0.0f;
-    const uint32_t w[4] = {code.x, code.y, code.z, code.w};
-    const char* base = reinterpret_cast<const char*>(lut);
+    for (int n = 0; n < 8; ++n) v[n] = *reinterpret_cast<const T*>(base + n * 16 * kEnt + off[n]);
+}
+
+// acc (+)= the batch, groups in ascending order; the first batch of a token starts the sums.
+template <int HB>
+__device__ __forceinline__ void add_batch(bool first, const typename TableEntry<HB>::type (&v)[8], float* acc) {
 #pragma unroll
-    for (int dw = 0; dw < 4; ++dw) {
-#pragma unroll
-        for (int by = 0; by < 4; ++by) {
-            // byte (4 dw + by) of the token: high nibble = Code of group g, low nibble = group g+1
-            const int g = 8 * dw + 2 * by;
-            const uint32_t bits = w[dw] >> (8 * by);
-            if constexpr (HB == 4) {
-                const uint32_t off_hi = bits & 0xf0u;  // Code * 16 B
-                const uint32_t off_lo = (bits & 0x0fu) << 4;
-                const float4 v0 = *reinterpret_cast<const float4*>(base + g * 256 + off_hi);
-                acc[0] += v0.x;
-                acc[1] += v0.y;
-                acc[2] += v0.z;
-                acc[3] += v0.w;
-                const float4 v1 = *reinterpret_cast<const float4*>(base + (g + 1) * 256 + off_lo);
-                acc[0] += v1.x;
-                acc[1] += v1.y;
-                acc[2] += v1.z;
-                acc[3] += v1.w;
+    for (int n = 0; n < 8; ++n) {
+        if constexpr (HB == 4) {
+            if (first && n == 0) {
+                acc[0] = v[n].x, acc[1] = v[n].y, acc[2] = v[n].z, acc[3] = v[n].w;
             } else {
-                const uint32_t off_hi = (bits & 0xf0u) >> 2;  // Code * 4 B
-                const uint32_t off_lo = (bits & 0x0fu) << 2;
-                acc[0] += *reinterpret_cast<const float*>(base + g * 64 + off_hi);
-                acc[0] += *reinterpret_cast<const float*>(base + (g + 1) * 64 + off_lo);
+                acc[0] += v[n].x;
+                acc[1] += v[n].y;
+                acc[2] += v[n].z;
+                acc[3] += v[n].w;
             }
+        } else {
+            acc[0] = (first && n == 0) ? v[n] : acc[0] + v[n];
         }
     }
 }
@@ -292,12 +338,35 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
                 if (i < end) cur[j] = cp[i];
             }
         }
+        if (t_new >= base && t_new < nbase) {  // the appended token's code was written before the barriers above
+#pragma unroll
+            for (int j = 0; j < kTokPerIter; ++j)
+                if (base + j * BLK + tid == t_new) code[j] = *reinterpret_cast<const uint4*>(newcode);
+        }
+        // Software pipeline over the 4 * kTokPerIter batches of this thread's tokens: the lookups of batch i + 1
+        // are issued before the adds of batch i, so that 8 to 16 LDS reads are in flight per wavefront at under
+        // 128 registers (left to itself the compiler either waits for each read or holds a whole token's 32).
+        typename TableEntry<HB>::type v[2][8];
+        auto word = [&](int i) {
+            const uint4& cw = code[i >> 2];
+            return (i & 3) == 0 ? cw.x : ((i & 3) == 1 ? cw.y : ((i & 3) == 2 ? cw.z : cw.w));
+        };
+        lookup_batch<HB>(word(0), 0, lut, v[0]);
 #pragma unroll
         for (int j = 0; j < kTokPerIter; ++j) {
             const int tok = base + j * BLK + tid;
             float acc[HB];
-            if (tok == t_new) code[j] = *reinterpret_cast<const uint4*>(newcode);  // written before the barriers above
-            score_token<HB>(code[j], lut, acc);
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const int i = 4 * j + dw;
+                if (i + 1 < 4 * kTokPerIter) lookup_batch<HB>(word(i + 1), (i + 1) & 3, lut, v[(i + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                add_batch<HB>(dw == 0, v[i & 1], acc);
+                // (keeps the adds here: as they are only used under "tok < end" they would move down there)
+#pragma unroll
+                for (int s = 0; s < HB; ++s) asm volatile("" : "+v"(acc[s]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if (tok < end) {
                 bool forced = false;
                 if constexpr (FORCED) forced = (fbits[(tok - start) >> 5] >> ((tok - start) & 31)) & 1u;
@@ -324,21 +393,17 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     SIK_TL(4);
 }
 
-// Workgroup size.  Small launches (one sequence) are latency-bound: 512 threads = two wavefronts per SIMD share one
-// table build and interleave their LDS reads and adds (measured on 1 x 8 KV heads: 5.6 against 6.5 us at 32K,
-// 13.4 against 14.6 us at 128K).  Large launches are bound by LDS bandwidth either way and run a little faster
-// as twice as many 256-thread workgroups (38 against 41 us on 32 x 8 heads x 16K).
-static int score_block(const Dims& d, int nhb) {
-    return static_cast<int64_t>(d.units()) * nhb * d.Lmax <= (2 << 20) ? 512 : 256;
-}
+constexpr int kScoreBlock = 512;  // two wavefronts per SIMD share one table build; 256-thread workgroups were
+                                  // measured slower at every size (32 x 8 KV heads x 16K: 37 against 33 us)
 
-// Tokens per workgroup: about 2 x 256 or 1 x 512 threads per compute unit, whole loop iterations of 1024
-// tokens (so that the table build and the 2 KB histogram per head are amortised), at most kMaxChunks per head.
+// Tokens per workgroup: one workgroup per compute unit for small launches (latency-bound: fewest table builds),
+// two (scalar tables: four) for large ones; whole loop iterations of 1024 tokens (so that the table build and
+// the 2 KB histogram per head are amortised), at most kMaxChunks per head.
 void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
     const int nhb = (d.R + kHB - 1) / kHB;
     const int units = d.units() * nhb;
-    // (scalar tables, R = 1: 62 registers, 8 wavefronts per SIMD fit, and a table costs 512 entries to build)
-    const int target = score_block(d, nhb) == 512 ? 256 : (d.R == 1 ? 2048 : 512);
+    const bool small = static_cast<int64_t>(units) * d.Lmax <= (2 << 20);
+    const int target = small ? 256 : (d.R == 1 ? 1024 : 512);
     int want = (target + units - 1) / units;
     if (want > kMaxChunks) want = kMaxChunks;
     int ch = (d.Lmax + want - 1) / want;
@@ -363,20 +428,19 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     score_plan(d, &nhb, &nchunk, &chunk);
     const int grid = nchunk * nhb * d.units();
     auto qp = static_cast<const uint16_t*>(q);
-#define SIK_SCORE1(HV, BLKV, FV, HBV)                                                                        \
-    score_kernel<DT, HV, BLKV, FV, HBV><<<grid, BLKV, 0, s>>>(                                               \
+#define SIK_SCORE1(HV, FV, HBV)                                                                              \
+    score_kernel<DT, HV, kScoreBlock, FV, HBV><<<grid, kScoreBlock, 0, s>>>(                                 \
         qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
         w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
         ap.alpha, static_cast<uint2*>(ap.kvq), forced_idx, n_forced, q_sum, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, \
         nhb)
-#define SIK_SCORE(HV, BLKV, FV)                                                                              \
+#define SIK_SCORE(HV, FV)                                                                                    \
     do {                                                                                                     \
-        if (d.R == 1) SIK_SCORE1(HV, BLKV, FV, 1); else SIK_SCORE1(HV, BLKV, FV, kHB);                       \
+        if (d.R == 1) SIK_SCORE1(HV, FV, 1); else SIK_SCORE1(HV, FV, kHB);                                   \
     } while (0)
-    const bool wide = score_block(d, nhb) == 512;
-    if (!w) { if (wide) SIK_SCORE(false, 512, false); else SIK_SCORE(false, 256, false); }
-    else if (n_forced > 0) { if (wide) SIK_SCORE(true, 512, true); else SIK_SCORE(true, 256, true); }
-    else { if (wide) SIK_SCORE(true, 512, false); else SIK_SCORE(true, 256, false); }
+    if (!w) SIK_SCORE(false, false);
+    else if (n_forced > 0) SIK_SCORE(true, true);
+    else SIK_SCORE(true, false);
 #undef SIK_SCORE
 #undef SIK_SCORE1
     return hipGetLastError();
