@@ -167,13 +167,25 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t* __r
 #pragma unroll 8
         for (int e = 0; e < kEncEntries; ++e) col[e * kWave] = 0.0f;
     }
+    // The rows of the next iteration are requested before the current ones are processed (the accumulator
+    // updates are a chain of dependent LDS accesses that would otherwise sit idle behind the HBM latency).
+    // Every request is an unconditional load (rows past the end re-read the last row and are ignored), so that
+    // the wait before processing counts the outstanding loads instead of draining them all.
+    uint2 nx[kEncUnroll];
+    const int last = end - 1;
+    auto request = [&](int i0) {
+#pragma unroll
+        for (int u = 0; u < kEncUnroll; ++u) {
+            const int i = min(i0 + u * kEncTokPerIter, last);
+            nx[u] = base[static_cast<size_t>(i) * 32 + g];
+        }
+    };
+    if (start < end) request(start + sub);
     for (int i0 = start + sub; i0 < end; i0 += kEncTokPerIter * kEncUnroll) {
         uint2 v[kEncUnroll];
 #pragma unroll
-        for (int u = 0; u < kEncUnroll; ++u) {
-            const int i = i0 + u * kEncTokPerIter;
-            v[u] = i < end ? base[static_cast<size_t>(i) * 32 + g] : make_uint2(0u, 0u);
-        }
+        for (int u = 0; u < kEncUnroll; ++u) v[u] = nx[u];
+        request(i0 + kEncTokPerIter * kEncUnroll);
 #pragma unroll
         for (int u = 0; u < kEncUnroll; ++u) {
             const int i = i0 + u * kEncTokPerIter;
