@@ -67,13 +67,20 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
 // Bin coordinate of a score, x = (s - lo) * scale evaluated as one fused multiply-add (-lo * scale is invariant
 // wherever this is used in a loop): non-decreasing in s for scale >= 0.  Every kernel that bins or classifies
 // scores goes through this one function, so that they agree on every score.
-__device__ __forceinline__ float bin_coord(float s, float lo, float scale) { return fmaf(s, scale, -lo * scale); }
+__device__ __forceinline__ float bin_shift(float lo, float scale) { return -lo * scale; }
+__device__ __forceinline__ float bin_coord_shifted(float s, float scale, float shift) { return fmaf(s, scale, shift); }
+__device__ __forceinline__ float bin_coord(float s, float lo, float scale) {
+    return bin_coord_shifted(s, scale, bin_shift(lo, scale));
+}
+__device__ __forceinline__ int bin_of_coord(float x) {
+    // clamp (median of x, 0, kBins - 1; 0 for a NaN), then truncate: equal to floor-then-clamp for every x
+    return static_cast<int>(__builtin_amdgcn_fmed3f(x, 0.0f, static_cast<float>(kBins - 1)));
+}
 
 // Histogram bin of a score: a non-decreasing function of s for fixed (lo, scale >= 0), so that
 // "bin above the threshold bin" implies "score above every score of the threshold bin".
 __device__ __forceinline__ int score_bin(float s, float lo, float scale) {
-    // clamp (median of x, 0, kBins - 1; 0 for a NaN), then truncate: equal to floor-then-clamp for every x
-    return static_cast<int>(__builtin_amdgcn_fmed3f(bin_coord(s, lo, scale), 0.0f, static_cast<float>(kBins - 1)));
+    return bin_of_coord(bin_coord(s, lo, scale));
 }
 
 // Agent-scope relaxed atomics on global memory.

@@ -326,6 +326,14 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
     }
 
     SIK_TL(2);
+    // bin scale and shift of each head in registers (read from LDS inside the loop they would be fetched again
+    // for every token: the histogram updates may alias them as far as the compiler knows)
+    float bscale[HB], bshift[HB];
+#pragma unroll
+    for (int s = 0; s < HB; ++s) {
+        bscale[s] = HIST ? bp[s][1] : 0.0f;
+        bshift[s] = HIST ? bin_shift(bp[s][0], bp[s][1]) : 0.0f;
+    }
     for (int base = start; base < end; base += kIterTokens) {
         uint4 code[kTokPerIter];
 #pragma unroll
@@ -376,7 +384,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__
                         // streamed once, read by the next kernel: keep it out of the way of the end-of-kernel write-back
                         __builtin_nontemporal_store(forced ? -INFINITY : acc[s], &scores[(row0 + s) * sstride + tok]);
                         if constexpr (HIST)
-                            if (!forced) atomicAdd(&lhist[s * kBins + score_bin(acc[s], bp[s][0], bp[s][1])], 1u);
+                            if (!forced)
+                                atomicAdd(&lhist[s * kBins + bin_of_coord(bin_coord_shifted(acc[s], bscale[s], bshift[s]))],
+                                          1u);
                     }
                 }
             }
