@@ -9,7 +9,9 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsik.so")
 SOURCES = ["sik_api.hip", "sik_quantize.hip", "sik_score.hip", "sik_topk.hip", "sik_attn.hip", "sik_fused.hip", "sik_kvq.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",
+         # the first kernel arguments arrive in scalar registers with the wavefront instead of through a load
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def build(verbose: bool = False, defines=(), lib: str = LIB, objdir_name: str = "_build") -> str:

@@ -38,16 +38,23 @@ constexpr int kCandWaveWords = 1 + 2 * kWaveCand;  // words per region
 // records of the 2-bit cache (kvq, alpha) and dequantised in registers, instead of as 16-bit K and V rows.
 template <int DT, int ODT, int NQ, bool KVQ>
 __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const uint2* __restrict__ kvq, const float* __restrict__ alpha, const float* __restrict__ scores, int sstride, int32_t* __restrict__ seq_len, int appended,
-    const uint32_t* __restrict__ parthist, const float* __restrict__ binp, uint32_t* __restrict__ counters,
-    uint32_t* __restrict__ cand, float* __restrict__ partial, int32_t* __restrict__ idx_ws,
-    int32_t* __restrict__ idx_out, void* __restrict__ out, float scale_log2e, int k, int Hkv, int Hq, int R,
-    int Lmax, int nchunk, int hchunks, const int32_t* __restrict__ forced_idx, int n_forced,
+    // The first 14 dwords are preloaded into scalar registers with the wavefront: what the index arithmetic and
+    // the first loads need comes first (small integers packed), so that they do not wait for a round trip to the
+    // argument block.  dims0 = Hkv | Hq << 16, dims1 = R | nchunk << 16,
+    // dims2 = hchunks | n_forced << 8 | shared << 16 | appended << 17.
+    const float* __restrict__ scores, const uint16_t* __restrict__ q, const uint32_t* __restrict__ parthist,
+    const float* __restrict__ binp, int32_t* __restrict__ seq_len, int sstride, uint32_t dims0, uint32_t dims1,
+    uint32_t dims2, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V, const uint2* __restrict__ kvq,
+    const float* __restrict__ alpha, uint32_t* __restrict__ counters, uint32_t* __restrict__ cand,
+    float* __restrict__ partial, int32_t* __restrict__ idx_ws, int32_t* __restrict__ idx_out,
+    void* __restrict__ out, float scale_log2e, int k, int Lmax, const int32_t* __restrict__ forced_idx,
     const uint16_t* __restrict__ fK, const uint16_t* __restrict__ fV, const float* __restrict__ mu,
-    int k_per_mille, int shared) {
+    int k_per_mille) {
     constexpr int kChunk = 1024 * NQ;
     constexpr int kListCap = 512;  // selected-token slots per wavefront; flushed to the gather when half full
+    const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nchunk = dims1 >> 16;
+    const int hchunks = dims2 & 0xffu, n_forced = (dims2 >> 8) & 0xffu;
+    const int shared = (dims2 >> 16) & 1u, appended = (dims2 >> 17) & 1u;
     __shared__ int32_t l_sel[kBlock / kWave][kListCap];
     __shared__ uint32_t red[(kBlock / kWave) * kBins];
     __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 64];
@@ -68,13 +75,8 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     // launch ran on the summed query), so the R query heads of a group find the same threshold and select the
     // same tokens, each attending with its own query; the group's first head writes the one index list.
     const size_t srow = shared ? unit : static_cast<size_t>(row);
-    int32_t* const orow = !idx_out ? nullptr
-                          : !shared ? idx_out + static_cast<size_t>(row) * k
-                                    : (hq % R == 0 ? idx_out + unit * k : nullptr);
 
     // ---- 1. every load that does not depend on another goes out now ---------------------------
-    // (the histogram loads come last in program order because their values are consumed as they
-    // arrive: whatever is issued after them would wait for them)
     const float4* s4 = reinterpret_cast<const float4*>(scores + srow * sstride + start);
     float4 sv[NQ];
 #pragma unroll
@@ -89,10 +91,17 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         al1 = reinterpret_cast<const float4*>(alpha + unit * kD)[2 * p + 1];
     }
     const float lo = binp[srow * 2], scale = binp[srow * 2 + 1];
+    const HistLoads hl = load_chunk_hists(parthist + srow * hchunks * kHistWords, hchunks);
+    int L = seq_len[b];
+    // Everything above comes from the preloaded arguments; what follows needs the rest of the argument block,
+    // which arrives a memory round trip after the wavefront started.
+    int32_t* const orow = !idx_out ? nullptr
+                          : !shared ? idx_out + static_cast<size_t>(row) * k
+                                    : (hq % R == 0 ? idx_out + unit * k : nullptr);
     // StepOptions set (n_forced > 0): thread t < n_forced looks after entry t.  The scoring launch gave these tokens
     // -infinity, so they are never selected below; workgroup 0 of the head attends them on top of its own.
     int fi = -1;
-    if (tid < n_forced) fi = forced_idx[unit * n_forced + tid];
+    if (n_forced > 0 && tid < n_forced) fi = forced_idx[unit * n_forced + tid];
     float mu_dot = 0.0f;  // q . mu over this lane's channels: centres the full-precision forced keys
     if (KVQ && fK != nullptr && c == 0) {
         float qf[8];
@@ -102,8 +111,6 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         mu_dot = qf[0] * m0.x + qf[1] * m0.y + qf[2] * m0.z + qf[3] * m0.w + qf[4] * m1.x + qf[5] * m1.y +
                  qf[6] * m1.z + qf[7] * m1.w;
     }
-    const HistLoads hl = load_chunk_hists(parthist + srow * hchunks * kHistWords, hchunks);
-    int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const bool grew = appended && L < Lmax;  // the scoring launch stored and scored one more token
     if (grew) L += 1;
@@ -486,7 +493,8 @@ bool fused_plan(const Dims& d, int* nchunk, int* chunk) {
     while (ch < 8192 && static_cast<int64_t>(ch) * want < d.Lmax) ch *= 2;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
-    return *nchunk <= kMaxChunks;
+    // (the kernel takes the head counts as 16-bit fields of its preloaded arguments)
+    return *nchunk <= kMaxChunks && d.Hkv <= 0xffff && d.Hq <= 0xffff;
 }
 
 size_t fused_cand_words(const Dims& d) {
@@ -514,11 +522,15 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     auto Kp = static_cast<const uint16_t*>(K);
     auto Vp = static_cast<const uint16_t*>(V);
     auto Rp = static_cast<const uint2*>(kvq);
+    if (d.Hkv > 0xffff || d.Hq > 0xffff || nchunk > 0xffff || hchunks > 0xff || fo.n > 0xff) return hipErrorInvalidValue;
+    const uint32_t dims0 = static_cast<uint32_t>(d.Hkv) | static_cast<uint32_t>(d.Hq) << 16;
+    const uint32_t dims1 = static_cast<uint32_t>(d.R) | static_cast<uint32_t>(nchunk) << 16;
+    const uint32_t dims2 = static_cast<uint32_t>(hchunks) | static_cast<uint32_t>(fo.n) << 8 |
+                           (fo.group_shared ? 1u << 16 : 0u) | (appended ? 1u << 17 : 0u);
 #define SIK_FUSED_Q(NQV, KVQV)                                                                              \
     select_attend_kernel<DT, ODT, NQV, KVQV><<<grid, kBlock, 0, s>>>(                                       \
-        qp, Kp, Vp, Rp, alpha, w.scores, w.sstride, seq_len, appended ? 1 : 0, w.parthist, w.binp, w.counters, \
-        w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, hchunks, fo.idx, fo.n,    \
-        fo.fK, fo.fV, fo.mu, fo.k_per_mille, fo.group_shared ? 1 : 0)
+        w.scores, qp, w.parthist, w.binp, seq_len, w.sstride, dims0, dims1, dims2, Kp, Vp, Rp, alpha, w.counters, \
+        w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Lmax, fo.idx, fo.fK, fo.fV, fo.mu, fo.k_per_mille)
 #define SIK_FUSED(NQV)                                                                                      \
     do {                                                                                                    \
         if (kvq) SIK_FUSED_Q(NQV, true); else SIK_FUSED_Q(NQV, false);                                      \

@@ -118,23 +118,16 @@ __device__ __forceinline__ void add_batch(bool first, const typename TableEntry<
 // the attention that follows and must not compete in the selection: their score is stored as -infinity and
 // they are left out of the histogram ("Full Precision Sink Tokens": a fixed set that is always attended).
 template <int DT, bool HIST, int BLK, bool FORCED, int HB>
-__global__ __launch_bounds__(BLK) void score_kernel(const uint16_t* __restrict__ q,
-                                                       const float* __restrict__ codebook,
-                                                       const uint8_t* __restrict__ codes,
-                                                       const int32_t* __restrict__ seq_len,
-                                                       float* __restrict__ scores, int sstride,
-                                                       uint32_t* __restrict__ parthist,
-                                                       float* __restrict__ binp,
-                                                       uint32_t* __restrict__ zero_counters,
-                                                       const uint16_t* __restrict__ k_new,
-                                                       const uint16_t* __restrict__ v_new,
-                                                       uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc,
-                                                       const float* __restrict__ mu,
-                                                       uint8_t* __restrict__ codes_w,
-                                                       const float* __restrict__ alpha, uint2* __restrict__ kvq,
-                                                       const int32_t* __restrict__ forced_idx, int n_forced,
-                                                       int q_sum, int Hkv, int Hq, int R,
-                                                       int Lmax, int nchunk, int chunk, int nhb) {
+__global__ __launch_bounds__(BLK) void score_kernel(
+    // the first 14 dwords are preloaded into scalar registers with the wavefront: what the index arithmetic and
+    // the first loads need comes first, so that they do not wait for a round trip to the argument block
+    const uint16_t* __restrict__ q, const float* __restrict__ codebook, const uint8_t* __restrict__ codes, int Hkv,
+    int Hq, int R, int Lmax, int nchunk, int chunk, int nhb, int q_sum, const int32_t* __restrict__ seq_len,
+    float* __restrict__ scores, int sstride, uint32_t* __restrict__ parthist, float* __restrict__ binp,
+    uint32_t* __restrict__ zero_counters, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+    uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc, const float* __restrict__ mu,
+    uint8_t* __restrict__ codes_w, const float* __restrict__ alpha, uint2* __restrict__ kvq,
+    const int32_t* __restrict__ forced_idx, int n_forced) {
     static_assert(HB == 1 || HB == kHB, "scalar or float4 table entries");
     constexpr int kTokPerIter = kIterTokens / BLK;
     __shared__ __align__(16) float lut[kG * 16 * HB];  // entry (g, j): HB consecutive floats, one per query head
@@ -440,10 +433,10 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     auto qp = static_cast<const uint16_t*>(q);
 #define SIK_SCORE1(HV, FV, HBV)                                                                              \
     score_kernel<DT, HV, kScoreBlock, FV, HBV><<<grid, kScoreBlock, 0, s>>>(                                 \
-        qp, codebook, codes, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr,          \
-        w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, \
-        ap.alpha, static_cast<uint2*>(ap.kvq), forced_idx, n_forced, q_sum, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, \
-        nhb)
+        qp, codebook, codes, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb, q_sum, seq_len, scores,           \
+        w ? w->sstride : d.Lmax, w ? w->parthist : nullptr, w ? w->binp : nullptr,                           \
+        zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, ap.alpha,            \
+        static_cast<uint2*>(ap.kvq), forced_idx, n_forced)
 #define SIK_SCORE(HV, FV)                                                                                    \
     do {                                                                                                     \
         if (d.R == 1) SIK_SCORE1(HV, FV, 1); else SIK_SCORE1(HV, FV, kHB);                                   \
