@@ -58,7 +58,8 @@ typedef enum {
 } sik_status;
 
 /* Shape of one attention layer's cache.  head_dim must be 128 (the head size of every
- * model the paper evaluates); n_q_heads must be a multiple of n_kv_heads. */
+ * model the paper evaluates); n_q_heads must be a multiple of n_kv_heads.  Limits (SIK_ERR_SHAPE beyond them):
+ * n_q_heads <= 65535, batch * n_q_heads <= 2^20, max_len <= 2^22. */
 typedef struct {
     int32_t batch;
     int32_t n_kv_heads;

@@ -12,6 +12,7 @@ static int check_layout(const sik_layout* l, Dims* d) {
     if (l->batch < 1 || l->n_kv_heads < 1 || l->n_q_heads < 1 || l->max_len < 1) return SIK_ERR_SHAPE;
     if (l->head_dim != kD) return SIK_ERR_SHAPE;
     if (l->n_q_heads % l->n_kv_heads != 0) return SIK_ERR_SHAPE;
+    if (l->n_q_heads > 0xffff) return SIK_ERR_SHAPE;  // kernels take the head counts as 16-bit argument fields
     if (static_cast<int64_t>(l->batch) * l->n_q_heads > (1 << 20)) return SIK_ERR_SHAPE;
     if (l->max_len > (1 << 22)) return SIK_ERR_SHAPE;  // 64 chunks of at most 65535 tokens per head
     if (l->kv_dtype != SIK_F16 && l->kv_dtype != SIK_BF16) return SIK_ERR_DTYPE;

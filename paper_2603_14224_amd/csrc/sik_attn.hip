@@ -16,19 +16,18 @@ namespace sik {
 SIK_TL_DEFINE(sik_dbg_tl_attn)
 
 template <int DT, int ODT>
-__global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict__ q,
-                                                      const uint16_t* __restrict__ K,
-                                                      const uint16_t* __restrict__ V,
-                                                      const int32_t* __restrict__ idx, int k,
-                                                      float scale_log2e, uint32_t* __restrict__ counters,
-                                                      float* __restrict__ partial, void* __restrict__ out,
-                                                      int Hkv, int Hq, int R, int Lmax, int nsplit, int per,
-                                                      int idx_per_unit) {
+__global__ __launch_bounds__(kBlock) void attn_kernel(
+    // (the first 14 dwords arrive in scalar registers with the wavefront: what the first loads need comes first;
+    // dims0 = Hkv | Hq << 16, dims1 = R | nsplit << 16)
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    const int32_t* __restrict__ idx, uint32_t dims0, uint32_t dims1, int k, int Lmax, int per, int idx_per_unit,
+    float scale_log2e, uint32_t* __restrict__ counters, float* __restrict__ partial, void* __restrict__ out) {
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ int s_flag;
 
     SIK_TL(16);
+    const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nsplit = dims1 >> 16;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int p = lane & 15;
     const int row = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
@@ -73,19 +72,17 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(const uint16_t* __restrict
 constexpr int kSharedHeads = 4;
 
 template <int DT, int ODT>
-__global__ __launch_bounds__(kBlock) void attn_shared_kernel(const uint16_t* __restrict__ q,
-                                                             const uint16_t* __restrict__ K,
-                                                             const uint16_t* __restrict__ V,
-                                                             const int32_t* __restrict__ idx, int k,
-                                                             float scale_log2e, uint32_t* __restrict__ counters,
-                                                             float* __restrict__ partial, void* __restrict__ out,
-                                                             int Hkv, int Hq, int R, int Lmax, int nsplit, int per,
-                                                             int nblk) {
+__global__ __launch_bounds__(kBlock) void attn_shared_kernel(
+    // (argument order and packing as in attn_kernel)
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    const int32_t* __restrict__ idx, uint32_t dims0, uint32_t dims1, int k, int Lmax, int per, int nblk,
+    float scale_log2e, uint32_t* __restrict__ counters, float* __restrict__ partial, void* __restrict__ out) {
     constexpr int NH = kSharedHeads;
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ int s_flag;
 
+    const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nsplit = dims1 >> 16;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int p = lane & 15;
     const int sp = blockIdx.x % nsplit, ub = blockIdx.x / nsplit;
@@ -164,12 +161,14 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
         attn_plan(db, k, &nsplit, &per);
         const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
         const int grid = nsplit * d.units() * nblk;
+        const uint32_t dims0 = static_cast<uint32_t>(d.Hkv) | static_cast<uint32_t>(d.Hq) << 16;
+        const uint32_t dims1 = static_cast<uint32_t>(d.R) | static_cast<uint32_t>(nsplit) << 16;
         auto qp = static_cast<const uint16_t*>(q);
         auto Kp = static_cast<const uint16_t*>(K);
         auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_ATTNS(DTV, ODTV)                                                                                  \
-    attn_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, k, sl2, w.counters, w.partial, out, \
-                                                          d.Hkv, d.Hq, d.R, d.Lmax, nsplit, per, nblk)
+    attn_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per, nblk, sl2, \
+                                                          w.counters, w.partial, out)
         if (d.kv_dtype == kBF16) {
             if (d.out_dtype == kF32) SIK_ATTNS(kBF16, kF32); else SIK_ATTNS(kBF16, kBF16);
         } else {
@@ -182,12 +181,14 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
     attn_plan(d, k, &nsplit, &per);
     const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
     const int grid = nsplit * d.rows();
+    const uint32_t dims0 = static_cast<uint32_t>(d.Hkv) | static_cast<uint32_t>(d.Hq) << 16;
+    const uint32_t dims1 = static_cast<uint32_t>(d.R) | static_cast<uint32_t>(nsplit) << 16;
     auto qp = static_cast<const uint16_t*>(q);
     auto Kp = static_cast<const uint16_t*>(K);
     auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_ATTN(DTV, ODTV)                                                                                  \
-    attn_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, k, sl2, w.counters, w.partial, out, d.Hkv, \
-                                                   d.Hq, d.R, d.Lmax, nsplit, per, idx_per_unit ? 1 : 0)
+    attn_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per,               \
+                                                   idx_per_unit ? 1 : 0, sl2, w.counters, w.partial, out)
     if (d.kv_dtype == kBF16) {
         if (d.out_dtype == kF32) SIK_ATTN(kBF16, kF32); else SIK_ATTN(kBF16, kBF16);
     } else {

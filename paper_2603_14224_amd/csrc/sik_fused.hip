@@ -493,8 +493,7 @@ bool fused_plan(const Dims& d, int* nchunk, int* chunk) {
     while (ch < 8192 && static_cast<int64_t>(ch) * want < d.Lmax) ch *= 2;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
-    // (the kernel takes the head counts as 16-bit fields of its preloaded arguments)
-    return *nchunk <= kMaxChunks && d.Hkv <= 0xffff && d.Hq <= 0xffff;
+    return *nchunk <= kMaxChunks;
 }
 
 size_t fused_cand_words(const Dims& d) {
@@ -522,7 +521,7 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     auto Kp = static_cast<const uint16_t*>(K);
     auto Vp = static_cast<const uint16_t*>(V);
     auto Rp = static_cast<const uint2*>(kvq);
-    if (d.Hkv > 0xffff || d.Hq > 0xffff || nchunk > 0xffff || hchunks > 0xff || fo.n > 0xff) return hipErrorInvalidValue;
+    static_assert(kMaxChunks <= 0xff && kMaxForced <= 0xff, "8-bit argument fields");
     const uint32_t dims0 = static_cast<uint32_t>(d.Hkv) | static_cast<uint32_t>(d.Hq) << 16;
     const uint32_t dims1 = static_cast<uint32_t>(d.R) | static_cast<uint32_t>(nchunk) << 16;
     const uint32_t dims2 = static_cast<uint32_t>(hchunks) | static_cast<uint32_t>(fo.n) << 8 |

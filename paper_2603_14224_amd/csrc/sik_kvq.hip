@@ -111,18 +111,17 @@ __global__ __launch_bounds__(kBlock) void quantize_kv_kernel(const uint16_t* __r
 
 // Sparse attention over records: the split-K structure of attn_kernel with the record gather core.
 template <int DT, int ODT>
-__global__ __launch_bounds__(kBlock) void attn_q2_kernel(const uint16_t* __restrict__ q,
-                                                         const uint2* __restrict__ rec,
-                                                         const float* __restrict__ alpha,
-                                                         const int32_t* __restrict__ idx, int k, float scale_log2e,
-                                                         uint32_t* __restrict__ counters,
-                                                         float* __restrict__ partial, void* __restrict__ out,
-                                                         int Hkv, int Hq, int R, int Lmax, int nsplit, int per,
-                                                         int idx_per_unit) {
+__global__ __launch_bounds__(kBlock) void attn_q2_kernel(
+    // (the first 14 dwords arrive in scalar registers with the wavefront: what the first loads need comes first;
+    // dims0 = Hkv | Hq << 16, dims1 = R | nsplit << 16)
+    const uint16_t* __restrict__ q, const uint2* __restrict__ rec, const float* __restrict__ alpha,
+    const int32_t* __restrict__ idx, uint32_t dims0, uint32_t dims1, int k, int Lmax, int per, int idx_per_unit,
+    float scale_log2e, uint32_t* __restrict__ counters, float* __restrict__ partial, void* __restrict__ out) {
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ int s_flag;
 
+    const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nsplit = dims1 >> 16;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int p = lane & 15;
     const int row = blockIdx.x / nsplit, sp = blockIdx.x % nsplit;
@@ -212,11 +211,13 @@ hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, cons
     const int nsplit = (k + per - 1) / per;
     const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
     const int grid = nsplit * rows;
+    const uint32_t dims0 = static_cast<uint32_t>(d.Hkv) | static_cast<uint32_t>(d.Hq) << 16;
+    const uint32_t dims1 = static_cast<uint32_t>(d.R) | static_cast<uint32_t>(nsplit) << 16;
     auto qp = static_cast<const uint16_t*>(q);
     auto rp = static_cast<const uint2*>(kvq);
 #define SIK_ATTNQ(DTV, ODTV)                                                                                 \
-    attn_q2_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, k, sl2, w.counters, w.partial, out, \
-                                                      d.Hkv, d.Hq, d.R, d.Lmax, nsplit, per, idx_per_unit ? 1 : 0)
+    attn_q2_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, dims0, dims1, k, d.Lmax, per,        \
+                                                      idx_per_unit ? 1 : 0, sl2, w.counters, w.partial, out)
     if (d.kv_dtype == kBF16) {
         if (d.out_dtype == kF32) SIK_ATTNQ(kBF16, kF32); else SIK_ATTNQ(kBF16, kBF16);
     } else {

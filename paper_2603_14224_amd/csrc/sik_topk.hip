@@ -89,14 +89,12 @@ __global__ __launch_bounds__(kBlock) void hist_kernel(const float* __restrict__ 
 }
 
 // ---- select: compaction against the threshold bin, exact resolution of the bin ---------------
-__global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict__ scores, int sstride,
-                                                        const int32_t* __restrict__ seq_len,
-                                                        const uint32_t* __restrict__ parthist, int hchunks,
-                                                        int hchunk, const float* __restrict__ binp,
-                                                        uint32_t* __restrict__ counters,
-                                                        uint32_t* __restrict__ cand,
-                                                        int32_t* __restrict__ idx, int Hq, int Lmax, int k,
-                                                        int nchunk, int chunk) {
+__global__ __launch_bounds__(kBlock) void select_kernel(
+    // (the first 14 dwords arrive in scalar registers with the wavefront: what the first loads need comes first;
+    // chunks = hchunks | nchunk << 16)
+    const float* __restrict__ scores, const int32_t* __restrict__ seq_len, const uint32_t* __restrict__ parthist,
+    const float* __restrict__ binp, int sstride, int Hq, int Lmax, int chunk, int hchunk, uint32_t chunks,
+    uint32_t* __restrict__ counters, uint32_t* __restrict__ cand, int32_t* __restrict__ idx, int k) {
     // 17 KB of LDS per workgroup, so that eight of them fit a compute unit: the selected tokens are kept as 16-bit
     // offsets into the chunk, and the candidate list shares its storage with the histogram staging of
     // find_threshold (dead after the barrier that follows it).
@@ -110,6 +108,7 @@ __global__ __launch_bounds__(kBlock) void select_kernel(const float* __restrict_
     __shared__ uint32_t s_nsel, s_ncand, s_base[2], sh[4];
 
     SIK_TL(8);
+    const int hchunks = chunks & 0xffffu, nchunk = chunks >> 16;
     const int row = blockIdx.x / nchunk, c = blockIdx.x % nchunk, tid = threadIdx.x;
     int L = seq_len[row / Hq];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
@@ -277,9 +276,9 @@ hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score
         score_plan(d, &nhb, &hchunks, &hchunk);
     else
         hist_plan(d, &hchunks, &hchunk);
-    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(scores, hist_from_score ? w.sstride : d.Lmax, seq_len,
-                                                       w.parthist, hchunks, hchunk, w.binp,
-                                                       w.counters, w.cand, idx, d.Hq, d.Lmax, k, nchunk, chunk);
+    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(
+        scores, seq_len, w.parthist, w.binp, hist_from_score ? w.sstride : d.Lmax, d.Hq, d.Lmax, chunk, hchunk,
+        static_cast<uint32_t>(hchunks) | static_cast<uint32_t>(nchunk) << 16, w.counters, w.cand, idx, k);
     return hipGetLastError();
 }
 
