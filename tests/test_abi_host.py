@@ -43,7 +43,7 @@ def test_workspace_bytes_and_layout_validation():
     assert sik.sik_workspace_bytes(L(), 256) % 256 == 0
     assert sik.sik_workspace_bytes(L(batch=32), 256) > sik.sik_workspace_bytes(L(), 256)
     for bad in (L(head_dim=96), L(n_q_heads=30), L(batch=0), L(max_len=0), L(kv_dtype=sik.SIK_F32),
-                L(out_dtype=sik.SIK_F16)):
+                L(out_dtype=sik.SIK_F16), L(n_kv_heads=1, n_q_heads=65536)):  # head counts are 16-bit kernel fields
         assert sik.sik_workspace_bytes(bad, 16) == 0
     assert sik.sik_workspace_bytes(L(), 5000) == 0  # k > max_len
 
