@@ -396,8 +396,11 @@ __global__ __launch_bounds__(BLK) void score_kernel(
     SIK_TL(4);
 }
 
-constexpr int kScoreBlock = 512;  // two wavefronts per SIMD share one table build; 256-thread workgroups were
-                                  // measured slower at every size (32 x 8 KV heads x 16K: 37 against 33 us)
+// Workgroup size: 512 threads (two wavefronts per SIMD share one table build; 256-thread workgroups were measured
+// slower at every size: 37 against 33 us on 32 x 8 KV heads x 16K), and 1024 for small launches, which run one
+// workgroup per compute unit: four wavefronts per SIMD hide the LDS latency there (128K context, one sequence:
+// 10.5 against 11.3 us; no difference at 32K).
+constexpr int kScoreBlock = 512;
 
 // Tokens per workgroup: one workgroup per compute unit for small launches (latency-bound: fewest table builds),
 // two (scalar tables: four) for large ones; whole loop iterations of 1024 tokens (so that the table build and
@@ -430,13 +433,18 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
     const int grid = nchunk * nhb * d.units();
+    const bool small_launch = static_cast<int64_t>(d.units()) * nhb * d.Lmax <= (2 << 20);
     auto qp = static_cast<const uint16_t*>(q);
-#define SIK_SCORE1(HV, FV, HBV)                                                                              \
-    score_kernel<DT, HV, kScoreBlock, FV, HBV><<<grid, kScoreBlock, 0, s>>>(                                 \
+#define SIK_SCORE2(HV, FV, HBV, BLKV)                                                                        \
+    score_kernel<DT, HV, BLKV, FV, HBV><<<grid, BLKV, 0, s>>>(                                               \
         qp, codebook, codes, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb, q_sum, seq_len, scores,           \
         w ? w->sstride : d.Lmax, w ? w->parthist : nullptr, w ? w->binp : nullptr,                           \
         zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, ap.alpha,            \
         static_cast<uint2*>(ap.kvq), forced_idx, n_forced)
+#define SIK_SCORE1(HV, FV, HBV)                                                                              \
+    do {                                                                                                     \
+        if (small_launch) SIK_SCORE2(HV, FV, HBV, 1024); else SIK_SCORE2(HV, FV, HBV, kScoreBlock);          \
+    } while (0)
 #define SIK_SCORE(HV, FV)                                                                                    \
     do {                                                                                                     \
         if (d.R == 1) SIK_SCORE1(HV, FV, 1); else SIK_SCORE1(HV, FV, kHB);                                   \
@@ -446,6 +454,7 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     else SIK_SCORE(true, false);
 #undef SIK_SCORE
 #undef SIK_SCORE1
+#undef SIK_SCORE2
     return hipGetLastError();
 }
 
