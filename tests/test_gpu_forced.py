@@ -99,6 +99,13 @@ def test_forced_rows_everything_selected_and_tiny_sequences(oracle):
     run_rows(oracle, cfg, 704, steps=1, append=False, n_forced=16, seq_len=[600, 5, 0])
 
 
+def test_forced_rows_large_launch(oracle):
+    # more than 2 M keys in the launch: the scoring kernel's large-launch workgroups (512 threads, two per
+    # compute unit) with the forced-token bitmap, ragged lengths, append
+    cfg = cfg_small("C2", batch=5, n_kv_heads=8, n_q_heads=32, context=56000, top_k=300)
+    run_rows(oracle, cfg, 56008, steps=1, append=True, n_forced=64, seq_len=[56000, 31000, 56000, 9, 44444])
+
+
 def test_forced_empty_set_equals_plain_step(oracle):
     cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=6000, top_k=128)
     st = GpuState(cfg, oracle, out_dtype=torch.float32)
