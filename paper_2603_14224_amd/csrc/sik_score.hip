@@ -1,20 +1,20 @@
 // LUT-GEMV retrieval over the packed sign codes for gfx950 (section "Compressed-Domain
 // Top-k Retrieval"): Table^(g)[j] = q^(g) . c_j^(g), score_i = sum_g Table^(g)[Code_g(k_i)].
 //
-// One workgroup of 512 threads serves one (batch, kv head) for a block of up to 4 query heads of its GQA
-// group (a wider group is served by several head blocks that re-read the codes from L2: two float4
+// One workgroup (512 threads, 1024 in small launches) serves one (batch, kv head) for a block of up to 4 query
+// heads of its GQA group (a wider group is served by several head blocks that re-read the codes from L2: two float4
 // tables in one workgroup were measured slower, 65 us against 2 x 18 us on the 8:1 workload)
 // and a contiguous chunk of tokens.  The tables live in LDS as float4 entries holding the
 // same (g, j) entry of four query heads: the 16 entries of a group span 256 B = all 64 LDS
 // banks once, so the data-dependent ds_read_b128 of a wavefront (all lanes are at the same g)
 // is bank-conflict free whatever the codes are.  Each lane owns one token per load: a single
 // 128-bit load brings its 32 codes, i.e. a wavefront streams 1 KB of the code plane per load;
-// two such loads per lane are in flight while the previous two tokens are scored.
+// the loads of the next 1024 tokens of the workgroup are in flight while the current ones are scored.
 //
-// What bounds the scan is vector-instruction issue: 4 x 32 adds per token for a block of four heads cannot be
-// avoided (no packed fp32 here), so everything around them is kept small - one instruction per table offset,
-// four per histogram count - and the kernel stays under 128 registers, i.e. four wavefronts per SIMD, which
-// hide the LDS latency (ds_read_b128 itself sustains over 200 B/clk per compute unit, twice what the scan asks).
+// What bounds the scan is vector-instruction issue, with the LDS reads close behind: 4 x 32 adds per token for
+// a block of four heads cannot be avoided (no packed fp32 here), so everything around them is kept small - one
+// instruction per table offset, four per histogram count - and the kernel stays under 128 registers, i.e. four
+// wavefronts per SIMD, which hide the LDS latency (ds_read_b128 sustains over 200 B/clk per compute unit).
 //
 // A launch with one query head per KV head (no GQA, or the summed query of a group-shared selection) uses
 // scalar table entries instead (HB = 1).
