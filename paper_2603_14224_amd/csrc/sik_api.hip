@@ -254,10 +254,12 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if (shared_unfused) {
         // prep, score (summed query), stand-alone selector per KV head, attention reading one index list per KV
         // head.  idx_out, if given, is [B, Hkv, k].
-        if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
+        // (nothing to append: no prep launch, the scoring launch clears the per-head counters itself)
+        if (e == hipSuccess && k_new) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
         if (e == hipSuccess) e = mark(1);
         if (e == hipSuccess)
-            e = launch_score(ds, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, q_sum, s);
+            e = launch_score(ds, &w, k_new == nullptr, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0,
+                             q_sum, s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = launch_select(ds, w, true, w.scores, seq_len, k, idx, s);
         if (e == hipSuccess) e = mark(3);
@@ -283,10 +285,11 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
                              k_new != nullptr, k, softmax_scale, idx_out, out, s);
     } else {
         // contexts beyond 512K tokens: prep (append + clear counters), score, select, attention
-        if (e == hipSuccess) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
+        if (e == hipSuccess && k_new) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
         if (e == hipSuccess) e = mark(1);
         if (e == hipSuccess)
-            e = launch_score(d, &w, false, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, 1, s);
+            e = launch_score(d, &w, k_new == nullptr, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, 1,
+                             s);
         if (e == hipSuccess) e = mark(2);
         if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
         if (e == hipSuccess) e = mark(3);

@@ -196,7 +196,8 @@ __global__ __launch_bounds__(BLK) void score_kernel(
         // chunk 0 of each head block clears those of its heads
         // (a launch on the summed query of q_sum heads stands for q_sum rows of the kernel that follows)
         const int nrows = q_sum > 1 ? q_sum : nh;
-        if (zero_counters && c == 0 && tid < nrows * 8) zero_counters[row0 * (q_sum > 1 ? q_sum : 1) * 8 + tid] = 0u;
+        if (zero_counters && c == 0)
+            for (int t = tid; t < nrows * 8; t += BLK) zero_counters[row0 * (q_sum > 1 ? q_sum : 1) * 8 + t] = 0u;
     }
     // decode-time append (k_new != nullptr): the new key/value row of this KV head goes to row t =
     // seq_len[b]; every workgroup counts it in (L = t + 1), the one whose chunk holds t encodes it
