@@ -69,7 +69,6 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(
 // Group-shared selection: the query heads of a KV head attend over ONE index list (idx [B, Hkv, k]).  A workgroup
 // takes a block of up to kSharedHeads query heads of one KV head and a slice of the list, gathers every row
 // once and feeds it to all its heads: the gathered bytes are those of one head, not of R.
-constexpr int kSharedHeads = 4;
 
 template <int DT, int ODT>
 __global__ __launch_bounds__(kBlock) void attn_shared_kernel(

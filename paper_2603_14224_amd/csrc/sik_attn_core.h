@@ -7,6 +7,7 @@
 namespace sik {
 
 constexpr int kPartStride = kD + 2;
+constexpr int kSharedHeads = 4;  // query heads that share one gather in the group-shared attention kernels
 
 struct SoftmaxState {
     float m, l;

@@ -200,4 +200,90 @@ __device__ __forceinline__ void attend_list_q2(Fetch fetch, int n, int first, in
     for (int e = 0; e < 8; ++e) st.acc[e] += zsum;
 }
 
+// attend_list_q2 for NH query heads that share one index list (group-shared selection): every record is
+// gathered and dequantised once - K'_e / alpha_e = s_e (qs Q_e + zp) per channel - and each head then costs one
+// multiply-add per channel against its q_e alpha_e (qa[h][e]).  Entries first + it * step + (0..15) per wavefront
+// iteration (4 rows per 16-lane group); step is a multiple of 16.
+template <int NH, class Fetch>
+__device__ __forceinline__ void attend_list_q2_multi(Fetch fetch, int n, int first, int step,
+                                                     const uint2* __restrict__ rec, const float (&qa)[NH][8],
+                                                     float scale_log2e, int Lmax, SoftmaxState (&st)[NH]) {
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63;
+    const int slot = lane >> 4, p = lane & 15;
+    float zsum[NH];  // sum of weight * V zero point per head: the same for this lane's 8 channels
+#pragma unroll
+    for (int h = 0; h < NH; ++h) zsum[h] = 0.0f;
+    for (int base = first; base < n; base += step) {
+        const int jj = base + p;
+        const int mine = jj < n ? fetch(jj) : -1;
+        int id[U];
+        uint2 r[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            id[u] = __shfl(mine, (lane & 48) + 4 * u + slot, 64);
+            const bool ok = id[u] >= 0 && id[u] < Lmax;
+            const size_t t = ok ? static_cast<size_t>(id[u]) : 0;
+            id[u] = ok ? id[u] : -1;
+            r[u] = rec[t * kRecSlots + p];
+        }
+        float z[NH][U], vqs[U], vzp[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t par = r[u].y >> 16;
+            const float kqs = fp16_value(quad_bcast<0>(par)), kzp = fp16_value(quad_bcast<1>(par));
+            vqs[u] = fp16_value(quad_bcast<2>(par));
+            vzp[u] = fp16_value(quad_bcast<3>(par));
+            const uint32_t kb = r[u].x >> 16;
+            const uint32_t minus = (~r[u].x) << 24;  // bit 31-e set: K' of channel e is negative (code bit clear)
+            float w[8];                              // K'_e / alpha_e
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float mag = fmaf(kqs, static_cast<float>((kb >> (2 * e)) & 3u), kzp);  // >= 0
+                w[e] = __uint_as_float(__float_as_uint(mag) | ((minus << e) & 0x80000000u));
+            }
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                float dot = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = fmaf(qa[h][e], w[e], dot);
+                dot = row16_sum(dot) * scale_log2e;
+                z[h][u] = id[u] >= 0 ? dot : kNegBig;
+            }
+        }
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            float mnew = st[h].m;
+#pragma unroll
+            for (int u = 0; u < U; ++u) mnew = fmaxf(mnew, z[h][u]);
+            const float corr = fast_exp2(st[h].m - mnew);
+            st[h].l *= corr;
+            zsum[h] *= corr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st[h].acc[e] *= corr;
+            st[h].m = mnew;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t vb = r[u].y;
+            float cv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) cv[e] = static_cast<float>((vb >> (2 * e)) & 3u);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const float pu = id[u] >= 0 ? fast_exp2(z[h][u] - st[h].m) : 0.0f;
+                st[h].l += pu;
+                const float ps = pu * vqs[u];
+                zsum[h] = fmaf(pu, vzp[u], zsum[h]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) st[h].acc[e] = fmaf(ps, cv[e], st[h].acc[e]);
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st[h].acc[e] += zsum[h];
+}
+
 }  // namespace sik

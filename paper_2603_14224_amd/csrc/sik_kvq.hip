@@ -160,6 +160,81 @@ __global__ __launch_bounds__(kBlock) void attn_q2_kernel(
     if (tid < kD) store_out<ODT>(out, static_cast<size_t>(row) * kD + tid, merge_partials(prow, nsplit, tid));
 }
 
+// The same for a block of up to kSharedHeads query heads of one KV head that share an index list (group-shared
+// selection): every record is gathered and dequantised once for the block.  Grid = units x head blocks x splits.
+template <int DT, int ODT>
+__global__ __launch_bounds__(kBlock) void attn_q2_shared_kernel(
+    // (argument order and packing as in attn_q2_kernel)
+    const uint16_t* __restrict__ q, const uint2* __restrict__ rec, const float* __restrict__ alpha,
+    const int32_t* __restrict__ idx, uint32_t dims0, uint32_t dims1, int k, int Lmax, int per, int nblk,
+    float scale_log2e, uint32_t* __restrict__ counters, float* __restrict__ partial, void* __restrict__ out) {
+    constexpr int NH = kSharedHeads;
+    __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
+    __shared__ float sacc[kBlock / kWave][kD];
+    __shared__ int s_flag;
+
+    const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nsplit = dims1 >> 16;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int p = lane & 15;
+    const int sp = blockIdx.x % nsplit, ub = blockIdx.x / nsplit;
+    const int blk = ub % nblk;
+    const size_t unit = ub / nblk;
+    const int b = static_cast<int>(unit / Hkv), h = static_cast<int>(unit % Hkv);
+    const int hq0 = h * R + blk * NH;      // first query head of this workgroup
+    const int nh = min(NH, R - blk * NH);  // real heads in the block
+    const size_t row0 = static_cast<size_t>(b) * Hq + hq0;
+    const uint2* rp = rec + unit * Lmax * kRecSlots;
+    const int32_t* ip = idx + unit * k;
+
+    float a8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a8[e] = alpha[unit * kD + 8 * p + e];
+    float qa[NH][8];  // q_e alpha_e of this lane's channels, per head
+    SoftmaxState st[NH];
+#pragma unroll
+    for (int x = 0; x < NH; ++x) {
+        const uint4 qraw =
+            x < nh ? reinterpret_cast<const uint4*>(q + (row0 + x) * kD)[p] : make_uint4(0u, 0u, 0u, 0u);
+        float qf[8];
+        widen8<DT>(qraw, qf);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qa[x][e] = qf[e] * a8[e];
+        init_state(st[x]);
+    }
+    const int j0 = sp * per, j1 = min(k, j0 + per);
+    attend_list_q2_multi<NH>([&](int j) { return ip[j0 + j]; }, j1 - j0, wv * 16, (kBlock / kWave) * 16, rp, qa,
+                             scale_log2e, Lmax, st);
+    float M[NH], Lsum[NH], o[NH];
+#pragma unroll
+    for (int x = 0; x < NH; ++x) {
+        workgroup_merge(st[x], sm, sl, sacc, M[x], Lsum[x], o[x]);
+        __syncthreads();  // the LDS staging is reused by the next head
+    }
+    if (nsplit == 1) {
+#pragma unroll
+        for (int x = 0; x < NH; ++x)
+            if (x < nh && tid < kD)
+                store_out<ODT>(out, (row0 + x) * kD + tid, Lsum[x] > 0.0f ? o[x] / Lsum[x] : 0.0f);
+        return;
+    }
+#pragma unroll
+    for (int x = 0; x < NH; ++x) {
+        if (x < nh && tid < kD) {
+            float* pp = partial + ((row0 + x) * kMaxSplit + sp) * kPartStride;
+            st_agent(&pp[2 + tid], o[x]);
+            if (tid == 0) {
+                st_agent(&pp[0], M[x]);
+                st_agent(&pp[1], Lsum[x]);
+            }
+        }
+    }
+    if (!last_arriver(&counters[row0 * 8 + 3], static_cast<uint32_t>(nsplit), &s_flag)) return;
+    // two heads at a time: threads 0..127 and 128..255 each take a channel of one head
+    for (int x = tid >> 7; x < nh; x += kBlock / kD)
+        store_out<ODT>(out, (row0 + x) * kD + (tid & (kD - 1)),
+                       merge_partials(partial + (row0 + x) * kMaxSplit * kPartStride, nsplit, tid & (kD - 1)));
+}
+
 static int kvq_workgroups(const Dims& d, int tokens) {
     int nwg = (tokens + 255) / 256;
     const int cap = 4096 / d.units() < 1 ? 1 : 4096 / d.units();
@@ -199,15 +274,20 @@ hipError_t launch_quantize_kv(const Dims& d, const void* K, const void* V, const
 
 hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, const void* kvq, const float* alpha,
                           const int32_t* idx, bool idx_per_unit, int k, float scale, void* out, hipStream_t s) {
-    // splits of whole 128-entry steps (4 wavefronts x 32 entries), about 1024 workgroups
-    const int rows = d.rows();
+    // one index list per KV head and a GQA group: one gather per block of up to kSharedHeads query heads
+    const bool shared = idx_per_unit && d.R > 1;
+    const int nblk = shared ? (d.R + kSharedHeads - 1) / kSharedHeads : 1;
+    // splits of whole steps of the workgroup (4 wavefronts x 32 entries, x 16 in the shared kernel), about 1024
+    // workgroups
+    const int stepw = shared ? 64 : 128;
+    const int rows = shared ? d.units() * nblk : d.rows();
     int ns = (1024 + rows - 1) / rows;
-    const int by_k = (k + 127) / 128;
+    const int by_k = (k + stepw - 1) / stepw;
     if (ns > by_k) ns = by_k;
     if (ns > kMaxSplit) ns = kMaxSplit;
     if (ns < 1) ns = 1;
     int per = (k + ns - 1) / ns;
-    per = (per + 127) / 128 * 128;
+    per = (per + stepw - 1) / stepw * stepw;
     const int nsplit = (k + per - 1) / per;
     const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
     const int grid = nsplit * rows;
@@ -216,8 +296,14 @@ hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, cons
     auto qp = static_cast<const uint16_t*>(q);
     auto rp = static_cast<const uint2*>(kvq);
 #define SIK_ATTNQ(DTV, ODTV)                                                                                 \
-    attn_q2_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, dims0, dims1, k, d.Lmax, per,        \
-                                                      idx_per_unit ? 1 : 0, sl2, w.counters, w.partial, out)
+    do {                                                                                                     \
+        if (shared)                                                                                          \
+            attn_q2_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, dims0, dims1, k, d.Lmax, per, \
+                                                                     nblk, sl2, w.counters, w.partial, out); \
+        else                                                                                                 \
+            attn_q2_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, dims0, dims1, k, d.Lmax, per, \
+                                                              idx_per_unit ? 1 : 0, sl2, w.counters, w.partial, out); \
+    } while (0)
     if (d.kv_dtype == kBF16) {
         if (d.out_dtype == kF32) SIK_ATTNQ(kBF16, kF32); else SIK_ATTNQ(kBF16, kBF16);
     } else {
