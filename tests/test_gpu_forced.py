@@ -357,7 +357,7 @@ def test_shared_selection_beyond_the_fused_plan(oracle):
     check_attention(out.cpu().numpy().astype(np.float64), ref, True)
 
 
-@pytest.mark.parametrize("R,q2", [(5, False), (4, True)])
+@pytest.mark.parametrize("R,q2", [(5, False), (4, True), (6, True)])
 def test_shared_selection_large_launch_gathers_once(oracle, R, q2):
     # above 2 M keys the plain shared step selects once per KV head and the attention kernel feeds each gathered
     # row to the query heads of the group (blocks of 4: R = 5 leaves a block with a single head)
