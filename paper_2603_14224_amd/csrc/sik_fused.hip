@@ -26,13 +26,14 @@ namespace sik {
 
 SIK_TL_DEFINE(sik_dbg_tl_fused)
 
-// Candidate exchange area of one query head: regions = 4 * nchunk (one per chunk and wavefront);
-// word w of region r lives at cand_row[w * regions + r], so that the last workgroup, which reads one
-// region per lane, issues coalesced loads.  Word 0 = count (may exceed kWaveCand: the surplus is in the pool),
-// then (key, index) pairs.  The pool of a head follows the regions of all heads: kCandCap (key, index) pairs,
-// filled in the order of reservations on counter 4 of the head.
+// Candidate exchange area of one query head: regions = 4 * nchunk (one per chunk and wavefront), kCandWaveWords
+// words per region.  First the regions' counts, one word each (a count may exceed kWaveCand: the surplus is in
+// the pool); then, 8-byte aligned, the (key, index) pairs as 64-bit words (key below), pair e of region r at
+// pairs[e * regions + r]: the last workgroup, which reads one region per lane, issues 16 coalesced 64-bit loads.
+// The pool of a head follows the regions of all heads: kCandCap (key, index) pairs, filled in the order of
+// reservations on counter 4 of the head.
 constexpr int kWaveCand = 16;                      // candidate slots per wavefront and chunk
-constexpr int kCandWaveWords = 1 + 2 * kWaveCand;  // words per region
+constexpr int kCandWaveWords = 2 + 2 * kWaveCand;  // words per region (even: the pairs stay 8-byte aligned)
 
 // NQ float4 of scores per lane: chunk = 1024 * NQ tokens.  KVQ: the selected tokens are gathered as 128-byte
 // records of the 2-bit cache (kvq, alpha) and dequantised in registers, instead of as 16-bit K and V rows.
@@ -168,7 +169,8 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     int n_sel = 0, n_cand = 0;  // wave-uniform
     const int regions = nchunk * (kBlock / kWave);
     uint32_t* crow = cand + static_cast<size_t>(row) * regions * kCandWaveWords;
-    uint32_t* cw = crow + c * (kBlock / kWave) + wv;  // word w of this wavefront's region: cw[w * regions]
+    const int myreg = c * (kBlock / kWave) + wv;  // this wavefront's region
+    uint64_t* cpairs = reinterpret_cast<uint64_t*>(crow + ((regions + 1) & ~1));
     uint32_t* pool = cand + static_cast<size_t>(gridDim.x / nchunk) * regions * kCandWaveWords +
                      static_cast<size_t>(row) * kCandCap * 2;
     const uint64_t lt_mask = (1ull << lane) - 1ull;
@@ -229,8 +231,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         const int pos = n_cand + __popcll(bc & lt_mask);
         const uint32_t tok = static_cast<uint32_t>(start + (((bit >> 2) * kBlock + tid) * 4 + (bit & 3)));
         if (has && pos < kWaveCand) {
-            st_agent(&cw[(1 + 2 * pos) * regions], float_to_key(v));
-            st_agent(&cw[(2 + 2 * pos) * regions], tok);
+            st_agent(&cpairs[pos * regions + myreg], static_cast<uint64_t>(tok) << 32 | float_to_key(v));
         }
         n_cand += __popcll(bc);
         if (n_cand > kWaveCand) {  // rare: the surplus of this round goes to the head's pool
@@ -301,7 +302,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
         }
         n_sel += __popcll(bal);
     }
-    if (lane == 0) st_agent(&cw[0], static_cast<uint32_t>(n_cand));
+    if (lane == 0) st_agent(&crow[myreg], static_cast<uint32_t>(n_cand));
     // optional index output: reserve this wave's slots now, write them after the gather
     uint32_t out_base = 0u;
     if (orow && n_sel > 0) {
@@ -350,10 +351,13 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const bool want_cands = need > 0 && ranked;
     uint32_t cn = 0u, ent[2 * kWaveCand];
     if (want_cands && tid < nact * 4) {
-        const uint32_t* reg = crow + tid;
-        cn = ld_agent(&reg[0]);
+        cn = ld_agent(&crow[tid]);
 #pragma unroll
-        for (int e = 0; e < 2 * kWaveCand; ++e) ent[e] = ld_agent(&reg[(1 + e) * regions]);
+        for (int e = 0; e < kWaveCand; ++e) {
+            const uint64_t pr = ld_agent(&cpairs[e * regions + tid]);
+            ent[2 * e] = static_cast<uint32_t>(pr);
+            ent[2 * e + 1] = static_cast<uint32_t>(pr >> 32);
+        }
     }
     float* pml = reinterpret_cast<float*>(l_sel[0]);  // [2][kMaxChunks] in LDS (l_sel is free by now)
     if (tid < kMaxChunks) {
