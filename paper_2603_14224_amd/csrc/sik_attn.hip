@@ -35,14 +35,18 @@ __global__ __launch_bounds__(kBlock) void attn_kernel(
     const size_t unit = static_cast<size_t>(b) * Hkv + hq / R;
     const uint4* Kp = reinterpret_cast<const uint4*>(K + unit * Lmax * kD);
     const uint4* Vp = reinterpret_cast<const uint4*>(V + unit * Lmax * kD);
-    const int32_t* ip = idx + (idx_per_unit ? unit : static_cast<size_t>(row)) * k;
+    const int32_t* ip = idx + ((idx_per_unit & 1) ? unit : static_cast<size_t>(row)) * k;  // bit 1: stream
 
     const uint4 qraw = reinterpret_cast<const uint4*>(q + static_cast<size_t>(row) * kD)[p];
 
     SoftmaxState st;
     init_state(st);
     const int j0 = sp * per, j1 = min(k, j0 + per);
-    attend_list<DT>([&](int j) { return ip[j0 + j]; }, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
+    auto fetch = [&](int j) { return ip[j0 + j]; };
+    if (idx_per_unit & 2)
+        attend_list<DT, true>(fetch, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
+    else
+        attend_list<DT, false>(fetch, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e, Lmax, st);
     SIK_TL(17);
     float M, Lsum, o;
     workgroup_merge(st, sm, sl, sacc, M, Lsum, o);
@@ -74,9 +78,10 @@ template <int DT, int ODT>
 __global__ __launch_bounds__(kBlock) void attn_shared_kernel(
     // (argument order and packing as in attn_kernel)
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const int32_t* __restrict__ idx, uint32_t dims0, uint32_t dims1, int k, int Lmax, int per, int nblk,
+    const int32_t* __restrict__ idx, uint32_t dims0, uint32_t dims1, int k, int Lmax, int per, int nblk_flags,
     float scale_log2e, uint32_t* __restrict__ counters, float* __restrict__ partial, void* __restrict__ out) {
     constexpr int NH = kSharedHeads;
+    const int nblk = nblk_flags & 0xffff;  // head blocks per KV head; bit 16: non-temporal row loads
     __shared__ float sm[kBlock / kWave], sl[kBlock / kWave];
     __shared__ float sacc[kBlock / kWave][kD];
     __shared__ int s_flag;
@@ -103,8 +108,13 @@ __global__ __launch_bounds__(kBlock) void attn_shared_kernel(
         init_state(st[x]);
     }
     const int j0 = sp * per, j1 = min(k, j0 + per);
-    attend_list_multi<DT, NH>([&](int j) { return ip[j0 + j]; }, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw,
-                              scale_log2e, Lmax, st);
+    auto fetch = [&](int j) { return ip[j0 + j]; };
+    if (nblk_flags >> 16)
+        attend_list_multi<DT, NH, true>(fetch, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e,
+                                        Lmax, st);
+    else
+        attend_list_multi<DT, NH, false>(fetch, j1 - j0, wv * 16, (kBlock / kWave) * 16, Kp, Vp, qraw, scale_log2e,
+                                         Lmax, st);
     float M[NH], Lsum[NH], o[NH];
 #pragma unroll
     for (int x = 0; x < NH; ++x) {
@@ -160,14 +170,17 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
         attn_plan(db, k, &nsplit, &per);
         const float sl2 = (scale > 0.0f ? scale : 1.0f / sqrtf(static_cast<float>(d.D))) * 1.4426950408889634f;
         const int grid = nsplit * d.units() * nblk;
+        // every selected row is gathered once per head block here
+        const bool stream = static_cast<int64_t>(d.units()) * nblk * k * 512 >= (64ll << 20);
         const uint32_t dims0 = static_cast<uint32_t>(d.Hkv) | static_cast<uint32_t>(d.Hq) << 16;
         const uint32_t dims1 = static_cast<uint32_t>(d.R) | static_cast<uint32_t>(nsplit) << 16;
         auto qp = static_cast<const uint16_t*>(q);
         auto Kp = static_cast<const uint16_t*>(K);
         auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_ATTNS(DTV, ODTV)                                                                                  \
-    attn_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per, nblk, sl2, \
-                                                          w.counters, w.partial, out)
+    attn_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per,          \
+                                                          nblk | (stream ? 1 << 16 : 0), sl2, w.counters,        \
+                                                          w.partial, out)
         if (d.kv_dtype == kBF16) {
             if (d.out_dtype == kF32) SIK_ATTNS(kBF16, kF32); else SIK_ATTNS(kBF16, kBF16);
         } else {
@@ -187,7 +200,8 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
     auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_ATTN(DTV, ODTV)                                                                                  \
     attn_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per,               \
-                                                   idx_per_unit ? 1 : 0, sl2, w.counters, w.partial, out)
+                                                   (idx_per_unit ? 1 : 0) | (gather_streams(d, k) ? 2 : 0), sl2,   \
+                                                   w.counters, w.partial, out)
     if (d.kv_dtype == kBF16) {
         if (d.out_dtype == kF32) SIK_ATTN(kBF16, kF32); else SIK_ATTN(kBF16, kBF16);
     } else {

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     // The first 14 dwords are preloaded into scalar registers with the wavefront: what the index arithmetic and
     // the first loads need comes first (small integers packed), so that they do not wait for a round trip to the
     // argument block.  dims0 = Hkv | Hq << 16, dims1 = R | nchunk << 16,
-    // dims2 = hchunks | n_forced << 8 | shared << 16 | appended << 17.
+    // dims2 = hchunks | n_forced << 8 | shared << 16 | appended << 17 | stream << 18 (non-temporal row loads).
     const float* __restrict__ scores, const uint16_t* __restrict__ q, const uint32_t* __restrict__ parthist,
     const float* __restrict__ binp, int32_t* __restrict__ seq_len, int sstride, uint32_t dims0, uint32_t dims1,
     uint32_t dims2, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V, const uint2* __restrict__ kvq,
@@ -56,6 +56,7 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nchunk = dims1 >> 16;
     const int hchunks = dims2 & 0xffu, n_forced = (dims2 >> 8) & 0xffu;
     const int shared = (dims2 >> 16) & 1u, appended = (dims2 >> 17) & 1u;
+    const bool stream = (dims2 >> 18) & 1u;
     __shared__ int32_t l_sel[kBlock / kWave][kListCap];
     __shared__ uint32_t red[(kBlock / kWave) * kBins];
     __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 64];
@@ -163,8 +164,10 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     auto attend = [&](auto fetch, int n, int first, int step, SoftmaxState& s_) {
         if constexpr (KVQ)
             attend_list_q2(fetch, n, first, step, Rp, qq, scale_log2e, Lmax, s_);
+        else if (stream)  // one branch per list, not per load: each variant keeps its loads back to back
+            attend_list<DT, true>(fetch, n, first, step, Kp, Vp, qraw, scale_log2e, Lmax, s_);
         else
-            attend_list<DT>(fetch, n, first, step, Kp, Vp, qraw, scale_log2e, Lmax, s_);
+            attend_list<DT, false>(fetch, n, first, step, Kp, Vp, qraw, scale_log2e, Lmax, s_);
     };
     int n_sel = 0, n_cand = 0;  // wave-uniform
     const int regions = nchunk * (kBlock / kWave);
@@ -529,7 +532,8 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
     const uint32_t dims0 = static_cast<uint32_t>(d.Hkv) | static_cast<uint32_t>(d.Hq) << 16;
     const uint32_t dims1 = static_cast<uint32_t>(d.R) | static_cast<uint32_t>(nchunk) << 16;
     const uint32_t dims2 = static_cast<uint32_t>(hchunks) | static_cast<uint32_t>(fo.n) << 8 |
-                           (fo.group_shared ? 1u << 16 : 0u) | (appended ? 1u << 17 : 0u);
+                           (fo.group_shared ? 1u << 16 : 0u) | (appended ? 1u << 17 : 0u) |
+                           (gather_streams(d, k) ? 1u << 18 : 0u);
 #define SIK_FUSED_Q(NQV, KVQV)                                                                              \
     select_attend_kernel<DT, ODT, NQV, KVQV><<<grid, kBlock, 0, s>>>(                                       \
         w.scores, qp, w.parthist, w.binp, seq_len, w.sstride, dims0, dims1, dims2, Kp, Vp, Rp, alpha, w.counters, \

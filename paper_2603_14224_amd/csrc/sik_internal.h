@@ -43,6 +43,12 @@ struct Workspace {
 
 constexpr int kFitMaxWg = 64;
 
+// Launches that gather at least 64 MB of 16-bit rows (512 B per query head and selected token) read them with
+// non-temporal loads, smaller ones with plain loads (measured both ways on either side, see load_row_slice).
+inline bool gather_streams(const Dims& d, int k) {
+    return static_cast<int64_t>(d.rows()) * k * 512 >= (64ll << 20);
+}
+
 Workspace carve(const Dims& d, int k, void* base);
 
 // launchers (return hipError_t of the launch)
