@@ -56,7 +56,9 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nchunk = dims1 >> 16;
     const int hchunks = dims2 & 0xffu, n_forced = (dims2 >> 8) & 0xffu;
     const int shared = (dims2 >> 16) & 1u, appended = (dims2 >> 17) & 1u;
-    const bool stream = (dims2 >> 18) & 1u;
+    // non-temporal row loads (large launches), except in the workgroup that also gathers the forced tokens: those
+    // rows are read by every query head of the sequence and should stay cached
+    const bool stream = ((dims2 >> 18) & 1u) && !(n_forced > 0 && blockIdx.x % nchunk == 0);
     __shared__ int32_t l_sel[kBlock / kWave][kListCap];
     __shared__ uint32_t red[(kBlock / kWave) * kBins];
     __shared__ __align__(8) uint32_t l_cand[2 * kCandCap + 64];
