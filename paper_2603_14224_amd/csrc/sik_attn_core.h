@@ -42,13 +42,10 @@ __device__ __forceinline__ void store_out(void* out, size_t pos, float v) {
 // in small launches the plain load is faster (one sequence, 32K context: 13.2 against 14.6 us).
 template <bool STREAM>
 __device__ __forceinline__ uint4 load_row_slice(const uint4* p) {
-    if constexpr (STREAM) {
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-        const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-        return make_uint4(x.x, x.y, x.z, x.w);
-    } else {
+    if constexpr (STREAM)
+        return ld_stream(p);
+    else
         return *p;
-    }
 }
 
 // Attend over token indices supplied by fetch(j): this wavefront takes entries first + it * step +

@@ -83,6 +83,19 @@ __device__ __forceinline__ int score_bin(float s, float lo, float scale) {
     return bin_of_coord(bin_coord(s, lo, scale));
 }
 
+// Streaming (non-temporal) loads for data a kernel reads once: they do not displace what the launches around it
+// keep in the caches.
+__device__ __forceinline__ uint4 ld_stream(const uint4* p) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ uint2 ld_stream(const uint2* p) {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 x = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+    return make_uint2(x.x, x.y);
+}
+
 // Agent-scope relaxed atomics on global memory.
 __device__ __forceinline__ uint32_t atomic_add_u32(uint32_t* p, uint32_t v) {
     return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kBlock) void alpha_kernel(const uint16_t* __restric
     for (; i + 48 < end; i += 64) {
         uint4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = base[static_cast<size_t>(i + 16 * u) * 16 + p];
+        for (int u = 0; u < 4; ++u) v[u] = ld_stream(&base[static_cast<size_t>(i + 16 * u) * 16 + p]);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             float f[8];
@@ -99,8 +99,9 @@ __global__ __launch_bounds__(kBlock) void quantize_kv_kernel(const uint16_t* __r
     }
     int i = start + r;
     for (; i + 16 < end; i += 32) {  // two rows (K and V of each) in flight per lane
-        const uint4 k0 = Kb[static_cast<size_t>(i) * 16 + p], v0 = Vb[static_cast<size_t>(i) * 16 + p];
-        const uint4 k1 = Kb[static_cast<size_t>(i + 16) * 16 + p], v1 = Vb[static_cast<size_t>(i + 16) * 16 + p];
+        const uint4 k0 = ld_stream(&Kb[static_cast<size_t>(i) * 16 + p]), v0 = ld_stream(&Vb[static_cast<size_t>(i) * 16 + p]);
+        const uint4 k1 = ld_stream(&Kb[static_cast<size_t>(i + 16) * 16 + p]),
+                    v1 = ld_stream(&Vb[static_cast<size_t>(i + 16) * 16 + p]);
         rec[(row0 + i) * kRecSlots + p] = kvq_make_slot<DT>(k0, v0, m, a, p);
         rec[(row0 + i + 16) * kRecSlots + p] = kvq_make_slot<DT>(k1, v1, m, a, p);
     }

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kBlock) void colsum_kernel(const uint16_t* __restri
     for (; i + 48 < end; i += 64) {  // four independent loads in flight
         uint4 v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = base[static_cast<size_t>(i + 16 * u) * 16 + p];
+        for (int u = 0; u < 4; ++u) v[u] = ld_stream(&base[static_cast<size_t>(i + 16 * u) * 16 + p]);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             float f[8];
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t* __r
 #pragma unroll
         for (int u = 0; u < kEncUnroll; ++u) {
             const int i = min(i0 + u * kEncTokPerIter, last);
-            nx[u] = base[static_cast<size_t>(i) * 32 + g];
+            nx[u] = ld_stream(&base[static_cast<size_t>(i) * 32 + g]);
         }
     };
     if (start < end) request(start + sub);
