@@ -96,6 +96,12 @@ __device__ __forceinline__ uint2 ld_stream(const uint2* p) {
     return make_uint2(x.x, x.y);
 }
 
+__device__ __forceinline__ void st_stream(uint2* p, uint2 v) {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 x = {v.x, v.y};
+    __builtin_nontemporal_store(x, reinterpret_cast<u32x2*>(p));
+}
+
 // Agent-scope relaxed atomics on global memory.
 __device__ __forceinline__ uint32_t atomic_add_u32(uint32_t* p, uint32_t v) {
     return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -102,8 +102,8 @@ __global__ __launch_bounds__(kBlock) void quantize_kv_kernel(const uint16_t* __r
         const uint4 k0 = ld_stream(&Kb[static_cast<size_t>(i) * 16 + p]), v0 = ld_stream(&Vb[static_cast<size_t>(i) * 16 + p]);
         const uint4 k1 = ld_stream(&Kb[static_cast<size_t>(i + 16) * 16 + p]),
                     v1 = ld_stream(&Vb[static_cast<size_t>(i + 16) * 16 + p]);
-        rec[(row0 + i) * kRecSlots + p] = kvq_make_slot<DT>(k0, v0, m, a, p);
-        rec[(row0 + i + 16) * kRecSlots + p] = kvq_make_slot<DT>(k1, v1, m, a, p);
+        st_stream(&rec[(row0 + i) * kRecSlots + p], kvq_make_slot<DT>(k0, v0, m, a, p));
+        st_stream(&rec[(row0 + i + 16) * kRecSlots + p], kvq_make_slot<DT>(k1, v1, m, a, p));
     }
     for (; i < end; i += 16)
         rec[(row0 + i) * kRecSlots + p] =
