@@ -127,8 +127,9 @@ __global__ __launch_bounds__(kBlock) void mean_kernel(const double* __restrict__
 //
 // One lane owns one sign group of one token: lane = 32 * half + g reads the 8 bytes holding channels
 // 4g .. 4g+3 (a wavefront load covers two complete 256 B rows) and derives the group's 4-bit Code.
-// The cluster accumulators are private to the lane - an LDS column tab[entry][lane], entry = 5 * Code
-// + component (4 sums, 1 count), always on the lane's own bank - so they are updated with plain
+// The cluster accumulators are private to the lane - LDS columns tabs[Code][lane] (the four sums as one
+// float4: a 16-lane phase of the 128-bit access covers all 64 banks once, whatever the Codes) and
+// tabc[Code][lane] (the count), always on the lane's own banks - so they are updated with plain
 // read-add-write in token order: no atomics (LDS float atomics ran this kernel at 0.4 TB/s) and a
 // sum order that does not depend on scheduling.  Workgroup partials go to part[unit][wg][g][80].
 constexpr int kEncThreads = 128;                 // two wavefronts
@@ -143,7 +144,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t* __r
                                                              uint8_t* __restrict__ codes,
                                                              float* __restrict__ part, int Hkv, int Lmax,
                                                              int nwg) {
-    __shared__ float tab[CLUSTER ? (kEncThreads / kWave) * kEncEntries * kWave : 1];
+    __shared__ float4 tabs[CLUSTER ? (kEncThreads / kWave) * 16 * kWave : 1];  // [wave][code][lane]: 4 sums
+    __shared__ float tabc[CLUSTER ? (kEncThreads / kWave) * 16 * kWave : 1];    // [wave][code][lane]: count
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int g = lane & 31, sub = wv * 2 + (lane >> 5);  // sub: which of the 4 tokens of a step
     const int unit = blockIdx.x / nwg, wg = blockIdx.x % nwg;
@@ -162,10 +164,14 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t* __r
     const uint2* base = reinterpret_cast<const uint2*>(K + static_cast<size_t>(unit) * Lmax * kD);
     uint8_t* cbase = codes + static_cast<size_t>(unit) * Lmax * kCodeBytes;
     const float4 m = reinterpret_cast<const float4*>(mu + static_cast<size_t>(unit) * kD)[g];
-    float* col = tab + (CLUSTER ? wv * kEncEntries * kWave + lane : 0);  // this lane's column, stride 64
+    float4* cols = tabs + (CLUSTER ? wv * 16 * kWave + lane : 0);  // this lane's columns, stride 64 per code
+    float* colc = tabc + (CLUSTER ? wv * 16 * kWave + lane : 0);
     if constexpr (CLUSTER) {
-#pragma unroll 8
-        for (int e = 0; e < kEncEntries; ++e) col[e * kWave] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            cols[c * kWave] = make_float4(0.f, 0.f, 0.f, 0.f);
+            colc[c * kWave] = 0.0f;
+        }
     }
     // The rows of the next iteration are requested before the current ones are processed (the accumulator
     // updates are a chain of dependent LDS accesses that would otherwise sit idle behind the HBM latency).
@@ -198,12 +204,13 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t* __r
                 const int other = __builtin_amdgcn_update_dpp(0, code, 0xB1 /* quad_perm:[1,0,3,2] */, 0xf, 0xf, false);
                 if ((g & 1) == 0) cbase[static_cast<size_t>(i) * kCodeBytes + (g >> 1)] = static_cast<uint8_t>((code << 4) | other);
                 if constexpr (CLUSTER) {
-                    float* ent = col + code * 5 * kWave;
-                    ent[0 * kWave] += f[0] - m.x;
-                    ent[1 * kWave] += f[1] - m.y;
-                    ent[2 * kWave] += f[2] - m.z;
-                    ent[3 * kWave] += f[3] - m.w;
-                    ent[4 * kWave] += 1.0f;
+                    float4 a = cols[code * kWave];
+                    a.x += f[0] - m.x;
+                    a.y += f[1] - m.y;
+                    a.z += f[2] - m.z;
+                    a.w += f[3] - m.w;
+                    cols[code * kWave] = a;
+                    colc[code * kWave] += 1.0f;
                 }
             }
         }
@@ -212,11 +219,15 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const uint16_t* __r
         __syncthreads();
         float* pw = part + (static_cast<size_t>(unit) * kFitMaxWg + wg) * kG * kEncEntries;
         for (int e = tid; e < kG * kEncEntries; e += kEncThreads) {
-            const int gg = e / kEncEntries, ent = e % kEncEntries;
+            const int gg = e / kEncEntries, ent = e % kEncEntries, code = ent / 5, comp = ent % 5;
             float sum = 0.0f;
 #pragma unroll
-            for (int w = 0; w < kEncThreads / kWave; ++w)
-                sum += tab[(w * kEncEntries + ent) * kWave + gg] + tab[(w * kEncEntries + ent) * kWave + 32 + gg];
+            for (int w = 0; w < kEncThreads / kWave; ++w) {
+                const int at = (w * 16 + code) * kWave + gg;
+                sum += comp < 4 ? reinterpret_cast<const float*>(&tabs[at])[comp] +
+                                      reinterpret_cast<const float*>(&tabs[at + 32])[comp]
+                                : tabc[at] + tabc[at + 32];
+            }
             pw[e] = sum;
         }
     }
