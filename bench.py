@@ -22,10 +22,13 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of the dominant kernel, from the FETCH_SIZE and WRITE_SIZE counter runs whose summary is
-# profiles/decode_step_C2_32k.md (counter units x the factor a 256 MiB plain copy calibrates: 2 KiB and 1 KiB).
-# Counters cannot be read from inside this process, so workloads without such a committed run report null.
-MEASURED_TRAFFIC_BYTES = {("C2", "select_attend_kernel"): int(14269.1 * 2048 + 252.9 * 1024)}
+# HBM bytes per launch of the dominant kernel, from the FETCH_SIZE and WRITE_SIZE counter runs whose summaries are
+# profiles/decode_step_C2_32k.md and profiles/decode_step_C3_C4_C5.md (counter units x the factor a 256 MiB plain
+# copy calibrates: 2 KiB and 1 KiB).  Counters cannot be read from inside this process, so workloads without such a
+# committed run report null.
+MEASURED_TRAFFIC_BYTES = {("C2", "select_attend_kernel"): int(14269.1 * 2048 + 252.9 * 1024),
+                          ("C4", "select_attend_kernel"): int(168768.0 * 2048 + 2679.4 * 1024),
+                          ("C5", "select_attend_kernel"): int(141435.2 * 2048 + 2586.5 * 1024)}
 # event intervals of sik_decode_step_profiled, in launch order; the third one is empty when selection and
 # attention run fused in one launch (every benchmark workload)
 KERNELS = ("prep_kernel", "score_kernel", "select_kernel_unfused_only", "select_attend_kernel")
