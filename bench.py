@@ -27,6 +27,7 @@ HBM_PEAK_GBPS = 8000.0
 # copy calibrates: 2 KiB and 1 KiB).  Counters cannot be read from inside this process, so workloads without such a
 # committed run report null.
 MEASURED_TRAFFIC_BYTES = {("C2", "select_attend_kernel"): int(14269.1 * 2048 + 252.9 * 1024),
+                          ("C3", "select_attend_kernel"): int(28470.9 * 2048 + 538.2 * 1024),
                           ("C4", "select_attend_kernel"): int(168768.0 * 2048 + 2679.4 * 1024),
                           ("C5", "select_attend_kernel"): int(141435.2 * 2048 + 2586.5 * 1024)}
 # event intervals of sik_decode_step_profiled, in launch order; the third one is empty when selection and
