@@ -83,3 +83,13 @@ def test_binding_raises_on_error_status():
     with pytest.raises(sik.SikError):
         sik.sik_topk(lay, torch.zeros(4), torch.zeros(1, dtype=torch.int32), 0, torch.zeros(4, dtype=torch.int32),
                      torch.zeros(256, dtype=torch.uint8))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: any other --gpus exits with a message before anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
