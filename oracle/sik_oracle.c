@@ -351,38 +351,39 @@ int sik_oracle_append_rows(uint16_t *K, uint16_t *V, const uint16_t *k_new, cons
  * Format") -- the compressed K/V form that sparse attention reads instead of
  * the 16-bit rows.
  *
- * The integer codes are decided by floating-point arithmetic, so this part is
- * written in binary32 with one fixed order of operations (the library must
- * take the same decisions bit for bit); everything downstream of the codes
- * (dequantisation, attention) is fp64 again.
+ * Like everything else in this file it is the paper's function evaluated in
+ * fp64 on exactly widened inputs, with true divisions; only the values the
+ * format STORES are rounded (qs and zp to IEEE binary16, alpha to binary32).
  *
  * Per token, each run of 32 consecutive channels is one quantisation group
- * with B = 2 bits:
- *     zp = fp16(min x),  qs = fp16((max x - min x) / 3)       (stored, 16 bit)
- *     Q(x) = clamp(round((x - zp) * (1 / qs)), 0, 3), round = nearest, ties to
+ * with B = 2 bits (quantisation equation):
+ *     zp = fp16(min x),  qs = fp16((max x - min x) / (2^B - 1))   (stored)
+ *     Q(x) = clamp(round((x - zp) / qs), 0, 2^B - 1), round = nearest, ties to
  *            even; qs = 0 (constant group) gives Q = 0
- *     D(x) = qs * Q(x) + zp
- * with the STORED (fp16-rounded) qs and zp used on both sides of the format.
- * For V, x is the value itself.  For K, x = |K'| * (1 / alpha) with K' = K - mu
- * (binary32 subtraction of the exactly widened key and the fp32 mean),
- * alpha_d = max over the fitted tokens of |K'_d|, and alpha_d = 0 gives x = 0.
- * Both divisions of the paper's formulas are taken as multiplications by a
- * binary32 reciprocal (one per channel, one per group): the paper fixes no
- * precision or operation order, and this is the order the library uses;
- * the sign of K' is not quantised: it is the sign bit of the 1-bit code.
- * The dequantised key is  s * alpha * D(x),  s = +1 where the code bit is 1.
+ *     D(x) = qs * Q(x) + zp                                 (dequantisation)
+ * with the STORED (fp16-rounded) qs and zp on both sides of the format, so
+ * that D inverts Q consistently.
+ * For V, x is the value itself.  For K (normalisation equation of the same
+ * section), x = |K'| / alpha with K' = K - mu (mu the stored fp32 mean),
+ * alpha_d = max over the fitted tokens of |K'_d| stored as fp32, and
+ * alpha_d = 0 gives x = 0.  The sign of K' is not quantised: it is the sign
+ * bit of the 1-bit code.  The dequantised key is  s * alpha * D(x),  s = +1
+ * where the code bit is 1.
+ *
+ * An implementation in lower precision takes the same decisions except where
+ * (x - zp) / qs falls within its own rounding error of a half-integer (or a
+ * stored parameter within its rounding error of a binary16 rounding boundary);
+ * the parity tests state that band and count the exceptions.
  * ========================================================================== */
 
-/* binary32 -> IEEE binary16 bits, round to nearest even, with subnormals and
- * overflow to infinity. */
-static uint16_t float_to_fp16_bits(float f)
+/* fp64 -> IEEE binary16 bits in ONE rounding (nearest, ties to even), with
+ * subnormals and overflow to infinity. */
+static uint16_t double_to_fp16_bits(double v)
 {
-    uint32_t u;
-    memcpy(&u, &f, sizeof u);
-    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
-    uint32_t mag = u & 0x7fffffffu;
-    if (mag >= 0x7f800000u) return (uint16_t)(sign | (mag > 0x7f800000u ? 0x7e00u : 0x7c00u));
-    double a = fabs((double)f);
+    uint16_t sign = (uint16_t)(signbit(v) ? 0x8000u : 0u);
+    if (isnan(v)) return (uint16_t)(sign | 0x7e00u);
+    if (isinf(v)) return (uint16_t)(sign | 0x7c00u);
+    double a = fabs(v);
     if (a == 0.0) return sign;
     int e;
     (void)frexp(a, &e);                  /* a = m * 2^e, 0.5 <= m < 1: a in [2^(e-1), 2^e) */
@@ -397,9 +398,16 @@ static uint16_t float_to_fp16_bits(float f)
     return (uint16_t)(sign | ((uint16_t)(re - 1 + 15) << 10) | frac);
 }
 
+/* Exposed so that a test can pin the conversion against numpy (binary32 and fp64 inputs). */
 int sik_oracle_to_fp16(const float *x, int64_t n, uint16_t *out)
 {
-    for (int64_t i = 0; i < n; ++i) out[i] = float_to_fp16_bits(x[i]);
+    for (int64_t i = 0; i < n; ++i) out[i] = double_to_fp16_bits((double)x[i]);
+    return 0;
+}
+
+int sik_oracle_f64_to_fp16(const double *x, int64_t n, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = double_to_fp16_bits(x[i]);
     return 0;
 }
 
@@ -408,44 +416,40 @@ int sik_oracle_alpha(const uint16_t *K, int dtype, int B, int Hkv, int Lmax, int
                      const int32_t *seq_len, const float *mu, float *alpha)
 {
     if (bad_shape(B, Hkv, Lmax, D) || (dtype != 0 && dtype != 1)) return -1;
+#pragma omp parallel for collapse(2) num_threads(g_threads)
     for (int b = 0; b < B; ++b)
         for (int h = 0; h < Hkv; ++h) {
             int64_t bh = (int64_t)b * Hkv + h;
             const uint16_t *Kh = K + bh * Lmax * D;
             for (int d = 0; d < D; ++d) {
-                float a = 0.0f;
+                double a = 0.0;
                 for (int i = 0; i < seq_len[b]; ++i) {
-                    float kp = (float)widen(Kh[(int64_t)i * D + d], dtype) - mu[bh * D + d];
-                    if (fabsf(kp) > a) a = fabsf(kp);
+                    double kp = widen(Kh[(int64_t)i * D + d], dtype) - (double)mu[bh * D + d];
+                    if (fabs(kp) > a) a = fabs(kp);
                 }
-                alpha[bh * D + d] = a;
+                alpha[bh * D + d] = (float)a;     /* stored as fp32 */
             }
         }
     return 0;
 }
 
-/* One group of 32 values: stored parameters and 2-bit codes. */
-static void quantize_group(const float *x, uint16_t *param /* qs, zp */, uint8_t *code)
+/* One group of 32 values: stored parameters and 2-bit codes (quantisation equation, B = 2). */
+static void quantize_group(const double *x, uint16_t *param /* qs, zp */, uint8_t *code)
 {
-    float lo = x[0], hi = x[0];
+    double lo = x[0], hi = x[0];
     for (int e = 1; e < 32; ++e) {
         if (x[e] < lo) lo = x[e];
         if (x[e] > hi) hi = x[e];
     }
-    float span = hi - lo;
-    lo = lo + 0.0f;                       /* a zero minimum is stored as +0 whatever the signs of the zeros */
-    volatile float third = span / 3.0f;   /* one rounded binary32 division */
-    param[0] = float_to_fp16_bits(third);
-    param[1] = float_to_fp16_bits(lo);
-    float qs = (float)fp16_to_double(param[0]);
-    float zp = (float)fp16_to_double(param[1]);
-    volatile float rqs = qs > 0.0f ? 1.0f / qs : 0.0f;
+    lo = lo + 0.0;                        /* a zero minimum is stored as +0 whatever the signs of the zeros */
+    param[0] = double_to_fp16_bits((hi - lo) / 3.0);
+    param[1] = double_to_fp16_bits(lo);
+    double qs = fp16_to_double(param[0]);
+    double zp = fp16_to_double(param[1]);
     for (int e = 0; e < 32; ++e) {
-        if (!(qs > 0.0f)) { code[e] = 0; continue; }
-        volatile float diff = x[e] - zp;
-        volatile float t = diff * rqs;
-        float r = nearbyintf(t);
-        code[e] = (uint8_t)(r < 0.0f ? 0 : (r > 3.0f ? 3 : (int)r));
+        if (!(qs > 0.0)) { code[e] = 0; continue; }
+        double r = nearbyint((x[e] - zp) / qs);      /* default rounding mode: ties to even */
+        code[e] = (uint8_t)(r < 0.0 ? 0 : (r > 3.0 ? 3 : (int)r));
     }
 }
 
@@ -459,21 +463,20 @@ int sik_oracle_quantize_kv(const uint16_t *K, const uint16_t *V, int dtype, int 
     if (bad_shape(B, Hkv, Lmax, D) || D % 32 || (dtype != 0 && dtype != 1)) return -1;
     if (t0 < 0 || n < 0 || t0 + n > Lmax) return -1;
     int NG = D / 32;
+#pragma omp parallel for collapse(2) num_threads(g_threads)
     for (int b = 0; b < B; ++b)
         for (int h = 0; h < Hkv; ++h) {
             int64_t bh = (int64_t)b * Hkv + h;
             for (int i = t0; i < t0 + n; ++i) {
                 int64_t row = bh * Lmax + i;
                 for (int g = 0; g < NG; ++g) {
-                    float xk[32], xv[32];
+                    double xk[32], xv[32];
                     for (int e = 0; e < 32; ++e) {
                         int d = 32 * g + e;
-                        volatile float kp = (float)widen(K[row * D + d], dtype) - mu[bh * D + d];
-                        float a = alpha[bh * D + d];
-                        volatile float ra = a > 0.0f ? 1.0f / a : 0.0f;
-                        volatile float khat = fabsf(kp) * ra;
-                        xk[e] = khat;
-                        xv[e] = (float)widen(V[row * D + d], dtype);
+                        double kp = widen(K[row * D + d], dtype) - (double)mu[bh * D + d];
+                        double a = (double)alpha[bh * D + d];
+                        xk[e] = a > 0.0 ? fabs(kp) / a : 0.0;      /* normalisation equation */
+                        xv[e] = widen(V[row * D + d], dtype);
                     }
                     quantize_group(xk, kpar + (row * NG + g) * 2, kq + row * D + 32 * g);
                     quantize_group(xv, vpar + (row * NG + g) * 2, vq + row * D + 32 * g);

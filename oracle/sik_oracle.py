@@ -178,8 +178,17 @@ def to_fp16(x):
     return out
 
 
+def f64_to_fp16(x):
+    """fp64 -> IEEE binary16 bit patterns in one rounding (nearest even): how the stored parameters are rounded."""
+    x = _c(x, np.float64)
+    out = np.empty(x.shape, np.uint16)
+    rc = lib().sik_oracle_f64_to_fp16(_p(x), ctypes.c_int64(x.size), _p(out))
+    assert rc == 0
+    return out
+
+
 def alpha(K, dtype, seq_len, mu):
-    """Per-channel max |K - mu| over the tokens below seq_len: [B, Hkv, D] fp32."""
+    """Per-channel max |K - mu| over the tokens below seq_len (fp64, stored as fp32): [B, Hkv, D]."""
     K = _c(K, np.uint16)
     B, Hkv, Lmax, D = K.shape
     sl = _c(seq_len, np.int32)

@@ -15,4 +15,6 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def oracle():
     from oracle import sik_oracle
+    # OpenMP over (batch, head) on the cores this process may use (the loops inside one head stay serial)
+    sik_oracle.set_threads(min(16, len(os.sched_getaffinity(0))))
     return sik_oracle

@@ -11,7 +11,7 @@ import torch
 
 import sik_workloads as W
 from helpers import dev, topk_sets_agree
-from test_gpu_kvq import Q2State
+from test_gpu_kvq import Q2State, adopt_appended_records
 from test_gpu_parity import GpuState, TDT, cfg_small, check_attention, sync
 
 pytestmark = pytest.mark.gpu
@@ -150,6 +150,8 @@ def run_q2(oracle, cfg, capacity, steps, append, n_forced, side_rows, seq_len=No
                                                         sl, st.mu, st.alpha, st.cb, codes, qkv, k, forced,
                                                         fK if side_rows else None, fV if side_rows else None)
         assert np.array_equal(st.dsl.cpu().numpy(), sl)
+        if append:
+            adopt_appended_records(oracle, kvq, kn, vn, cfg.dtype, st.mu, st.alpha, codes, qkv, sl)
         g_idx = idx.cpu().numpy()
         check_sets(g_idx, ref_idx, oracle.score(q, cfg.dtype, st.cb, codes, sl), forced, sl, k, R)
         if side_rows:
@@ -319,6 +321,7 @@ def test_shared_selection_with_forced_set_budget_and_append(oracle, q2):
         sync()
         if q2:
             oracle.decode_step_q2(q, kn, vn, cfg.dtype, sl, st.mu, st.alpha, st.cb, st.codes, st.qkv, 1)
+            adopt_appended_records(oracle, kvq, kn, vn, cfg.dtype, st.mu, st.alpha, st.codes, st.qkv, sl)
         else:
             oracle.decode_step(q, kn, vn, st.K, st.V, cfg.dtype, sl, st.mu, st.cb, st.codes, 1)
         assert np.array_equal(st.dsl.cpu().numpy(), sl)

@@ -8,7 +8,7 @@ import torch
 import sik_workloads as W
 from helpers import dev
 from test_gpu_forced import check_sets
-from test_gpu_kvq import Q2State
+from test_gpu_kvq import Q2State, adopt_appended_records
 from test_gpu_parity import GpuState, check_attention, cfg_small, sync
 
 pytestmark = pytest.mark.gpu
@@ -80,6 +80,7 @@ def test_random_decode_cases(oracle, seed):
             # the oracle's budget rule lives in decode_step_forced / topk_with_forced; reuse it for both formats
             if ap:
                 oracle.decode_step_q2(q, kn, vn, cfg.dtype, sl, st.mu, st.alpha, st.cb, st.codes, st.qkv, 1)
+                adopt_appended_records(oracle, kvq, kn, vn, cfg.dtype, st.mu, st.alpha, st.codes, st.qkv, sl)
             s_ref = oracle.score(q, cfg.dtype, st.cb, st.codes, sl)
             ref_idx = oracle.topk_with_forced(s_ref, sl, k, forced, R, c["pm"])
         else:

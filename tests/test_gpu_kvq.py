@@ -1,17 +1,20 @@
 """Parity of the 2-bit token-wise K/V path (records, attention on records, decode step on records) against the
 CPU oracle, through the C ABI.
 
-Bars: alpha bit-equal (a maximum of binary32 values); records byte-for-byte equal to the oracle's fields packed
-into the documented layout (the codes are integer decisions taken in binary32 on both sides); attention within
-the same bars as the 16-bit path (1e-5 relative for fp32 output) against the oracle's fp64 attention over the
-dequantised rows; top-k sets as in the 16-bit decode step (scoring does not depend on the K/V format).
+Bars: alpha bit-equal; records against the oracle's fields (the quantisation function in fp64 with true
+divisions) under the rule of helpers.records_agree: sign bytes equal, stored parameters and 2-bit codes equal
+except where the exact value lies within the library's binary32 rounding error of an fp16 rounding boundary /
+of a half-integer of t = (x - zp) / qs (the exceptions are counted and printed; where nothing is near a tie the
+records are byte-for-byte the oracle's); attention within the same bars as the 16-bit path (1e-5 relative for
+fp32 output) against the oracle's fp64 attention over the dequantised rows of THE SAME records; top-k sets as in
+the 16-bit decode step (scoring does not depend on the K/V format).
 """
 import numpy as np
 import pytest
 import torch
 
 import sik_workloads as W
-from helpers import dev, topk_sets_agree
+from helpers import dev, records_agree, topk_sets_agree
 from test_gpu_parity import TDT, check_attention, cfg_small, sync
 
 pytestmark = pytest.mark.gpu
@@ -43,6 +46,31 @@ class Q2State:
         return self.o.pack_records(self.codes, self.qkv)
 
 
+def check_records(st, got, K, V, qkv, codes, ranges, label):
+    """got against the oracle's fields on token ranges [(b, t0, t1)]; prints the near-tie exceptions."""
+    exc = np.zeros(4, np.int64)
+    for b, t0, t1 in ranges:
+        exc += records_agree(st.o, got, K, V, st.cfg.dtype, st.mu, st.alpha, codes, qkv, b, t0, t1)
+    print(f"{label}: {exc[0]} of {exc[2]} parameters and {exc[1]} of {exc[3]} codes inside the near-tie band")
+    return exc
+
+
+def adopt_appended_records(oracle, kvq, kn, vn, dtype, mu, alpha, codes, qkv, sl):
+    """After a decode step that appended token sl[b] - 1 on both sides: the library's record of that token must
+    match the oracle's (already in qkv) under the near-tie rule; the oracle then takes over the library's own row,
+    so that attention is compared on identical records."""
+    B, Hkv = kn.shape[0], kn.shape[1]
+    for b in range(B):
+        t = int(sl[b]) - 1
+        row = np.zeros((B, Hkv, 1, 128), np.uint8)
+        row[b] = kvq[b, :, t:t + 1].cpu().numpy()
+        records_agree(oracle, row, kn[:, :, None, :], vn[:, :, None, :], dtype, mu, alpha, codes, qkv, b, t, t + 1,
+                      base=t)
+        _, one = oracle.unpack_records(row[b:b + 1])
+        for f in ("kq", "vq", "kpar", "vpar"):
+            getattr(qkv, f)[b, :, t] = getattr(one, f)[0, :, 0]
+
+
 def gpu_fit(st):
     dal = torch.full(st.mu.shape, -1.0, device="cuda")
     kvq = sik.alloc_kvq(st.layout)
@@ -53,14 +81,16 @@ def gpu_fit(st):
 
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
 @pytest.mark.parametrize("offset", [0.0, 1.5])
-def test_fit_alpha_and_records_bit_exact(oracle, dtype, offset):
+def test_fit_alpha_and_records_match_oracle(oracle, dtype, offset):
     cfg = cfg_small(batch=2, n_kv_heads=3, n_q_heads=6, context=1337, top_k=64, dtype=dtype, seed=41)
     st = Q2State(cfg, oracle, capacity=1400, seq_len=[1337, 801], offset_std=offset)
     dal, kvq = gpu_fit(st)
     assert np.array_equal(dal.cpu().numpy(), st.alpha)
-    got, want = kvq.cpu().numpy(), st.records()
+    got = kvq.cpu().numpy()
+    exc = check_records(st, got, st.K, st.V, st.qkv, st.codes, [(b, 0, int(L)) for b, L in enumerate(st.sl)],
+                        f"fit {dtype} offset {offset}")
+    assert exc[0] <= exc[2] // 500 and exc[1] <= exc[3] // 10000     # a sliver, not a systematic difference
     for b, L in enumerate(st.sl):
-        assert np.array_equal(got[b, :, :L], want[b, :, :L])
         assert not got[b, :, L:].any()            # records beyond seq_len are not written
     assert sik.sik_kvq_bytes(st.layout) == got.nbytes
 
@@ -80,8 +110,9 @@ def test_encode_range_against_frozen_parameters(oracle):
     sik.sik_quantize_kv(st.layout, dev(K2, cfg.dtype), dev(V2, cfg.dtype), None, 500, 133, sik.SIK_Q_ENCODE, st.dmu,
                         dal, kvq)
     sync()
-    got, want = kvq.cpu().numpy(), oracle.pack_records(codes, qkv)
-    assert np.array_equal(got[:, :, :633], want[:, :, :633]) and not got[:, :, 633:].any()
+    got = kvq.cpu().numpy()
+    check_records(st, got, K2, V2, qkv, codes, [(0, 0, 633), (1, 0, 633)], "encode range")
+    assert not got[:, :, 633:].any()
     assert np.array_equal(dal.cpu().numpy(), st.alpha)      # frozen
     # empty range: nothing happens
     sik.sik_quantize_kv(st.layout, st.dK, st.dV, None, 10, 0, sik.SIK_Q_ENCODE, st.dmu, dal, kvq)
@@ -105,7 +136,17 @@ def test_degenerate_groups_and_channels(oracle):
     assert st.alpha[0, 0, 5] == 0.0
     dal, kvq = gpu_fit(st)
     assert np.array_equal(dal.cpu().numpy(), st.alpha)
-    assert np.array_equal(kvq.cpu().numpy(), st.records())
+    got = kvq.cpu().numpy()
+    check_records(st, got, K, V, st.qkv, st.codes, [(0, 0, 130)], "degenerate groups")
+    # the planted groups are exact in any precision: constant row, zero group, zeros of both signs, the ramp with
+    # its exact ties
+    _, g = oracle.unpack_records(got)
+    for (h, t, sl_) in ((0, 3, slice(0, 128)), (1, 9, slice(32, 64)), (1, 11, slice(0, 32)), (1, 12, slice(0, 32))):
+        assert np.array_equal(g.vq[0, h, t, sl_], st.qkv.vq[0, h, t, sl_])
+        gs = slice(sl_.start // 32, sl_.stop // 32)
+        assert np.array_equal(g.vpar[0, h, t, gs], st.qkv.vpar[0, h, t, gs])
+    assert not g.vpar[0, 0, 3, :, 0].any() and not g.vq[0, 0, 3].any()      # qs = 0 -> Q = 0
+    assert not g.kq[0, 0, :, 5].any()        # dead channel: x = 0
 
 
 @pytest.mark.parametrize("dtype,out_f32", [("bf16", True), ("fp16", True), ("bf16", False), ("fp16", False)])
@@ -165,11 +206,9 @@ def run_decode_q2_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0
                                                  st.mu, st.alpha, st.cb, codes, qkv, k)
         assert np.array_equal(st.dsl.cpu().numpy(), sl)
         if append:
-            want = oracle.pack_records(codes, qkv)
-            got = kvq.cpu().numpy()
+            adopt_appended_records(oracle, kvq, kn, vn, cfg.dtype, st.mu, st.alpha, codes, qkv, sl)
             for b in range(B):
-                t = sl[b] - 1
-                assert np.array_equal(got[b, :, t], want[b, :, t]), (step, b)
+                t = int(sl[b]) - 1
                 assert np.array_equal(st.dcodes[b, :, t].cpu().numpy(), codes[b, :, t])
         g_idx = idx.cpu().numpy()
         s_ref = oracle.score(q, cfg.dtype, st.cb, codes, sl)

@@ -15,7 +15,7 @@ import pytest
 import torch
 
 import sik_workloads as W
-from helpers import bits_of_tensor, dev, f64, topk_sets_agree
+from helpers import bits_of_tensor, check_attention, dev, f64, half_ulp, topk_sets_agree  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 
@@ -211,28 +211,6 @@ def test_sparse_attention_on_oracle_indices(oracle, dtype, out_f32):
     got = out.float().cpu().numpy().astype(np.float64)
     check_attention(got, ref, out_f32, dtype)
     assert np.all(got[1, 0] == 0)
-
-
-def half_ulp(x, dtype):
-    """Half a unit in the last place of the 16-bit type at |x| (8 significand bits bf16, 11 fp16)."""
-    e = np.floor(np.log2(np.maximum(np.abs(x), 1e-30)))
-    return np.exp2(e - (8 if dtype == "bf16" else 11))
-
-
-def check_attention(got, ref, out_f32, dtype="bf16"):
-    """fp32 output: max|d| <= 1e-5 * max|ref| per (b, hq).  16-bit output: max|d| <= 2e-3, except
-    where the 16-bit grid itself is coarser than that (|out| above ~1 for bf16): there the value must
-    be the correctly rounded one up to the fp32 error, |d| <= half-ulp(ref) + 1e-5 * max|ref|."""
-    for b in range(ref.shape[0]):
-        for hq in range(ref.shape[1]):
-            d = np.abs(got[b, hq] - ref[b, hq])
-            scale = max(np.abs(ref[b, hq]).max(), 1e-30)
-            if out_f32:
-                assert d.max() <= 1e-5 * scale, (b, hq, float(d.max()), scale)
-            else:
-                bar = np.maximum(2e-3, half_ulp(ref[b, hq], dtype) + 1e-5 * scale)
-                worst = float((d / bar).max())
-                assert worst <= 1.0, (b, hq, worst, float(d.max()))
 
 
 def test_sparse_attention_all_tokens_matches_dense(oracle):

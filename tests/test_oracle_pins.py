@@ -396,7 +396,7 @@ def test_fp16_conversion_matches_numpy(oracle):
 
 def test_two_bit_groups_worked_by_hand(oracle):
     rows = [l for l in open(os.path.join(GOLDEN, "eq9_two_bit_groups.txt")) if l[0] not in "#\n"]
-    assert len(rows) == 6
+    assert len(rows) == 8
     for line in rows:
         vals, par, codes = [np.array(p.split(), np.float64) for p in line.split("|")]
         V = np.tile(vals, 16).astype(np.float32).reshape(1, 1, 1, 128)     # 4 groups of 32, all alike
@@ -427,32 +427,75 @@ def test_two_bit_memory_model_matches_overhead_analysis(oracle):
 
 @pytest.mark.parametrize("dtype", ["fp16", "bf16"])
 def test_alpha_and_two_bit_quantiser_against_numpy(oracle, dtype):
+    # the quantisation and normalisation equations written out plainly in fp64 (true divisions; numpy's own
+    # fp64 -> fp16 conversion rounds once, to nearest even)
     cfg = q2_cfg(dtype=dtype)
     K, V = W.make_cache(cfg, channel_offset_std=1.5)
     sl = np.array([150, 97], np.int32)
     mu, codes, _, _ = oracle.fit(K, dtype, sl)
     al, qkv = oracle.fit_q2(K, V, dtype, sl, mu)
-    K32, V32 = W.from_bits(K, dtype).astype(np.float32), W.from_bits(V, dtype).astype(np.float32)
+    K64, V64 = f64(K, dtype), f64(V, dtype)
     for b in range(2):
         L = int(sl[b])
-        Kp = K32[b, :, :L] - mu[b, :, None, :]                      # binary32 subtraction
-        assert np.array_equal(al[b], np.abs(Kp).max(axis=1))
-        with np.errstate(divide="ignore"):
-            ral = np.where(al[b] > 0, np.float32(1) / al[b], np.float32(0)).astype(np.float32)
-        khat = np.abs(Kp) * ral[:, None, :]
-        for x, q, par in ((khat, qkv.kq, qkv.kpar), (V32[b, :, :L], qkv.vq, qkv.vpar)):
+        Kp = K64[b, :, :L] - mu[b, :, None, :].astype(np.float64)
+        assert np.array_equal(al[b], np.abs(Kp).max(axis=1).astype(np.float32))
+        a64 = al[b].astype(np.float64)[:, None, :]
+        with np.errstate(divide="ignore", invalid="ignore"):
+            khat = np.where(a64 > 0, np.abs(Kp) / a64, 0.0)
+        for x, q, par in ((khat, qkv.kq, qkv.kpar), (V64[b, :, :L], qkv.vq, qkv.vpar)):
             g = x.reshape(x.shape[0], L, 4, 32)
             lo, hi = g.min(-1), g.max(-1)
             zp16 = lo.astype(np.float16)
-            qs16 = ((hi - lo) / np.float32(3)).astype(np.float16)
+            qs16 = ((hi - lo) / 3.0).astype(np.float16)
             assert np.array_equal(par[b, :, :L, :, 0], qs16.view(np.uint16))
             assert np.array_equal(par[b, :, :L, :, 1], zp16.view(np.uint16))
-            qs, zp = qs16.astype(np.float32)[..., None], zp16.astype(np.float32)[..., None]
+            qs, zp = qs16.astype(np.float64)[..., None], zp16.astype(np.float64)[..., None]
             with np.errstate(divide="ignore", invalid="ignore"):
-                rqs = (np.float32(1) / qs).astype(np.float32)
-                want = np.where(qs > 0, np.clip(np.rint((g - zp) * rqs), 0, 3), 0).astype(np.uint8)
+                want = np.where(qs > 0, np.clip(np.rint((g - zp) / qs), 0, 3), 0).astype(np.uint8)
             assert np.array_equal(q[b, :, :L].reshape(g.shape), want)
         assert not qkv.kq[b, :, L:].any() and not qkv.vpar[b, :, L:].any()   # untouched beyond seq_len
+
+
+def test_two_bit_code_decision_is_a_true_division(oracle):
+    # qs = fp16(1/3) has no exact reciprocal.  x = qs / 2 sits exactly on the tie t = 0.5 (-> 0, ties to even);
+    # one fp16 step above it t > 0.5 (-> 1).  A product with a rounded reciprocal, or arithmetic in binary32,
+    # may move either: the oracle must not.
+    qs = np.float16(1.0 / 3.0).astype(np.float64)
+    assert qs == 1365.0 / 4096.0
+    for zp in (0.0, -0.25, -0.125):
+        v = np.full(32, zp)
+        v[1] = zp + 1.0                                  # span 1 -> qs = fp16(1/3)
+        v[2] = zp + qs / 2                               # t = 0.5 exactly
+        v[3] = zp + qs / 2 + 2.0 ** -13                  # t just above the tie
+        v[4] = zp + qs / 2 - 2.0 ** -13
+        V = np.tile(v, 4).astype(np.float32).reshape(1, 1, 1, 128)
+        assert np.array_equal(V.astype(np.float16).astype(np.float64).ravel(), np.tile(v, 4)), "fp16-exact inputs"
+        qkv = oracle.quantize_kv(np.zeros((1, 1, 1, 128), np.uint16), bits_of(V, "fp16"), "fp16",
+                                 np.zeros((1, 1, 128), np.float32), np.ones((1, 1, 128), np.float32), 0, 1)
+        assert oracle.widen(qkv.vpar[0, 0, 0, 0], "fp16").tolist() == [qs, zp]
+        assert qkv.vq[0, 0, 0, :5].tolist() == [0, 3, 0, 1, 0]
+    # the K side divides by alpha: |K'| / alpha with alpha = 3 is not |K'| times a rounded 1/3
+    Kv = np.zeros(128, np.float32)
+    Kv[:4] = [3.0, 0.0, 0.5, 1.5]                        # x = 1, 0, 1/6, 1/2  ->  qs = fp16(1/3), t = 3, 0, 0.50018, 1.50037
+    al = np.ones((1, 1, 128), np.float32)
+    al[0, 0, :32] = 3.0
+    qkv = oracle.quantize_kv(bits_of(Kv.reshape(1, 1, 1, 128), "fp16"), np.zeros((1, 1, 1, 128), np.uint16), "fp16",
+                             np.zeros((1, 1, 128), np.float32), al, 0, 1)
+    assert oracle.widen(qkv.kpar[0, 0, 0, 0], "fp16").tolist() == [qs, 0.0]
+    assert qkv.kq[0, 0, 0, :4].tolist() == [3, 0, 1, 2]
+
+
+def test_stored_parameters_round_once_from_fp64(oracle):
+    # 1 + 2^-11 + 2^-30 lies above the fp16 tie between 1 and 1 + 2^-10: one rounding gives the upper value,
+    # rounding to binary32 first lands on the tie and then falls to the even (lower) one
+    x = np.array([1 + 2.0 ** -11 + 2.0 ** -30, 1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11 - 2.0 ** -40, 1 / 3, 2 / 3, 1e-7,
+                  6.1e-5, 65519.999, 65520.0, -0.0])
+    with np.errstate(over="ignore"):
+        assert np.array_equal(oracle.f64_to_fp16(x), x.astype(np.float16).view(np.uint16))
+    assert oracle.f64_to_fp16(x[:1])[0] == np.float16(1 + 2.0 ** -10).view(np.uint16)
+    rng = np.random.default_rng(5)
+    y = np.concatenate([rng.normal(0, 1, 20000), rng.normal(0, 1e-6, 5000), rng.uniform(0, 1, 5000) / 3])
+    assert np.array_equal(oracle.f64_to_fp16(y), y.astype(np.float16).view(np.uint16))
 
 
 def test_two_bit_reconstruction_error_bound_and_signs(oracle):
