@@ -59,7 +59,9 @@ typedef enum {
 
 /* Shape of one attention layer's cache.  head_dim must be 128 (the head size of every
  * model the paper evaluates); n_q_heads must be a multiple of n_kv_heads.  Limits (SIK_ERR_SHAPE beyond them):
- * n_q_heads <= 65535, batch * n_q_heads <= 2^20, max_len <= 2^22. */
+ * n_q_heads <= 65535, batch * n_q_heads <= 2^20, max_len <= SIK_MAX_LEN (64 token chunks per head of at most
+ * 64512 tokens each: the per-chunk selection histograms count in 16 bits). */
+#define SIK_MAX_LEN 4128768
 typedef struct {
     int32_t batch;
     int32_t n_kv_heads;
@@ -81,6 +83,15 @@ const char *sik_strerror(int status);
 
 /* Library version, major * 100 + minor. */
 int sik_version(void);
+
+/* Launch geometry the library derives for a layout (diagnostic: tests and tuning read it; no device is touched).
+ * info (host pointer, SIK_PLAN_INFO_LEN int32): [0] token chunks per head of the scoring launch, [1] tokens per such
+ * chunk, [2] blocks of up to 4 query heads per KV head, [3] chunks per row of the stand-alone histogram pass of
+ * sik_topk, [4] tokens per such chunk, [5] chunks per query head of the fused selection + attention launch (0: max_len
+ * is beyond that path), [6] tokens per such chunk, [7] reserved (0).  Every chunk holds at most 64512 tokens and
+ * there are at most 64 per head; a layout that cannot be cut that way is SIK_ERR_SHAPE here and in every other call. */
+#define SIK_PLAN_INFO_LEN 8
+int sik_plan_info(const sik_layout *layout, int32_t *info);
 
 /* Size in bytes of the scratch buffer the calls below need for this layout and k
  * (k may be 0 for sik_quantize_keys / sik_score only).  The same buffer may be
@@ -142,12 +153,13 @@ int sik_decode_step(const sik_layout *layout, const void *q, const void *k_new, 
                     uint8_t *codes, int32_t k, float softmax_scale, void *out, int32_t *idx_out,
                     void *workspace, size_t workspace_bytes, void *stream);
 
-/* Measurement aid for benchmarks (not for serving loops): runs exactly the kernels of
- * sik_decode_step with the same arguments, bracketing each with a HIP event on `stream`, then
- * waits for the stream and returns the event-to-event intervals in microseconds in kernel_us
- * (host pointer, SIK_N_KERNELS + 1 floats: prep/append, score, select, attention in launch
- * order, then one EMPTY interval between two back-to-back events, i.e. the cost of the event pair
- * itself, which the caller subtracts from the others). */
+/* Measurement aid for benchmarks (not for serving loops): runs exactly the kernels of sik_decode_step with the
+ * same arguments, each dispatched with its own start / stop event pair (the begin and end timestamps of the
+ * dispatch itself, as a profiler reports them, not an interval between events recorded around the launch), then
+ * waits for the stream and returns, in microseconds, in kernel_us (host pointer, SIK_N_KERNELS + 1 floats): the
+ * execution time of the prep / append, scoring, selection and attention (or fused selection + attention) kernels
+ * in launch order, 0 for a kernel this step did not launch, then the span from the start of the first kernel to
+ * the end of the last (the step as the GPU saw it, gaps between the kernels included). */
 #define SIK_N_KERNELS 4
 int sik_decode_step_profiled(const sik_layout *layout, const void *q, const void *k_new,
                              const void *v_new, void *K, void *V, int32_t *seq_len, const float *mu,

@@ -17,7 +17,7 @@ SIK_F16, SIK_BF16, SIK_F32 = 0, 1, 2
 SIK_Q_FIT, SIK_Q_ENCODE = 1, 2
 _TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: SIK_F32}
 
-EXPORTS = ("sik_strerror", "sik_version", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
+EXPORTS = ("sik_strerror", "sik_version", "sik_plan_info", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
            "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_profiled", "sik_kvq_bytes",
            "sik_quantize_kv", "sik_sparse_attn_q2", "sik_decode_step_q2", "sik_decode_step_ex")
 
@@ -63,6 +63,8 @@ def lib():
         L.sik_strerror.restype = ctypes.c_char_p
         L.sik_strerror.argtypes = [ctypes.c_int]
         L.sik_version.restype = ctypes.c_int
+        L.sik_plan_info.restype = ctypes.c_int
+        L.sik_plan_info.argtypes = [lp, ctypes.POINTER(i32)]
         L.sik_workspace_bytes.restype = sz
         L.sik_workspace_bytes.argtypes = [lp, i32]
         L.sik_quantize_keys.restype = ctypes.c_int
@@ -119,6 +121,13 @@ def make_layout(batch, n_kv_heads, n_q_heads, head_dim, max_len, kv_dtype, out_d
 
 def sik_strerror(status: int) -> str:
     return lib().sik_strerror(status).decode()
+
+
+def sik_plan_info(layout: Layout):
+    """Launch geometry of a layout (SIK_PLAN_INFO_LEN ints, see include/sik.h); raises on a bad layout."""
+    info = (ctypes.c_int32 * 8)()
+    _check(lib().sik_plan_info(ctypes.byref(layout), info))
+    return [int(x) for x in info]
 
 
 def sik_workspace_bytes(layout: Layout, k: int) -> int:

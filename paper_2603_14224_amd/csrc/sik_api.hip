@@ -2,8 +2,11 @@
 // kernel sequencing.  Declarations and argument contracts live in include/sik.h.
 #include "sik_device.h"
 #include "sik_internal.h"
+#include "sik_select.h"
 
 namespace sik {
+
+thread_local LaunchEvents g_launch_events;
 
 static size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
@@ -14,7 +17,7 @@ static int check_layout(const sik_layout* l, Dims* d) {
     if (l->n_q_heads % l->n_kv_heads != 0) return SIK_ERR_SHAPE;
     if (l->n_q_heads > 0xffff) return SIK_ERR_SHAPE;  // kernels take the head counts as 16-bit argument fields
     if (static_cast<int64_t>(l->batch) * l->n_q_heads > (1 << 20)) return SIK_ERR_SHAPE;
-    if (l->max_len > (1 << 22)) return SIK_ERR_SHAPE;  // 64 chunks of at most 65535 tokens per head
+    if (l->max_len > kMaxLen) return SIK_ERR_SHAPE;  // kMaxChunks chunks of at most kChunkCap tokens per head
     if (l->kv_dtype != SIK_F16 && l->kv_dtype != SIK_BF16) return SIK_ERR_DTYPE;
     if (l->out_dtype != l->kv_dtype && l->out_dtype != SIK_F32) return SIK_ERR_DTYPE;
     d->B = l->batch;
@@ -25,6 +28,9 @@ static int check_layout(const sik_layout* l, Dims* d) {
     d->Lmax = l->max_len;
     d->kv_dtype = l->kv_dtype;
     d->out_dtype = l->out_dtype;
+    // every kernel that builds or sums chunk histograms relies on these bounds (16-bit counts per bin and chunk,
+    // one bitmap bit per token of a chunk, kMaxChunks histograms per head)
+    if (!score_plan_ok(*d) || !hist_plan_ok(*d)) return SIK_ERR_SHAPE;
     return SIK_OK;
 }
 
@@ -47,6 +53,7 @@ Workspace carve(const Dims& d, int k, void* base) {
     const size_t nc = static_cast<size_t>(nc_score > nc_hist ? nc_score : nc_hist);
     w.parthist = reinterpret_cast<uint32_t*>(take(rows * nc * (kBins / 2) * 4));
     w.binp = reinterpret_cast<float*>(take(rows * 2 * 4));
+    w.lens = reinterpret_cast<int32_t*>(take(static_cast<size_t>(d.B) * 4));
     size_t cand_words = rows * kCandCap * 2;
     if (fused_cand_words(d) > cand_words) cand_words = fused_cand_words(d);
     w.cand = reinterpret_cast<uint32_t*>(take(cand_words * 4));
@@ -92,6 +99,22 @@ const char* sik_strerror(int status) {
 }
 
 int sik_version(void) { return 100; }
+
+int sik_plan_info(const sik_layout* layout, int32_t* info) {
+    Dims d;
+    const int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (!info) return SIK_ERR_NULL;
+    int nhb, nchunk, chunk;
+    score_plan(d, &nhb, &nchunk, &chunk);
+    info[0] = nchunk, info[1] = chunk, info[2] = nhb;
+    hist_plan(d, &nchunk, &chunk);
+    info[3] = nchunk, info[4] = chunk;
+    const bool fused = fused_plan(d, &nchunk, &chunk);
+    info[5] = fused ? nchunk : 0, info[6] = chunk;
+    info[7] = 0;
+    return SIK_OK;
+}
 
 size_t sik_workspace_bytes(const sik_layout* layout, int32_t k) {
     Dims d;
@@ -204,12 +227,18 @@ int sik_sparse_attn_q2(const sik_layout* layout, const void* q, const void* kvq,
     return launched(e);
 }
 
+// Start / stop events of the (at most) SIK_N_KERNELS kernels of one profiled decode step.
+struct StepTimers {
+    hipEvent_t start[SIK_N_KERNELS], stop[SIK_N_KERNELS];
+    bool used[SIK_N_KERNELS];
+};
+
 // kvq == nullptr: 16-bit cache (K, V); else the 2-bit cache (kvq, alpha), K and V unused.
 static int decode_step_impl(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
                             void* K, void* V, void* kvq, const float* alpha, int32_t* seq_len, const float* mu,
                             const float* codebook, uint8_t* codes, int32_t k, float softmax_scale, void* out,
                             int32_t* idx_out, void* workspace, size_t workspace_bytes, void* stream,
-                            hipEvent_t* ev, const StepOptions& opt = StepOptions{}) {
+                            StepTimers* tm, const StepOptions& opt = StepOptions{}) {
     Dims d;
     int rc = check_layout(layout, &d);
     if (rc) return rc;
@@ -230,7 +259,18 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     if (rc) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int32_t* idx = idx_out ? idx_out : w.idx;
-    auto mark = [&](int i) { return ev ? hipEventRecord(ev[i], s) : hipSuccess; };
+    // profiled call: kernel i of the step (0 prep / append, 1 scoring, 2 selection, 3 attention or selection +
+    // attention) is dispatched with its own start / stop event pair
+    auto timed = [&](int i) {
+        if (tm) g_launch_events = LaunchEvents{tm->start[i], tm->stop[i]};
+    };
+    auto done = [&](int i, hipError_t e) {
+        if (tm) {
+            tm->used[i] = e == hipSuccess && g_launch_events.start == nullptr;
+            g_launch_events = LaunchEvents{};
+        }
+        return e;
+    };
     int fchunks, fchunk;
     const bool fused = fused_plan(d, &fchunks, &fchunk);
     if ((kvq || opt.n > 0 || opt.k_per_mille > 0) && !fused)
@@ -250,75 +290,77 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     const bool plain = opt.n == 0 && opt.k_per_mille == 0 && !(kvq && k_new);
     const bool shared_unfused =
         opt.group_shared && (!fused || (plain && static_cast<int64_t>(d.units()) * d.Lmax > (2 << 20)));
-    hipError_t e = mark(0);
-    if (shared_unfused) {
-        // prep, score (summed query), stand-alone selector per KV head, attention reading one index list per KV
-        // head.  idx_out, if given, is [B, Hkv, k].
-        // (nothing to append: no prep launch, the scoring launch clears the per-head counters itself)
-        if (e == hipSuccess && k_new) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
-        if (e == hipSuccess) e = mark(1);
-        if (e == hipSuccess)
-            e = launch_score(ds, &w, k_new == nullptr, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0,
-                             q_sum, s);
-        if (e == hipSuccess) e = mark(2);
-        if (e == hipSuccess) e = launch_select(ds, w, true, w.scores, seq_len, k, idx, s);
-        if (e == hipSuccess) e = mark(3);
-        if (e == hipSuccess)
-            e = kvq ? launch_attn_q2(d, w, q, kvq, alpha, idx, true, k, softmax_scale, out, s)
-                    : launch_attn(d, w, q, K, V, idx, true, k, softmax_scale, out, s);
-    } else if (fused) {
+    hipError_t e = hipSuccess;
+    if (shared_unfused || !fused) {
+        // prep (append + counters; skipped when nothing is appended: the scoring launch then clears the per-head
+        // counters itself), scoring (on the summed query when the selection is shared), stand-alone selector (per
+        // KV head when shared: idx_out is then [B, Hkv, k]), attention reading that index list.  Contexts beyond
+        // 512K tokens take this route too.
+        const Dims& dsel = shared_unfused ? ds : d;
+        if (k_new) {
+            timed(0);
+            e = done(0, launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s));
+        }
+        if (e == hipSuccess) {
+            timed(1);
+            e = done(1, launch_score(dsel, &w, k_new == nullptr, Append{}, q, codebook, codes, seq_len, w.scores,
+                                     nullptr, 0, shared_unfused ? q_sum : 1, s));
+        }
+        if (e == hipSuccess) {
+            timed(2);
+            e = done(2, launch_select(dsel, w, true, w.scores, seq_len, k, idx, s));
+        }
+        if (e == hipSuccess) {
+            timed(3);
+            e = done(3, kvq ? launch_attn_q2(d, w, q, kvq, alpha, idx, shared_unfused, k, softmax_scale, out, s)
+                            : launch_attn(d, w, q, K, V, idx, shared_unfused, k, softmax_scale, out, s));
+        }
+    } else {
         // Two launches: scoring (which also stores, encodes and scores an appended row and clears the
-        // per-call counters), then selection + attention (which publishes the new length).  The first
-        // and third event intervals are empty.
+        // per-call counters), then selection + attention (which publishes the new length).
         const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
                         static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
-        if (e == hipSuccess) e = mark(1);
-        if (e == hipSuccess)
-            e = launch_score(ds, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, opt.idx,
-                             opt.n, q_sum, s);
-        if (e == hipSuccess) e = mark(2);
-        if (e == hipSuccess) e = mark(3);
-        if (e == hipSuccess)
-            e = launch_fused(d, w, q, K, V, kvq, alpha,
-                             StepOptions{opt.idx, opt.n, opt.fK, opt.fV, mu, opt.k_per_mille, opt.group_shared},
-                             seq_len,
-                             k_new != nullptr, k, softmax_scale, idx_out, out, s);
-    } else {
-        // contexts beyond 512K tokens: prep (append + clear counters), score, select, attention
-        if (e == hipSuccess && k_new) e = launch_prep(d, w, k_new, v_new, K, V, seq_len, mu, codes, s);
-        if (e == hipSuccess) e = mark(1);
-        if (e == hipSuccess)
-            e = launch_score(d, &w, k_new == nullptr, Append{}, q, codebook, codes, seq_len, w.scores, nullptr, 0, 1,
-                             s);
-        if (e == hipSuccess) e = mark(2);
-        if (e == hipSuccess) e = launch_select(d, w, true, w.scores, seq_len, k, idx, s);
-        if (e == hipSuccess) e = mark(3);
-        if (e == hipSuccess) e = launch_attn(d, w, q, K, V, idx, false, k, softmax_scale, out, s);
+        timed(1);
+        e = done(1, launch_score(ds, &w, true, k_new ? ap : Append{}, q, codebook, codes, seq_len, w.scores, opt.idx,
+                                 opt.n, q_sum, s));
+        if (e == hipSuccess) {
+            timed(3);
+            e = done(3, launch_fused(d, w, q, K, V, kvq, alpha,
+                                     StepOptions{opt.idx, opt.n, opt.fK, opt.fV, mu, opt.k_per_mille, opt.group_shared},
+                                     seq_len, k_new != nullptr, k, softmax_scale, idx_out, out, s));
+        }
     }
-    if (e == hipSuccess) e = mark(4);
-    if (e == hipSuccess && ev) e = hipEventRecord(ev[5], s);  // empty interval: cost of an event pair
     return launched(e);
 }
 
-// Runs decode_step_impl between HIP events and converts them to intervals (see sik_decode_step_profiled).
+// Runs one decode step with every kernel dispatched between its own start / stop events, waits for the stream
+// and converts the events to execution times (see sik_decode_step_profiled).
 extern "C++" template <class Run>
 static int profiled(void* stream, float* kernel_us, Run run) {
     if (!kernel_us) return SIK_ERR_NULL;
-    constexpr int kEvents = SIK_N_KERNELS + 2;
-    hipEvent_t ev[kEvents];
+    StepTimers tm{};
     int made = 0;
-    for (; made < kEvents; ++made)
-        if (hipEventCreate(&ev[made]) != hipSuccess) break;
-    int rc = made == kEvents ? SIK_OK : SIK_ERR_LAUNCH;
-    if (rc == SIK_OK) rc = run(ev);
-    if (rc == SIK_OK && hipEventSynchronize(ev[SIK_N_KERNELS + 1]) != hipSuccess) rc = SIK_ERR_LAUNCH;
-    for (int i = 0; rc == SIK_OK && i <= SIK_N_KERNELS; ++i) {
+    for (; made < 2 * SIK_N_KERNELS; ++made)
+        if (hipEventCreate(made & 1 ? &tm.stop[made / 2] : &tm.start[made / 2]) != hipSuccess) break;
+    int rc = made == 2 * SIK_N_KERNELS ? SIK_OK : SIK_ERR_LAUNCH;
+    if (rc == SIK_OK) rc = run(&tm);
+    if (rc == SIK_OK && hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess) rc = SIK_ERR_LAUNCH;
+    int first = -1, last = -1;
+    for (int i = 0; rc == SIK_OK && i < SIK_N_KERNELS; ++i) {
         float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, ev[i], ev[i + 1]) != hipSuccess) rc = SIK_ERR_LAUNCH;
+        if (tm.used[i]) {
+            if (hipEventElapsedTime(&ms, tm.start[i], tm.stop[i]) != hipSuccess) rc = SIK_ERR_LAUNCH;
+            if (first < 0) first = i;
+            last = i;
+        }
         kernel_us[i] = ms * 1000.0f;
     }
-    for (int i = 0; i < made; ++i) (void)hipEventDestroy(ev[i]);
-    (void)stream;
+    if (rc == SIK_OK) {
+        float ms = 0.0f;
+        if (first >= 0 && hipEventElapsedTime(&ms, tm.start[first], tm.stop[last]) != hipSuccess) rc = SIK_ERR_LAUNCH;
+        kernel_us[SIK_N_KERNELS] = ms * 1000.0f;
+    }
+    for (int i = 0; i < made; ++i) (void)hipEventDestroy(i & 1 ? tm.stop[i / 2] : tm.start[i / 2]);
     return rc;
 }
 
@@ -334,7 +376,7 @@ int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void
                              void* K, void* V, int32_t* seq_len, const float* mu, const float* codebook,
                              uint8_t* codes, int32_t k, float softmax_scale, void* out, int32_t* idx_out,
                              void* workspace, size_t workspace_bytes, void* stream, float* kernel_us) {
-    return profiled(stream, kernel_us, [&](hipEvent_t* ev) {
+    return profiled(stream, kernel_us, [&](StepTimers* ev) {
         return decode_step_impl(layout, q, k_new, v_new, K, V, nullptr, nullptr, seq_len, mu, codebook, codes, k,
                                 softmax_scale, out, idx_out, workspace, workspace_bytes, stream, ev);
     });
@@ -348,7 +390,7 @@ int sik_decode_step_q2(const sik_layout* layout, const void* q, const void* k_ne
     if (!kernel_us)
         return decode_step_impl(layout, q, k_new, v_new, nullptr, nullptr, kvq, alpha, seq_len, mu, codebook, codes,
                                 k, softmax_scale, out, idx_out, workspace, workspace_bytes, stream, nullptr);
-    return profiled(stream, kernel_us, [&](hipEvent_t* ev) {
+    return profiled(stream, kernel_us, [&](StepTimers* ev) {
         return decode_step_impl(layout, q, k_new, v_new, nullptr, nullptr, kvq, alpha, seq_len, mu, codebook, codes,
                                 k, softmax_scale, out, idx_out, workspace, workspace_bytes, stream, ev);
     });
@@ -358,7 +400,7 @@ int sik_decode_step_ex(const sik_layout* layout, const sik_decode_args* a) {
     if (!a) return SIK_ERR_NULL;
     const StepOptions opt{a->forced_idx, a->n_forced, static_cast<const uint16_t*>(a->forced_K),
                         static_cast<const uint16_t*>(a->forced_V), a->mu, a->k_per_mille, a->group_shared != 0};
-    auto run = [&](hipEvent_t* ev) {
+    auto run = [&](StepTimers* ev) {
         return decode_step_impl(layout, a->q, a->k_new, a->v_new, a->K, a->V, a->kvq, a->alpha, a->seq_len, a->mu,
                                 a->codebook, a->codes, a->k, a->softmax_scale, a->out, a->idx_out, a->workspace,
                                 a->workspace_bytes, a->stream, ev, opt);

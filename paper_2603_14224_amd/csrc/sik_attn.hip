@@ -178,16 +178,11 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
         auto Kp = static_cast<const uint16_t*>(K);
         auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_ATTNS(DTV, ODTV)                                                                                  \
-    attn_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per,          \
-                                                          nblk | (stream ? 1 << 16 : 0), sl2, w.counters,        \
-                                                          w.partial, out)
-        if (d.kv_dtype == kBF16) {
-            if (d.out_dtype == kF32) SIK_ATTNS(kBF16, kF32); else SIK_ATTNS(kBF16, kBF16);
-        } else {
-            if (d.out_dtype == kF32) SIK_ATTNS(kF16, kF32); else SIK_ATTNS(kF16, kF16);
-        }
+    launch_kernel(attn_shared_kernel<DTV, ODTV>, grid, kBlock, s, qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per, \
+                  nblk | (stream ? 1 << 16 : 0), sl2, w.counters, w.partial, out)
+        if (d.kv_dtype == kBF16) return d.out_dtype == kF32 ? SIK_ATTNS(kBF16, kF32) : SIK_ATTNS(kBF16, kBF16);
+        return d.out_dtype == kF32 ? SIK_ATTNS(kF16, kF32) : SIK_ATTNS(kF16, kF16);
 #undef SIK_ATTNS
-        return hipGetLastError();
     }
     int nsplit, per;
     attn_plan(d, k, &nsplit, &per);
@@ -199,16 +194,11 @@ hipError_t launch_attn(const Dims& d, const Workspace& w, const void* q, const v
     auto Kp = static_cast<const uint16_t*>(K);
     auto Vp = static_cast<const uint16_t*>(V);
 #define SIK_ATTN(DTV, ODTV)                                                                                  \
-    attn_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per,               \
-                                                   (idx_per_unit ? 1 : 0) | (gather_streams(d, k) ? 2 : 0), sl2,   \
-                                                   w.counters, w.partial, out)
-    if (d.kv_dtype == kBF16) {
-        if (d.out_dtype == kF32) SIK_ATTN(kBF16, kF32); else SIK_ATTN(kBF16, kBF16);
-    } else {
-        if (d.out_dtype == kF32) SIK_ATTN(kF16, kF32); else SIK_ATTN(kF16, kF16);
-    }
+    launch_kernel(attn_kernel<DTV, ODTV>, grid, kBlock, s, qp, Kp, Vp, idx, dims0, dims1, k, d.Lmax, per,      \
+                  (idx_per_unit ? 1 : 0) | (gather_streams(d, k) ? 2 : 0), sl2, w.counters, w.partial, out)
+    if (d.kv_dtype == kBF16) return d.out_dtype == kF32 ? SIK_ATTN(kBF16, kF32) : SIK_ATTN(kBF16, kBF16);
+    return d.out_dtype == kF32 ? SIK_ATTN(kF16, kF32) : SIK_ATTN(kF16, kF16);
 #undef SIK_ATTN
-    return hipGetLastError();
 }
 
 }  // namespace sik

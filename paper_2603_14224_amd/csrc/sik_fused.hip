@@ -44,13 +44,13 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     // argument block.  dims0 = Hkv | Hq << 16, dims1 = R | nchunk << 16,
     // dims2 = hchunks | n_forced << 8 | shared << 16 | appended << 17 | stream << 18 (non-temporal row loads).
     const float* __restrict__ scores, const uint16_t* __restrict__ q, const uint32_t* __restrict__ parthist,
-    const float* __restrict__ binp, int32_t* __restrict__ seq_len, int sstride, uint32_t dims0, uint32_t dims1,
+    const float* __restrict__ binp, const int32_t* __restrict__ lens, int sstride, uint32_t dims0, uint32_t dims1,
     uint32_t dims2, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V, const uint2* __restrict__ kvq,
     const float* __restrict__ alpha, uint32_t* __restrict__ counters, uint32_t* __restrict__ cand,
     float* __restrict__ partial, int32_t* __restrict__ idx_ws, int32_t* __restrict__ idx_out,
     void* __restrict__ out, float scale_log2e, int k, int Lmax, const int32_t* __restrict__ forced_idx,
     const uint16_t* __restrict__ fK, const uint16_t* __restrict__ fV, const float* __restrict__ mu,
-    int k_per_mille) {
+    int k_per_mille, int32_t* __restrict__ seq_len) {
     constexpr int kChunk = 1024 * NQ;
     constexpr int kListCap = 512;  // selected-token slots per wavefront; flushed to the gather when half full
     const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16, R = dims1 & 0xffffu, nchunk = dims1 >> 16;
@@ -96,7 +96,8 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     }
     const float lo = binp[srow * 2], scale = binp[srow * 2 + 1];
     const HistLoads hl = load_chunk_hists(parthist + srow * hchunks * kHistWords, hchunks);
-    int L = seq_len[b];
+    // the length as the scoring launch counted it (an appended token included): this launch only WRITES seq_len[b]
+    int L = lens[b];
     // Everything above comes from the preloaded arguments; what follows needs the rest of the argument block,
     // which arrives a memory round trip after the wavefront started.
     int32_t* const orow = !idx_out ? nullptr
@@ -116,8 +117,6 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
                  qf[6] * m1.z + qf[7] * m1.w;
     }
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
-    const bool grew = appended && L < Lmax;  // the scoring launch stored and scored one more token
-    if (grew) L += 1;
     const int nact = L > 0 ? (L + kChunk - 1) / kChunk : 1;
     if (c >= nact) return;  // no token of this chunk is valid; the ticket below counts nact workgroups
     const int end = min(L, start + kChunk);
@@ -484,9 +483,9 @@ __global__ __launch_bounds__(kBlock, 4) void select_attend_kernel(
     }
     if (orow)
         for (int j = nfv + kk + tid; j < k; j += kBlock) olist[j] = -1;
-    // the last query head of the sequence to finish publishes the new length: by then every workgroup of
-    // every head of this sequence has read the old one
-    if (grew && tid == 0) {
+    // the last query head of the sequence to finish publishes the new length (nothing in this launch reads
+    // seq_len; at capacity nothing was appended and L is the old value)
+    if (appended && tid == 0) {
         if (atomic_add_u32(&counters[static_cast<size_t>(b) * Hq * 8 + 7], 1u) == static_cast<uint32_t>(Hq) - 1u)
             seq_len[b] = L;
     }
@@ -500,6 +499,7 @@ bool fused_plan(const Dims& d, int* nchunk, int* chunk) {
     int want = (384 + d.rows() - 1) / d.rows();
     int ch = 1024;
     while (ch < 8192 && static_cast<int64_t>(ch) * want < d.Lmax) ch *= 2;
+    while (ch < 8192 && (d.Lmax + ch - 1) / ch > kMaxChunks) ch *= 2;  // few rows, long context: fewer, larger chunks
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
     return *nchunk <= kMaxChunks;
@@ -537,23 +537,19 @@ static hipError_t launch_fused_t(const Dims& d, const Workspace& w, const void* 
                            (fo.group_shared ? 1u << 16 : 0u) | (appended ? 1u << 17 : 0u) |
                            (gather_streams(d, k) ? 1u << 18 : 0u);
 #define SIK_FUSED_Q(NQV, KVQV)                                                                              \
-    select_attend_kernel<DT, ODT, NQV, KVQV><<<grid, kBlock, 0, s>>>(                                       \
-        w.scores, qp, w.parthist, w.binp, seq_len, w.sstride, dims0, dims1, dims2, Kp, Vp, Rp, alpha, w.counters, \
-        w.cand, w.partial, w.idx, idx_out, out, sl2, k, d.Lmax, fo.idx, fo.fK, fo.fV, fo.mu, fo.k_per_mille)
-#define SIK_FUSED(NQV)                                                                                      \
-    do {                                                                                                    \
-        if (kvq) SIK_FUSED_Q(NQV, true); else SIK_FUSED_Q(NQV, false);                                      \
-    } while (0)
+    launch_kernel(select_attend_kernel<DT, ODT, NQV, KVQV>, grid, kBlock, s, w.scores, qp, w.parthist, w.binp,   \
+                  w.lens, w.sstride, dims0, dims1, dims2, Kp, Vp, Rp, alpha, w.counters, w.cand, w.partial, w.idx, \
+                  idx_out, out, sl2, k, d.Lmax, fo.idx, fo.fK, fo.fV, fo.mu, fo.k_per_mille, seq_len)
+#define SIK_FUSED(NQV) (kvq ? SIK_FUSED_Q(NQV, true) : SIK_FUSED_Q(NQV, false))
     switch (chunk) {
-        case 1024: SIK_FUSED(1); break;
-        case 2048: SIK_FUSED(2); break;
-        case 4096: SIK_FUSED(4); break;
-        case 8192: SIK_FUSED(8); break;
+        case 1024: return SIK_FUSED(1);
+        case 2048: return SIK_FUSED(2);
+        case 4096: return SIK_FUSED(4);
+        case 8192: return SIK_FUSED(8);
         default: return hipErrorInvalidValue;
     }
 #undef SIK_FUSED
 #undef SIK_FUSED_Q
-    return hipGetLastError();
 }
 
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,

@@ -1,6 +1,7 @@
 // Host-side plan (grid shapes, workspace carving) and kernel launchers behind the C ABI.
 #pragma once
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -28,6 +29,8 @@ struct Workspace {
     // plain scratch
     uint32_t* parthist;     // [rows][nchunk][kBins/2]  per-chunk histograms, two 16-bit counts per word
     float* binp;            // [rows][2]          histogram origin, scale
+    int32_t* lens;          // [B]  decode step: length of each sequence as the scoring launch counted it (the
+                            //      appended token included), read by the selection + attention launch
     uint32_t* cand;         // (key, index) of threshold-bin members: per row [kCandCap][2] words for the
                             // stand-alone selector; for the fused kernel per row [33][4 * nchunk] words of
                             // wavefront regions, then per row an overflow pool of [kCandCap][2] words
@@ -42,6 +45,36 @@ struct Workspace {
 };
 
 constexpr int kFitMaxWg = 64;
+
+// ---- kernel launches of the decode step ------------------------------------------------------------------
+// The profiled entry points want each kernel's own execution time, as a profiler reports it (begin and end
+// timestamps of the dispatch, not the interval between two events recorded around the launch, which contains
+// the cost of the events themselves).  They set this pair before a launch; launch_kernel then hands it to the
+// runtime with the dispatch and clears it.  Unset (the serving path): a plain launch.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+extern thread_local LaunchEvents g_launch_events;
+
+template <class T>
+struct SameType {
+    using type = T;
+};
+
+// Launches kernel<<<grid, block, 0, s>>>(p...); the arguments convert to the kernel's parameter types here.
+template <class... P>
+inline hipError_t launch_kernel(void (*kernel)(P...), int grid, int block, hipStream_t s,
+                                typename SameType<P>::type... p) {
+    if (g_launch_events.start) {
+        const LaunchEvents ev = g_launch_events;
+        g_launch_events = LaunchEvents{};
+        void* args[] = {const_cast<void*>(static_cast<const void*>(&p))...};
+        return hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(block), args, 0, s, ev.start,
+                                  ev.stop, 0);
+    }
+    kernel<<<grid, block, 0, s>>>(p...);
+    return hipGetLastError();
+}
 
 // Launches that gather at least 64 MB of 16-bit rows (512 B per query head and selected token) read them with
 // non-temporal loads, smaller ones with plain loads (measured both ways on either side, see load_row_slice).
@@ -82,6 +115,7 @@ hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scor
 void score_plan(const Dims& d, int* nhb, int* nchunk, int* chunk);
 bool score_plan_ok(const Dims& d);
 void hist_plan(const Dims& d, int* nchunk, int* chunk);
+bool hist_plan_ok(const Dims& d);
 void select_plan(const Dims& d, int* nchunk, int* chunk);
 // hist_from_score: the chunk histograms come from the scoring kernel (else from launch_topk_hist)
 hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score, const float* scores,

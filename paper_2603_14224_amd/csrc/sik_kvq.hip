@@ -297,21 +297,13 @@ hipError_t launch_attn_q2(const Dims& d, const Workspace& w, const void* q, cons
     auto qp = static_cast<const uint16_t*>(q);
     auto rp = static_cast<const uint2*>(kvq);
 #define SIK_ATTNQ(DTV, ODTV)                                                                                 \
-    do {                                                                                                     \
-        if (shared)                                                                                          \
-            attn_q2_shared_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, dims0, dims1, k, d.Lmax, per, \
-                                                                     nblk, sl2, w.counters, w.partial, out); \
-        else                                                                                                 \
-            attn_q2_kernel<DTV, ODTV><<<grid, kBlock, 0, s>>>(qp, rp, alpha, idx, dims0, dims1, k, d.Lmax, per, \
-                                                              idx_per_unit ? 1 : 0, sl2, w.counters, w.partial, out); \
-    } while (0)
-    if (d.kv_dtype == kBF16) {
-        if (d.out_dtype == kF32) SIK_ATTNQ(kBF16, kF32); else SIK_ATTNQ(kBF16, kBF16);
-    } else {
-        if (d.out_dtype == kF32) SIK_ATTNQ(kF16, kF32); else SIK_ATTNQ(kF16, kF16);
-    }
+    (shared ? launch_kernel(attn_q2_shared_kernel<DTV, ODTV>, grid, kBlock, s, qp, rp, alpha, idx, dims0, dims1, k, \
+                            d.Lmax, per, nblk, sl2, w.counters, w.partial, out)                              \
+            : launch_kernel(attn_q2_kernel<DTV, ODTV>, grid, kBlock, s, qp, rp, alpha, idx, dims0, dims1, k, d.Lmax, \
+                            per, idx_per_unit ? 1 : 0, sl2, w.counters, w.partial, out))
+    if (d.kv_dtype == kBF16) return d.out_dtype == kF32 ? SIK_ATTNQ(kBF16, kF32) : SIK_ATTNQ(kBF16, kBF16);
+    return d.out_dtype == kF32 ? SIK_ATTNQ(kF16, kF32) : SIK_ATTNQ(kF16, kF16);
 #undef SIK_ATTNQ
-    return hipGetLastError();
 }
 
 }  // namespace sik

@@ -274,13 +274,8 @@ hipError_t launch_prep(const Dims& d, const Workspace& w, const void* k_new, con
     auto vn = static_cast<const uint16_t*>(v_new);
     auto Kp = static_cast<uint16_t*>(K);
     auto Vp = static_cast<uint16_t*>(V);
-    if (d.kv_dtype == kBF16)
-        prep_kernel<kBF16><<<nb, kBlock, 0, s>>>(w.zero_begin, w.zero_words, nzb, kn, vn, Kp, Vp, seq_len, mu,
-                                                 codes, d.Hkv, d.Lmax);
-    else
-        prep_kernel<kF16><<<nb, kBlock, 0, s>>>(w.zero_begin, w.zero_words, nzb, kn, vn, Kp, Vp, seq_len, mu,
-                                                codes, d.Hkv, d.Lmax);
-    return hipGetLastError();
+    return launch_kernel(d.kv_dtype == kBF16 ? prep_kernel<kBF16> : prep_kernel<kF16>, nb, kBlock, s, w.zero_begin,
+                         w.zero_words, nzb, kn, vn, Kp, Vp, seq_len, mu, codes, d.Hkv, d.Lmax);
 }
 
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,

@@ -127,7 +127,7 @@ __global__ __launch_bounds__(BLK) void score_kernel(
     uint32_t* __restrict__ zero_counters, const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
     uint16_t* __restrict__ Kc, uint16_t* __restrict__ Vc, const float* __restrict__ mu,
     uint8_t* __restrict__ codes_w, const float* __restrict__ alpha, uint2* __restrict__ kvq,
-    const int32_t* __restrict__ forced_idx, int n_forced) {
+    const int32_t* __restrict__ forced_idx, int n_forced, int32_t* __restrict__ lens_out) {
     static_assert(HB == 1 || HB == kHB, "scalar or float4 table entries");
     constexpr int kTokPerIter = kIterTokens / BLK;
     __shared__ __align__(16) float lut[kG * 16 * HB];  // entry (g, j): HB consecutive floats, one per query head
@@ -227,6 +227,9 @@ __global__ __launch_bounds__(BLK) void score_kernel(
         t_new = L;
         L += 1;
     }
+    // The launch that follows takes the sequence's length (the appended token counted in) from this copy: it
+    // publishes the new seq_len[b] itself and must not read a location it writes.
+    if (HIST && lens_out != nullptr && c == 0 && hb == 0 && h == 0 && tid == 0) lens_out[b] = L;
     const bool holds_new = t_new >= start && t_new < start + chunk;
     if (holds_new && tid < 16) {
         float f[8];
@@ -405,7 +408,8 @@ constexpr int kScoreBlock = 512;
 
 // Tokens per workgroup: one workgroup per compute unit for small launches (latency-bound: fewest table builds),
 // two (scalar tables: four) for large ones; whole loop iterations of 1024 tokens (so that the table build and
-// the 2 KB histogram per head are amortised), at most kMaxChunks per head.
+// the 2 KB histogram per head are amortised), at most kChunkCap tokens (the published histogram counts and the
+// forced-token bitmap are sized for that) and at most kMaxChunks chunks per head: max_len <= kMaxLen.
 void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
     const int nhb = (d.R + kHB - 1) / kHB;
     const int units = d.units() * nhb;
@@ -415,7 +419,7 @@ void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
     if (want > kMaxChunks) want = kMaxChunks;
     int ch = (d.Lmax + want - 1) / want;
     ch = (ch + kIterTokens - 1) / kIterTokens * kIterTokens;
-    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += kIterTokens;
+    if (ch > kChunkCap) ch = kChunkCap;  // more chunks instead
     *nhb_out = nhb;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
@@ -424,7 +428,7 @@ void score_plan(const Dims& d, int* nhb_out, int* nchunk, int* chunk) {
 bool score_plan_ok(const Dims& d) {
     int nhb, nchunk, chunk;
     score_plan(d, &nhb, &nchunk, &chunk);
-    return chunk <= kMaxChunkTokens;
+    return chunk <= kChunkCap && nchunk <= kMaxChunks;
 }
 
 template <int DT>
@@ -437,26 +441,18 @@ static hipError_t launch_score_t(const Dims& d, const Workspace* w, bool zero, c
     const bool small_launch = static_cast<int64_t>(d.units()) * nhb * d.Lmax <= (2 << 20);
     auto qp = static_cast<const uint16_t*>(q);
 #define SIK_SCORE2(HV, FV, HBV, BLKV)                                                                        \
-    score_kernel<DT, HV, BLKV, FV, HBV><<<grid, BLKV, 0, s>>>(                                               \
-        qp, codebook, codes, d.Hkv, d.Hq, d.R, d.Lmax, nchunk, chunk, nhb, q_sum, seq_len, scores,           \
-        w ? w->sstride : d.Lmax, w ? w->parthist : nullptr, w ? w->binp : nullptr,                           \
-        zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu, ap.codes, ap.alpha,            \
-        static_cast<uint2*>(ap.kvq), forced_idx, n_forced)
-#define SIK_SCORE1(HV, FV, HBV)                                                                              \
-    do {                                                                                                     \
-        if (small_launch) SIK_SCORE2(HV, FV, HBV, 1024); else SIK_SCORE2(HV, FV, HBV, kScoreBlock);          \
-    } while (0)
-#define SIK_SCORE(HV, FV)                                                                                    \
-    do {                                                                                                     \
-        if (d.R == 1) SIK_SCORE1(HV, FV, 1); else SIK_SCORE1(HV, FV, kHB);                                   \
-    } while (0)
-    if (!w) SIK_SCORE(false, false);
-    else if (n_forced > 0) SIK_SCORE(true, true);
-    else SIK_SCORE(true, false);
+    launch_kernel(score_kernel<DT, HV, BLKV, FV, HBV>, grid, BLKV, s, qp, codebook, codes, d.Hkv, d.Hq, d.R, d.Lmax, \
+                  nchunk, chunk, nhb, q_sum, seq_len, scores, w ? w->sstride : d.Lmax, w ? w->parthist : nullptr, \
+                  w ? w->binp : nullptr, zero ? w->counters : nullptr, ap.k_new, ap.v_new, ap.K, ap.V, ap.mu,   \
+                  ap.codes, ap.alpha, static_cast<uint2*>(ap.kvq), forced_idx, n_forced, w ? w->lens : nullptr)
+#define SIK_SCORE1(HV, FV, HBV) (small_launch ? SIK_SCORE2(HV, FV, HBV, 1024) : SIK_SCORE2(HV, FV, HBV, kScoreBlock))
+#define SIK_SCORE(HV, FV) (d.R == 1 ? SIK_SCORE1(HV, FV, 1) : SIK_SCORE1(HV, FV, kHB))
+    if (!w) return SIK_SCORE(false, false);
+    if (n_forced > 0) return SIK_SCORE(true, true);
+    return SIK_SCORE(true, false);
 #undef SIK_SCORE
 #undef SIK_SCORE1
 #undef SIK_SCORE2
-    return hipGetLastError();
 }
 
 hipError_t launch_score(const Dims& d, const Workspace* w, bool zero_counters, const Append& ap, const void* q,

@@ -11,6 +11,8 @@ static_assert(kBins == 2 * kBlock, "one thread owns two adjacent histogram bins"
 constexpr int kHistWords = kBins / 2;  // 32-bit words per (query head, chunk): bins 2w | 2w+1 << 16
 constexpr int kMaxChunks = 64;         // chunks per query head in the histogram-producing kernels
 constexpr int kMaxChunkTokens = 65535; // a 16-bit count per bin must hold a whole chunk
+constexpr int kChunkCap = 64512;       // largest chunk the plans hand out: a multiple of 1024 below kMaxChunkTokens
+constexpr int kMaxLen = kMaxChunks * kChunkCap;  // longest context the chunk plans cover (4 128 768 tokens)
 
 struct Threshold {
     int bstar;  // threshold bin, -1: every token is selected

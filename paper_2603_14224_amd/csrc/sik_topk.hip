@@ -245,6 +245,8 @@ void select_plan(const Dims& d, int* nchunk, int* chunk) {
     *nchunk = (d.Lmax + ch - 1) / ch;
 }
 
+// Chunks of the stand-alone histogram pass: at most kChunkCap tokens each (16-bit counts per bin and chunk) and
+// at most kMaxChunks of them per row: max_len <= kMaxLen.
 void hist_plan(const Dims& d, int* nchunk, int* chunk) {
     const int rows = d.rows();
     int want = (512 + rows - 1) / rows;
@@ -252,9 +254,15 @@ void hist_plan(const Dims& d, int* nchunk, int* chunk) {
     int ch = (d.Lmax + want - 1) / want;
     ch = (ch + kBlock - 1) / kBlock * kBlock;
     if (ch < 2048) ch = 2048;
-    while ((d.Lmax + ch - 1) / ch > kMaxChunks) ch += kBlock;
+    if (ch > kChunkCap) ch = kChunkCap;
     *chunk = ch;
     *nchunk = (d.Lmax + ch - 1) / ch;
+}
+
+bool hist_plan_ok(const Dims& d) {
+    int nchunk, chunk;
+    hist_plan(d, &nchunk, &chunk);
+    return chunk <= kChunkCap && nchunk <= kMaxChunks;
 }
 
 hipError_t launch_topk_hist(const Dims& d, const Workspace& w, const float* scores, const int32_t* seq_len,
@@ -276,10 +284,10 @@ hipError_t launch_select(const Dims& d, const Workspace& w, bool hist_from_score
         score_plan(d, &nhb, &hchunks, &hchunk);
     else
         hist_plan(d, &hchunks, &hchunk);
-    select_kernel<<<nchunk * d.rows(), kBlock, 0, s>>>(
-        scores, seq_len, w.parthist, w.binp, hist_from_score ? w.sstride : d.Lmax, d.Hq, d.Lmax, chunk, hchunk,
-        static_cast<uint32_t>(hchunks) | static_cast<uint32_t>(nchunk) << 16, w.counters, w.cand, idx, k);
-    return hipGetLastError();
+    return launch_kernel(select_kernel, nchunk * d.rows(), kBlock, s, scores, seq_len, w.parthist, w.binp,
+                         hist_from_score ? w.sstride : d.Lmax, d.Hq, d.Lmax, chunk, hchunk,
+                         static_cast<uint32_t>(hchunks) | static_cast<uint32_t>(nchunk) << 16, w.counters, w.cand, idx,
+                         k);
 }
 
 }  // namespace sik

@@ -93,3 +93,37 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode == 2
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_chunk_plans_stay_inside_their_limits():
+    """Every layout the header admits is cut into at most 64 chunks of at most 64512 tokens per head (the
+    published histogram counts are 16 bits wide and the forced-token bitmap has one bit per token of a chunk);
+    anything else is SIK_ERR_SHAPE from every entry point, and sik_workspace_bytes returns 0."""
+    max_len = 4128768
+    seen_big = False
+    for batch in (1, 2, 7, 64, 512):
+        for hkv, hq in ((1, 1), (1, 4), (8, 32), (8, 64), (2, 24)):
+            if batch * hq > (1 << 20):
+                continue
+            for ml in (1, 1000, 4096, 65535, 65536, 66000, 131072, 524288, 524289, 1 << 20, 1 << 21, 4000000, max_len):
+                lay = L(batch=batch, n_kv_heads=hkv, n_q_heads=hq, max_len=ml)
+                info = sik.sik_plan_info(lay)
+                s_n, s_ch, nhb, h_n, h_ch, f_n, f_ch = info[:7]
+                assert 1 <= s_n <= 64 and 1024 <= s_ch <= 64512 and s_ch % 1024 == 0 and s_n * s_ch >= ml
+                assert nhb == (hq // hkv + 3) // 4
+                assert 1 <= h_n <= 64 and h_ch <= 64512 and h_n * h_ch >= ml
+                assert (f_n == 0) == (ml > 524288) and (f_n == 0 or (f_n * f_ch >= ml and f_n <= 64))
+                seen_big |= s_ch > 32768
+                if sik.sik_workspace_bytes(lay, 1) == 0:           # only the sheer size may stop it
+                    assert batch * hq * ml > 1 << 36
+    assert seen_big
+    # one 131072-token chunk used to be planned here (64 x 8 KV heads of 32 query heads): now three chunks
+    assert sik.sik_plan_info(L(batch=64, max_len=131072))[:2] == [3, 64512]
+    assert sik.sik_plan_info(L(batch=16, n_kv_heads=1, n_q_heads=32, max_len=131072))[3:5] == [3, 64512]
+    too_long = L(max_len=max_len + 1)
+    with pytest.raises(sik.SikError) as e:
+        sik.sik_plan_info(too_long)
+    assert e.value.status == -2
+    assert sik.sik_workspace_bytes(too_long, 16) == 0
+    assert sik.lib().sik_score(ctypes.byref(too_long), FAKE, FAKE, FAKE, FAKE, FAKE, None) == -2
+    assert sik.lib().sik_topk(ctypes.byref(too_long), FAKE, FAKE, 16, FAKE, FAKE, 1 << 40, None) == -2

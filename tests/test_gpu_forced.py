@@ -366,3 +366,58 @@ def test_shared_selection_large_launch_gathers_once(oracle, R, q2):
     # row to the query heads of the group (blocks of 4: R = 5 leaves a block with a single head)
     cfg = cfg_small("C2", batch=8, n_kv_heads=8, n_q_heads=8 * R, context=33000, top_k=300)
     run_shared(oracle, cfg, 33000, steps=1, append=False, q2=q2, seq_len=[33000, 20000, 5, 33000, 1000, 0, 33000, 777])
+
+
+def test_many_units_long_context_forced_set_and_equal_scores(oracle):
+    """512 (sequence, KV head) units of 66000 tokens: a launch large enough for one scoring workgroup per unit,
+    whose token range must still be cut into chunks of at most 64512 tokens (16-bit histogram counts, one forced
+    bitmap bit per token of a chunk).  Forced tokens sit on both sides of token 65536; the first step has an
+    all-zero query (every score equal: one histogram bin holds the whole context and the smaller index wins),
+    the second a random one.  Every unit holds the same seeded cache, so the oracle computes one unit per distinct
+    sequence length and every (b, query head) is compared with it."""
+    B, Hkv, Hq, L, k, nf = 64, 8, 16, 66000, 256, 64
+    R = Hq // Hkv
+    cfg1 = cfg_small("C2", batch=1, n_kv_heads=1, n_q_heads=R, context=L, top_k=k, seed=91)
+    dt = cfg1.dtype
+    assert sik.sik_plan_info(sik.make_layout(B, Hkv, Hq, 128, L, TDT[dt], torch.float32))[:2] == [2, 64512]
+    K1, V1 = W.make_cache(cfg1)
+    mu1, codes1, cb1, _ = oracle.fit(K1, dt, np.array([L], np.int32))
+    lens = np.full(B, L, np.int32)
+    lens[3], lens[5], lens[9], lens[63] = 40000, 65536, 64513, 100
+    rng = np.random.default_rng(7)
+    forced1 = np.concatenate([rng.choice(64000, nf - 8, replace=False), 65500 + 7 * np.arange(8)]).astype(np.int32)
+    lay = sik.make_layout(B, Hkv, Hq, 128, L, TDT[dt], torch.float32)
+    ws = sik.alloc_workspace(lay, k)
+    tile = lambda t, *shape: t.expand(*shape).contiguous()  # noqa: E731
+    dK, dV = tile(dev(K1, dt), B, Hkv, L, 128), tile(dev(V1, dt), B, Hkv, L, 128)
+    dcodes = tile(torch.from_numpy(codes1).cuda(), B, Hkv, L, 16)
+    dmu, dcb = tile(torch.from_numpy(mu1).cuda(), B, Hkv, 128), tile(torch.from_numpy(cb1).cuda(), B, Hkv, 32, 16, 4)
+    dsl = torch.from_numpy(lens).cuda()
+    dforced = tile(torch.from_numpy(forced1).cuda().view(1, 1, nf), B, Hkv, nf)
+    out = torch.empty(B, Hq, 128, device="cuda")
+    idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
+    q_rand, _, _ = W.make_step_inputs(cfg1, 0)
+    for step, q1 in enumerate((np.zeros_like(q_rand), q_rand)):
+        dq = tile(dev(q1, dt).view(1, 1, R, 128), B, Hkv, R, 128).view(B, Hq, 128)
+        sik.sik_decode_step_ex(lay, q=dq, K=dK, V=dV, seq_len=dsl, mu=dmu, codebook=dcb, codes=dcodes, k=k, out=out,
+                               idx_out=idx, workspace=ws, forced_idx=dforced)
+        sync()
+        g_idx, g_out = idx.cpu().numpy(), out.cpu().numpy().astype(np.float64)
+        ref = {}
+        for Lb in sorted(set(lens.tolist())):
+            sl1 = np.array([Lb], np.int32)
+            _, r_idx = oracle.decode_step_forced(q1, None, None, K1, V1, dt, sl1, mu1, cb1, codes1, k,
+                                                 forced1.reshape(1, 1, nf))
+            ref[Lb] = (r_idx, oracle.score(q1, dt, cb1, codes1, sl1), sl1)
+        for b in range(B):
+            r_idx, s_ref, sl1 = ref[int(lens[b])]
+            for h in range(Hkv):
+                gi = g_idx[b:b + 1, h * R:(h + 1) * R]
+                if step == 0:   # all scores equal: the library's own rule (smaller index first) decides, exactly
+                    assert np.array_equal(np.sort(gi, -1), np.sort(r_idx, -1)), (b, h)
+                else:
+                    check_sets(gi, r_idx, s_ref, forced1.reshape(1, 1, nf), sl1, k, R)
+        # attention over the library's own sets: all 1024 query heads as heads of the one oracle unit
+        q_all = np.tile(q1, (1, B * Hkv, 1))
+        att = oracle.sparse_attn(q_all, K1, V1, dt, g_idx.reshape(1, B * Hq, k))
+        check_attention(g_out.reshape(1, B * Hq, 128), att, True)

@@ -185,6 +185,26 @@ def test_topk_is_deterministic(oracle):
         assert np.array_equal(np.sort(run_topk(s, [40000], 1024), axis=-1), a)
 
 
+def test_topk_many_rows_long_context_crowded_bins(oracle):
+    # 512 rows of 70000 scores: enough rows for one histogram workgroup per row, whose range must still be cut
+    # into chunks of at most 64512 tokens (the chunk histograms count in 16 bits): all scores equal, and all
+    # but one equal with the bins spread by an outlier, put 70000 tokens into one bin
+    L, k = 70000, 300
+    assert sik.sik_plan_info(sik.make_layout(64, 1, 8, 128, L, torch.bfloat16))[3:5] == [2, 64512]
+    rng = np.random.default_rng(11)
+    s = np.zeros((64, 8, L), np.float32)
+    s[0, 1] = 3.5
+    s[0, 2, 69999] = 100.0
+    s[0, 3, 5] = -100.0
+    s[1] = rng.normal(size=(8, L)).astype(np.float32)
+    s[2:] = np.round(rng.normal(size=(1, 8, L)) * 8).astype(np.float32)       # a few dozen distinct values
+    sl = np.full(64, L, np.int32)
+    sl[5], sl[6] = 64513, 65536
+    got = run_topk(s, sl.tolist(), k)
+    ref = oracle.topk(s.astype(np.float64), sl, k)
+    assert np.array_equal(np.sort(got, -1), np.sort(ref, -1))
+
+
 def test_topk_empty_sequence(oracle):
     s = np.zeros((2, 2, 64), np.float32)
     got = run_topk(s, [0, 64], 16)
