@@ -22,27 +22,30 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of the dominant kernel, from the FETCH_SIZE and WRITE_SIZE counter runs whose summaries are
-# profiles/decode_step_C2_32k.md and profiles/decode_step_C3_C4_C5.md (counter units x the factor a 256 MiB plain
-# copy calibrates: 2 KiB and 1 KiB).  Counters cannot be read from inside this process, so workloads without such a
-# committed run report null.
-MEASURED_TRAFFIC_BYTES = {("C2", "select_attend_kernel"): int(14269.1 * 2048 + 252.9 * 1024),
-                          ("C3", "select_attend_kernel"): int(28470.9 * 2048 + 538.2 * 1024),
-                          ("C4", "select_attend_kernel"): int(168768.0 * 2048 + 2679.4 * 1024),
-                          ("C5", "select_attend_kernel"): int(141435.2 * 2048 + 2586.5 * 1024)}
-# event intervals of sik_decode_step_profiled, in launch order; the third one is empty when selection and
-# attention run fused in one launch (every benchmark workload)
-KERNELS = ("prep_kernel", "score_kernel", "select_kernel_unfused_only", "select_attend_kernel")
+# HBM bytes per launch of the dominant kernel.  Hardware counters cannot be read from inside this process: these are
+# the FETCH_SIZE + WRITE_SIZE figures of the committed rocprofv3 --pmc runs of this same command (file named beside
+# each; counter units x the factor a 256 MiB plain copy calibrates there).  Workloads or variants without such a
+# run report null.
+MEASURED_TRAFFIC = {}
+# execution times returned by sik_decode_step_profiled, in launch order; the benchmark workloads run two launches
+# (scoring, then fused selection + attention)
+KERNELS = ("prep_kernel", "score_kernel", "select_kernel", "select_attend_kernel")
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--steps", type=int, default=400, help="decode steps per timed block")
     ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--reps", type=int, default=11,
+                    help="timed repetitions of the block of --steps steps; the median block gives `value`")
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "T4"])
+    ap.add_argument("--also", default=None,
+                    help="comma-separated further workloads measured the same way and nested under \"also\" "
+                         "(default: C3, the 128K context of the metric, when --config is C2 and no variant is on; "
+                         "\"none\" switches it off)")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer states to rotate over (0 = auto)")
-    ap.add_argument("--no-graph", action="store_true", help="time plain stream launches instead of HIP-graph replay")
+    ap.add_argument("--no-graph", action="store_true", help="time plain stream launches only, no HIP-graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--kv", default="rows", choices=["rows", "q2"],
@@ -54,9 +57,7 @@ def parse():
     ap.add_argument("--shared", action="store_true",
                     help="group-shared selection: one index set per KV head from the summed scores of its query heads")
     ap.add_argument("--fit", action="store_true",
-                    help="measure the prefill-side quantiser instead of the decode step: sik_quantize_keys FIT "
-                         "(channel means, sign codes, codebook) and, with --kv q2, sik_quantize_kv FIT (alpha, records) "
-                         "of one layer of the workload")
+                    help="measure the prefill-side quantiser instead of the decode step (one layer of the workload)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run one plain elementwise copy of 256 MiB (read 256 MiB, write 256 MiB): under "
                          "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counters' scale factor")
@@ -70,12 +71,7 @@ def main():
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
-
-    import paper_2603_14224_amd as sik
-    import sik_workloads as W
-    from helpers import dev
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -86,20 +82,42 @@ def main():
         torch.add(src, 1.0, out=dst)  # one launch: 256 MiB read + 256 MiB written
         torch.cuda.synchronize()
         del src, dst
-    cfg = W.CONFIGS[args.config]
+    if args.fit:
+        return bench_fit(args)
+    variant = args.kv != "rows" or args.forced or args.shared
+    also = args.also if args.also is not None else ("C3" if args.config == "C2" and not variant else "none")
+    result = bench_decode(args, args.config, cpu=not args.no_cpu_baseline and not args.forced and not args.shared)
+    extra = [bench_decode(args, name, cpu=False) for name in also.split(",") if name not in ("", "none", args.config)]
+    if extra:
+        keep = ("value", "unit", "steps", "warmup", "reps", "ms_per_step", "config", "effective_hbm_GBps",
+                "effective_hbm_frac_of_8TBps", "algorithmic_bytes_per_step", "us_per_step_stream_launch",
+                "us_per_step_hipgraph", "us_per_block_percentiles", "kernel_us", "roofline")
+        result["also"] = [{k_: r[k_] for k_ in keep} for r in extra]
+    print(json.dumps(result))
+
+
+def bench_decode(args, name, cpu):
+    """One workload: resident state, warm-up, --reps timed blocks of exactly --steps steps (stream launches and
+    HIP-graph replay), per-kernel execution times, roofline.  Returns the result dictionary."""
+    import numpy as np
+    import torch
+
+    import paper_2603_14224_amd as sik
+    import sik_workloads as W
+    from helpers import dev
+
+    cfg = W.CONFIGS[name]
     B, Hkv, Hq, D, L, k = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.context, cfg.top_k
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float16
     q2 = args.kv == "q2"
+    K_steps, reps = args.steps, max(1, args.reps)
     per_layer = (B * Hkv * L * 128 if q2 else 2 * B * Hkv * L * D * 2) + B * Hkv * L * (D // 8)
     n_layers = args.layers or max(2, min(16, -(-2 * 256 * 2 ** 20 // per_layer)))
-    total_steps = args.warmup + args.steps
-    # capacity: room for the appended rows of every step that lands on a layer
-    cap = L + (-(-total_steps * 3 // n_layers) + 8 if cfg.append else 0)
-    cap = (cap + 7) // 8 * 8
+    # capacity: room for the rows one block (or the warm-up) appends to a layer; lengths are reset between blocks
+    n_new = -(-max(K_steps, args.warmup) // n_layers) + 1 if cfg.append else 1
+    cap = (L + (n_new + 8 if cfg.append else 0) + 7) // 8 * 8
     lay = sik.make_layout(B, Hkv, Hq, D, cap, tdt, tdt)
     ws = sik.alloc_workspace(lay, k)
-    if args.fit:
-        return bench_fit(args, cfg, lay, ws, cap, q2)
 
     # ---- resident state: n_layers independent draws of the recipe, quantised by the library itself
     layers = []
@@ -126,137 +144,99 @@ def main():
             if q2:
                 st["fK"] = dev(Kb[:, :, :args.forced], cfg.dtype).contiguous()
                 st["fV"] = dev(Vb[:, :, :args.forced], cfg.dtype).contiguous()
-        if li == 0:
+        if li == 0 and cpu:
             host0 = (Kb, Vb)
         layers.append(st)
+    del Kb, Vb
     torch.cuda.synchronize()
-    # step inputs: 8 distinct queries reused in turn; appended key/value rows are distinct for every
-    # step a layer sees (repeating a key would plant exact score ties that real decoding does not have)
+    # step inputs: 8 distinct queries reused in turn (each selects its own rows, so a replayed block does not find
+    # the rows it gathers still cached from the same query on the same layer); appended key/value rows are
+    # distinct for every step a layer sees inside a block (repeating a key would plant exact score ties that real
+    # decoding does not have)
     n_q = 8
     qs = [dev(W.make_step_inputs(cfg, s)[0], cfg.dtype) for s in range(n_q)]
-    n_new = (-(-total_steps // n_layers) + 2) if cfg.append else 1
     kn_all, vn_all = [], []
     for s in range(n_new):
         _, kn, vn = W.make_step_inputs(cfg, 1000 + s)
-        kn_all.append(kn); vn_all.append(vn)
+        kn_all.append(kn)
+        vn_all.append(vn)
     kns = dev(np.stack(kn_all), cfg.dtype)   # [n_new, B, Hkv, D]
     vns = dev(np.stack(vn_all), cfg.dtype)
     out = torch.empty(B, Hq, D, dtype=tdt, device="cuda")
     gen_s = time.time() - t0
 
-    def step(i, profiled=False, base=0):
+    def step(i, profiled=False, idx_out=None):
+        """Step i of a block: layer i mod n_layers, query i mod 8, the (i div n_layers)-th new row of that layer."""
         st = layers[i % n_layers]
         j = i % n_q
-        a = ((i - base) // n_layers) % n_new  # how many rows this layer has been given since its reset
+        a = (i // n_layers) % n_new
         kn, vn = (kns[a], vns[a]) if cfg.append else (None, None)
         if args.forced or args.shared:
             return sik.sik_decode_step_ex(lay, q=qs[j], k_new=kn, v_new=vn, K=st["K"], V=st["V"], kvq=st.get("kvq"),
                                           alpha=st.get("alpha"), seq_len=st["sl"], mu=st["mu"], codebook=st["cb"],
-                                          codes=st["codes"], k=k, out=out, workspace=ws, forced_idx=st.get("fidx"),
-                                          forced_K=st.get("fK"), forced_V=st.get("fV"), group_shared=args.shared,
-                                          profiled=profiled)
+                                          codes=st["codes"], k=k, out=out, idx_out=idx_out, workspace=ws,
+                                          forced_idx=st.get("fidx"), forced_K=st.get("fK"), forced_V=st.get("fV"),
+                                          group_shared=args.shared, profiled=profiled)
         if q2:
             return sik.sik_decode_step_q2(lay, qs[j], kn, vn, st["kvq"], st["sl"], st["mu"], st["alpha"], st["cb"],
-                                          st["codes"], k, 0.0, out, None, ws, profiled=profiled)
+                                          st["codes"], k, 0.0, out, idx_out, ws, profiled=profiled)
         fn = sik.sik_decode_step_profiled if profiled else sik.sik_decode_step
-        return fn(lay, qs[j], kn, vn, st["K"], st["V"], st["sl"], st["mu"], st["cb"], st["codes"], k, 0.0, out, None,
-                  ws)
+        return fn(lay, qs[j], kn, vn, st["K"], st["V"], st["sl"], st["mu"], st["cb"], st["codes"], k, 0.0, out,
+                  idx_out, ws)
 
     def reset_lengths():
         for st in layers:
             st["sl"].fill_(L)
+        torch.cuda.synchronize()
 
-    # ---- warm-up (untimed), then the timed region: exactly --steps steps between two synchronisations
+    # ---- warm-up (untimed)
     for i in range(args.warmup):
         step(i)
-    torch.cuda.synchronize()
+    reset_lengths()
 
-    def timed_stream():
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for i in range(args.steps):
-            step(args.warmup + i)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / args.steps
+    # ---- the timed region: a block = exactly --steps steps between two synchronisations, --reps blocks, each
+    # starting from the same state (lengths reset outside the timed region); `value` is the median block
+    def timed_blocks(run_block):
+        secs = []
+        for _ in range(reps):
+            reset_lengths()
+            t = time.perf_counter()
+            run_block()
+            torch.cuda.synchronize()
+            secs.append((time.perf_counter() - t) / K_steps)
+        return np.sort(np.array(secs))
 
-    launch = "stream"
-    sec_stream = timed_stream()
-    sec_step = sec_stream
+    def stream_block():
+        for i in range(K_steps):
+            step(i)
+
+    s_stream = timed_blocks(stream_block)
+    sec_stream = float(np.median(s_stream))
+    s_best, sec_step, launch = s_stream, sec_stream, "stream"
     sec_graph = None
     if not args.no_graph:
-        # one graph = `rounds` decode steps on every layer in turn.  With append, the graph first resets
-        # the lengths (one small fill per layer, inside the timed region) so that every replay appends
-        # the same `rounds` distinct rows at the same positions instead of piling up copies.
-        # A graph covers every one of the n_q queries (each selects its own rows), so that replays do not
-        # find the rows they gather still in the Infinity Cache from the previous replay.
-        rounds = min(n_q, n_new - 1) if cfg.append else math.lcm(n_layers, n_q) // n_layers
-        per_graph = n_layers * rounds
-        reps = max(1, args.steps // per_graph)
-
-        def graph_body():
-            if cfg.append:
-                reset_lengths()
-            for i in range(per_graph):
-                step(i)
-
         reset_lengths()
         side = torch.cuda.Stream()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
-            graph_body()
-            torch.cuda.synchronize()
+            stream_block()
             reset_lengths()
-            torch.cuda.synchronize()
-            with torch.cuda.graph(g, stream=side):
-                graph_body()
+            with torch.cuda.graph(g, stream=side):   # one graph = the --steps steps of a block, nothing else
+                stream_block()
         torch.cuda.synchronize()
         reset_lengths()
-        for _ in range(max(1, args.warmup // per_graph)):
-            g.replay()
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for _ in range(reps):
-            g.replay()
-        torch.cuda.synchronize()
-        sec_graph = (time.perf_counter() - t) / (reps * per_graph)
+        g.replay()
+        s_graph = timed_blocks(g.replay)
+        sec_graph = float(np.median(s_graph))
         if sec_graph < sec_stream:
-            sec_step, launch = sec_graph, "hipgraph"
+            s_best, sec_step, launch = s_graph, sec_graph, "hipgraph"
     reset_lengths()
-
-    # ---- spread of the step time: events on the launch stream around groups of `grp` consecutive steps (a
-    # single step is shorter than the cost of an event pair); percentiles of the group means
-    grp = 2 * n_layers
-    n_grp = max(1, min(40, total_steps // grp))
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_grp)]
-    for gi, (e0, e1) in enumerate(ev):
-        e0.record()
-        for i in range(grp):
-            step(gi * grp + i)
-        e1.record()
-    torch.cuda.synchronize()
-    grp_us = np.sort(np.array([e0.elapsed_time(e1) for e0, e1 in ev]) * 1e3 / grp)
-    pct = {f"p{p}": round(float(np.percentile(grp_us, p)), 3) for p in (10, 50, 90)}
-    reset_lengths()
+    pct = {f"p{p}": round(float(np.percentile(s_best, p)) * 1e6, 3) for p in (10, 50, 90)}
+    pct.update(min=round(float(s_best[0]) * 1e6, 3), blocks=reps, steps_per_block=K_steps, launch=launch)
 
     # ---- rows the gather really touches: query heads of one GQA group may select the same token
-    idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
-    st0 = layers[0]
-    if args.shared:
-        idx = torch.empty(B, Hkv, k, dtype=torch.int32, device="cuda")
-    if args.forced or args.shared:
-        sik.sik_decode_step_ex(lay, q=qs[0], k_new=kns[0] if cfg.append else None,
-                               v_new=vns[0] if cfg.append else None, K=st0["K"], V=st0["V"], kvq=st0.get("kvq"),
-                               alpha=st0.get("alpha"), seq_len=st0["sl"], mu=st0["mu"], codebook=st0["cb"],
-                               codes=st0["codes"], k=k, out=out, idx_out=idx, workspace=ws,
-                               forced_idx=st0.get("fidx"), forced_K=st0.get("fK"), forced_V=st0.get("fV"),
-                               group_shared=args.shared)
-    elif q2:
-        sik.sik_decode_step_q2(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None,
-                               st0["kvq"], st0["sl"], st0["mu"], st0["alpha"], st0["cb"], st0["codes"], k, 0.0, out,
-                               idx, ws)
-    else:
-        sik.sik_decode_step(lay, qs[0], kns[0] if cfg.append else None, vns[0] if cfg.append else None, st0["K"],
-                            st0["V"], st0["sl"], st0["mu"], st0["cb"], st0["codes"], k, 0.0, out, idx, ws)
+    idx = torch.empty(B, Hkv if args.shared else Hq, k, dtype=torch.int32, device="cuda")
+    step(0, idx_out=idx)
     torch.cuda.synchronize()
     srt = idx.view(B * Hkv, -1).sort(dim=1).values
     fresh = torch.ones_like(srt, dtype=torch.bool)
@@ -266,15 +246,14 @@ def main():
     del idx, srt, fresh
     reset_lengths()
 
-    # ---- per-kernel durations, HIP events on the launch stream, same steps as the timed region
-    # (each interval includes the cost of the event pair; an empty interval measured in the same call
-    # is subtracted)
+    # ---- execution time of each kernel: the begin / end timestamps of its dispatch (what a profiler's kernel
+    # trace reports), over the steps of one block; the last figure is the span of the step on the GPU
     raw = np.zeros(5)
-    n_prof = min(args.steps, 200)
+    n_prof = min(K_steps, 200)
     for i in range(n_prof):
-        raw += np.array(step(args.warmup + i, profiled=True))
+        raw += np.array(step(i, profiled=True))
     raw /= n_prof
-    kus = np.maximum(raw[:4] - raw[4], 0.05)
+    kus = raw[:4]
     reset_lengths()
 
     ab = W.algorithmic_bytes(cfg)
@@ -285,12 +264,14 @@ def main():
         ab = dict(ab, gathered=ab["gathered"] // (Hq // Hkv))
         ab["total"] = ab["codes"] + ab["gathered"]
     alg_by_kernel = {"prep_kernel": (B * Hkv * (2 * D * 2 + D // 8)) if cfg.append else 0,
-                     "score_kernel": ab["codes"], "select_kernel_unfused_only": 0,
-                     "select_attend_kernel": ab["gathered"]}
-    dom = max((1, 3), key=lambda i: kus[i])  # the two kernels that move the algorithmic bytes
+                     "score_kernel": ab["codes"], "select_kernel": 0,
+                     "select_attend_kernel": ab["gathered"] + (ab["codes"] if kus[1] == 0 else 0)}
+    dom = max((1, 3), key=lambda i: kus[i])  # the kernels that move the algorithmic bytes
     dom_name = KERNELS[dom]
     dom_bytes = alg_by_kernel[dom_name]
     achieved = dom_bytes / (kus[dom] * 1e-6) / 1e9
+    variant = q2 or args.forced or args.shared
+    traffic = None if variant else MEASURED_TRAFFIC.get((name, dom_name))
 
     step_us = sec_step * 1e6
     result = {
@@ -298,39 +279,45 @@ def main():
         "value": round(step_us, 3),
         "unit": "us/step",
         "n_gpus": 1,
-        "steps": args.steps,
+        "steps": K_steps,
         "warmup": args.warmup,
+        "reps": reps,
         "ms_per_step": round(sec_step * 1e3, 6),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": cfg.dtype,
+        "arithmetic": f"{cfg.dtype} storage of K, V, q and the output; fp32 lookup tables, score sums and softmax",
         "data": "synthetic",
         "config": {"workload": cfg.name, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "head_dim": D,
-                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv, "forced_tokens": args.forced, "group_shared": args.shared, "append": cfg.append,
+                   "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv,
+                   "forced_tokens": args.forced, "group_shared": args.shared, "append": cfg.append,
                    "layers_rotated": n_layers, "launch": launch},
         "effective_hbm_GBps": round(ab["total"] / sec_step / 1e9, 1),
         "effective_hbm_frac_of_8TBps": round(ab["total"] / sec_step / 1e9 / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": ab["total"],
         "us_per_step_stream_launch": round(sec_stream * 1e6, 3),
         "us_per_step_hipgraph": None if sec_graph is None else round(sec_graph * 1e6, 3),
-        "us_per_step_percentiles": dict(pct, groups=n_grp, steps_per_group=grp, launch="stream"),
+        "us_per_block_percentiles": pct,
         "gathered_rows": {"nominal": rows_nominal, "unique_per_kv_head": rows_unique},
-        "kernel_us_hip_events": {KERNELS[i]: round(float(kus[i]), 3) for i in range(4)},
-        "hip_event_pair_overhead_us": round(float(raw[4]), 3),
+        "kernel_us": dict({KERNELS[i]: round(float(kus[i]), 3) for i in range(4) if kus[i] > 0},
+                          sum=round(float(kus.sum()), 3), steps_profiled=n_prof, how="begin/end timestamps of each dispatch (HIP events handed to "
+                                                      "the launch), mean over the steps of one block"),
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": None if q2 else MEASURED_TRAFFIC_BYTES.get((args.config, dom_name)),
+                     "traffic": None if traffic is None else traffic[0],
+                     "traffic_source": None if traffic is None else traffic[1],
                      "algorithmic_bytes_per_launch": dom_bytes},
         "setup_seconds": round(gen_s, 1),
     }
-
-    if not args.no_cpu_baseline and not args.forced and not args.shared:
+    if cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, host0, args.cpu_seconds, q2)
-    print(json.dumps(result))
+    del layers, ws
+    torch.cuda.empty_cache()
+    return result
 
 
-def bench_fit(args, cfg, lay, ws, cap, q2):
+def bench_fit(args):
     """Prefill-compress of one layer ("one-pass sign-based clustering": means, codes, codebook; plus the 2-bit
     records with --kv q2): two (q2: four) passes over K, one over V, all HBM-bound; rotates over enough layer
     copies of K (and V) to stay out of the Infinity Cache."""
@@ -340,6 +327,12 @@ def bench_fit(args, cfg, lay, ws, cap, q2):
     import sik_workloads as W
     from helpers import dev
 
+    cfg = W.CONFIGS[args.config]
+    q2 = args.kv == "q2"
+    cap = cfg.context
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float16
+    lay = sik.make_layout(cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cap, tdt, tdt)
+    ws = sik.alloc_workspace(lay, cfg.top_k)
     B, Hkv, D, L = cfg.batch, cfg.n_kv_heads, cfg.head_dim, cfg.context
     kv_bytes = B * Hkv * L * D * 2
     n_layers = args.layers or max(2, min(8, -(-2 * 256 * 2 ** 20 // kv_bytes)))
@@ -376,7 +369,7 @@ def bench_fit(args, cfg, lay, ws, cap, q2):
     print(json.dumps({
         "metric": "us per prefill-compress of one layer (quantiser FIT)", "value": round(sec * 1e6, 2),
         "unit": "us/layer", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(sec * 1e3, 5),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name + " / prefill-compress", "batch": B, "n_kv_heads": Hkv, "head_dim": D,
                    "context": L, "kv_dtype": cfg.dtype, "kv_format": args.kv, "layers_rotated": n_layers},
         "roofline": {"bound": "hbm", "kernel": "colsum + encode" + (" + alpha + quantize_kv" if q2 else ""),

@@ -493,7 +493,10 @@ def test_profiled_decode_step_same_result_and_five_intervals(oracle):
     us = sik.sik_decode_step_profiled(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128,
                                       0.0, b, None, st.ws)
     sync()
-    assert len(us) == 5 and all(u >= 0 for u in us) and us[1] > 0 and us[3] > 0
+    # scoring and fused selection + attention ran (no prep, no stand-alone selector); the step's span on the GPU
+    # covers both kernels and the gap between them
+    assert len(us) == 5 and us[0] == 0 and us[2] == 0 and 0.5 < us[1] < 1000 and 0.5 < us[3] < 1000
+    assert us[1] + us[3] <= us[4] * 1.001 < 2000
     assert torch.equal(a, b)
 
 
