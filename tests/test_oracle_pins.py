@@ -498,6 +498,29 @@ def test_stored_parameters_round_once_from_fp64(oracle):
     assert np.array_equal(oracle.f64_to_fp16(y), y.astype(np.float16).view(np.uint16))
 
 
+@pytest.mark.parametrize("dtype", ["fp16", "bf16"])
+def test_alpha_from_channel_extremes(oracle, dtype):
+    # x -> |x - mu| is largest at an end of the range, and rounding to fp32 is monotone: alpha, a maximum over
+    # all fitted tokens, is already fixed by the smallest and the largest key of each channel.  A prefill pass
+    # that keeps per-channel minima and maxima next to the column sums therefore has alpha without reading K again.
+    cfg = q2_cfg(dtype=dtype, batch=2, context=700)
+    K, _ = W.make_cache(cfg, channel_offset_std=2.0)
+    sl = np.array([700, 333], np.int32)
+    mu = oracle.mean(K, dtype, sl)
+    al = oracle.alpha(K, dtype, sl, mu)
+    K64 = f64(K, dtype)
+    for b in range(2):
+        kmin, kmax = K64[b, :, :sl[b]].min(axis=1), K64[b, :, :sl[b]].max(axis=1)
+        m = mu[b].astype(np.float64)
+        want = np.maximum(np.abs(kmax - m), np.abs(kmin - m)).astype(np.float32)
+        assert np.array_equal(al[b], want)
+        # and in binary32 arithmetic (what a GPU pass would do): the same bits
+        k32min, k32max = kmin.astype(np.float32), kmax.astype(np.float32)
+        want32 = np.maximum(np.abs(k32max - mu[b]), np.abs(k32min - mu[b]))
+        assert want32.dtype == np.float32 and np.array_equal(al[b], want32)
+    assert np.array_equal(oracle.alpha(K, dtype, np.array([0, 0], np.int32), mu), np.zeros_like(mu))
+
+
 def test_two_bit_reconstruction_error_bound_and_signs(oracle):
     cfg = q2_cfg(batch=1, context=300)
     K, V = W.make_cache(cfg, channel_offset_std=1.0)
