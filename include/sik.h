@@ -54,7 +54,9 @@ typedef enum {
     SIK_ERR_CAPACITY = -5,  /* token range outside [0, max_len]                              */
     SIK_ERR_WORKSPACE = -6, /* workspace NULL, misaligned or smaller than sik_workspace_bytes */
     SIK_ERR_LAUNCH = -7,    /* the HIP runtime reported an error while enqueueing           */
-    SIK_ERR_FLAGS = -8      /* unknown quantiser mode                                        */
+    SIK_ERR_FLAGS = -8,     /* unknown quantiser mode                                        */
+    SIK_ERR_STATIC_LIMIT = -9 /* sik_decode_step_static: the layout needs more scratch memory than the
+                                 library's built-in buffer holds (SIK_STATIC_SCRATCH_BYTES)       */
 } sik_status;
 
 /* Shape of one attention layer's cache.  head_dim must be 128 (the head size of every
@@ -152,6 +154,21 @@ int sik_decode_step(const sik_layout *layout, const void *q, const void *k_new, 
                     void *K, void *V, int32_t *seq_len, const float *mu, const float *codebook,
                     uint8_t *codes, int32_t k, float softmax_scale, void *out, int32_t *idx_out,
                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* sik_decode_step for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture that must not call hipMalloc, tight serving loops, harnesses that forbid allocation.  Same arguments
+ * and results as sik_decode_step without the workspace pair: the scratch memory is a buffer of
+ * SIK_STATIC_SCRATCH_BYTES built into the library (one copy per GPU, held until the process ends).  A layout / k
+ * whose sik_workspace_bytes exceeds that returns SIK_ERR_STATIC_LIMIT and launches nothing (the benchmark
+ * workloads of one sequence, 32K and 128K tokens, fit; large batches do not).  The call allocates nothing and
+ * frees nothing.  Every call on one GPU shares that GPU's buffer, whatever the stream or thread: calls that
+ * overlap in time on one GPU race; calls on one stream are ordered and safe.  The buffer keeps the previous
+ * call's contents; the step clears what it needs cleared itself.  The first call on a GPU looks the buffer's
+ * address up (hipGetSymbolAddress) and must therefore be made outside stream capture. */
+#define SIK_STATIC_SCRATCH_BYTES (32u << 20)
+int sik_decode_step_static(const sik_layout *layout, const void *q, const void *k_new, const void *v_new, void *K,
+                           void *V, int32_t *seq_len, const float *mu, const float *codebook, uint8_t *codes,
+                           int32_t k, float softmax_scale, void *out, int32_t *idx_out, void *stream);
 
 /* Measurement aid for benchmarks (not for serving loops): runs exactly the kernels of sik_decode_step with the
  * same arguments, each dispatched with its own start / stop event pair (the begin and end timestamps of the

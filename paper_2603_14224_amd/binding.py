@@ -18,7 +18,7 @@ SIK_Q_FIT, SIK_Q_ENCODE = 1, 2
 _TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: SIK_F32}
 
 EXPORTS = ("sik_strerror", "sik_version", "sik_plan_info", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
-           "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_profiled", "sik_kvq_bytes",
+           "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_static", "sik_decode_step_profiled", "sik_kvq_bytes",
            "sik_quantize_kv", "sik_sparse_attn_q2", "sik_decode_step_q2", "sik_decode_step_ex")
 
 
@@ -77,6 +77,8 @@ def lib():
         L.sik_sparse_attn.argtypes = [lp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.sik_decode_step.restype = ctypes.c_int
         L.sik_decode_step.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp, sz, vp]
+        L.sik_decode_step_static.restype = ctypes.c_int
+        L.sik_decode_step_static.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp]
         L.sik_decode_step_profiled.restype = ctypes.c_int
         L.sik_decode_step_profiled.argtypes = L.sik_decode_step.argtypes + [ctypes.POINTER(ctypes.c_float)]
         L.sik_kvq_bytes.restype = sz
@@ -225,6 +227,16 @@ def sik_decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes,
                                  _ptr(seq_len), _ptr(mu), _ptr(codebook), _ptr(codes), int(k),
                                  float(softmax_scale), _ptr(out), _ptr(idx_out), _ptr(workspace),
                                  workspace.numel() if workspace is not None else 0, _stream()))
+
+
+SIK_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def sik_decode_step_static(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out, idx_out):
+    """sik_decode_step on the library's built-in scratch buffer (no workspace argument, nothing allocated)."""
+    _check(lib().sik_decode_step_static(ctypes.byref(layout), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V),
+                                        _ptr(seq_len), _ptr(mu), _ptr(codebook), _ptr(codes), int(k),
+                                        float(softmax_scale), _ptr(out), _ptr(idx_out), _stream()))
 
 
 def sik_decode_step_profiled(layout, q, k_new, v_new, K, V, seq_len, mu, codebook, codes, k, softmax_scale, out,

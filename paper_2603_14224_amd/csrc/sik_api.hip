@@ -4,9 +4,29 @@
 #include "sik_internal.h"
 #include "sik_select.h"
 
+#include <atomic>
+
 namespace sik {
 
 thread_local LaunchEvents g_launch_events;
+
+// Scratch memory of sik_decode_step_static: one copy per GPU, part of the loaded code object.  On the host this
+// name is only a handle for hipGetSymbolAddress; the device address it yields (per device) is what kernels get.
+static __device__ __align__(256) unsigned char scratch[SIK_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr on an error.
+static void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return nullptr;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // every thread finds the same address
+    }
+    return p;
+}
 
 static size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
@@ -94,6 +114,9 @@ const char* sik_strerror(int status) {
         case SIK_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or smaller than sik_workspace_bytes";
         case SIK_ERR_LAUNCH: return "HIP runtime error while enqueueing";
         case SIK_ERR_FLAGS: return "unknown quantiser mode";
+        case SIK_ERR_STATIC_LIMIT:
+            return "sik_decode_step_static: this layout / k needs more scratch memory than the library's built-in "
+                   "buffer (SIK_STATIC_SCRATCH_BYTES); use sik_decode_step with a workspace";
         default: return "unknown status";
     }
 }
@@ -370,6 +393,20 @@ int sik_decode_step(const sik_layout* layout, const void* q, const void* k_new, 
                     void* stream) {
     return decode_step_impl(layout, q, k_new, v_new, K, V, nullptr, nullptr, seq_len, mu, codebook, codes, k,
                             softmax_scale, out, idx_out, workspace, workspace_bytes, stream, nullptr);
+}
+
+int sik_decode_step_static(const sik_layout* layout, const void* q, const void* k_new, const void* v_new, void* K,
+                           void* V, int32_t* seq_len, const float* mu, const float* codebook, uint8_t* codes,
+                           int32_t k, float softmax_scale, void* out, int32_t* idx_out, void* stream) {
+    Dims d;
+    const int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (k < 1 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    if (carve(d, k, nullptr).total_bytes > SIK_STATIC_SCRATCH_BYTES) return SIK_ERR_STATIC_LIMIT;
+    void* ws = static_scratch();
+    if (ws == nullptr) return SIK_ERR_LAUNCH;
+    return decode_step_impl(layout, q, k_new, v_new, K, V, nullptr, nullptr, seq_len, mu, codebook, codes, k,
+                            softmax_scale, out, idx_out, ws, SIK_STATIC_SCRATCH_BYTES, stream, nullptr);
 }
 
 int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_version_and_strerror():
     assert sik.lib().sik_version() >= 100
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         assert sik.sik_strerror(code) not in ("", "unknown status")
     assert sik.sik_strerror(-99) == "unknown status"
 
