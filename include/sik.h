@@ -219,6 +219,19 @@ int sik_quantize_kv(const sik_layout *layout, const void *K, const void *V, cons
                     int32_t t0, int32_t n, int mode, const float *mu, float *alpha, void *kvq,
                     void *stream);
 
+/* Prefill-side compression of one layer in one call: everything sik_quantize_keys(SIK_Q_FIT) followed by
+ * sik_quantize_kv(SIK_Q_FIT) writes - mu, codes, codebook, counts, alpha and the records of tokens
+ * i < seq_len[b] - with identical bits, in two passes over K and one over V instead of four and one (sections
+ * "One-Pass Sign-Based Clustering", "Entropy-Aware Normalization" and "Token-Wise Quantization Format"; this is the
+ * work the paper prices as the overhead on the time to the second token, "End to End Efficiency" (i), and as
+ * "Clustering" in its module-timing table).  The first pass takes the column sums and, per channel, the smallest
+ * and the largest key, which fix alpha = max_i |K_i - mu| (|x - mu| peaks at an end of the range); the second
+ * writes codes, cluster sums and records.  All outputs are device pointers as in those two calls; K and V are
+ * read only; the workspace is sik_workspace_bytes(layout, k) for any k >= 0. */
+int sik_prefill_compress(const sik_layout *layout, const void *K, const void *V, const int32_t *seq_len, float *mu,
+                         float *codebook, int32_t *counts, uint8_t *codes, float *alpha, void *kvq, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
 /* Sparse attention as sik_sparse_attn, on records: the logit of token j is
  * softmax_scale * sum_d q_d * s_d alpha_d D(K)_jd (the centred key: the dropped q . mu is one
  * constant per query head and cancels in the softmax, normalisation section), the value row is

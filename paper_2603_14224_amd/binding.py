@@ -19,7 +19,7 @@ _TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: S
 
 EXPORTS = ("sik_strerror", "sik_version", "sik_plan_info", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
            "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_static", "sik_decode_step_profiled", "sik_kvq_bytes",
-           "sik_quantize_kv", "sik_sparse_attn_q2", "sik_decode_step_q2", "sik_decode_step_ex")
+           "sik_quantize_kv", "sik_prefill_compress", "sik_sparse_attn_q2", "sik_decode_step_q2", "sik_decode_step_ex")
 
 
 class SikError(RuntimeError):
@@ -85,6 +85,8 @@ def lib():
         L.sik_kvq_bytes.argtypes = [lp]
         L.sik_quantize_kv.restype = ctypes.c_int
         L.sik_quantize_kv.argtypes = [lp, vp, vp, vp, i32, i32, ctypes.c_int, vp, vp, vp, vp]
+        L.sik_prefill_compress.restype = ctypes.c_int
+        L.sik_prefill_compress.argtypes = [lp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.sik_sparse_attn_q2.restype = ctypes.c_int
         L.sik_sparse_attn_q2.argtypes = [lp, vp, vp, vp, vp, i32, f32, vp, vp, sz, vp]
         L.sik_decode_step_ex.restype = ctypes.c_int
@@ -180,6 +182,13 @@ def alloc_kvq(layout: Layout, device="cuda") -> torch.Tensor:
 def sik_quantize_kv(layout, K, V, seq_len, t0, n, mode, mu, alpha, kvq):
     _check(lib().sik_quantize_kv(ctypes.byref(layout), _ptr(K), _ptr(V), _ptr(seq_len), int(t0), int(n), int(mode),
                                  _ptr(mu), _ptr(alpha), _ptr(kvq), _stream()))
+
+
+def sik_prefill_compress(layout, K, V, seq_len, mu, codebook, counts, codes, alpha, kvq, workspace):
+    """mu, codes, codebook, counts, alpha and records of the fitted tokens in two passes over K and one over V."""
+    _check(lib().sik_prefill_compress(ctypes.byref(layout), _ptr(K), _ptr(V), _ptr(seq_len), _ptr(mu), _ptr(codebook),
+                                      _ptr(counts), _ptr(codes), _ptr(alpha), _ptr(kvq), _ptr(workspace),
+                                      workspace.numel() if workspace is not None else 0, _stream()))
 
 
 def sik_sparse_attn_q2(layout, q, kvq, alpha, idx, k, softmax_scale, out, workspace):

@@ -82,6 +82,7 @@ Workspace carve(const Dims& d, int k, void* base) {
     w.sstride = (d.Lmax + 3) & ~3;
     w.scores = reinterpret_cast<float*>(take(rows * static_cast<size_t>(w.sstride) * 4));
     w.colsum = reinterpret_cast<double*>(take(units * kFitMaxWg * kD * 8));
+    w.colmm = reinterpret_cast<float*>(take(units * kFitMaxWg * 2 * kD * 4));
     w.cpart = reinterpret_cast<float*>(take(units * kFitMaxWg * kG * 80 * 4));
     w.total_bytes = off;
     return w;
@@ -162,7 +163,21 @@ int sik_quantize_keys(const sik_layout* layout, const void* K, const int32_t* se
     Workspace w;
     rc = check_ws(d, 0, workspace, workspace_bytes, &w);
     if (rc) return rc;
-    return launched(launch_fit(d, w, K, seq_len, mu, codebook, counts, codes, s));
+    return launched(launch_fit(d, w, K, nullptr, seq_len, mu, codebook, counts, codes, nullptr, nullptr, s));
+}
+
+int sik_prefill_compress(const sik_layout* layout, const void* K, const void* V, const int32_t* seq_len, float* mu,
+                         float* codebook, int32_t* counts, uint8_t* codes, float* alpha, void* kvq, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (!K || !V || !seq_len || !mu || !codebook || !counts || !codes || !alpha || !kvq) return SIK_ERR_NULL;
+    Workspace w;
+    rc = check_ws(d, 0, workspace, workspace_bytes, &w);
+    if (rc) return rc;
+    return launched(launch_fit(d, w, K, V, seq_len, mu, codebook, counts, codes, alpha, kvq,
+                               static_cast<hipStream_t>(stream)));
 }
 
 int sik_score(const sik_layout* layout, const void* q, const float* codebook, const uint8_t* codes,

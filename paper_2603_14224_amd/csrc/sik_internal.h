@@ -40,6 +40,7 @@ struct Workspace {
     int sstride;            // Lmax rounded up to a multiple of 4 (16-byte aligned score rows)
     // quantiser fit
     double* colsum;         // [units][kFitMaxWg][D]
+    float* colmm;           // [units][kFitMaxWg][2][D]  per-workgroup channel minima and maxima of K
     float* cpart;           // [units][kFitMaxWg][G][16][5]  per-workgroup cluster sums and counts
     size_t total_bytes;
 };
@@ -143,8 +144,9 @@ hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const 
                         int k, float scale, int32_t* idx_out, void* out, hipStream_t s);
 bool fused_plan(const Dims& d, int* nchunk, int* chunk);
 size_t fused_cand_words(const Dims& d);
-hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const int32_t* seq_len, float* mu,
-                      float* codebook, int32_t* counts, uint8_t* codes, hipStream_t s);
+hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const void* V, const int32_t* seq_len,
+                      float* mu, float* codebook, int32_t* counts, uint8_t* codes, float* alpha, void* kvq,
+                      hipStream_t s);
 hipError_t launch_encode(const Dims& d, const void* K, int t0, int n, const float* mu, uint8_t* codes,
                          hipStream_t s);
 

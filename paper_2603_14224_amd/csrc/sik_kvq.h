@@ -54,31 +54,54 @@ __device__ __forceinline__ float fp16_value(uint32_t h) {
     return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
 }
 
-// Parameters and 2-bit codes of this lane's 8 values of one 32-value group; the 4 lanes of the quad hold the
-// group and must all be active.  Returns the 16 code bits; qs_h, zp_h = the stored fp16 bits.
-__device__ __forceinline__ uint32_t quantize_octet(const float (&x)[8], uint32_t& qs_h, uint32_t& zp_h) {
+// Minimum / maximum over the 8 lanes 8j .. 8j+7 (every lane gets it): the quad, then the other quad of the
+// half row (row_half_mirror: lane i of each 8 reads lane 7 - i, which holds its own quad's result).
+__device__ __forceinline__ float oct_min(float v) {
+    v = quad_min(v);
+    return fminf(v, __uint_as_float(static_cast<uint32_t>(
+                        __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false))));
+}
+__device__ __forceinline__ float oct_max(float v) {
+    v = quad_max(v);
+    return fmaxf(v, __uint_as_float(static_cast<uint32_t>(
+                        __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false))));
+}
+
+// Parameters and 2-bit codes of this lane's N values of one 32-value group that 32 / N neighbouring lanes hold
+// together (all of them active); group_min / group_max reduce over those lanes.  Returns the 2 N code bits
+// (value e in bits 2e+1:2e); qs_h, zp_h = the stored fp16 bits.  One function for every lane mapping, so that
+// every kernel that builds records takes the same decisions.
+template <int N, class GroupMin, class GroupMax>
+__device__ __forceinline__ uint32_t quantize_lane(const float (&x)[N], GroupMin group_min, GroupMax group_max,
+                                                  uint32_t& qs_h, uint32_t& zp_h) {
     float lo = x[0], hi = x[0];
 #pragma unroll
-    for (int e = 1; e < 8; ++e) {
+    for (int e = 1; e < N; ++e) {
         lo = fminf(lo, x[e]);
         hi = fmaxf(hi, x[e]);
     }
-    lo = quad_min(lo) + 0.0f;  // a zero minimum is stored as +0 whatever the signs of the zeros
-    hi = quad_max(hi);
+    lo = group_min(lo) + 0.0f;  // a zero minimum is stored as +0 whatever the signs of the zeros
+    hi = group_max(hi);
     qs_h = fp16_bits((hi - lo) / 3.0f);
     zp_h = fp16_bits(lo);
     const float qs = fp16_value(qs_h), zp = fp16_value(zp_h);
-    uint32_t bits = 0u;
+    // The code word is assembled in floating point: sum_e c_e 4^e with c_e in {0, 1, 2, 3} stays below 2^16 and is
+    // exact in binary32, so one fused multiply-add per value replaces a conversion, a shift and an OR.
+    float word = 0.0f;
     if (qs > 0.0f) {
         const float rqs = 1.0f / qs;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float r = rintf((x[e] - zp) * rqs);
-            const int c = static_cast<int>(fminf(fmaxf(r, 0.0f), 3.0f));
-            bits |= static_cast<uint32_t>(c) << (2 * e);
+        for (int e = 0; e < N; ++e) {
+            const float c = __builtin_amdgcn_fmed3f(rintf((x[e] - zp) * rqs), 0.0f, 3.0f);  // clamp to [0, 3]
+            word = fmaf(c, static_cast<float>(1u << (2 * e)), word);
         }
     }
-    return bits;
+    return static_cast<uint32_t>(word);
+}
+
+// 8 values per lane, the group in the 4 lanes of a quad (the 16-lanes-per-row mapping).
+__device__ __forceinline__ uint32_t quantize_octet(const float (&x)[8], uint32_t& qs_h, uint32_t& zp_h) {
+    return quantize_lane<8>(x, [](float v) { return quad_min(v); }, [](float v) { return quad_max(v); }, qs_h, zp_h);
 }
 
 // 1 / alpha, and 0 for a channel that never leaves its mean.

@@ -49,7 +49,7 @@ def fit_both_sides(oracle, cfg, cap, K, lay, ws):
         Kp = np.abs(W.from_bits(K[b, :, :L], cfg.dtype).astype(np.float64) - mu[b, :, None, :]).max(axis=1)
         assert np.all(np.abs(g_cb[b] - cb[b]) <= 1e-5 * Kp.reshape(Hkv, 32, 1, 4)), ("codebook", b)
     dcb.copy_(torch.from_numpy(cb))
-    return dict(sl=sl, mu=mu, codes=codes, cb=cb), dK, dsl, dmu, dcb, dcodes
+    return dict(sl=sl, mu=mu, codes=codes, cb=cb, gpu_cb=g_cb, gpu_cnt=dcnt), dK, dsl, dmu, dcb, dcodes
 
 
 def check_sets(g_idx, r_idx, s_ref, sl, k):
@@ -139,8 +139,14 @@ def run_full_q2(oracle, name, steps, extra_cap=32):
     dal = torch.empty(B, Hkv, D, device="cuda")
     kvq = sik.alloc_kvq(lay)
     sik.sik_quantize_kv(lay, dK, dV, dsl, 0, 0, sik.SIK_Q_FIT, dmu, dal, kvq)
+    # the same in one call (two passes over K, one over V): identical bits in every output
+    mu2, cb2, cnt2 = torch.empty_like(dmu), torch.empty_like(dcb), torch.empty_like(o["gpu_cnt"])
+    codes2, al2, kvq2 = torch.zeros_like(dcodes), torch.empty_like(dal), sik.alloc_kvq(lay)
+    sik.sik_prefill_compress(lay, dK, dV, dsl, mu2, cb2, cnt2, codes2, al2, kvq2, ws)
     torch.cuda.synchronize()
-    del dK, dV
+    assert torch.equal(mu2, dmu) and torch.equal(codes2, dcodes) and torch.equal(cnt2, o["gpu_cnt"])
+    assert np.array_equal(cb2.cpu().numpy(), o["gpu_cb"]) and torch.equal(al2, dal) and torch.equal(kvq2, kvq)
+    del dK, dV, mu2, cb2, cnt2, codes2, al2, kvq2
     al, qkv = oracle.fit_q2(K, V, cfg.dtype, sl, mu)
     assert np.array_equal(dal.cpu().numpy(), al), "alpha differs"
     got = kvq.cpu().numpy()

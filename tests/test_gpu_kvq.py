@@ -307,3 +307,49 @@ def test_decode_q2_rejects_contexts_without_a_fused_plan(oracle):
     with pytest.raises(sik.SikError) as e:
         sik.sik_decode_step_q2(lay, t, None, None, t, t, t, t, t, t, 16, 0.0, t, None, ws)
     assert e.value.status == -2
+
+
+# --------------------------------------------------------------------------- prefill-compress in one call
+@pytest.mark.parametrize("dtype,seq_len", [("bf16", [5000, 1337, 1, 0]), ("fp16", [4099, 4100, 777, 64])])
+def test_prefill_compress_equals_the_separate_calls_and_the_oracle(oracle, dtype, seq_len):
+    # one call, two passes over K and one over V: every output has the bits of sik_quantize_keys FIT followed by
+    # sik_quantize_kv FIT, and agrees with the oracle as those do
+    cfg = cfg_small(batch=4, n_kv_heads=3, n_q_heads=6, context=max(seq_len), top_k=64, dtype=dtype, seed=47)
+    st = Q2State(cfg, oracle, capacity=max(seq_len) + 20, seq_len=seq_len, offset_std=1.2)
+    B, H, cap = 4, 3, max(seq_len) + 20
+
+    def fresh():
+        return (torch.full((B, H, 128), -3.0, device="cuda"), torch.full((B, H, 32, 16, 4), -3.0, device="cuda"),
+                torch.full((B, H, 32, 16), -3, dtype=torch.int32, device="cuda"),
+                torch.zeros(B, H, cap, 16, dtype=torch.uint8, device="cuda"), torch.full((B, H, 128), -3.0, device="cuda"),
+                sik.alloc_kvq(st.layout))
+
+    mu1, cb1, cnt1, codes1, al1, rec1 = fresh()
+    sik.sik_quantize_keys(st.layout, st.dK, st.dsl, 0, 0, sik.SIK_Q_FIT, mu1, cb1, cnt1, codes1, st.ws)
+    sik.sik_quantize_kv(st.layout, st.dK, st.dV, st.dsl, 0, 0, sik.SIK_Q_FIT, mu1, al1, rec1)
+    mu2, cb2, cnt2, codes2, al2, rec2 = fresh()
+    sik.sik_prefill_compress(st.layout, st.dK, st.dV, st.dsl, mu2, cb2, cnt2, codes2, al2, rec2, st.ws)
+    sync()
+    for name, a, b in (("mu", mu1, mu2), ("codebook", cb1, cb2), ("counts", cnt1, cnt2), ("codes", codes1, codes2),
+                       ("alpha", al1, al2), ("records", rec1, rec2)):
+        assert torch.equal(a, b), name
+    assert np.array_equal(mu2.cpu().numpy(), st.mu) and np.array_equal(al2.cpu().numpy(), st.alpha)
+    assert np.array_equal(cnt2.cpu().numpy(), oracle.fit(st.K, dtype, st.sl)[3])
+    got = rec2.cpu().numpy()
+    check_records(st, got, st.K, st.V, st.qkv, st.codes, [(b, 0, int(L)) for b, L in enumerate(st.sl)],
+                  f"prefill-compress {dtype}")
+    for b, L in enumerate(st.sl):
+        assert np.array_equal(codes2[b, :, :L].cpu().numpy(), st.codes[b, :, :L])
+        assert not got[b, :, L:].any() and not codes2[b, :, L:].any()
+
+
+def test_prefill_compress_argument_errors():
+    lay = sik.make_layout(1, 2, 4, 128, 512, torch.bfloat16)
+    ws = sik.alloc_workspace(lay, 0)
+    t = torch.zeros(16, device="cuda")
+    with pytest.raises(sik.SikError) as e:
+        sik.sik_prefill_compress(lay, t, None, t, t, t, t, t, t, t, ws)
+    assert e.value.status == -1
+    with pytest.raises(sik.SikError) as e:
+        sik.sik_prefill_compress(lay, t, t, t, t, t, t, t, t, t, torch.zeros(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -6
