@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0
 # each; counter units x the factor a 256 MiB plain copy calibrates there).  Workloads or variants without such a
 # run report null.
 MEASURED_TRAFFIC = {}
-# execution times returned by sik_decode_step_profiled, in launch order; the benchmark workloads run two launches
-# (scoring, then fused selection + attention)
+# execution times returned by sik_decode_step_profiled, in launch order: small launches run scoring, then fused
+# selection + attention; large ones run as one launch, reported in the last slot and named step_kernel here
 KERNELS = ("prep_kernel", "score_kernel", "select_kernel", "select_attend_kernel")
 
 
@@ -56,6 +56,9 @@ def parse():
                          "--kv q2 kept as 16-bit side rows); the budget top_k then counts them")
     ap.add_argument("--shared", action="store_true",
                     help="group-shared selection: one index set per KV head from the summed scores of its query heads")
+    ap.add_argument("--launches", type=int, default=0, choices=[0, 1, 2],
+                    help="0: the library's choice; 1: the one-launch step whenever its plan allows; 2: scoring and "
+                         "selection + attention as two launches (comparison runs; the headline uses 0)")
     ap.add_argument("--fit", action="store_true",
                     help="measure the prefill-side quantiser instead of the decode step (one layer of the workload)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -171,12 +174,12 @@ def bench_decode(args, name, cpu):
         j = i % n_q
         a = (i // n_layers) % n_new
         kn, vn = (kns[a], vns[a]) if cfg.append else (None, None)
-        if args.forced or args.shared:
+        if args.forced or args.shared or args.launches:
             return sik.sik_decode_step_ex(lay, q=qs[j], k_new=kn, v_new=vn, K=st["K"], V=st["V"], kvq=st.get("kvq"),
                                           alpha=st.get("alpha"), seq_len=st["sl"], mu=st["mu"], codebook=st["cb"],
                                           codes=st["codes"], k=k, out=out, idx_out=idx_out, workspace=ws,
                                           forced_idx=st.get("fidx"), forced_K=st.get("fK"), forced_V=st.get("fV"),
-                                          group_shared=args.shared, profiled=profiled)
+                                          group_shared=args.shared, profiled=profiled, launches=args.launches)
         if q2:
             return sik.sik_decode_step_q2(lay, qs[j], kn, vn, st["kvq"], st["sl"], st["mu"], st["alpha"], st["cb"],
                                           st["codes"], k, 0.0, out, idx_out, ws, profiled=profiled)
@@ -255,6 +258,10 @@ def bench_decode(args, name, cpu):
     raw /= n_prof
     kus = raw[:4]
     reset_lengths()
+    # a step that ran as one launch reports its only kernel in the last slot
+    names = list(KERNELS)
+    if kus[1] == 0 and kus[3] > 0:
+        names[3] = "step_kernel"
 
     ab = W.algorithmic_bytes(cfg)
     if q2:  # a selected (query head, token) costs one 128-byte record instead of 2 x 256 bytes of rows
@@ -265,9 +272,9 @@ def bench_decode(args, name, cpu):
         ab["total"] = ab["codes"] + ab["gathered"]
     alg_by_kernel = {"prep_kernel": (B * Hkv * (2 * D * 2 + D // 8)) if cfg.append else 0,
                      "score_kernel": ab["codes"], "select_kernel": 0,
-                     "select_attend_kernel": ab["gathered"] + (ab["codes"] if kus[1] == 0 else 0)}
+                     "select_attend_kernel": ab["gathered"], "step_kernel": ab["codes"] + ab["gathered"]}
     dom = max((1, 3), key=lambda i: kus[i])  # the kernels that move the algorithmic bytes
-    dom_name = KERNELS[dom]
+    dom_name = names[dom]
     dom_bytes = alg_by_kernel[dom_name]
     achieved = dom_bytes / (kus[dom] * 1e-6) / 1e9
     variant = q2 or args.forced or args.shared
@@ -292,7 +299,8 @@ def bench_decode(args, name, cpu):
         "config": {"workload": cfg.name, "batch": B, "n_kv_heads": Hkv, "n_q_heads": Hq, "head_dim": D,
                    "context": L, "top_k": k, "kv_dtype": cfg.dtype, "kv_format": args.kv,
                    "forced_tokens": args.forced, "group_shared": args.shared, "append": cfg.append,
-                   "layers_rotated": n_layers, "launch": launch},
+                   "layers_rotated": n_layers, "launch": launch,
+                   "kernels_per_step": int((kus > 0).sum())},
         "effective_hbm_GBps": round(ab["total"] / sec_step / 1e9, 1),
         "effective_hbm_frac_of_8TBps": round(ab["total"] / sec_step / 1e9 / HBM_PEAK_GBPS, 4),
         "algorithmic_bytes_per_step": ab["total"],
@@ -300,7 +308,7 @@ def bench_decode(args, name, cpu):
         "us_per_step_hipgraph": None if sec_graph is None else round(sec_graph * 1e6, 3),
         "us_per_block_percentiles": pct,
         "gathered_rows": {"nominal": rows_nominal, "unique_per_kv_head": rows_unique},
-        "kernel_us": dict({KERNELS[i]: round(float(kus[i]), 3) for i in range(4) if kus[i] > 0},
+        "kernel_us": dict({names[i]: round(float(kus[i]), 3) for i in range(4) if kus[i] > 0},
                           sum=round(float(kus.sum()), 3), steps_profiled=n_prof, how="begin/end timestamps of each dispatch (HIP events handed to "
                                                       "the launch), mean over the steps of one block"),
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,

@@ -90,7 +90,8 @@ int sik_version(void);
  * info (host pointer, SIK_PLAN_INFO_LEN int32): [0] token chunks per head of the scoring launch, [1] tokens per such
  * chunk, [2] blocks of up to 4 query heads per KV head, [3] chunks per row of the stand-alone histogram pass of
  * sik_topk, [4] tokens per such chunk, [5] chunks per query head of the fused selection + attention launch (0: max_len
- * is beyond that path), [6] tokens per such chunk, [7] reserved (0).  Every chunk holds at most 64512 tokens and
+ * is beyond that path), [6] tokens per such chunk, [7] tokens per thread of the one-launch decode step on the
+ * current device (its chunks hold 1024 times that; 0: the plain step of this layout takes two launches).  Every chunk holds at most 64512 tokens and
  * there are at most 64 per head; a layout that cannot be cut that way is SIK_ERR_SHAPE here and in every other call. */
 #define SIK_PLAN_INFO_LEN 8
 int sik_plan_info(const sik_layout *layout, int32_t *info);
@@ -98,8 +99,23 @@ int sik_plan_info(const sik_layout *layout, int32_t *info);
 /* Size in bytes of the scratch buffer the calls below need for this layout and k
  * (k may be 0 for sik_quantize_keys / sik_score only).  The same buffer may be
  * reused by every call on one stream; calls sharing it must not overlap in time.
- * Contents need not be initialised and are not preserved.  Returns 0 on a bad layout. */
+ * Contents are not preserved.  Returns 0 on a bad layout.
+ * The decode-step entry points additionally need the buffer's first words (a status word and the counters
+ * through which the workgroups of a one-launch step meet) to be ZERO the first time they see the buffer:
+ * call sik_workspace_init once after allocating it (or zero-fill it).  Every step leaves them at zero again. */
 size_t sik_workspace_bytes(const sik_layout *layout, int32_t k);
+
+/* Enqueues the zero-fill of the status word and step counters at the start of a workspace (a small fill kernel on
+ * `stream`; may be captured into a graph).  Needed once per allocation, before the first decode step, and again
+ * after a step that gave up (see sik_workspace_status). */
+int sik_workspace_init(const sik_layout *layout, int32_t k, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Waits for `stream` and copies the workspace's status word to *status (host pointer).  0: every decode step on this
+ * workspace since its initialisation completed.  Non-zero: a workgroup of a one-launch step waited for its peers
+ * beyond the spin limit and left (bit 0: histogram exchange, bit 1: publishing the appended length); that step's
+ * outputs are invalid, no kernel hangs, and the workspace must be initialised again.  This can only happen when the
+ * step's workgroups were not all resident (another process occupying the compute units for seconds). */
+int sik_workspace_status(const void *workspace, void *stream, uint32_t *status);
 
 /* One-pass sign-based quantiser of the key cache (sections "One-Pass Sign-Based
  * Clustering" and "Entropy-Aware Normalization").
@@ -301,6 +317,9 @@ typedef struct {
     size_t workspace_bytes;
     void *stream;
     float *kernel_us;
+    int32_t launches;     /* 0: the library chooses; 1: the one-launch step whenever its plan allows (sik_plan_info);
+                             2: always separate scoring and selection + attention launches                      */
+    int32_t spin_limit;   /* polls a bounded wait of the one-launch step may take; 0 = default (about a second)  */
 } sik_decode_args;
 
 int sik_decode_step_ex(const sik_layout *layout, const sik_decode_args *args);

@@ -17,7 +17,8 @@ SIK_F16, SIK_BF16, SIK_F32 = 0, 1, 2
 SIK_Q_FIT, SIK_Q_ENCODE = 1, 2
 _TORCH2SIK = {torch.float16: SIK_F16, torch.bfloat16: SIK_BF16, torch.float32: SIK_F32}
 
-EXPORTS = ("sik_strerror", "sik_version", "sik_plan_info", "sik_workspace_bytes", "sik_quantize_keys", "sik_score",
+EXPORTS = ("sik_strerror", "sik_version", "sik_plan_info", "sik_workspace_bytes", "sik_workspace_init",
+           "sik_workspace_status", "sik_quantize_keys", "sik_score",
            "sik_topk", "sik_sparse_attn", "sik_decode_step", "sik_decode_step_static", "sik_decode_step_profiled", "sik_kvq_bytes",
            "sik_quantize_kv", "sik_prefill_compress", "sik_sparse_attn_q2", "sik_decode_step_q2", "sik_decode_step_ex")
 
@@ -38,7 +39,8 @@ class DecodeArgs(ctypes.Structure):
                 ("forced_idx", ctypes.c_void_p), ("n_forced", ctypes.c_int32), ("forced_K", ctypes.c_void_p),
                 ("forced_V", ctypes.c_void_p), ("out", ctypes.c_void_p), ("idx_out", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t), ("stream", ctypes.c_void_p),
-                ("kernel_us", ctypes.POINTER(ctypes.c_float))]
+                ("kernel_us", ctypes.POINTER(ctypes.c_float)), ("launches", ctypes.c_int32),
+                ("spin_limit", ctypes.c_int32)]
 
 
 class Layout(ctypes.Structure):
@@ -66,6 +68,10 @@ def lib():
         L.sik_plan_info.restype = ctypes.c_int
         L.sik_plan_info.argtypes = [lp, ctypes.POINTER(i32)]
         L.sik_workspace_bytes.restype = sz
+        L.sik_workspace_init.restype = ctypes.c_int
+        L.sik_workspace_init.argtypes = [lp, i32, vp, sz, vp]
+        L.sik_workspace_status.restype = ctypes.c_int
+        L.sik_workspace_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_uint32)]
         L.sik_workspace_bytes.argtypes = [lp, i32]
         L.sik_quantize_keys.restype = ctypes.c_int
         L.sik_quantize_keys.argtypes = [lp, vp, vp, i32, i32, ctypes.c_int, vp, vp, vp, vp, vp, sz, vp]
@@ -139,10 +145,24 @@ def sik_workspace_bytes(layout: Layout, k: int) -> int:
 
 
 def alloc_workspace(layout: Layout, k: int, device="cuda") -> torch.Tensor:
+    """Device buffer of sik_workspace_bytes, initialised with sik_workspace_init."""
     n = sik_workspace_bytes(layout, k)
     if n == 0:
         raise SikError(-2, "sik_workspace_bytes rejected the layout / k")
-    return torch.empty(n, dtype=torch.uint8, device=device)
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    sik_workspace_init(layout, k, ws)
+    return ws
+
+
+def sik_workspace_init(layout: Layout, k: int, workspace):
+    _check(lib().sik_workspace_init(ctypes.byref(layout), int(k), _ptr(workspace), workspace.numel(), _stream()))
+
+
+def sik_workspace_status(workspace) -> int:
+    """Status word of the workspace after waiting for the current stream (0 = every step completed)."""
+    st = ctypes.c_uint32(0)
+    _check(lib().sik_workspace_status(_ptr(workspace), _stream(), ctypes.byref(st)))
+    return int(st.value)
 
 
 def sik_quantize_keys(layout, K, seq_len, t0, n, mode, mu, codebook, counts, codes, workspace):
@@ -210,7 +230,8 @@ def sik_decode_step_q2(layout, q, k_new, v_new, kvq, seq_len, mu, alpha, codeboo
 
 def sik_decode_step_ex(layout, *, q, seq_len, codebook, codes, k, out, workspace, k_new=None, v_new=None, K=None,
                        V=None, kvq=None, alpha=None, mu=None, softmax_scale=0.0, forced_idx=None, forced_K=None,
-                       forced_V=None, idx_out=None, k_per_mille=0, group_shared=False, profiled=False):
+                       forced_V=None, idx_out=None, k_per_mille=0, group_shared=False, profiled=False,
+                       launches=0, spin_limit=0):
     """General decode step (argument block of include/sik.h): either cache format, optional forced set."""
     us = (ctypes.c_float * 5)() if profiled else None
 
@@ -225,7 +246,8 @@ def sik_decode_step_ex(layout, *, q, seq_len, codebook, codes, k, out, workspace
                    n_forced=0 if forced_idx is None else int(forced_idx.shape[-1]), forced_K=vp(forced_K),
                    forced_V=vp(forced_V), out=vp(out), idx_out=vp(idx_out), workspace=vp(workspace),
                    workspace_bytes=workspace.numel() if workspace is not None else 0,
-                   stream=None if st is None else st.value, kernel_us=us)
+                   stream=None if st is None else st.value, kernel_us=us, launches=int(launches),
+                   spin_limit=int(spin_limit))
     _check(lib().sik_decode_step_ex(ctypes.byref(layout), ctypes.byref(a)))
     return [float(x) for x in us] if profiled else None
 

@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsik.so")
-SOURCES = ["sik_api.hip", "sik_quantize.hip", "sik_score.hip", "sik_topk.hip", "sik_attn.hip", "sik_fused.hip", "sik_kvq.hip"]
+SOURCES = ["sik_api.hip", "sik_quantize.hip", "sik_score.hip", "sik_topk.hip", "sik_attn.hip", "sik_fused.hip", "sik_kvq.hip", "sik_step.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",
          # the first kernel arguments arrive in scalar registers with the wavefront instead of through a load

@@ -64,13 +64,16 @@ Workspace carve(const Dims& d, int k, void* base) {
         off += align256(bytes);
         return r;
     };
+    w.sync = reinterpret_cast<uint32_t*>(take(step_sync_words(d) * 4));  // first: sik_workspace_init finds it there
+    const size_t sync_bytes = off;
     w.counters = reinterpret_cast<uint32_t*>(take(rows * 8 * 4));
     w.zero_begin = w.counters;
-    w.zero_words = off / 4;
+    w.zero_words = (off - sync_bytes) / 4;
     int nhb, nc_score, nc_hist, ch;
     score_plan(d, &nhb, &nc_score, &ch);
     hist_plan(d, &nc_hist, &ch);
-    const size_t nc = static_cast<size_t>(nc_score > nc_hist ? nc_score : nc_hist);
+    size_t nc = static_cast<size_t>(nc_score > nc_hist ? nc_score : nc_hist);
+    if (static_cast<size_t>(step_max_chunks(d)) > nc) nc = static_cast<size_t>(step_max_chunks(d));
     w.parthist = reinterpret_cast<uint32_t*>(take(rows * nc * (kBins / 2) * 4));
     w.binp = reinterpret_cast<float*>(take(rows * 2 * 4));
     w.lens = reinterpret_cast<int32_t*>(take(static_cast<size_t>(d.B) * 4));
@@ -136,7 +139,31 @@ int sik_plan_info(const sik_layout* layout, int32_t* info) {
     info[3] = nchunk, info[4] = chunk;
     const bool fused = fused_plan(d, &nchunk, &chunk);
     info[5] = fused ? nchunk : 0, info[6] = chunk;
-    info[7] = 0;
+    // one-launch decode step: tokens per thread (chunk = 1024 x that) on the current device, 0 = not taken
+    size_t dyn;
+    int listcap, snc;
+    const int tt = step_plan(d, 1, false, device_compute_units(), &snc, &dyn, &listcap);
+    info[7] = tt / 100 + tt % 100;
+    return SIK_OK;
+}
+
+int sik_workspace_init(const sik_layout* layout, int32_t k, void* workspace, size_t workspace_bytes, void* stream) {
+    Dims d;
+    int rc = check_layout(layout, &d);
+    if (rc) return rc;
+    if (k < 0 || k > d.Lmax) return SIK_ERR_K_RANGE;
+    Workspace w;
+    rc = check_ws(d, k, workspace, workspace_bytes, &w);
+    if (rc) return rc;
+    return launched(launch_sync_init(d, w, static_cast<hipStream_t>(stream)));
+}
+
+int sik_workspace_status(const void* workspace, void* stream, uint32_t* status) {
+    if (!workspace || !status) return SIK_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(status, workspace, sizeof(uint32_t), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return SIK_ERR_LAUNCH;
     return SIK_OK;
 }
 
@@ -329,7 +356,24 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     const bool shared_unfused =
         opt.group_shared && (!fused || (plain && static_cast<int64_t>(d.units()) * d.Lmax > (2 << 20)));
     hipError_t e = hipSuccess;
-    if (shared_unfused || !fused) {
+    // One launch for the whole step whenever the plain step's grid fits the compute units (sik_step.hip): scores
+    // stay in registers, chunks of a head exchange only histograms, partials and threshold-bin candidates.
+    size_t step_dyn = 0;
+    int step_nchunk = 0, step_listcap = 0;
+    // (by default only for large launches: with one sequence the histogram exchange between the many chunks of a
+    // head and the heavier barriers of 1024-thread workgroups cost more than the launch boundary they save)
+    const bool large = static_cast<int64_t>(d.units()) * ((d.R + 3) / 4) * d.Lmax > (2 << 20);
+    const int step_T = (!kvq && plain && !opt.group_shared && opt.launches != 2 && (large || opt.launches == 1))
+                           ? step_plan(d, k, k_new != nullptr, device_compute_units(), &step_nchunk, &step_dyn,
+                                       &step_listcap)
+                           : 0;
+    if (step_T > 0) {
+        const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+                        static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, nullptr, nullptr};
+        timed(3);
+        e = done(3, launch_step(d, w, step_T, step_nchunk, step_dyn, step_listcap, q, k_new ? ap : Append{}, codebook,
+                                codes, seq_len, K, V, k, softmax_scale, opt.spin_limit, idx_out, out, s));
+    } else if (shared_unfused || !fused) {
         // prep (append + counters; skipped when nothing is appended: the scoring launch then clears the per-head
         // counters itself), scoring (on the summed query when the selection is shared), stand-alone selector (per
         // KV head when shared: idx_out is then [B, Hkv, k]), attention reading that index list.  Contexts beyond
@@ -364,7 +408,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
         if (e == hipSuccess) {
             timed(3);
             e = done(3, launch_fused(d, w, q, K, V, kvq, alpha,
-                                     StepOptions{opt.idx, opt.n, opt.fK, opt.fV, mu, opt.k_per_mille, opt.group_shared},
+                                     StepOptions{opt.idx, opt.n, opt.fK, opt.fV, mu, opt.k_per_mille, opt.group_shared, 0, 0},
                                      seq_len, k_new != nullptr, k, softmax_scale, idx_out, out, s));
         }
     }
@@ -451,7 +495,9 @@ int sik_decode_step_q2(const sik_layout* layout, const void* q, const void* k_ne
 int sik_decode_step_ex(const sik_layout* layout, const sik_decode_args* a) {
     if (!a) return SIK_ERR_NULL;
     const StepOptions opt{a->forced_idx, a->n_forced, static_cast<const uint16_t*>(a->forced_K),
-                        static_cast<const uint16_t*>(a->forced_V), a->mu, a->k_per_mille, a->group_shared != 0};
+                        static_cast<const uint16_t*>(a->forced_V), a->mu, a->k_per_mille, a->group_shared != 0,
+                        a->launches, a->spin_limit};
+    if (a->spin_limit < 0 || a->launches < 0 || a->launches > 2) return SIK_ERR_FLAGS;
     auto run = [&](StepTimers* ev) {
         return decode_step_impl(layout, a->q, a->k_new, a->v_new, a->K, a->V, a->kvq, a->alpha, a->seq_len, a->mu,
                                 a->codebook, a->codes, a->k, a->softmax_scale, a->out, a->idx_out, a->workspace,

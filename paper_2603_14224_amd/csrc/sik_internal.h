@@ -22,6 +22,7 @@ struct Workspace {
     // zeroed by the prep kernel at the start of every call that selects or attends
     uint32_t* zero_begin;   // start of the zero-initialised region
     size_t zero_words;      // its length in 32-bit words
+    uint32_t* sync;         // one-launch decode step: status word and self-clearing counters (sik_workspace_init)
     uint32_t* counters;     // [rows][8]  0 index-output reservation, 1 candidate count (stand-alone selector),
                             //            2 select ticket, 3 attention / fused ticket, 4 ~min key (stand-alone
                             //            top-k) or candidate-pool reservation (fused kernel), 5 max key
@@ -62,18 +63,19 @@ struct SameType {
     using type = T;
 };
 
-// Launches kernel<<<grid, block, 0, s>>>(p...); the arguments convert to the kernel's parameter types here.
+// Launches kernel<<<grid, block, lds, s>>>(p...); the arguments convert to the kernel's parameter types here
+// (lds = bytes of dynamic LDS, the optional last argument).
 template <class... P>
 inline hipError_t launch_kernel(void (*kernel)(P...), int grid, int block, hipStream_t s,
-                                typename SameType<P>::type... p) {
+                                typename SameType<P>::type... p, size_t lds = 0) {
     if (g_launch_events.start) {
         const LaunchEvents ev = g_launch_events;
         g_launch_events = LaunchEvents{};
         void* args[] = {const_cast<void*>(static_cast<const void*>(&p))...};
-        return hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(block), args, 0, s, ev.start,
-                                  ev.stop, 0);
+        return hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(grid), dim3(block), args, lds, s,
+                                  ev.start, ev.stop, 0);
     }
-    kernel<<<grid, block, 0, s>>>(p...);
+    kernel<<<grid, block, lds, s>>>(p...);
     return hipGetLastError();
 }
 
@@ -138,11 +140,23 @@ struct StepOptions {  // what sik_decode_step_ex adds to the plain decode step
     const float* mu;
     int k_per_mille;    // > 0: per-sequence budget min(k, ceil(L * k_per_mille / 1000))
     bool group_shared;  // one index set per KV head from the summed scores of its query heads (unfused path)
+    int launches;       // 0: the library chooses; 1: the one-launch step whenever its plan allows; 2: never
+    int spin_limit;     // polls a bounded wait of the one-launch step may take (0: the default)
 };
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
                         const void* kvq, const float* alpha, const StepOptions& forced, int32_t* seq_len, bool appended,
                         int k, float scale, int32_t* idx_out, void* out, hipStream_t s);
 bool fused_plan(const Dims& d, int* nchunk, int* chunk);
+// one-launch decode step (sik_step.hip)
+size_t step_sync_words(const Dims& d);
+int step_max_chunks(const Dims& d);
+int step_plan(const Dims& d, int k, bool appended, int cus, int* nchunk, size_t* dyn_lds, int* listcap);
+int device_compute_units();
+hipError_t launch_sync_init(const Dims& d, const Workspace& w, hipStream_t s);
+hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn_lds, int listcap, const void* q,
+                       const Append& ap, const float* codebook, const uint8_t* codes, int32_t* seq_len,
+                       const void* K, const void* V, int k, float scale, int spin_limit, int32_t* idx_out, void* out,
+                       hipStream_t s);
 size_t fused_cand_words(const Dims& d);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const void* V, const int32_t* seq_len,
                       float* mu, float* codebook, int32_t* counts, uint8_t* codes, float* alpha, void* kvq,

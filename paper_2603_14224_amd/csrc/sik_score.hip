@@ -24,6 +24,7 @@
 #include "sik_device.h"
 #include "sik_internal.h"
 #include "sik_kvq.h"
+#include "sik_scan.h"
 #include "sik_select.h"
 
 namespace sik {
@@ -31,88 +32,6 @@ namespace sik {
 SIK_TL_DEFINE(sik_dbg_tl_score)
 
 constexpr int kIterTokens = 1024;  // tokens a workgroup scores per loop iteration: BLK threads x 1024 / BLK each
-
-constexpr int kHB = 4;  // query heads per workgroup = components of one float4 table entry
-
-// (byte BY of w) & mask in one instruction (sub-dword operand select), for any BY; the compiler finds this form
-// for the upper byte and the upper half only.
-template <int BY>
-__device__ __forceinline__ uint32_t byte_and(uint32_t w, uint32_t mask) {
-    uint32_t r;
-    if constexpr (BY == 0)
-        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD"
-            : "=v"(r) : "v"(w), "v"(mask));
-    else if constexpr (BY == 1)
-        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD"
-            : "=v"(r) : "v"(w), "v"(mask));
-    else if constexpr (BY == 2)
-        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD"
-            : "=v"(r) : "v"(w), "v"(mask));
-    else
-        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD"
-            : "=v"(r) : "v"(w), "v"(mask));
-    return r;
-}
-
-// Table lookups.  HB = 4: float4 entries (four query heads at once), 256 B per group; HB = 1: scalar entries,
-// 64 B per group (one query head per KV head: multi-head attention, or the summed query of a group-shared
-// selection) - a quarter of the LDS traffic, the 16 entries of a group on 16 different banks.
-// A batch = the 8 lookups of one 32-bit word of a token's code (groups 8 dw .. 8 dw + 7).  A table offset costs
-// one instruction: byte b of the code word, or of the word shifted by one nibble, under the mask that leaves
-// Code x entry size (9 instructions per batch instead of 16).
-template <int HB>
-struct TableEntry {
-    using type = float;
-};
-template <>
-struct TableEntry<4> {
-    using type = float4;
-};
-
-template <int HB>
-__device__ __forceinline__ void lookup_batch(uint32_t word, int dw, const float* lut,
-                                             typename TableEntry<HB>::type (&v)[8]) {
-    using T = typename TableEntry<HB>::type;
-    constexpr int kEnt = 4 * HB;            // bytes per table entry
-    constexpr uint32_t kMask = 15u * kEnt;  // Code * kEnt
-    constexpr int kUp = HB == 4 ? 0 : 2;    // high nibble (Code * 16) -> Code * kEnt: shift right by kUp
-    constexpr int kDown = HB == 4 ? 4 : 2;  // low nibble -> Code * kEnt: shift left by kDown
-    // byte `by` of the word: high nibble = Code of group 8 dw + 2 by, low nibble = Code of the next group
-    const uint32_t whi = kUp ? word >> kUp : word;
-    const uint32_t wlo = word << kDown;
-    uint32_t off[8];
-    off[0] = byte_and<0>(whi, kMask);
-    off[1] = byte_and<0>(wlo, kMask);
-    off[2] = byte_and<1>(whi, kMask);
-    off[3] = byte_and<1>(wlo, kMask);
-    off[4] = byte_and<2>(whi, kMask);
-    off[5] = byte_and<2>(wlo, kMask);
-    off[6] = byte_and<3>(whi, kMask);
-    off[7] = byte_and<3>(wlo, kMask);
-    const char* base = reinterpret_cast<const char*>(lut) + dw * 8 * 16 * kEnt;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) v[n] = *reinterpret_cast<const T*>(base + n * 16 * kEnt + off[n]);
-}
-
-// acc (+)= the batch, groups in ascending order; the first batch of a token starts the sums.
-template <int HB>
-__device__ __forceinline__ void add_batch(bool first, const typename TableEntry<HB>::type (&v)[8], float* acc) {
-#pragma unroll
-    for (int n = 0; n < 8; ++n) {
-        if constexpr (HB == 4) {
-            if (first && n == 0) {
-                acc[0] = v[n].x, acc[1] = v[n].y, acc[2] = v[n].z, acc[3] = v[n].w;
-            } else {
-                acc[0] += v[n].x;
-                acc[1] += v[n].y;
-                acc[2] += v[n].z;
-                acc[3] += v[n].w;
-            }
-        } else {
-            acc[0] = (first && n == 0) ? v[n] : acc[0] + v[n];
-        }
-    }
-}
 
 // FORCED: tokens named in forced_idx [B, Hkv, n_forced] (entries outside [0, L) ignored) always take part in
 // the attention that follows and must not compete in the selection: their score is stored as -infinity and

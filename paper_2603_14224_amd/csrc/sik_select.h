@@ -111,18 +111,22 @@ __device__ __forceinline__ Threshold find_threshold(const HistLoads& h, int kk, 
 
 // ---- level 2 fallback: radix select inside the threshold bin, one workgroup -----------------
 // Picks the `need` largest (score, then smaller index) among {i < L : bin(s_i) == bstar} and
-// writes their indices to out[0 .. need).
+// writes their indices to out[0 .. need).  NT = threads of the workgroup (all of them call); COHERENT: the
+// scores were written by other workgroups of this launch and are read with agent-scope loads.
+// h256: LDS, 256 words; sh: LDS, 4 words.
+template <int NT = kBlock, bool COHERENT = false>
 __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, float lo, float scale, int bstar,
-                                    int need, int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
+                                           int need, int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
     const int tid = threadIdx.x;
+    auto score = [&](int i) { return COHERENT ? ld_agent(&s[i]) : s[i]; };
     uint32_t prefix = 0, mask = 0;
     uint32_t remaining = static_cast<uint32_t>(need);
     for (int pass = 3; pass >= 0; --pass) {
-        h256[tid] = 0u;
+        if (tid < 256) h256[tid] = 0u;
         __syncthreads();
 #pragma unroll 8
-        for (int i = tid; i < L; i += kBlock) {
-            const float v = s[i];
+        for (int i = tid; i < L; i += NT) {
+            const float v = score(i);
             const uint32_t key = float_to_key(v);
             if (score_bin(v, lo, scale) == bstar && (key & mask) == prefix)
                 atomicAdd(&h256[(key >> (8 * pass)) & 255u], 1u);
@@ -159,27 +163,30 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
     __syncthreads();
     // larger members: any order, one barrier-free sweep
 #pragma unroll 8
-    for (int i = tid; i < L; i += kBlock) {
-        const float v = s[i];
+    for (int i = tid; i < L; i += NT) {
+        const float v = score(i);
         if (score_bin(v, lo, scale) == bstar && float_to_key(v) > tau) out[atomicAdd(&sh[2], 1u)] = i;
     }
-    // equal members: the first need_eq of them in index order; tiles of 256 tokens, stop when served
-    for (int base = 0; base < L && need_eq > 0u; base += kBlock) {
+    // equal members: the first need_eq of them in index order; tiles of NT tokens, stop when served
+    constexpr int kWaves = NT / kWave;
+    for (int base = 0; base < L && need_eq > 0u; base += NT) {
         const int i = base + tid;
         bool eq = false;
         if (i < L) {
-            const float v = s[i];
+            const float v = score(i);
             eq = score_bin(v, lo, scale) == bstar && float_to_key(v) == tau;
         }
         const uint64_t bal = __ballot(eq);
         const int lane = tid & 63, wv = tid >> 6;
         if (lane == 0) h256[wv] = static_cast<uint32_t>(__popcll(bal));
         __syncthreads();
-        uint32_t before = sh[3];
-        for (int w = 0; w < wv; ++w) before += h256[w];
+        uint32_t before = sh[3], total = sh[3];
+        for (int w = 0; w < kWaves; ++w) {
+            if (w < wv) before += h256[w];
+            total += h256[w];
+        }
         const uint32_t ord = before + static_cast<uint32_t>(__popcll(bal & ((1ull << lane) - 1ull)));
         if (eq && ord < need_eq) out[n_gt + ord] = i;
-        const uint32_t total = sh[3] + h256[0] + h256[1] + h256[2] + h256[3];
         __syncthreads();
         if (tid == 0) sh[3] = total;
         if (total >= need_eq) break;  // uniform: every thread computed the same total

@@ -112,12 +112,18 @@ def test_forced_empty_set_equals_plain_step(oracle):
     q, _, _ = W.make_step_inputs(cfg, 0)
     a, b_ = torch.empty(1, 8, 128, device="cuda"), torch.empty(1, 8, 128, device="cuda")
     none = torch.full((1, 2, 8), -1, dtype=torch.int32, device="cuda")
-    sik.sik_decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128,
-                        0.0, a, None, st.ws)
+    # (the same kernels on both sides: a forced set always takes the scoring + selection/attention launches)
+    sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
+                           codebook=st.dcb, codes=st.dcodes, k=128, out=a, workspace=st.ws, launches=2)
     sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
                            codebook=st.dcb, codes=st.dcodes, k=128, out=b_, forced_idx=none, workspace=st.ws)
     sync()
     assert torch.equal(a, b_)
+    # the one-launch step selects the same tokens and differs only in the order of its fp32 sums
+    sik.sik_decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128,
+                        0.0, b_, None, st.ws)
+    sync()
+    assert float((a - b_).abs().max()) <= 2e-5 * float(a.abs().max())   # each within 1e-5 of the exact result
 
 
 def run_q2(oracle, cfg, capacity, steps, append, n_forced, side_rows, seq_len=None, seed=5):

@@ -247,8 +247,21 @@ def test_sparse_attention_all_tokens_matches_dense(oracle):
 
 
 # --------------------------------------------------------------------------- fused decode step
+# launches = 0: the path the library picks for the layout (small launches: scoring, then selection + attention);
+# launches = 1: the one-launch step whenever its plan allows, so that the reduced shapes below exercise it too.
+BOTH_PATHS = pytest.mark.parametrize("launches", [0, 1], ids=["auto", "one_launch"])
+
+
+def decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, cb, codes, k, out, idx, ws, launches=0):
+    if launches == 0:
+        sik.sik_decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, cb, codes, k, 0.0, out, idx, ws)
+    else:
+        sik.sik_decode_step_ex(layout, q=q, k_new=k_new, v_new=v_new, K=K, V=V, seq_len=seq_len, mu=mu, codebook=cb,
+                               codes=codes, k=k, out=out, idx_out=idx, workspace=ws, launches=launches)
+
+
 def run_decode_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0, seq_len=None, out_f32=True,
-                         sample_rows=None):
+                         sample_rows=None, launches=0):
     st = GpuState(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=offset_std,
                   out_dtype=torch.float32 if out_f32 else None)
     B, Hq, k = cfg.batch, cfg.n_q_heads, min(cfg.top_k, capacity)
@@ -261,9 +274,10 @@ def run_decode_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0, s
         dq = dev(q, cfg.dtype)
         dkn = dev(kn, cfg.dtype) if append else None
         dvn = dev(vn, cfg.dtype) if append else None
-        sik.sik_decode_step(st.layout, dq, dkn, dvn, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, k, 0.0, out,
-                            idx, st.ws)
+        decode_step(st.layout, dq, dkn, dvn, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, k, out, idx, st.ws,
+                    launches)
         sync()
+        assert sik.sik_workspace_status(st.ws) == 0
         # oracle: same step on the host copies (appends in place)
         if append:
             ref_out, ref_idx = oracle.decode_step(q, kn, vn, K, V, cfg.dtype, sl, st.mu, st.cb, codes, k)
@@ -287,63 +301,73 @@ def run_decode_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0, s
     return total_diff
 
 
-def test_decode_step_c1_full(oracle):
+@BOTH_PATHS
+def test_decode_step_c1_full(oracle, launches):
     cfg = W.CONFIGS["C1"]
-    run_decode_and_check(oracle, cfg, capacity=4096, steps=2, append=False)
+    run_decode_and_check(oracle, cfg, capacity=4096, steps=2, append=False, launches=launches)
 
 
-def test_decode_step_c1_16bit_out(oracle):
-    run_decode_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=1, append=False, out_f32=False)
+@BOTH_PATHS
+def test_decode_step_c1_16bit_out(oracle, launches):
+    run_decode_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=1, append=False, out_f32=False, launches=launches)
 
 
-def test_decode_step_c2_shape_reduced(oracle):
+@BOTH_PATHS
+def test_decode_step_c2_shape_reduced(oracle, launches):
     cfg = cfg_small("C2", context=8192, top_k=256)
-    run_decode_and_check(oracle, cfg, capacity=8192, steps=2, append=False, offset_std=1.0)
+    run_decode_and_check(oracle, cfg, capacity=8192, steps=2, append=False, offset_std=1.0, launches=launches)
 
 
-def test_decode_step_c3_shape_reduced_with_append(oracle):
+@BOTH_PATHS
+def test_decode_step_c3_shape_reduced_with_append(oracle, launches):
     cfg = cfg_small("C3", context=9000, top_k=300)
-    run_decode_and_check(oracle, cfg, capacity=9004, steps=3, append=True, offset_std=1.0)
+    run_decode_and_check(oracle, cfg, capacity=9004, steps=3, append=True, offset_std=1.0, launches=launches)
 
 
-def test_decode_step_c4_shape_reduced_ragged_batch(oracle):
+@BOTH_PATHS
+def test_decode_step_c4_shape_reduced_ragged_batch(oracle, launches):
     cfg = cfg_small("C4", batch=4, context=2048, top_k=512)
-    run_decode_and_check(oracle, cfg, capacity=2050, steps=1, append=True, seq_len=[2048, 1, 511, 700])
+    run_decode_and_check(oracle, cfg, capacity=2050, steps=1, append=True, seq_len=[2048, 1, 511, 700], launches=launches)
 
 
-def test_decode_step_c5_shape_reduced_gqa8(oracle):
+@BOTH_PATHS
+def test_decode_step_c5_shape_reduced_gqa8(oracle, launches):
     cfg = cfg_small("C5", batch=2, n_kv_heads=2, n_q_heads=16, context=6000, top_k=1536)
-    run_decode_and_check(oracle, cfg, capacity=6016, steps=3, append=True)
+    run_decode_and_check(oracle, cfg, capacity=6016, steps=3, append=True, launches=launches)
 
 
-def test_decode_step_k_not_below_context(oracle):
+@BOTH_PATHS
+def test_decode_step_k_not_below_context(oracle, launches):
     # k >= L: everything is selected and the result is dense attention
     cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=700, top_k=1024)
-    run_decode_and_check(oracle, cfg, capacity=1100, steps=1, append=True)
+    run_decode_and_check(oracle, cfg, capacity=1100, steps=1, append=True, launches=launches)
 
 
-def test_decode_step_dense_selection_flushes_the_wave_lists(oracle):
+@BOTH_PATHS
+def test_decode_step_dense_selection_flushes_the_wave_lists(oracle, launches):
     # k = L with 4096-token chunks: every wavefront selects all 1024 tokens of its share, far more than
     # its 512-slot list holds, so the list is gathered and refilled several times
     cfg = cfg_small("C2", context=40000, top_k=40000)
-    run_decode_and_check(oracle, cfg, capacity=40000, steps=1, append=False)
+    run_decode_and_check(oracle, cfg, capacity=40000, steps=1, append=False, launches=launches)
 
 
-def test_decode_step_half_selected(oracle):
+@BOTH_PATHS
+def test_decode_step_half_selected(oracle, launches):
     # k = L / 2: the threshold sits in the middle of the score distribution
     cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=30000, top_k=15000)
-    run_decode_and_check(oracle, cfg, capacity=30008, steps=1, append=True)
+    run_decode_and_check(oracle, cfg, capacity=30008, steps=1, append=True, launches=launches)
 
 
-def test_decode_step_zero_query_all_scores_equal(oracle):
+@BOTH_PATHS
+def test_decode_step_zero_query_all_scores_equal(oracle, launches):
     # q = 0 makes every score equal: the selector must still return k distinct smallest indices
     cfg = cfg_small("C2", n_kv_heads=1, n_q_heads=4, context=3000, top_k=100)
     st = GpuState(cfg, oracle, out_dtype=torch.float32)
     q = np.zeros((1, 4, 128), np.uint16)
     out = torch.empty(1, 4, 128, device="cuda")
     idx = torch.empty(1, 4, 100, dtype=torch.int32, device="cuda")
-    sik.sik_decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes,
-                        100, 0.0, out, idx, st.ws)
+    decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 100, out,
+                idx, st.ws, launches)
     sync()
     g = idx.cpu().numpy()
     for hq in range(4):
@@ -352,8 +376,9 @@ def test_decode_step_zero_query_all_scores_equal(oracle):
     check_attention(out.cpu().numpy().astype(np.float64), ref, True)
 
 
+@BOTH_PATHS
 @pytest.mark.parametrize("ndup", [40, 300])
-def test_decode_step_duplicate_keys_at_threshold(oracle, ndup):
+def test_decode_step_duplicate_keys_at_threshold(oracle, ndup, launches):
     # identical keys in a row have identical scores; with k chosen so that the cut falls inside that plateau,
     # one wavefront's share of the threshold bin (40 keys), or the shares of wavefronts of two workgroups (300
     # keys), exceed the per-wavefront candidate slots: the surplus travels through the head's overflow pool and
@@ -375,9 +400,9 @@ def test_decode_step_duplicate_keys_at_threshold(oracle, ndup):
     out = torch.empty(1, 4, 128, device="cuda")
     idx = torch.empty(1, 4, k, dtype=torch.int32, device="cuda")
     dsl = torch.from_numpy(sl.copy()).cuda()
-    sik.sik_decode_step(lay, dev(q, cfg.dtype), None, None, dev(K, cfg.dtype), dev(V, cfg.dtype), dsl,
-                        torch.from_numpy(mu).cuda(), torch.from_numpy(cb).cuda(), torch.from_numpy(codes).cuda(), k,
-                        0.0, out, idx, ws)
+    decode_step(lay, dev(q, cfg.dtype), None, None, dev(K, cfg.dtype), dev(V, cfg.dtype), dsl,
+                torch.from_numpy(mu).cuda(), torch.from_numpy(cb).cuda(), torch.from_numpy(codes).cuda(), k, out, idx, ws,
+                launches)
     sync()
     g = idx.cpu().numpy()
     ref_idx = oracle.topk(s_ref, sl, k)
@@ -396,21 +421,23 @@ def test_decode_step_very_long_context_takes_the_unfused_path(oracle):
     run_decode_and_check(oracle, cfg, capacity=530004, steps=1, append=True)
 
 
-def test_decode_step_long_context_fused_many_chunks(oracle):
+@BOTH_PATHS
+def test_decode_step_long_context_fused_many_chunks(oracle, launches):
     # 300K tokens: 37 chunks of 8192 in the fused kernel, more than the 32 whose partials the last
     # arriver prefetches; 64 scoring chunks
     cfg = cfg_small("C2", n_kv_heads=1, n_q_heads=4, context=300000, top_k=2048)
-    run_decode_and_check(oracle, cfg, capacity=300000, steps=1, append=False)
+    run_decode_and_check(oracle, cfg, capacity=300000, steps=1, append=False, launches=launches)
 
 
-def test_decode_step_empty_and_single_token_sequences(oracle):
+@BOTH_PATHS
+def test_decode_step_empty_and_single_token_sequences(oracle, launches):
     cfg = cfg_small("C2", batch=3, n_kv_heads=2, n_q_heads=4, context=1500, top_k=8)
     st = GpuState(cfg, oracle, capacity=1504, seq_len=[0, 1, 1500], out_dtype=torch.float32)
     q, _, _ = W.make_step_inputs(cfg, 0)
     out = torch.full((3, 4, 128), 7.0, device="cuda")
     idx = torch.full((3, 4, 8), -5, dtype=torch.int32, device="cuda")
-    sik.sik_decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes,
-                        8, 0.0, out, idx, st.ws)
+    decode_step(st.layout, dev(q, cfg.dtype), None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 8, out, idx,
+                st.ws, launches)
     sync()
     g, o = idx.cpu().numpy(), out.cpu().numpy().astype(np.float64)
     assert np.all(g[0] == -1) and np.all(o[0] == 0)                      # empty sequence: zero rows
@@ -422,7 +449,8 @@ def test_decode_step_empty_and_single_token_sequences(oracle):
     check_attention(o[2:3], ref[2:3], True)
 
 
-def test_decode_step_output_is_bit_reproducible(oracle):
+@BOTH_PATHS
+def test_decode_step_output_is_bit_reproducible(oracle, launches):
     # fixed-order merges and rank-ordered candidates: the same inputs give the same output bits and the
     # same index set on every run, whatever the arrival order of the workgroups
     cfg = cfg_small("C2", context=20000, top_k=700)
@@ -433,8 +461,8 @@ def test_decode_step_output_is_bit_reproducible(oracle):
     for _ in range(4):
         o = torch.empty(1, 32, 128, device="cuda")
         idx = torch.empty(1, 32, 700, dtype=torch.int32, device="cuda")
-        sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 700, 0.0, o,
-                            idx, st.ws)
+        decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 700, o, idx, st.ws,
+                    launches)
         sync()
         outs.append(o.clone())
         sets.append(torch.sort(idx, dim=-1).values.clone())
@@ -442,7 +470,8 @@ def test_decode_step_output_is_bit_reproducible(oracle):
         assert torch.equal(o, outs[0]) and torch.equal(s_, sets[0])
 
 
-def test_decode_step_graph_replay_matches_eager(oracle):
+@BOTH_PATHS
+def test_decode_step_graph_replay_matches_eager(oracle, launches):
     # the step is captured into a HIP graph (kernels only, no memset nodes) and replayed several times with
     # eager work and synchronisations in between; every replay must reproduce the eager result, including the
     # device-side append (the graph resets the length first, as bench.py does)
@@ -455,8 +484,8 @@ def test_decode_step_graph_replay_matches_eager(oracle):
 
     def body():
         st.dsl.fill_(20000)
-        sik.sik_decode_step(st.layout, dq, dkn, dvn, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 600, 0.0, out,
-                            idx, st.ws)
+        decode_step(st.layout, dq, dkn, dvn, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 600, out, idx, st.ws,
+                    launches)
 
     body()
     sync()
@@ -487,20 +516,64 @@ def test_profiled_decode_step_same_result_and_five_intervals(oracle):
     st = GpuState(cfg, oracle, out_dtype=torch.float32)
     q, _, _ = W.make_step_inputs(cfg, 0)
     dq = dev(q, cfg.dtype)
-    a = torch.empty(1, 8, 128, device="cuda")
-    b = torch.empty(1, 8, 128, device="cuda")
+    a, b, c, d = (torch.empty(1, 8, 128, device="cuda") for _ in range(4))
+    kw = dict(q=dq, K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu, codebook=st.dcb, codes=st.dcodes, k=128,
+              workspace=st.ws)
     sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128, 0.0, a, None, st.ws)
     us = sik.sik_decode_step_profiled(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 128,
                                       0.0, b, None, st.ws)
     sync()
-    # scoring and fused selection + attention ran (no prep, no stand-alone selector); the step's span on the GPU
-    # covers both kernels and the gap between them
+    # a launch this small runs as scoring, then fused selection + attention (no prep, no stand-alone selector)
     assert len(us) == 5 and us[0] == 0 and us[2] == 0 and 0.5 < us[1] < 1000 and 0.5 < us[3] < 1000
-    assert us[1] + us[3] <= us[4] * 1.001 < 2000
+    assert us[1] + us[3] <= us[4] * 1.001         # (the gap may hold the one-time loading of the second kernel)
     assert torch.equal(a, b)
+    us2 = sik.sik_decode_step_ex(st.layout, out=c, launches=2, profiled=True, **kw)
+    assert us2[0] == 0 and us2[2] == 0 and us2[1] > 0.5 and us2[3] > 0.5 and torch.equal(a, c)
+    # forced into one launch: one kernel, reported in the last slot; the span is that kernel
+    assert sik.sik_plan_info(st.layout)[7] > 0
+    us1 = sik.sik_decode_step_ex(st.layout, out=d, launches=1, profiled=True, **kw)
+    assert us1[0] == 0 and us1[1] == 0 and us1[2] == 0 and 0.5 < us1[3] < 1000
+    assert abs(us1[4] - us1[3]) <= 0.01 * us1[3] + 0.1
+    assert float((a - d).abs().max()) <= 2e-5 * float(a.abs().max())   # each within 1e-5 of the exact result
+    assert sik.sik_workspace_status(st.ws) == 0
 
 
-def test_decode_step_without_idx_out_matches(oracle):
+def test_one_launch_bounded_wait_gives_up_and_reports(oracle):
+    # The one-launch step waits, inside the kernel, for the histograms of a head's other chunks.  The wait is bounded:
+    # with a spin limit of one poll it gives up (forced from the host, every workgroup still runs to its end), the
+    # status word of the workspace says so, and after sik_workspace_init the same workspace serves normal steps again.
+    cfg = cfg_small("C3", context=20000, top_k=600)
+    st = GpuState(cfg, oracle, capacity=20008, out_dtype=torch.float32)
+    assert sik.sik_plan_info(st.layout)[7] > 0
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    dq, dkn, dvn = dev(q, cfg.dtype), dev(kn, cfg.dtype), dev(vn, cfg.dtype)
+    ref = torch.empty(1, 32, 128, device="cuda")
+    ref_idx = torch.empty(1, 32, 600, dtype=torch.int32, device="cuda")
+    out = torch.empty(1, 32, 128, device="cuda")
+    idx = torch.empty(1, 32, 600, dtype=torch.int32, device="cuda")
+    kw = dict(q=dq, k_new=dkn, v_new=dvn, K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu, codebook=st.dcb,
+              codes=st.dcodes, k=600, workspace=st.ws)
+    sik.sik_decode_step_ex(st.layout, out=ref, idx_out=ref_idx, launches=2, **kw)
+    sync()
+    assert int(st.dsl[0]) == 20001 and sik.sik_workspace_status(st.ws) == 0
+    for limit in (1, 0):
+        st.dsl.fill_(20000)
+        print(f"one-launch step, spin_limit={limit}", flush=True)
+        sik.sik_decode_step_ex(st.layout, out=out, idx_out=idx, launches=1, spin_limit=limit, **kw)
+        sync()
+        status = sik.sik_workspace_status(st.ws)
+        if limit == 1:
+            assert status & 1, status         # a first arriver cannot see 20 chunks after one poll
+            sik.sik_workspace_init(st.layout, 600, st.ws)
+            assert sik.sik_workspace_status(st.ws) == 0
+        else:
+            assert status == 0 and int(st.dsl[0]) == 20001
+            assert torch.equal(torch.sort(idx, dim=-1).values, torch.sort(ref_idx, dim=-1).values)
+            assert float((out - ref).abs().max()) <= 2e-5 * float(ref.abs().max())
+
+
+@BOTH_PATHS
+def test_decode_step_without_idx_out_matches(oracle, launches):
     cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=5000, top_k=200)
     st = GpuState(cfg, oracle, out_dtype=torch.float32)
     q, _, _ = W.make_step_inputs(cfg, 0)
@@ -508,7 +581,7 @@ def test_decode_step_without_idx_out_matches(oracle):
     a = torch.empty(1, 8, 128, device="cuda")
     b = torch.empty(1, 8, 128, device="cuda")
     idx = torch.empty(1, 8, 200, dtype=torch.int32, device="cuda")
-    sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 200, 0.0, a, idx, st.ws)
-    sik.sik_decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 200, 0.0, b, None, st.ws)
+    decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 200, a, idx, st.ws, launches)
+    decode_step(st.layout, dq, None, None, st.dK, st.dV, st.dsl, st.dmu, st.dcb, st.dcodes, 200, b, None, st.ws, launches)
     sync()
     assert torch.allclose(a, b, rtol=1e-5, atol=1e-6)
