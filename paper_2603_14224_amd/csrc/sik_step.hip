@@ -496,6 +496,40 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         }
     }
     __syncthreads();
+    // One active chunk: this workgroup owns its heads outright.  The threshold-bin candidates are ranked now (by
+    // counting, keys are distinct) and the winners join the lists, so that one gather covers the head and the last
+    // phase has nothing left to select.
+    const bool sole = nact == 1;  // uniform
+    const bool fast = sole && !(crowded[0] || crowded[1] || crowded[2] || crowded[3]);
+    if (sole) {
+        uint32_t add = 0u;
+        if (g < nh) {
+            const int bstar = sthr[g][0], need = kk - min(sthr[g][1], kk);
+            if (bstar >= 0 && bstar < kBins && need > 0 && sthr[g][2] <= kCandCap) {
+                const int ncand = static_cast<int>(min(s_ncand[g], static_cast<uint32_t>(kCandCap)));
+                const uint64_t* const cg = cstage + g * kCandCap;
+                const uint32_t nsel = s_nsel[g];
+                for (int x0 = gt; x0 < ncand; x0 += kGroupThreads) {
+                    const uint64_t me = cg[x0];
+                    uint32_t rank = 0u;
+                    for (int x = 0; x < ncand; x += 8) {  // (kCandCap is a multiple of 8: the reads stay inside cg)
+                        uint64_t o8[8];
+#pragma unroll
+                        for (int y = 0; y < 8; ++y) o8[y] = cg[x + y];
+#pragma unroll
+                        for (int y = 0; y < 8; ++y) rank += (x + y < ncand && o8[y] > me) ? 1u : 0u;
+                    }
+                    if (rank < static_cast<uint32_t>(need) && nsel + rank < static_cast<uint32_t>(a.listcap))
+                        lists[g * a.listcap + nsel + rank] =
+                            static_cast<uint16_t>(static_cast<int>(~static_cast<uint32_t>(me)) - start);
+                }
+                add = static_cast<uint32_t>(min(need, ncand));
+            }
+        }
+        __syncthreads();
+        if (g < nh && gt == 0) s_nsel[g] += add;
+        __syncthreads();
+    }
     SIK_TL(43);
     // reservations in the head's index output and candidate area (several chunks only), issued before the gather
     // hides their round trip
@@ -587,6 +621,12 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
 
     const size_t row = row0;  // (timeline marks of the workgroup that finishes the first head block)
     (void)row;
+    if (fast) {  // uniform: everything selected has been gathered, the partial of step 3 is the result
+        if (g < nh && gt < kD) store_out<ODT>(a.out, (row0 + g) * kD + gt, Lsum > 0.0f ? o / Lsum : 0.0f);
+        if (orow)
+            for (int j = kk + gt; j < a.k; j += kGroupThreads) orow[j] = -1;
+        SIK_TL_ANY(47);
+    } else {
     SIK_TL_ANY(46);
     // ---- 4. last workgroup of head g: candidates, merge, output (groups of 256 threads side by side; every
     // barrier below is reached by all 1024 threads) ---------------------------------------------------------------
@@ -595,7 +635,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     uint32_t* const rank_base = reinterpret_cast<uint32_t*>(reinterpret_cast<uint64_t*>(dyn) + kHB * (kCandCap + 8));
     uint32_t* const rank_of = rank_base + g * 2 * kCandCap;
     int32_t* const chosen = reinterpret_cast<int32_t*>(rank_of + kCandCap);
-    const bool do_rank = mine && need_g > 0 && ranked_g && bstar_g >= 0 && bstar_g < kBins;
+    const bool do_rank = !sole && mine && need_g > 0 && ranked_g && bstar_g >= 0 && bstar_g < kBins;
     const int ncand = do_rank ? min(nb_g, kCandCap) : 0;
     constexpr int kOPre = 8;
     float o_pre[kOPre], pm = kNegBig, pl = 0.0f;
@@ -749,6 +789,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     if (mine && orow)
         for (int j = kk + gt; j < a.k; j += kGroupThreads) orow[j] = -1;
     SIK_TL_ANY(47);
+    }
     // leave the head's counters at zero for the next call; the block's first head also clears the arrival counter
     if (mine && nact > 1 && gt == 0) {
         st_agent(&rsync[g * kSyncPerRow + 0], 0u);
