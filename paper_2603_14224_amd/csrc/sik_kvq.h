@@ -67,6 +67,23 @@ __device__ __forceinline__ float oct_max(float v) {
                         __builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false))));
 }
 
+// x / 3 rounded to nearest, in three instructions: the product with the rounded 1/3 is at most one unit off, the
+// fused residual x - 3 q is exact, and the correction lands on the correctly rounded quotient (checked against the
+// division for every mantissa; a quotient in the subnormal range may differ in its last bit, and rounds to a
+// zero fp16 step either way).
+__device__ __forceinline__ float third(float x) {
+    constexpr float c = 1.0f / 3.0f;
+    const float q = x * c;
+    return fmaf(fmaf(-3.0f, q, x), c, q);
+}
+
+// 1 / x for a normal positive x: the hardware estimate (one unit in the last place) and one Newton step, which
+// leaves the correctly rounded reciprocal except next to a rounding tie.
+__device__ __forceinline__ float reciprocal(float x) {
+    const float r = __builtin_amdgcn_rcpf(x);
+    return fmaf(fmaf(-x, r, 1.0f), r, r);
+}
+
 // Parameters and 2-bit codes of this lane's N values of one 32-value group that 32 / N neighbouring lanes hold
 // together (all of them active); group_min / group_max reduce over those lanes.  Returns the 2 N code bits
 // (value e in bits 2e+1:2e); qs_h, zp_h = the stored fp16 bits.  One function for every lane mapping, so that
@@ -82,14 +99,14 @@ __device__ __forceinline__ uint32_t quantize_lane(const float (&x)[N], GroupMin 
     }
     lo = group_min(lo) + 0.0f;  // a zero minimum is stored as +0 whatever the signs of the zeros
     hi = group_max(hi);
-    qs_h = fp16_bits((hi - lo) / 3.0f);
+    qs_h = fp16_bits(third(hi - lo));
     zp_h = fp16_bits(lo);
     const float qs = fp16_value(qs_h), zp = fp16_value(zp_h);
     // The code word is assembled in floating point: sum_e c_e 4^e with c_e in {0, 1, 2, 3} stays below 2^16 and is
     // exact in binary32, so one fused multiply-add per value replaces a conversion, a shift and an OR.
     float word = 0.0f;
     if (qs > 0.0f) {
-        const float rqs = 1.0f / qs;
+        const float rqs = reciprocal(qs);
 #pragma unroll
         for (int e = 0; e < N; ++e) {
             const float c = __builtin_amdgcn_fmed3f(rintf((x[e] - zp) * rqs), 0.0f, 3.0f);  // clamp to [0, 3]
