@@ -26,7 +26,10 @@ HBM_PEAK_GBPS = 8000.0
 # the FETCH_SIZE + WRITE_SIZE figures of the committed rocprofv3 --pmc runs of this same command (file named beside
 # each; counter units x the factor a 256 MiB plain copy calibrates there).  Workloads or variants without such a
 # run report null.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("C2", "select_attend_kernel"): (29490510, "profiles/decode_step_two_launches_C2_C3.md"),
+    ("C4", "step_kernel"): (334941598, "profiles/decode_step_one_launch_C4_C5.md"),
+}
 # execution times returned by sik_decode_step_profiled, in launch order: small launches run scoring, then fused
 # selection + attention; large ones run as one launch, reported in the last slot and named step_kernel here
 KERNELS = ("prep_kernel", "score_kernel", "select_kernel", "select_attend_kernel")

@@ -433,6 +433,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             if (crowded[s] && tok < end) st_agent(&a.scores[(row0 + s) * a.sstride + tok], v4[s]);
         }
     }
+    SIK_TL(8);
     // Stage B: selected tokens per wavefront, in rounds of "every lane pops one mask bit" (as many rounds as the
     // busiest lane has selected tokens): ballots and scalar counts only
     const uint64_t lt_mask = (1ull << lane) - 1ull;
@@ -447,7 +448,9 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             m &= m - 1u;
         }
         if (lane == 0) wcnt[s][wv] = tot;
-        // candidates (about one token in a thousand): popped from the mask one by one
+        // candidates (about one token in a thousand): popped from the mask one by one (a wavefront-uniform loop
+        // over the holders with scalar branches to the score's register was measured slower: the scalar unit is
+        // shared by the 16 wavefronts)
         uint32_t cm = has_cand[s] ? (gmask[s] & ~smask[s]) : 0u;
         while (cm != 0u) {
             const int it = __ffs(static_cast<int>(cm)) - 1;
@@ -465,7 +468,9 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
                 cstage[s * kCandCap + at] = static_cast<uint64_t>(float_to_key(v)) << 32 | (~tok);
         }
     }
+    SIK_TL(9);
     __syncthreads();
+    SIK_TL(10);
     if (tid < kHB * kStepWaves) {  // per head: offsets of the wavefronts (one 16-lane row per head)
         const int s = tid >> 4, w = tid & 15;
         const uint32_t cnt = wcnt[s][w];
@@ -496,6 +501,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         }
     }
     __syncthreads();
+    SIK_TL(11);
     // One active chunk: this workgroup owns its heads outright.  The threshold-bin candidates are ranked now (by
     // counting, keys are distinct) and the winners join the lists, so that one gather covers the head and the last
     // phase has nothing left to select.
