@@ -59,7 +59,7 @@ def parse():
                          "--kv q2 kept as 16-bit side rows); the budget top_k then counts them")
     ap.add_argument("--shared", action="store_true",
                     help="group-shared selection: one index set per KV head from the summed scores of its query heads")
-    ap.add_argument("--launches", type=int, default=0, choices=[0, 1, 2],
+    ap.add_argument("--launches", type=int, default=0, choices=[0, 1, 2, 3],
                     help="0: the library's choice; 1: the one-launch step whenever its plan allows; 2: scoring and "
                          "selection + attention as two launches (comparison runs; the headline uses 0)")
     ap.add_argument("--fit", action="store_true",

@@ -318,7 +318,8 @@ typedef struct {
     void *stream;
     float *kernel_us;
     int32_t launches;     /* 0: the library chooses; 1: the one-launch step whenever its plan allows (sik_plan_info);
-                             2: always separate scoring and selection + attention launches                      */
+                             2: always separate scoring and selection + attention launches; 3: as 1, with the
+                             first scoring pass in 16-bit fixed point (exact scores for the band around the cut) */
     int32_t spin_limit;   /* polls a bounded wait of the one-launch step may take; 0 = default (about a second)  */
 } sik_decode_args;
 

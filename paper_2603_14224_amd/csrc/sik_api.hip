@@ -142,7 +142,7 @@ int sik_plan_info(const sik_layout* layout, int32_t* info) {
     // one-launch decode step: tokens per thread (chunk = 1024 x that) on the current device, 0 = not taken
     size_t dyn;
     int listcap, snc;
-    const int tt = step_plan(d, 1, false, device_compute_units(), &snc, &dyn, &listcap);
+    const int tt = step_plan(d, 1, false, device_compute_units(), false, &snc, &dyn, &listcap);
     info[7] = tt / 100 + tt % 100;
     return SIK_OK;
 }
@@ -363,10 +363,13 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     // (by default only for large launches: with one sequence the histogram exchange between the many chunks of a
     // head and the heavier barriers of 1024-thread workgroups cost more than the launch boundary they save)
     const bool large = static_cast<int64_t>(d.units()) * ((d.R + 3) / 4) * d.Lmax > (2 << 20);
-    const int step_T = (!kvq && plain && !opt.group_shared && opt.launches != 2 && (large || opt.launches == 1))
-                           ? step_plan(d, k, k_new != nullptr, device_compute_units(), &step_nchunk, &step_dyn,
-                                       &step_listcap)
-                           : 0;
+    const bool one_launch = !kvq && plain && !opt.group_shared && opt.launches != 2 && (large || opt.launches != 0);
+    const bool first_pass_16 = opt.launches == 3;
+    int step_T = 0;
+    if (one_launch && first_pass_16)
+        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), true, &step_nchunk, &step_dyn, &step_listcap);
+    if (one_launch && step_T == 0)
+        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), false, &step_nchunk, &step_dyn, &step_listcap);
     if (step_T > 0) {
         const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
                         static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, nullptr, nullptr};
@@ -497,7 +500,7 @@ int sik_decode_step_ex(const sik_layout* layout, const sik_decode_args* a) {
     const StepOptions opt{a->forced_idx, a->n_forced, static_cast<const uint16_t*>(a->forced_K),
                         static_cast<const uint16_t*>(a->forced_V), a->mu, a->k_per_mille, a->group_shared != 0,
                         a->launches, a->spin_limit};
-    if (a->spin_limit < 0 || a->launches < 0 || a->launches > 2) return SIK_ERR_FLAGS;
+    if (a->spin_limit < 0 || a->launches < 0 || a->launches > 3) return SIK_ERR_FLAGS;
     auto run = [&](StepTimers* ev) {
         return decode_step_impl(layout, a->q, a->k_new, a->v_new, a->K, a->V, a->kvq, a->alpha, a->seq_len, a->mu,
                                 a->codebook, a->codes, a->k, a->softmax_scale, a->out, a->idx_out, a->workspace,

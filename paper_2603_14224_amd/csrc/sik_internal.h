@@ -140,7 +140,8 @@ struct StepOptions {  // what sik_decode_step_ex adds to the plain decode step
     const float* mu;
     int k_per_mille;    // > 0: per-sequence budget min(k, ceil(L * k_per_mille / 1000))
     bool group_shared;  // one index set per KV head from the summed scores of its query heads (unfused path)
-    int launches;       // 0: the library chooses; 1: the one-launch step whenever its plan allows; 2: never
+    int launches;       // 0: the library chooses; 1 / 3: the one-launch step whenever its plan allows (3: with the
+                        // 16-bit first pass); 2: never
     int spin_limit;     // polls a bounded wait of the one-launch step may take (0: the default)
 };
 hipError_t launch_fused(const Dims& d, const Workspace& w, const void* q, const void* K, const void* V,
@@ -150,7 +151,7 @@ bool fused_plan(const Dims& d, int* nchunk, int* chunk);
 // one-launch decode step (sik_step.hip)
 size_t step_sync_words(const Dims& d);
 int step_max_chunks(const Dims& d);
-int step_plan(const Dims& d, int k, bool appended, int cus, int* nchunk, size_t* dyn_lds, int* listcap);
+int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, int* nchunk, size_t* dyn_lds, int* listcap);
 int device_compute_units();
 hipError_t launch_sync_init(const Dims& d, const Workspace& w, hipStream_t s);
 hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn_lds, int listcap, const void* q,

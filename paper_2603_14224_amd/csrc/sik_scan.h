@@ -68,6 +68,45 @@ __device__ __forceinline__ void lookup_batch(uint32_t word, int dw, const float*
     for (int n = 0; n < 8; ++n) v[n] = *reinterpret_cast<const T*>(base + n * 16 * kEnt + off[n]);
 }
 
+// The same batch from a table of 8-byte entries (four 16-bit values, one per query head) kept at the 16-byte stride
+// of the float4 table, so that the offsets are the same ones: 16 entries x 8 B of a group lie on 32 different banks.
+__device__ __forceinline__ void lookup_batch_x(uint32_t word, int dw, const void* lutx, uint2 (&v)[8]) {
+    constexpr uint32_t kMask = 15u * 16u;
+    const uint32_t wlo = word << 4;
+    uint32_t off[8];
+    off[0] = byte_and<0>(word, kMask);
+    off[1] = byte_and<0>(wlo, kMask);
+    off[2] = byte_and<1>(word, kMask);
+    off[3] = byte_and<1>(wlo, kMask);
+    off[4] = byte_and<2>(word, kMask);
+    off[5] = byte_and<2>(wlo, kMask);
+    off[6] = byte_and<3>(word, kMask);
+    off[7] = byte_and<3>(wlo, kMask);
+    const char* base = static_cast<const char*>(lutx) + dw * 8 * 16 * 16;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) v[n] = *reinterpret_cast<const uint2*>(base + n * 16 * 16 + off[n]);
+}
+
+// The fp32 score of one token and one of the table's four heads, summed in ascending group order exactly as the
+// batches above are added (the same bits), for the few tokens that are scored one at a time.
+__device__ __forceinline__ float exact_score(const float* lut, const uint4 code, int s) {
+    const uint32_t w[4] = {code.x, code.y, code.z, code.w};
+    float acc = 0.0f;
+#pragma unroll
+    for (int dw = 0; dw < 4; ++dw) {
+#pragma unroll
+        for (int by = 0; by < 4; ++by) {
+            const uint32_t b = (w[dw] >> (8 * by)) & 0xffu;
+            const int g0 = dw * 8 + by * 2;
+            const float t0 = lut[(g0 * 16 + static_cast<int>(b >> 4)) * kHB + s];
+            const float t1 = lut[((g0 + 1) * 16 + static_cast<int>(b & 15u)) * kHB + s];
+            acc = g0 == 0 ? t0 : acc + t0;
+            acc += t1;
+        }
+    }
+    return acc;
+}
+
 // Half a batch: the 4 lookups of bytes 2 HALF and 2 HALF + 1 of the code word (groups 8 dw + 4 HALF .. + 3), for
 // kernels that cannot spare the registers of a whole batch in flight.
 template <int HALF>

@@ -114,9 +114,10 @@ __device__ __forceinline__ Threshold find_threshold(const HistLoads& h, int kk, 
 // writes their indices to out[0 .. need).  NT = threads of the workgroup (all of them call); COHERENT: the
 // scores were written by other workgroups of this launch and are read with agent-scope loads.
 // h256: LDS, 256 words; sh: LDS, 4 words.
-template <int NT = kBlock, bool COHERENT = false>
-__device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, float lo, float scale, int bstar,
-                                           int need, int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
+// radix_select_members: the same with the membership test handed in (member(v): does a token with score v compete).
+template <int NT, bool COHERENT, class Member>
+__device__ inline void radix_select_members(const float* __restrict__ s, int L, Member member, int need,
+                                            int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
     const int tid = threadIdx.x;
     auto score = [&](int i) { return COHERENT ? ld_agent(&s[i]) : s[i]; };
     uint32_t prefix = 0, mask = 0;
@@ -128,7 +129,7 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
         for (int i = tid; i < L; i += NT) {
             const float v = score(i);
             const uint32_t key = float_to_key(v);
-            if (score_bin(v, lo, scale) == bstar && (key & mask) == prefix)
+            if (member(v) && (key & mask) == prefix)
                 atomicAdd(&h256[(key >> (8 * pass)) & 255u], 1u);
         }
         __syncthreads();
@@ -165,7 +166,7 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
 #pragma unroll 8
     for (int i = tid; i < L; i += NT) {
         const float v = score(i);
-        if (score_bin(v, lo, scale) == bstar && float_to_key(v) > tau) out[atomicAdd(&sh[2], 1u)] = i;
+        if (member(v) && float_to_key(v) > tau) out[atomicAdd(&sh[2], 1u)] = i;
     }
     // equal members: the first need_eq of them in index order; tiles of NT tokens, stop when served
     constexpr int kWaves = NT / kWave;
@@ -174,7 +175,7 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
         bool eq = false;
         if (i < L) {
             const float v = score(i);
-            eq = score_bin(v, lo, scale) == bstar && float_to_key(v) == tau;
+            eq = member(v) && float_to_key(v) == tau;
         }
         const uint64_t bal = __ballot(eq);
         const int lane = tid & 63, wv = tid >> 6;
@@ -192,6 +193,13 @@ __device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, f
         if (total >= need_eq) break;  // uniform: every thread computed the same total
     }
     __syncthreads();
+}
+
+template <int NT = kBlock, bool COHERENT = false>
+__device__ inline void radix_select_in_bin(const float* __restrict__ s, int L, float lo, float scale, int bstar,
+                                           int need, int32_t* __restrict__ out, uint32_t* h256, uint32_t* sh) {
+    radix_select_members<NT, COHERENT>(s, L, [=](float v) { return score_bin(v, lo, scale) == bstar; }, need, out,
+                                       h256, sh);
 }
 
 }  // namespace sik

@@ -20,6 +20,7 @@
 // Every counter the kernel uses is left at zero by its last user, so the workspace's sync words need zeroing only
 // once (sik_workspace_init).
 #include <atomic>
+#include <climits>
 
 #include "sik_attn_core.h"
 #include "sik_device.h"
@@ -111,7 +112,7 @@ constexpr int kSyncHeader = 8;  // word 0: status bits
 constexpr int kSyncPerRow = 4;  // ticket, index-output reservation, candidate reservation, histogram arrivals
 constexpr int kSyncPerSeq = 2;  // workgroups that have read the length, heads finished
 
-template <int DT, int ODT, int T, int TL>
+template <int DT, int ODT, int T, int TL, bool FX = false>
 __global__ __launch_bounds__(kStepThreads) void step_kernel(
     // (the first 14 dwords arrive in scalar registers with the wavefront: what the first loads need comes first;
     // dims0 = Hkv | Hq << 16, dims1 = R | nhb << 8 | nchunk << 16 | stream << 24)
@@ -121,6 +122,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     constexpr int TT = T + TL;  // tokens per thread: T with their scores in registers, TL with their scores in LDS
     constexpr int kChunk = kStepThreads * TT;
     static_assert(TT <= 32, "one mask bit per token of a thread");
+    static_assert(!FX || TL == 0, "the 16-bit sums of the first pass all stay in registers");
     const int Hkv = dims0 & 0xffffu, Hq = dims0 >> 16;
     const int R = dims1 & 0xffu, nhb = (dims1 >> 8) & 0xffu, nchunk = (dims1 >> 16) & 0xffu;
     const bool stream = (dims1 >> 24) & 1u;
@@ -128,6 +130,9 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     __shared__ __align__(16) float lut[kG * 16 * kHB];
     __shared__ float qs[kHB][kD];
     __shared__ float bp[kHB][2];
+    // first pass in 16-bit fixed point (FX): entries at the float4 table's stride, bin base and band per head
+    __shared__ __align__(16) uint16_t lutx[FX ? kG * 16 * 8 : 8];
+    __shared__ int bpx[kHB][3], sband[kHB][2];
     __shared__ uint32_t lhist[kHB * kBins];  // this chunk's histograms, later the heads' totals
     __shared__ __align__(16) uint8_t newcode[kCodeBytes];
     __shared__ uint32_t wcnt[kHB][kStepWaves];
@@ -258,14 +263,68 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             bp[s][0] = mean - 0.5f * span;
             bp[s][1] = (span > 1e-30f && span < 3.0e38f) ? static_cast<float>(kBins) / span : 0.0f;
         }
+        if constexpr (FX) {
+            // Fixed-point table of head s: E[g][j] = round((T[g][j] - min_j T[g]) / delta), delta chosen so that the
+            // sum F of 32 entries fits 16 bits.  With S the exact sum of the looked-up T's and c = sum_g min_j T[g]:
+            // |S - (delta F + c)| <= 32 x 0.52 delta (rounding of the entries, and of their binary32 evaluation),
+            // and the binary32 score differs from S by at most gam = 31 x 2^-24 x sum_g max_j |T[g][j]| (1 + 1e-5).
+            // Hence F_a - F_b >= D = 2 G implies score_a > score_b, with G = ceil(17 + 1.01 gam / delta) + 1.
+            float mn = 3.4028235e38f, mx = -3.4028235e38f, ma = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const float x = lf[((j + gg) & 15) * kHB];
+                mn = fminf(mn, x);
+                mx = fmaxf(mx, x);
+                ma = fmaxf(ma, fabsf(x));
+            }
+            float R = mx - mn, A = ma;
+#pragma unroll
+            for (int o = 16; o >= 1; o >>= 1) {
+                R += __shfl_xor(R, o, 32);
+                A += __shfl_xor(A, o, 32);
+            }
+            const float inv = (R > 1e-30f && R < 3.0e38f) ? 65495.0f / R : 0.0f;  // 1 / delta
+            float sumE = 0.0f, sqE = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int jj = (j + gg) & 15;
+                const float e = rintf((lf[jj * kHB] - mn) * inv);
+                lutx[(gg * 16 + jj) * 8 + s] = static_cast<uint16_t>(static_cast<int>(e));
+                sumE += e;
+                sqE = fmaf(e, e, sqE);
+            }
+            float meanE = sumE * (1.0f / 16.0f);
+            float varE = fmaxf(sqE * (1.0f / 16.0f) - meanE * meanE, 0.0f);
+#pragma unroll
+            for (int o = 16; o >= 1; o >>= 1) {
+                meanE += __shfl_xor(meanE, o, 32);
+                varE += __shfl_xor(varE, o, 32);
+            }
+            if (gg == 0) {
+                const float gam = 31.0f * 5.9604645e-8f * A;
+                const float G = fminf(ceilf(17.0f + 1.01f * gam * inv) + 1.0f, 1.0e6f);
+                const int D = 2 * static_cast<int>(G);
+                // 512 bins of 2^sh units around the mean of F over uniform codes, wide enough for +- 4.5 sigma:
+                // bin = (F >> sh) - base (any choice is correct, this one keeps the band small); a band of m bins on
+                // either side of the threshold bin covers every F within D of it
+                const int wreq = static_cast<int>(fminf(9.0f * sqrtf(varE) * (1.0f / kBins), 60000.0f));
+                const int sh = wreq <= 1 ? 0 : 32 - __clz(wreq - 1);
+                bpx[s][0] = (static_cast<int>(meanE) >> sh) - kBins / 2;
+                bpx[s][1] = (D - 1 + (1 << sh) - 1) >> sh;
+                bpx[s][2] = sh;
+            }
+        }
     }
     __syncthreads();
     float blo[kHB], bscale[kHB], bshift[kHB];
+    int base6[kHB], shx[kHB];  // FX: bin = (F >> shx) - base6
 #pragma unroll
     for (int s = 0; s < kHB; ++s) {
         blo[s] = bp[s][0];
         bscale[s] = bp[s][1];
         bshift[s] = bin_shift(bp[s][0], bp[s][1]);
+        base6[s] = FX ? bpx[s][0] : 0;
+        shx[s] = FX ? bpx[s][2] : 0;
     }
     SIK_TL(38);
     // The scores of this thread's tokens stay on the chip: the first T tokens' in registers, the other TL tokens'
@@ -276,6 +335,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     uint64_t* const cstage = reinterpret_cast<uint64_t*>(dyn + lists_bytes);
     float4* const lsc = reinterpret_cast<float4*>(dyn + lists_bytes + static_cast<size_t>(kHB) * kCandCap * 8);
     float sc[T][kHB];
+    uint32_t fx[FX ? TT : 1][2];  // FX: the 16-bit sums of a token, heads 0 | 1 << 16 and 2 | 3 << 16
 #pragma unroll
     for (int it = 0; it < TT; ++it) {
         const int tok = start + it * kStepThreads + tid;
@@ -285,6 +345,37 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             cur[it & 1] = i < end ? cp[i] : make_uint4(0u, 0u, 0u, 0u);
         }
         if (tok == t_new) code = *reinterpret_cast<const uint4*>(newcode);
+        if constexpr (FX) {
+            // 8-byte entries, two packed 16-bit adds per lookup: half the adds and half the LDS bytes of the
+            // fp32 scan; the sums only place the token in a bin (exact scores follow for the band, below)
+            typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+            us2 a01 = {0, 0}, a23 = {0, 0};
+#pragma unroll
+            for (int dw = 0; dw < 4; ++dw) {
+                const uint32_t word = dw == 0 ? code.x : (dw == 1 ? code.y : (dw == 2 ? code.z : code.w));
+                uint2 v[8];
+                lookup_batch_x(word, dw, lutx, v);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int n = 0; n < 8; ++n) {
+                    a01 += __builtin_bit_cast(us2, v[n].x);
+                    a23 += __builtin_bit_cast(us2, v[n].y);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const uint32_t w01 = __builtin_bit_cast(uint32_t, a01), w23 = __builtin_bit_cast(uint32_t, a23);
+            fx[it][0] = w01;
+            fx[it][1] = w23;
+            if (tok < end) {
+#pragma unroll
+                for (int s = 0; s < kHB; ++s) {
+                    const uint32_t w = s < 2 ? w01 : w23;
+                    const int f6 = static_cast<int>(((s & 1) ? w >> 16 : w & 0xffffu) >> shx[s]);
+                    if (s < nh) atomicAdd(&lhist[s * kBins + min(max(f6 - base6[s], 0), kBins - 1)], 1u);
+                }
+            }
+            continue;
+        }
         float acc[kHB];
         if constexpr (TT < 6) {
             // the lookups run one 8-group batch ahead of the adds (8 to 16 LDS reads in flight per wavefront)
@@ -385,7 +476,25 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             if (cum < ukk && ukk <= cum + c1) bstar = 2 * gt + 1, cgt = static_cast<int>(cum), nb = static_cast<int>(c1);
             cum += c1;
             if (cum < ukk && ukk <= cum + c0) bstar = 2 * gt, cgt = static_cast<int>(cum), nb = static_cast<int>(c0);
-            if (bstar >= 0) sthr[g][0] = bstar, sthr[g][1] = cgt, sthr[g][2] = nb;
+            if (bstar >= 0) {
+                if constexpr (FX) {
+                    // the band: m bins on either side of the threshold bin; bins above it are selected outright,
+                    // the band's tokens are scored exactly and ranked
+                    const int m = bpx[g][1];
+                    const int lo_b = max(bstar - m, 0), hi_b = min(bstar + m, kBins - 1);
+                    int above = 0, band = 0;
+                    for (int bb = lo_b; bb <= hi_b; ++bb) {
+                        const int cnt = static_cast<int>(lhist[g * kBins + bb]);
+                        band += cnt;
+                        above += bb > bstar ? cnt : 0;
+                    }
+                    cgt -= above;
+                    nb = band;
+                    sband[g][0] = lo_b;
+                    sband[g][1] = hi_b;
+                }
+                sthr[g][0] = bstar, sthr[g][1] = cgt, sthr[g][2] = nb;
+            }
         } else if (gt == 0) {  // everything is selected (or nothing exists)
             sthr[g][0] = kk > 0 ? -1 : kBins;
             sthr[g][1] = kk > 0 ? Lc : 0;
@@ -414,6 +523,54 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     // score for the rare candidates measured 3 us slower on 16 tokens per thread).  A threshold bin too crowded to
     // rank (e.g. all scores equal) sends the head's scores to memory for the radix selection of the last phase.
     uint32_t smask[kHB] = {0u, 0u, 0u, 0u}, gmask[kHB] = {0u, 0u, 0u, 0u};
+    if constexpr (FX) {
+        // the same two masks from the 16-bit sums: selected = a bin above the band, candidate = a bin of the band
+        // (compared as F >> sh against the bins' lower edges; the clamped end bins take everything beyond them)
+        int thr_s[kHB], thr_c[kHB];
+#pragma unroll
+        for (int s = 0; s < kHB; ++s) {
+            const int bstar = sthr[s][0];
+            const bool in = bstar >= 0 && bstar < kBins;
+            thr_s[s] = bstar < 0 ? INT_MIN : ((!in || sband[s][1] >= kBins - 1) ? INT_MAX : sband[s][1] + 1 + base6[s]);
+            thr_c[s] = !in ? INT_MAX : (sband[s][0] <= 0 ? INT_MIN : sband[s][0] + base6[s]);
+        }
+#pragma unroll
+        for (int it = 0; it < TT; ++it) {
+#pragma unroll
+            for (int s = 0; s < kHB; ++s) {
+                const uint32_t w = fx[it][s >> 1];
+                const int f6 = static_cast<int>(((s & 1) ? w >> 16 : w & 0xffffu) >> shx[s]);
+                smask[s] |= (f6 >= thr_s[s] ? 1u : 0u) << it;
+                gmask[s] |= (f6 >= thr_c[s] ? 1u : 0u) << it;
+            }
+        }
+        // token slots at or beyond the sequence's end are in no mask
+        const int nv = end - start - tid;
+        const int nit = nv <= 0 ? 0 : min((nv + kStepThreads - 1) / kStepThreads, TT);
+        const uint32_t vmask = nit >= 32 ? 0xffffffffu : (1u << nit) - 1u;
+#pragma unroll
+        for (int s = 0; s < kHB; ++s) {
+            smask[s] &= vmask;
+            gmask[s] &= vmask;
+        }
+        // a band too crowded to rank: the exact scores of its members go to memory for the radix selection of the
+        // last phase, minus infinity for everything else
+        if (crowded[0] || crowded[1] || crowded[2] || crowded[3]) {  // uniform
+            for (int it = 0; it < TT; ++it) {
+                const int tok = start + it * kStepThreads + tid;
+                if (tok < end) {
+                    const uint4 code = tok == t_new ? *reinterpret_cast<const uint4*>(newcode) : cp[tok];
+#pragma unroll
+                    for (int s = 0; s < kHB; ++s) {
+                        if (crowded[s]) {
+                            const bool member = ((gmask[s] & ~smask[s]) >> it) & 1u;
+                            st_agent(&a.scores[(row0 + s) * a.sstride + tok], member ? exact_score(lut, code, s) : -INFINITY);
+                        }
+                    }
+                }
+            }
+        }
+    } else {
 #pragma unroll
     for (int it = 0; it < TT; ++it) {
         float v4[kHB];
@@ -432,6 +589,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             gmask[s] |= (x >= lo_f[s] ? 1u : 0u) << it;
             if (crowded[s] && tok < end) st_agent(&a.scores[(row0 + s) * a.sstride + tok], v4[s]);
         }
+    }
     }
     SIK_TL(8);
     // Stage B: selected tokens per wavefront, in rounds of "every lane pops one mask bit" (as many rounds as the
@@ -455,22 +613,38 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         while (cm != 0u) {
             const int it = __ffs(static_cast<int>(cm)) - 1;
             cm &= cm - 1u;
-            float v = 0.0f;
-            if (it < T) {
-#pragma unroll
-                for (int j = 0; j < T; ++j) v = it == j ? sc[j][s] : v;
-            } else {
-                v = reinterpret_cast<const float*>(&lsc[(it - T) * kStepThreads + tid])[s];
-            }
-            const uint32_t at = atomicAdd(&s_ncand[s], 1u);
             const uint32_t tok = static_cast<uint32_t>(start + it * kStepThreads + tid);
-            if (at < static_cast<uint32_t>(kCandCap))
-                cstage[s * kCandCap + at] = static_cast<uint64_t>(float_to_key(v)) << 32 | (~tok);
+            if constexpr (FX) {  // only the token is staged: its exact score follows below
+                const uint32_t at = atomicAdd(&s_ncand[s], 1u);
+                if (at < static_cast<uint32_t>(kCandCap)) cstage[s * kCandCap + at] = tok;
+            } else {
+                float v = 0.0f;
+                if (it < T) {
+#pragma unroll
+                    for (int j = 0; j < T; ++j) v = it == j ? sc[j][s] : v;
+                } else {
+                    v = reinterpret_cast<const float*>(&lsc[(it - T) * kStepThreads + tid])[s];
+                }
+                const uint32_t at = atomicAdd(&s_ncand[s], 1u);
+                if (at < static_cast<uint32_t>(kCandCap))
+                    cstage[s * kCandCap + at] = static_cast<uint64_t>(float_to_key(v)) << 32 | (~tok);
+            }
         }
     }
     SIK_TL(9);
     __syncthreads();
     SIK_TL(10);
+    // FX: the band's tokens get their binary32 scores, one thread per (head, token): the same sum, in the same
+    // order, as the fp32 scan computes, so every path ranks by the same bits.  The code loads go out here and are
+    // used after the lists have been written.
+    const bool rescore = FX && g < nh && sthr[g][0] >= 0 && sthr[g][0] < kBins && sthr[g][2] <= kCandCap;
+    const int nres = rescore ? static_cast<int>(min(s_ncand[g], static_cast<uint32_t>(kCandCap))) : 0;
+    int rtok = -1;
+    uint4 rcode = make_uint4(0u, 0u, 0u, 0u);
+    if (gt < nres) {
+        rtok = static_cast<int>(cstage[g * kCandCap + gt]);
+        rcode = rtok == t_new ? *reinterpret_cast<const uint4*>(newcode) : cp[rtok];
+    }
     if (tid < kHB * kStepWaves) {  // per head: offsets of the wavefronts (one 16-lane row per head)
         const int s = tid >> 4, w = tid & 15;
         const uint32_t cnt = wcnt[s][w];
@@ -498,6 +672,16 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
                 lists[s * a.listcap + at] = static_cast<uint16_t>((__ffs(static_cast<int>(m)) - 1) * kStepThreads + tid);
             base += static_cast<uint32_t>(__popcll(bal));
             m &= m - 1u;
+        }
+    }
+    if constexpr (FX) {
+        for (int j = gt; j < nres; j += kGroupThreads) {
+            if (j != gt) {
+                rtok = static_cast<int>(cstage[g * kCandCap + j]);
+                rcode = rtok == t_new ? *reinterpret_cast<const uint4*>(newcode) : cp[rtok];
+            }
+            cstage[g * kCandCap + j] = static_cast<uint64_t>(float_to_key(exact_score(lut, rcode, g))) << 32 |
+                                       (~static_cast<uint32_t>(rtok));
         }
     }
     __syncthreads();
@@ -722,8 +906,13 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             int32_t* dst = (a.idx_out ? a.idx_out : a.idx_ws) + (row0 + s) * a.k + sthr[s][1];
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
-            radix_select_in_bin<kStepThreads, true>(a.scores + (row0 + s) * a.sstride, L, blo[s], bscale[s], sthr[s][0],
-                                                    need_s, dst, lhist, &lds4[0][0]);
+            if constexpr (FX)
+                radix_select_members<kStepThreads, true>(a.scores + (row0 + s) * a.sstride, L,
+                                                         [](float v) { return v > -INFINITY; }, need_s, dst, lhist,
+                                                         &lds4[0][0]);
+            else
+                radix_select_in_bin<kStepThreads, true>(a.scores + (row0 + s) * a.sstride, L, blo[s], bscale[s],
+                                                        sthr[s][0], need_s, dst, lhist, &lds4[0][0]);
             __threadfence_block();
             __syncthreads();
         }
@@ -827,6 +1016,9 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
 // ---- host side ---------------------------------------------------------------------------------------------------
 // instantiated (tokens per thread with scores in registers, further tokens with scores in LDS); chunk = 1024 x sum
 constexpr int kStepT[][2] = {{1, 0}, {2, 0}, {3, 0}, {4, 0}, {6, 0}, {8, 0}, {12, 0}, {12, 4}, {14, 4}, {16, 4}};
+// instantiated tokens per thread of the variant with the 16-bit first pass (two registers per token)
+constexpr int kStepFx[] = {4, 8, 12, 16, 20};
+constexpr int kStepFxCode = 100000;  // added to T * 100 in the plan's return value
 constexpr size_t kStepLdsBudget = 120 * 1024;          // dynamic LDS the kernel may ask for beside its static 36 KB
 
 size_t step_sync_words(const Dims& d) {
@@ -853,23 +1045,31 @@ static size_t step_dyn_bytes(int chunk, int TL, int k, int* listcap) {
 // grid fits the compute units (workgroups of a head block wait for each other, so they must all be resident);
 // a single chunk per head block needs no wait and may exceed them, unless a row is appended (its new length is
 // published by a workgroup that waits for the others).
-int step_plan(const Dims& d, int k, bool appended, int cus, int* nchunk_out, size_t* dyn_out, int* listcap_out) {
+int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, int* nchunk_out, size_t* dyn_out,
+              int* listcap_out) {
     if (d.R < 2 || d.R > 255 || cus < 1) return 0;
     const int hbs = d.units() * ((d.R + kHB - 1) / kHB);
-    for (const auto& tt : kStepT) {
-        const int chunk = kStepThreads * (tt[0] + tt[1]);
+    auto fits = [&](int tokens, int tl) {
+        const int chunk = kStepThreads * tokens;
         const int nchunk = (d.Lmax + chunk - 1) / chunk;
-        if (nchunk > kMaxChunks || nchunk > step_max_chunks(d)) continue;
+        if (nchunk > kMaxChunks || nchunk > step_max_chunks(d)) return false;
         const bool resident = static_cast<int64_t>(hbs) * nchunk <= cus;
-        if (!resident && !(nchunk == 1 && !appended)) continue;
+        if (!resident && !(nchunk == 1 && !appended)) return false;
         int listcap;
-        const size_t dyn = step_dyn_bytes(chunk, tt[1], k, &listcap);
-        if (dyn > kStepLdsBudget) continue;
+        const size_t dyn = step_dyn_bytes(chunk, tl, k, &listcap);
+        if (dyn > kStepLdsBudget) return false;
         *nchunk_out = nchunk;
         *dyn_out = dyn;
         *listcap_out = listcap;
-        return tt[0] * 100 + tt[1];  // both numbers in one: T * 100 + TL
+        return true;
+    };
+    if (fx) {
+        for (const int t : kStepFx)
+            if (fits(t, 0)) return kStepFxCode + t * 100;
+        return 0;
     }
+    for (const auto& tt : kStepT)
+        if (fits(tt[0] + tt[1], tt[1])) return tt[0] * 100 + tt[1];  // both numbers in one: T * 100 + TL
     return 0;
 }
 
@@ -909,9 +1109,11 @@ static hipError_t launch_step_t(const Dims& d, int T, int nchunk, size_t dyn, co
     auto qp = static_cast<const uint16_t*>(q);
     auto Kp = static_cast<const uint16_t*>(K);
     auto Vp = static_cast<const uint16_t*>(V);
-#define SIK_STEP(TV, TLV)                                                                                       \
-    case TV * 100 + TLV: {                                                                                      \
-        auto kern = step_kernel<DT, ODT, TV, TLV>;                                                                \
+#define SIK_STEP(TV, TLV) SIK_STEP_(TV * 100 + TLV, TV, TLV, false)
+#define SIK_STEP_FX(TV) SIK_STEP_(kStepFxCode + TV * 100, TV, 0, true)
+#define SIK_STEP_(CODE, TV, TLV, FXV)                                                                           \
+    case CODE: {                                                                                                \
+        auto kern = step_kernel<DT, ODT, TV, TLV, FXV>;                                                           \
         static std::atomic<size_t> allowed{0};                                                                  \
         if (dyn > allowed.load(std::memory_order_relaxed)) {                                                    \
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
@@ -934,9 +1136,16 @@ static hipError_t launch_step_t(const Dims& d, int T, int nchunk, size_t dyn, co
         SIK_STEP(12, 4)
         SIK_STEP(14, 4)
         SIK_STEP(16, 4)
+        SIK_STEP_FX(4)
+        SIK_STEP_FX(8)
+        SIK_STEP_FX(12)
+        SIK_STEP_FX(16)
+        SIK_STEP_FX(20)
         default: return hipErrorInvalidValue;
     }
 #undef SIK_STEP
+#undef SIK_STEP_FX
+#undef SIK_STEP_
 }
 
 hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn, int listcap, const void* q,

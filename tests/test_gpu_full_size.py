@@ -84,6 +84,16 @@ def run_full(oracle, name, steps, extra_cap=32):
     n_diff = check_sets(g_idx, r_idx, oracle.score(q, cfg.dtype, cb, codes, sl), sl, k)
     check_attention(out16.float().cpu().numpy().astype(np.float64), oracle.sparse_attn(q, K, V, cfg.dtype, g_idx),
                     False, cfg.dtype, label=f"{name} full shape")
+    # every launch structure picks the same set, bit for bit (two launches, one launch, one launch with the 16-bit
+    # first pass: all rank by the same binary32 sums)
+    want = torch.sort(idx, dim=-1).values.clone()
+    for launches in (2, 1, 3):
+        idx_l = torch.full_like(idx, -7)
+        sik.sik_decode_step_ex(lay16, q=dev(q, cfg.dtype), K=dK, V=dV, seq_len=dsl, mu=dmu, codebook=dcb, codes=dcodes,
+                               k=k, out=out16, idx_out=idx_l, workspace=ws, launches=launches)
+        torch.cuda.synchronize()
+        assert sik.sik_workspace_status(ws) == 0
+        assert torch.equal(torch.sort(idx_l, dim=-1).values, want), (name, launches)
 
     out = torch.empty(B, Hq, D, device="cuda")
     for step in range(steps):

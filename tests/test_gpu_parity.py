@@ -248,8 +248,9 @@ def test_sparse_attention_all_tokens_matches_dense(oracle):
 
 # --------------------------------------------------------------------------- fused decode step
 # launches = 0: the path the library picks for the layout (small launches: scoring, then selection + attention);
-# launches = 1: the one-launch step whenever its plan allows, so that the reduced shapes below exercise it too.
-BOTH_PATHS = pytest.mark.parametrize("launches", [0, 1], ids=["auto", "one_launch"])
+# launches = 1: the one-launch step whenever its plan allows, so that the reduced shapes below exercise it too;
+# launches = 3: the one-launch step with its first scoring pass in 16-bit fixed point.
+BOTH_PATHS = pytest.mark.parametrize("launches", [0, 1, 3], ids=["auto", "one_launch", "one_launch_16bit"])
 
 
 def decode_step(layout, q, k_new, v_new, K, V, seq_len, mu, cb, codes, k, out, idx, ws, launches=0):
@@ -570,6 +571,57 @@ def test_one_launch_bounded_wait_gives_up_and_reports(oracle):
             assert status == 0 and int(st.dsl[0]) == 20001
             assert torch.equal(torch.sort(idx, dim=-1).values, torch.sort(ref_idx, dim=-1).values)
             assert float((out - ref).abs().max()) <= 2e-5 * float(ref.abs().max())
+
+
+@pytest.mark.parametrize("case", ["plain", "offset", "tiny_range", "two_groups", "huge_offset"])
+@pytest.mark.parametrize("shape", ["one_chunk", "five_chunks"])
+def test_16bit_first_pass_selects_exactly_the_sets_of_the_fp32_paths(oracle, case, shape):
+    # The first pass in 16-bit fixed point only sorts tokens into bins; every token within the guard band of the cut
+    # is rescored in binary32 and ranked, so the selected SET must equal that of the other paths bit for bit (all
+    # paths sum the same table entries in the same order).  Adversarial tables: a large common offset per group
+    # (wide band: the fp32 rounding of the sums dwarfs the fixed-point step), entries that barely differ (every
+    # token inside the band), a query that sees two groups only (256 distinct scores: plateaus at the cut).
+    if shape == "one_chunk":
+        cfg = cfg_small("C4", batch=2, n_kv_heads=2, n_q_heads=8, context=15000, top_k=512, seed=5)
+    else:
+        cfg = cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=20000, top_k=700, seed=6)
+    st = GpuState(cfg, oracle, out_dtype=torch.float32)
+    B, Hq, k = cfg.batch, cfg.n_q_heads, cfg.top_k
+    q, _, _ = W.make_step_inputs(cfg, 1)
+    cb = st.cb.copy()
+    if case == "offset":
+        cb += 3.0
+    elif case == "huge_offset":
+        cb += 4000.0
+    elif case == "tiny_range":
+        m = cb.mean(axis=3, keepdims=True)
+        cb = (m + 1e-4 * (cb - m)).astype(np.float32)
+    elif case == "two_groups":
+        qf = W.from_bits(q, cfg.dtype).copy()
+        qf[..., 8:] = 0
+        q = W.to_bits(qf, cfg.dtype)
+    dq, dcb = dev(q, cfg.dtype), torch.from_numpy(cb).cuda()
+    res = {}
+    for launches in (2, 1, 3):
+        out = torch.empty(B, Hq, 128, device="cuda")
+        idx = torch.empty(B, Hq, k, dtype=torch.int32, device="cuda")
+        sik.sik_decode_step_ex(st.layout, q=dq, K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu, codebook=dcb,
+                               codes=st.dcodes, k=k, out=out, idx_out=idx, workspace=st.ws, launches=launches)
+        sync()
+        assert sik.sik_workspace_status(st.ws) == 0
+        res[launches] = (out, torch.sort(idx, dim=-1).values)
+    for launches in (1, 3):
+        assert torch.equal(res[launches][1], res[2][1]), (case, launches)
+        assert float((res[launches][0] - res[2][0]).abs().max()) <= 2e-5 * float(res[2][0].abs().max())
+    # and that set is the oracle's, ties within 1e-5 of the k-th score aside (where the tables carry an offset far
+    # above their spread that tolerance says nothing about binary32 sums, and the comparison above is the test)
+    if case in ("plain", "two_groups"):
+        s_ref = oracle.score(q, cfg.dtype, cb, st.codes, st.sl)
+        ref_idx = oracle.topk(s_ref, st.sl, k)
+        g = res[3][1].cpu().numpy()
+        for b in range(B):
+            for hq in range(Hq):
+                topk_sets_agree(g[b, hq], ref_idx[b, hq], s_ref[b, hq], int(st.sl[b]), k)
 
 
 @BOTH_PATHS
