@@ -142,7 +142,7 @@ int sik_plan_info(const sik_layout* layout, int32_t* info) {
     // one-launch decode step: tokens per thread (chunk = 1024 x that) on the current device, 0 = not taken
     size_t dyn;
     int listcap, snc;
-    const int tt = step_plan(d, 1, false, device_compute_units(), false, &snc, &dyn, &listcap);
+    const int tt = step_plan(d, 1, false, device_compute_units(), false, false, &snc, &dyn, &listcap);
     info[7] = tt / 100 + tt % 100;
     return SIK_OK;
 }
@@ -363,19 +363,22 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     // (by default only for large launches: with one sequence the histogram exchange between the many chunks of a
     // head and the heavier barriers of 1024-thread workgroups cost more than the launch boundary they save)
     const bool large = static_cast<int64_t>(d.units()) * ((d.R + 3) / 4) * d.Lmax > (2 << 20);
-    const bool one_launch = !kvq && plain && !opt.group_shared && opt.launches != 2 && (large || opt.launches != 0);
-    const bool first_pass_16 = opt.launches == 3;
+    const bool one_launch = opt.n == 0 && opt.k_per_mille == 0 && !opt.group_shared && opt.launches != 2 &&
+                            (large || opt.launches != 0);
+    const bool first_pass_16 = opt.launches == 3 && !kvq;
     int step_T = 0;
     if (one_launch && first_pass_16)
-        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), true, &step_nchunk, &step_dyn, &step_listcap);
+        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), true, false, &step_nchunk, &step_dyn,
+                           &step_listcap);
     if (one_launch && step_T == 0)
-        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), false, &step_nchunk, &step_dyn, &step_listcap);
+        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), false, kvq != nullptr, &step_nchunk,
+                           &step_dyn, &step_listcap);
     if (step_T > 0) {
         const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
-                        static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, nullptr, nullptr};
+                        static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
         timed(3);
         e = done(3, launch_step(d, w, step_T, step_nchunk, step_dyn, step_listcap, q, k_new ? ap : Append{}, codebook,
-                                codes, seq_len, K, V, k, softmax_scale, opt.spin_limit, idx_out, out, s));
+                                codes, seq_len, K, V, kvq, alpha, k, softmax_scale, opt.spin_limit, idx_out, out, s));
     } else if (shared_unfused || !fused) {
         // prep (append + counters; skipped when nothing is appended: the scoring launch then clears the per-head
         // counters itself), scoring (on the summed query when the selection is shared), stand-alone selector (per

@@ -151,13 +151,14 @@ bool fused_plan(const Dims& d, int* nchunk, int* chunk);
 // one-launch decode step (sik_step.hip)
 size_t step_sync_words(const Dims& d);
 int step_max_chunks(const Dims& d);
-int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, int* nchunk, size_t* dyn_lds, int* listcap);
+int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, bool kvq, int* nchunk, size_t* dyn_lds,
+              int* listcap);
 int device_compute_units();
 hipError_t launch_sync_init(const Dims& d, const Workspace& w, hipStream_t s);
 hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn_lds, int listcap, const void* q,
                        const Append& ap, const float* codebook, const uint8_t* codes, int32_t* seq_len,
-                       const void* K, const void* V, int k, float scale, int spin_limit, int32_t* idx_out, void* out,
-                       hipStream_t s);
+                       const void* K, const void* V, const void* kvq, const float* alpha, int k, float scale,
+                       int spin_limit, int32_t* idx_out, void* out, hipStream_t s);
 size_t fused_cand_words(const Dims& d);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const void* V, const int32_t* seq_len,
                       float* mu, float* codebook, int32_t* counts, uint8_t* codes, float* alpha, void* kvq,

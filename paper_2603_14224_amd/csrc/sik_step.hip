@@ -25,6 +25,7 @@
 #include "sik_attn_core.h"
 #include "sik_device.h"
 #include "sik_internal.h"
+#include "sik_kvq.h"
 #include "sik_scan.h"
 #include "sik_select.h"
 
@@ -95,6 +96,10 @@ struct StepArgs {
     uint16_t* Vw;
     const float* mu;
     uint8_t* codes_w;
+    // 2-bit cache (KVQ): records read by the gather, written by the append; the frozen alpha
+    const uint2* kvq;
+    uint2* kvq_w;
+    const float* alpha;
     // exchange areas
     uint32_t* parthist;  // [rows][nchunk][kHistWords]
     uint32_t* pool;      // [rows][kCandCap][2]  threshold-bin candidates of a head: (key, index)
@@ -112,7 +117,7 @@ constexpr int kSyncHeader = 8;  // word 0: status bits
 constexpr int kSyncPerRow = 4;  // ticket, index-output reservation, candidate reservation, histogram arrivals
 constexpr int kSyncPerSeq = 2;  // workgroups that have read the length, heads finished
 
-template <int DT, int ODT, int T, int TL, bool FX = false>
+template <int DT, int ODT, int T, int TL, bool FX = false, bool KVQ = false>
 __global__ __launch_bounds__(kStepThreads) void step_kernel(
     // (the first 14 dwords arrive in scalar registers with the wavefront: what the first loads need comes first;
     // dims0 = Hkv | Hq << 16, dims1 = R | nhb << 8 | nchunk << 16 | stream << 24)
@@ -181,6 +186,11 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     const int nslice = kStepWaves / nh;
     const int gs = wv % nh, gj = wv / nh;
     const uint4 qraw = reinterpret_cast<const uint4*>(q + (row0 + gs) * kD)[p];
+    float4 al0 = make_float4(0.f, 0.f, 0.f, 0.f), al1 = al0;  // KVQ: alpha of this lane's 8 channels
+    if constexpr (KVQ) {
+        al0 = reinterpret_cast<const float4*>(a.alpha + static_cast<size_t>(unit) * kD)[2 * p];
+        al1 = reinterpret_cast<const float4*>(a.alpha + static_cast<size_t>(unit) * kD)[2 * p + 1];
+    }
     for (int e = tid; e < kHB * kBins; e += kStepThreads) lhist[e] = 0u;
     uint4 knew = make_uint4(0u, 0u, 0u, 0u), vnew = make_uint4(0u, 0u, 0u, 0u);
     float m8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -218,8 +228,17 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         for (int e = 0; e < 8; ++e) byte |= (f[e] >= m8[e] ? 1u : 0u) << (7 - e);
         newcode[tid] = static_cast<uint8_t>(byte);
         const size_t rowi = static_cast<size_t>(unit) * Lmax + t_new;
-        st_agent4(reinterpret_cast<uint4*>(a.Kw + rowi * kD) + tid, knew);
-        st_agent4(reinterpret_cast<uint4*>(a.Vw + rowi * kD) + tid, vnew);
+        if constexpr (KVQ) {  // the row is stored as one record (tid = p here: alpha of the same 8 channels)
+            const float ra[8] = {alpha_reciprocal(al0.x), alpha_reciprocal(al0.y), alpha_reciprocal(al0.z),
+                                 alpha_reciprocal(al0.w), alpha_reciprocal(al1.x), alpha_reciprocal(al1.y),
+                                 alpha_reciprocal(al1.z), alpha_reciprocal(al1.w)};
+            const uint2 slot = kvq_make_slot<DT>(knew, vnew, m8, ra, tid);
+            st_agent(reinterpret_cast<uint64_t*>(a.kvq_w + rowi * kRecSlots + tid),
+                     static_cast<uint64_t>(slot.y) << 32 | slot.x);
+        } else {
+            st_agent4(reinterpret_cast<uint4*>(a.Kw + rowi * kD) + tid, knew);
+            st_agent4(reinterpret_cast<uint4*>(a.Vw + rowi * kD) + tid, vnew);
+        }
         if (hb == 0) a.codes_w[rowi * kCodeBytes + tid] = static_cast<uint8_t>(byte);
     }
     __syncthreads();
@@ -733,15 +752,19 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             if (nc) my_res = atomic_add_u32(&rsync[s * kSyncPerRow + 2], nc);
         }
     }
-    const uint4* Kp = reinterpret_cast<const uint4*>(K + static_cast<size_t>(unit) * Lmax * kD);
-    const uint4* Vp = reinterpret_cast<const uint4*>(V + static_cast<size_t>(unit) * Lmax * kD);
+    const uint4* Kp = KVQ ? nullptr : reinterpret_cast<const uint4*>(K + static_cast<size_t>(unit) * Lmax * kD);
+    const uint4* Vp = KVQ ? nullptr : reinterpret_cast<const uint4*>(V + static_cast<size_t>(unit) * Lmax * kD);
+    const uint2* Rp = KVQ ? a.kvq + static_cast<size_t>(unit) * Lmax * kRecSlots : nullptr;
+    const float al8[8] = {al0.x, al0.y, al0.z, al0.w, al1.x, al1.y, al1.z, al1.w};
     SoftmaxState st;
     init_state(st);
     if (gj < nslice) {
         const int n = min(static_cast<int>(s_nsel[gs]), a.listcap);
         const uint16_t* lst = lists + gs * a.listcap;
         auto fetch = [&](int j) { return start + static_cast<int>(lst[j]); };
-        if (stream)
+        if constexpr (KVQ)  // records: 32 entries per wavefront step, dequantised in registers
+            attend_list_q2(fetch, n, gj * 32, nslice * 32, Rp, q2_prepare<DT>(qraw, al8), a.scale_log2e, Lmax, st);
+        else if (stream)
             attend_list<DT, true>(fetch, n, gj * 16, nslice * 16, Kp, Vp, qraw, a.scale_log2e, Lmax, st);
         else
             attend_list<DT, false>(fetch, n, gj * 16, nslice * 16, Kp, Vp, qraw, a.scale_log2e, Lmax, st);
@@ -922,11 +945,18 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     const bool radix_g = mine && need_g > 0 && !ranked_g && bstar_g >= 0 && bstar_g < kBins;
     if (mine && need_g > 0) {
         const uint4 qg = reinterpret_cast<const uint4*>(q + (row0 + g) * kD)[p];
-        if (do_rank) {
+        const int32_t* gl = (a.idx_out ? a.idx_out : a.idx_ws) + (row0 + g) * a.k + cgt_g;
+        if constexpr (KVQ) {
+            const Q2Query qq = q2_prepare<DT>(qg, al8);
+            if (do_rank)
+                attend_list_q2([&](int j) { return chosen[j]; }, min(need_g, ncand), wl * 32, 128, Rp, qq,
+                               a.scale_log2e, Lmax, st2);
+            else if (radix_g)
+                attend_list_q2([&](int j) { return gl[j]; }, need_g, wl * 32, 128, Rp, qq, a.scale_log2e, Lmax, st2);
+        } else if (do_rank) {
             attend_list<DT, false>([&](int j) { return chosen[j]; }, min(need_g, ncand), wl * 16, 64, Kp, Vp, qg,
                                    a.scale_log2e, Lmax, st2);
         } else if (radix_g) {
-            const int32_t* gl = (a.idx_out ? a.idx_out : a.idx_ws) + (row0 + g) * a.k + cgt_g;
             attend_list<DT, false>([&](int j) { return gl[j]; }, need_g, wl * 16, 64, Kp, Vp, qg, a.scale_log2e, Lmax,
                                    st2);
         }
@@ -1019,6 +1049,8 @@ constexpr int kStepT[][2] = {{1, 0}, {2, 0}, {3, 0}, {4, 0}, {6, 0}, {8, 0}, {12
 // instantiated tokens per thread of the variant with the 16-bit first pass (two registers per token)
 constexpr int kStepFx[] = {4, 8, 12, 16, 20};
 constexpr int kStepFxCode = 100000;  // added to T * 100 in the plan's return value
+// the pairs instantiated for the 2-bit cache as well
+constexpr int kStepQ2[][2] = {{1, 0}, {4, 0}, {12, 0}, {12, 4}, {14, 4}, {16, 4}};
 constexpr size_t kStepLdsBudget = 120 * 1024;          // dynamic LDS the kernel may ask for beside its static 36 KB
 
 size_t step_sync_words(const Dims& d) {
@@ -1045,7 +1077,7 @@ static size_t step_dyn_bytes(int chunk, int TL, int k, int* listcap) {
 // grid fits the compute units (workgroups of a head block wait for each other, so they must all be resident);
 // a single chunk per head block needs no wait and may exceed them, unless a row is appended (its new length is
 // published by a workgroup that waits for the others).
-int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, int* nchunk_out, size_t* dyn_out,
+int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, bool kvq, int* nchunk_out, size_t* dyn_out,
               int* listcap_out) {
     if (d.R < 2 || d.R > 255 || cus < 1) return 0;
     const int hbs = d.units() * ((d.R + kHB - 1) / kHB);
@@ -1064,8 +1096,14 @@ int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, int* nchunk
         return true;
     };
     if (fx) {
+        if (kvq) return 0;
         for (const int t : kStepFx)
             if (fits(t, 0)) return kStepFxCode + t * 100;
+        return 0;
+    }
+    if (kvq) {
+        for (const auto& tt : kStepQ2)
+            if (fits(tt[0] + tt[1], tt[1])) return tt[0] * 100 + tt[1];
         return 0;
     }
     for (const auto& tt : kStepT)
@@ -1109,11 +1147,12 @@ static hipError_t launch_step_t(const Dims& d, int T, int nchunk, size_t dyn, co
     auto qp = static_cast<const uint16_t*>(q);
     auto Kp = static_cast<const uint16_t*>(K);
     auto Vp = static_cast<const uint16_t*>(V);
-#define SIK_STEP(TV, TLV) SIK_STEP_(TV * 100 + TLV, TV, TLV, false)
-#define SIK_STEP_FX(TV) SIK_STEP_(kStepFxCode + TV * 100, TV, 0, true)
-#define SIK_STEP_(CODE, TV, TLV, FXV)                                                                           \
+#define SIK_STEP(TV, TLV) SIK_STEP_(TV * 100 + TLV, TV, TLV, false, false)
+#define SIK_STEP_Q2(TV, TLV) SIK_STEP_(kStepQ2Code + TV * 100 + TLV, TV, TLV, false, true)
+#define SIK_STEP_FX(TV) SIK_STEP_(kStepFxCode + TV * 100, TV, 0, true, false)
+#define SIK_STEP_(CODE, TV, TLV, FXV, Q2V)                                                                      \
     case CODE: {                                                                                                \
-        auto kern = step_kernel<DT, ODT, TV, TLV, FXV>;                                                           \
+        auto kern = step_kernel<DT, ODT, TV, TLV, FXV, Q2V>;                                                      \
         static std::atomic<size_t> allowed{0};                                                                  \
         if (dyn > allowed.load(std::memory_order_relaxed)) {                                                    \
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                       \
@@ -1125,7 +1164,8 @@ static hipError_t launch_step_t(const Dims& d, int T, int nchunk, size_t dyn, co
         return launch_kernel(kern, grid, kStepThreads, s, qp, codebook, codes, dims0, dims1, d.Lmax, seq_len, Kp, Vp, \
                              a, dyn);                                                                           \
     }
-    switch (T) {
+    constexpr int kStepQ2Code = 200000;
+    switch (a.kvq ? kStepQ2Code + T : T) {
         SIK_STEP(1, 0)
         SIK_STEP(2, 0)
         SIK_STEP(3, 0)
@@ -1141,19 +1181,27 @@ static hipError_t launch_step_t(const Dims& d, int T, int nchunk, size_t dyn, co
         SIK_STEP_FX(12)
         SIK_STEP_FX(16)
         SIK_STEP_FX(20)
+        SIK_STEP_Q2(1, 0)
+        SIK_STEP_Q2(4, 0)
+        SIK_STEP_Q2(12, 0)
+        SIK_STEP_Q2(12, 4)
+        SIK_STEP_Q2(14, 4)
+        SIK_STEP_Q2(16, 4)
         default: return hipErrorInvalidValue;
     }
 #undef SIK_STEP
+#undef SIK_STEP_Q2
 #undef SIK_STEP_FX
 #undef SIK_STEP_
 }
 
 hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn, int listcap, const void* q,
                        const Append& ap, const float* codebook, const uint8_t* codes, int32_t* seq_len,
-                       const void* K, const void* V, int k, float scale, int spin_limit, int32_t* idx_out, void* out,
-                       hipStream_t s) {
+                       const void* K, const void* V, const void* kvq, const float* alpha, int k, float scale,
+                       int spin_limit, int32_t* idx_out, void* out, hipStream_t s) {
     StepArgs a{};
     a.k_new = ap.k_new, a.v_new = ap.v_new, a.Kw = ap.K, a.Vw = ap.V, a.mu = ap.mu, a.codes_w = ap.codes;
+    a.kvq = static_cast<const uint2*>(kvq), a.kvq_w = static_cast<uint2*>(ap.kvq), a.alpha = alpha;
     a.parthist = w.parthist, a.pool = w.cand, a.partial = w.partial, a.scores = w.scores, a.sync = w.sync;
     a.idx_out = idx_out, a.idx_ws = w.idx, a.out = out;
     a.sstride = w.sstride, a.k = k, a.spin_limit = spin_limit > 0 ? spin_limit : (1 << 20), a.listcap = listcap;

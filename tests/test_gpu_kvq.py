@@ -185,7 +185,12 @@ def test_attention_on_records_all_tokens_and_small_selections(oracle):
 
 
 # --------------------------------------------------------------------------- decode step on records
-def run_decode_q2_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0, seq_len=None, out_f32=True):
+# launches = 1: the one-launch step on records whenever its plan allows (the library picks it for large launches only)
+BOTH_PATHS = pytest.mark.parametrize("launches", [0, 1], ids=["auto", "one_launch"])
+
+
+def run_decode_q2_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0, seq_len=None, out_f32=True,
+                            launches=0):
     st = Q2State(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=offset_std,
                  out_dtype=torch.float32 if out_f32 else None)
     B, Hq, k = cfg.batch, cfg.n_q_heads, min(cfg.top_k, capacity)
@@ -199,9 +204,15 @@ def run_decode_q2_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0
         q, kn, vn = W.make_step_inputs(cfg, step)
         dkn = dev(kn, cfg.dtype) if append else None
         dvn = dev(vn, cfg.dtype) if append else None
-        sik.sik_decode_step_q2(st.layout, dev(q, cfg.dtype), dkn, dvn, kvq, st.dsl, st.dmu, dal, st.dcb, st.dcodes, k,
-                               0.0, out, idx, st.ws)
+        if launches == 0:
+            sik.sik_decode_step_q2(st.layout, dev(q, cfg.dtype), dkn, dvn, kvq, st.dsl, st.dmu, dal, st.dcb, st.dcodes,
+                                   k, 0.0, out, idx, st.ws)
+        else:
+            sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), k_new=dkn, v_new=dvn, kvq=kvq, alpha=dal,
+                                   seq_len=st.dsl, mu=st.dmu, codebook=st.dcb, codes=st.dcodes, k=k, out=out,
+                                   idx_out=idx, workspace=st.ws, launches=launches)
         sync()
+        assert sik.sik_workspace_status(st.ws) == 0
         ref_out, ref_idx = oracle.decode_step_q2(q, kn if append else None, vn if append else None, cfg.dtype, sl,
                                                  st.mu, st.alpha, st.cb, codes, qkv, k)
         assert np.array_equal(st.dsl.cpu().numpy(), sl)
@@ -220,43 +231,51 @@ def run_decode_q2_and_check(oracle, cfg, capacity, steps, append, offset_std=0.0
     return total_diff
 
 
-def test_decode_q2_c1_full(oracle):
-    run_decode_q2_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=2, append=False)
+@BOTH_PATHS
+def test_decode_q2_c1_full(oracle, launches):
+    run_decode_q2_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=2, append=False, launches=launches)
 
 
-def test_decode_q2_c1_16bit_out(oracle):
-    run_decode_q2_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=1, append=False, out_f32=False)
+@BOTH_PATHS
+def test_decode_q2_c1_16bit_out(oracle, launches):
+    run_decode_q2_and_check(oracle, W.CONFIGS["C1"], capacity=4096, steps=1, append=False, out_f32=False, launches=launches)
 
 
-def test_decode_q2_c2_shape_reduced(oracle):
+@BOTH_PATHS
+def test_decode_q2_c2_shape_reduced(oracle, launches):
     run_decode_q2_and_check(oracle, cfg_small("C2", context=8192, top_k=256), capacity=8192, steps=2, append=False,
-                            offset_std=1.0)
+                            offset_std=1.0, launches=launches)
 
 
-def test_decode_q2_c3_shape_reduced_with_append(oracle):
+@BOTH_PATHS
+def test_decode_q2_c3_shape_reduced_with_append(oracle, launches):
     run_decode_q2_and_check(oracle, cfg_small("C3", context=9000, top_k=300), capacity=9004, steps=3, append=True,
-                            offset_std=1.0)
+                            offset_std=1.0, launches=launches)
 
 
-def test_decode_q2_c4_shape_reduced_ragged_batch(oracle):
+@BOTH_PATHS
+def test_decode_q2_c4_shape_reduced_ragged_batch(oracle, launches):
     run_decode_q2_and_check(oracle, cfg_small("C4", batch=4, context=2048, top_k=512), capacity=2050, steps=1,
-                            append=True, seq_len=[2048, 1, 511, 700])
+                            append=True, seq_len=[2048, 1, 511, 700], launches=launches)
 
 
-def test_decode_q2_c5_shape_reduced_gqa8_fp16(oracle):
+@BOTH_PATHS
+def test_decode_q2_c5_shape_reduced_gqa8_fp16(oracle, launches):
     cfg = cfg_small("C5", batch=2, n_kv_heads=2, n_q_heads=16, context=6000, top_k=1536, dtype="fp16")
-    run_decode_q2_and_check(oracle, cfg, capacity=6016, steps=3, append=True)
+    run_decode_q2_and_check(oracle, cfg, capacity=6016, steps=3, append=True, launches=launches)
 
 
-def test_decode_q2_dense_selection_and_k_above_context(oracle):
-    run_decode_q2_and_check(oracle, cfg_small("C2", context=20000, top_k=20000), capacity=20000, steps=1, append=False)
+@BOTH_PATHS
+def test_decode_q2_dense_selection_and_k_above_context(oracle, launches):
+    run_decode_q2_and_check(oracle, cfg_small("C2", context=20000, top_k=20000), capacity=20000, steps=1, append=False, launches=launches)
     run_decode_q2_and_check(oracle, cfg_small("C2", n_kv_heads=2, n_q_heads=8, context=700, top_k=1024),
-                            capacity=1100, steps=1, append=True)
+                            capacity=1100, steps=1, append=True, launches=launches)
 
 
-def test_decode_q2_empty_and_single_token_sequences(oracle):
+@BOTH_PATHS
+def test_decode_q2_empty_and_single_token_sequences(oracle, launches):
     cfg = cfg_small("C2", batch=3, n_kv_heads=2, n_q_heads=4, context=300, top_k=16)
-    run_decode_q2_and_check(oracle, cfg, capacity=320, steps=2, append=True, seq_len=[0, 1, 300])
+    run_decode_q2_and_check(oracle, cfg, capacity=320, steps=2, append=True, seq_len=[0, 1, 300], launches=launches)
 
 
 def test_decode_q2_graph_replay_and_profiled(oracle):
