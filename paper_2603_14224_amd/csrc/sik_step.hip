@@ -110,6 +110,7 @@ struct StepArgs {
     int32_t* idx_ws;     // [rows][k]  index rows when the caller passes no idx_out (radix winners only)
     void* out;
     int sstride, k, spin_limit, listcap;
+    int k_per_mille;     // > 0: the budget of a sequence is min(k, max(1, ceil(L * k_per_mille / 1000)))
     float scale_log2e;
 };
 
@@ -446,7 +447,10 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     SIK_TL(39);
     // ---- 2. histograms of the head block's chunks -----------------------------------------------------------------
     const int Lc = L;                 // tokens that compete
-    const int kk = min(a.k, Lc);      // picks per head
+    const int kb = a.k_per_mille > 0
+                       ? min(a.k, max(1, static_cast<int>((static_cast<int64_t>(Lc) * a.k_per_mille + 999) / 1000)))
+                       : a.k;
+    const int kk = min(kb, Lc);  // picks per head
     bool alive = true;
     if (nact > 1) {
         if (tid < kHistWords)
@@ -1197,9 +1201,10 @@ static hipError_t launch_step_t(const Dims& d, int T, int nchunk, size_t dyn, co
 
 hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn, int listcap, const void* q,
                        const Append& ap, const float* codebook, const uint8_t* codes, int32_t* seq_len,
-                       const void* K, const void* V, const void* kvq, const float* alpha, int k, float scale,
-                       int spin_limit, int32_t* idx_out, void* out, hipStream_t s) {
+                       const void* K, const void* V, const void* kvq, const float* alpha, int k, int k_per_mille,
+                       float scale, int spin_limit, int32_t* idx_out, void* out, hipStream_t s) {
     StepArgs a{};
+    a.k_per_mille = k_per_mille;
     a.k_new = ap.k_new, a.v_new = ap.v_new, a.Kw = ap.K, a.Vw = ap.V, a.mu = ap.mu, a.codes_w = ap.codes;
     a.kvq = static_cast<const uint2*>(kvq), a.kvq_w = static_cast<uint2*>(ap.kvq), a.alpha = alpha;
     a.parthist = w.parthist, a.pool = w.cand, a.partial = w.partial, a.scores = w.scores, a.sync = w.sync;

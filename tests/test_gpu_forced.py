@@ -206,8 +206,9 @@ def test_forced_argument_errors(oracle):
 
 
 # --------------------------------------------------------------------------- budgets that follow the context
+@pytest.mark.parametrize("launches", [0, 1], ids=["auto", "one_launch"])
 @pytest.mark.parametrize("per_mille,n_forced", [(75, 0), (75, 16), (4, 16), (1000, 0)])
-def test_budget_per_mille_ragged_batch(oracle, per_mille, n_forced):
+def test_budget_per_mille_ragged_batch(oracle, per_mille, n_forced, launches):
     # 7.5 % of each sequence's own length; 0.4 %: the forced tokens fill (or exceed) the budget; 100 %: capped by k
     cfg = cfg_small("C2", batch=4, n_kv_heads=2, n_q_heads=8, context=6000, top_k=500)
     st = GpuState(cfg, oracle, capacity=6000, seq_len=[6000, 2500, 40, 0], offset_std=0.5, out_dtype=torch.float32)
@@ -219,7 +220,8 @@ def test_budget_per_mille_ragged_batch(oracle, per_mille, n_forced):
     idx = torch.empty(4, 8, 500, dtype=torch.int32, device="cuda")
     sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
                            codebook=st.dcb, codes=st.dcodes, k=500, k_per_mille=per_mille, out=out, idx_out=idx,
-                           forced_idx=torch.from_numpy(forced).cuda(), workspace=st.ws)
+                           forced_idx=torch.from_numpy(forced).cuda() if n_forced else None, workspace=st.ws,
+                           launches=launches)   # (a forced set always runs as two launches)
     sync()
     sl = st.sl.copy()
     ref_out, ref_idx = oracle.decode_step_forced(q, None, None, st.K, st.V, cfg.dtype, sl, st.mu, st.cb, st.codes, 500,
