@@ -112,7 +112,7 @@ int sik_workspace_init(const sik_layout *layout, int32_t k, void *workspace, siz
 
 /* Waits for `stream` and copies the workspace's status word to *status (host pointer).  0: every decode step on this
  * workspace since its initialisation completed.  Non-zero: a workgroup of a one-launch step waited for its peers
- * beyond the spin limit and left (bit 0: histogram exchange, bit 1: publishing the appended length); that step's
+ * beyond the spin limit and left (bit 0: the exchange of the chunk histograms, the only wait there is); that step's
  * outputs are invalid, no kernel hangs, and the workspace must be initialised again.  This can only happen when the
  * step's workgroups were not all resident (another process occupying the compute units for seconds). */
 int sik_workspace_status(const void *workspace, void *stream, uint32_t *status);

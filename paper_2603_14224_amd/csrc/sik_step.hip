@@ -3,7 +3,8 @@
 // and Preliminaries"), with the scores never leaving the chip.
 //
 // Workgroup (1024 threads, one per compute unit) = (sequence, KV head, block of up to 4 query heads, token chunk
-// of 1024 T tokens).  A thread scores T tokens for the block's heads and KEEPS the fp32 scores in registers.
+// of 1024 (T + TL) tokens).  A thread scores T + TL tokens for the block's heads and KEEPS the fp32 scores on the
+// chip: T tokens' in registers, TL tokens' in LDS.
 //   1. tables in LDS, scan of the chunk's codes, one 512-bin LDS histogram per head (as in the scoring kernel);
 //   2. chunks of one head block exchange their histograms through memory: publish, arrive on a counter, wait
 //      until all active chunks arrived (a BOUNDED spin: on give-up the status word of the workspace is set and the
@@ -11,14 +12,17 @@
 //      exchange and no wait;
 //   3. every workgroup derives the head's threshold bin, classifies its scores from the registers, compacts the
 //      selected tokens of each head into an LDS list (deterministic order) and gathers them at once: 16
-//      wavefronts = (head, slice of the list);
-//   4. chunk partials (m, l, o[D]) and the threshold-bin candidates go to memory; the last workgroup of a head to
-//      arrive ranks the candidates exactly (score desc, index asc), attends the winners, merges the partials and
-//      writes the row.  With one chunk per head block all of this stays inside the workgroup.
-// The launch must be co-resident when workgroups wait for each other (more than one chunk, or an appended row
-// whose new length is published at the end): the host only takes this path when the grid fits the compute units.
-// Every counter the kernel uses is left at zero by its last user, so the workspace's sync words need zeroing only
-// once (sik_workspace_init).
+//      wavefronts = (head, slice of the list); with one chunk the threshold bin's candidates are ranked before
+//      the gather and join the list;
+//   4. several chunks: chunk partials (m, l, o[D]) and the threshold-bin candidates go to memory; the last
+//      workgroup of a head to arrive ranks the candidates exactly (score desc, index asc), attends the winners,
+//      merges the partials and writes the row.
+// Variants: KVQ gathers 128-byte records of the 2-bit cache and dequantises them in registers; FX runs the scan in
+// 16-bit fixed point and gives exact scores only to the tokens within a guard band of the threshold bin.
+// The launch must be co-resident when a head block has more than one chunk (its workgroups wait for each other):
+// the host only takes this path when the grid fits the compute units.  An appended row needs no wait: its new
+// length is published by the last workgroup of the sequence to leave.  Every counter the kernel uses is left at
+// zero by its last user, so the workspace's sync words need zeroing only once (sik_workspace_init).
 #include <atomic>
 #include <climits>
 
@@ -211,11 +215,20 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         t_new = L;
         L += 1;
     }
-    // The new length is published at the end of the launch by the sequence's last head; it waits until every
-    // workgroup of the sequence has read the old one (counted here).
-    if (appended && tid == 0) atomic_add_u32(&ssync[0], 1u);
+    // The new length is published by the LAST workgroup of the sequence to leave the kernel (a counter every
+    // workgroup adds to on its way out, whichever way): by then each of them has read the old one, and nobody waits.
+    auto leave = [&]() {
+        if (appended && tid == 0 &&
+            atomic_add_u32(&ssync[0], 1u) == static_cast<uint32_t>(Hkv) * nhb * nchunk - 1u) {
+            seq_len[b] = L;
+            st_agent(&ssync[0], 0u);
+        }
+    };
     const int nact = L > 0 ? (L + kChunk - 1) / kChunk : 1;
-    if (c >= nact) return;  // no token of this chunk is valid (chunk 0 always runs: it owns the outputs of L = 0)
+    if (c >= nact) {  // no token of this chunk is valid (chunk 0 always runs: it owns the outputs of L = 0)
+        leave();
+        return;
+    }
     const int end = min(L, start + kChunk);
     const bool holds_new = t_new >= start && t_new < start + kChunk;
     if (holds_new && tid < 16) {
@@ -463,7 +476,10 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         SIK_TL(40);
         for (int e = tid; e < kHB * kBins; e += kStepThreads) lhist[e] = 0u;
         alive = bounded_wait(&rsync[3], static_cast<uint32_t>(nact), a.spin_limit, status, 1u, &s_flag);
-        if (!alive) return;  // uniform: the launch is lost, the status word says so
+        if (!alive) {  // uniform: the launch is lost, the status word says so
+            leave();
+            return;
+        }
         SIK_TL(41);
         if (g < nh) {
             const uint32_t* prow = a.parthist + (row0 + g) * nchunk * kHistWords;
@@ -833,7 +849,10 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         mine = g < nh && s_last[g] != 0;
         bool any = false;
         for (int s = 0; s < nh; ++s) any |= s_last[s] != 0;
-        if (!any) return;  // uniform
+        if (!any) {  // uniform
+            leave();
+            return;
+        }
     }
 
     const size_t row = row0;  // (timeline marks of the workgroup that finishes the first head block)
@@ -1026,24 +1045,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         st_agent(&rsync[g * kSyncPerRow + 2], 0u);
         if (g == 0) st_agent(&rsync[3], 0u);
     }
-    // the last head of the sequence to finish publishes the new length, once every workgroup of the sequence has
-    // read the old one
-    if (appended) {
-        __syncthreads();
-        if (tid < nh) s_last[tid] = (nact > 1 ? s_last[tid] != 0 : true) &&
-                                    atomic_add_u32(&ssync[1], 1u) == static_cast<uint32_t>(Hq) - 1u;
-        __syncthreads();
-        bool pub = false;
-        for (int s = 0; s < nh; ++s) pub |= s_last[s] != 0;
-        if (pub) {  // uniform
-            const uint32_t all = static_cast<uint32_t>(Hkv) * nhb * nchunk;
-            if (bounded_wait(&ssync[0], all, a.spin_limit, status, 2u, &s_flag) && tid == 0) {
-                seq_len[b] = L;
-                st_agent(&ssync[0], 0u);
-                st_agent(&ssync[1], 0u);
-            }
-        }
-    }
+    leave();
 }
 
 
@@ -1079,8 +1081,7 @@ static size_t step_dyn_bytes(int chunk, int TL, int k, int* listcap) {
 
 // Tokens per thread of the one-launch step for this layout, or 0 when it does not apply: the smallest T whose
 // grid fits the compute units (workgroups of a head block wait for each other, so they must all be resident);
-// a single chunk per head block needs no wait and may exceed them, unless a row is appended (its new length is
-// published by a workgroup that waits for the others).
+// a single chunk per head block needs no wait and may exceed them.
 int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, bool kvq, int* nchunk_out, size_t* dyn_out,
               int* listcap_out) {
     if (d.R < 2 || d.R > 255 || cus < 1) return 0;
@@ -1090,7 +1091,7 @@ int step_plan(const Dims& d, int k, bool appended, int cus, bool fx, bool kvq, i
         const int nchunk = (d.Lmax + chunk - 1) / chunk;
         if (nchunk > kMaxChunks || nchunk > step_max_chunks(d)) return false;
         const bool resident = static_cast<int64_t>(hbs) * nchunk <= cus;
-        if (!resident && !(nchunk == 1 && !appended)) return false;
+        if (!resident && nchunk != 1) return false;
         int listcap;
         const size_t dyn = step_dyn_bytes(chunk, tl, k, &listcap);
         if (dyn > kStepLdsBudget) return false;

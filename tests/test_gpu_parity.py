@@ -539,6 +539,32 @@ def test_profiled_decode_step_same_result_and_five_intervals(oracle):
     assert sik.sik_workspace_status(st.ws) == 0
 
 
+def test_one_launch_append_with_more_workgroups_than_compute_units(oracle):
+    # one chunk per head block: nothing waits, so the grid (40 x 8 = 320 workgroups) may exceed the compute units even
+    # when a row is appended; the last workgroup of a sequence to leave publishes its new length
+    cfg = cfg_small("C4", batch=40, n_kv_heads=8, n_q_heads=32, context=3000, top_k=128, seed=12)
+    st = GpuState(cfg, oracle, capacity=3008, seq_len=[3000 - 7 * (i % 5) for i in range(40)], out_dtype=torch.float32)
+    assert sik.sik_plan_info(st.layout)[7] > 0
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    dq, dkn, dvn = dev(q, cfg.dtype), dev(kn, cfg.dtype), dev(vn, cfg.dtype)
+    res = {}
+    for launches in (2, 1):
+        dK, dV, dcodes = st.dK.clone(), st.dV.clone(), st.dcodes.clone()
+        dsl = torch.from_numpy(st.sl.copy()).cuda()
+        out = torch.empty(40, 32, 128, device="cuda")
+        idx = torch.empty(40, 32, 128, dtype=torch.int32, device="cuda")
+        sik.sik_decode_step_ex(st.layout, q=dq, k_new=dkn, v_new=dvn, K=dK, V=dV, seq_len=dsl, mu=st.dmu,
+                               codebook=st.dcb, codes=dcodes, k=128, out=out, idx_out=idx, workspace=st.ws,
+                               launches=launches)
+        sync()
+        assert sik.sik_workspace_status(st.ws) == 0
+        res[launches] = (out, torch.sort(idx, dim=-1).values, dK, dV, dcodes, dsl)
+    a, b = res[2], res[1]
+    assert np.array_equal(b[5].cpu().numpy(), st.sl + 1) and torch.equal(a[5], b[5])
+    assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2]) and torch.equal(a[3], b[3]) and torch.equal(a[4], b[4])
+    assert float((a[0] - b[0]).abs().max()) <= 2e-5 * float(a[0].abs().max())
+
+
 def test_one_launch_bounded_wait_gives_up_and_reports(oracle):
     # The one-launch step waits, inside the kernel, for the histograms of a head's other chunks.  The wait is bounded:
     # with a spin limit of one poll it gives up (forced from the host, every workgroup still runs to its end), the
