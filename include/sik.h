@@ -179,8 +179,9 @@ int sik_decode_step(const sik_layout *layout, const void *q, const void *k_new, 
  * workloads of one sequence, 32K and 128K tokens, fit; large batches do not).  The call allocates nothing and
  * frees nothing.  Every call on one GPU shares that GPU's buffer, whatever the stream or thread: calls that
  * overlap in time on one GPU race; calls on one stream are ordered and safe.  The buffer keeps the previous
- * call's contents; the step clears what it needs cleared itself.  The first call on a GPU looks the buffer's
- * address up (hipGetSymbolAddress) and must therefore be made outside stream capture. */
+ * call's contents; the step clears what it needs cleared itself, and always runs as separate scoring and selection
+ * + attention launches (no workgroup waits for another, so the buffer needs no initialisation).  The first call on
+ * a GPU looks the buffer's address up (hipGetSymbolAddress) and must therefore be made outside stream capture. */
 #define SIK_STATIC_SCRATCH_BYTES (32u << 20)
 int sik_decode_step_static(const sik_layout *layout, const void *q, const void *k_new, const void *v_new, void *K,
                            void *V, int32_t *seq_len, const float *mu, const float *codebook, uint8_t *codes,

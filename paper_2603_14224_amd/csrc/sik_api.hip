@@ -471,8 +471,12 @@ int sik_decode_step_static(const sik_layout* layout, const void* q, const void* 
     if (carve(d, k, nullptr).total_bytes > SIK_STATIC_SCRATCH_BYTES) return SIK_ERR_STATIC_LIMIT;
     void* ws = static_scratch();
     if (ws == nullptr) return SIK_ERR_LAUNCH;
+    // always the two launches: nothing in them waits on another workgroup, so the shared buffer never needs the
+    // one-time initialisation (and re-initialisation after a give-up) that the one-launch step asks of a workspace
+    StepOptions opt{};
+    opt.launches = 2;
     return decode_step_impl(layout, q, k_new, v_new, K, V, nullptr, nullptr, seq_len, mu, codebook, codes, k,
-                            softmax_scale, out, idx_out, ws, SIK_STATIC_SCRATCH_BYTES, stream, nullptr);
+                            softmax_scale, out, idx_out, ws, SIK_STATIC_SCRATCH_BYTES, stream, nullptr, opt);
 }
 
 int sik_decode_step_profiled(const sik_layout* layout, const void* q, const void* k_new, const void* v_new,
