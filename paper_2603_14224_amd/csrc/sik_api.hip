@@ -363,9 +363,8 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
     // (by default only for large launches: with one sequence the histogram exchange between the many chunks of a
     // head and the heavier barriers of 1024-thread workgroups cost more than the launch boundary they save)
     const bool large = static_cast<int64_t>(d.units()) * ((d.R + 3) / 4) * d.Lmax > (2 << 20);
-    const bool one_launch = opt.n == 0 && !opt.group_shared && opt.launches != 2 &&
-                            (large || opt.launches != 0);
-    const bool first_pass_16 = opt.launches == 3 && !kvq;
+    const bool one_launch = !opt.group_shared && opt.launches != 2 && (large || opt.launches != 0);
+    const bool first_pass_16 = opt.launches == 3 && !kvq && opt.n == 0;
     int step_T = 0;
     if (one_launch && first_pass_16)
         step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), true, false, &step_nchunk, &step_dyn,
@@ -378,8 +377,7 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
                         static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
         timed(3);
         e = done(3, launch_step(d, w, step_T, step_nchunk, step_dyn, step_listcap, q, k_new ? ap : Append{}, codebook,
-                                codes, seq_len, K, V, kvq, alpha, k, opt.k_per_mille, softmax_scale, opt.spin_limit, idx_out,
-                                out, s));
+                                codes, seq_len, K, V, kvq, alpha, k, opt, softmax_scale, idx_out, out, s));
     } else if (shared_unfused || !fused) {
         // prep (append + counters; skipped when nothing is appended: the scoring launch then clears the per-head
         // counters itself), scoring (on the summed query when the selection is shared), stand-alone selector (per

@@ -157,8 +157,8 @@ int device_compute_units();
 hipError_t launch_sync_init(const Dims& d, const Workspace& w, hipStream_t s);
 hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn_lds, int listcap, const void* q,
                        const Append& ap, const float* codebook, const uint8_t* codes, int32_t* seq_len,
-                       const void* K, const void* V, const void* kvq, const float* alpha, int k, int k_per_mille,
-                       float scale, int spin_limit, int32_t* idx_out, void* out, hipStream_t s);
+                       const void* K, const void* V, const void* kvq, const float* alpha, int k, const StepOptions& fo,
+                       float scale, int32_t* idx_out, void* out, hipStream_t s);
 size_t fused_cand_words(const Dims& d);
 hipError_t launch_fit(const Dims& d, const Workspace& w, const void* K, const void* V, const int32_t* seq_len,
                       float* mu, float* codebook, int32_t* counts, uint8_t* codes, float* alpha, void* kvq,

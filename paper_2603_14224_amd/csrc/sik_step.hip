@@ -104,12 +104,18 @@ struct StepArgs {
     const uint2* kvq;
     uint2* kvq_w;
     const float* alpha;
+    // forced-inclusion set of every KV head ("Full Precision Sink Tokens"): forced_idx [B, Hkv, n_forced], entries
+    // outside [0, L) name no token; with the 2-bit cache optionally 16-bit side rows fK, fV [B, Hkv, n_forced, D]
+    const int32_t* forced_idx;
+    const uint16_t* fK;
+    const uint16_t* fV;
+    int n_forced;
     // exchange areas
-    uint32_t* parthist;  // [rows][nchunk][kHistWords]
+    uint32_t* parthist;  // [rows][nchunk][kHistWords]  chunk histograms, two 16-bit counts per word
     uint32_t* pool;      // [rows][kCandCap][2]  threshold-bin candidates of a head: (key, index)
     float* partial;      // [rows][kMaxChunks][kPartStride]
     float* scores;       // [rows][sstride]  only written when a threshold bin is too crowded to rank
-    uint32_t* sync;      // status word, per-row and per-sequence counters (see launch_step)
+    uint32_t* sync;      // status word, per-row and per-sequence counters (kSyncHeader / PerRow / PerSeq)
     int32_t* idx_out;
     int32_t* idx_ws;     // [rows][k]  index rows when the caller passes no idx_out (radix winners only)
     void* out;
@@ -120,7 +126,7 @@ struct StepArgs {
 
 constexpr int kSyncHeader = 8;  // word 0: status bits
 constexpr int kSyncPerRow = 4;  // ticket, index-output reservation, candidate reservation, histogram arrivals
-constexpr int kSyncPerSeq = 2;  // workgroups that have read the length, heads finished
+constexpr int kSyncPerSeq = 2;  // workgroups of the sequence that have left the kernel; one spare word
 
 template <int DT, int ODT, int T, int TL, bool FX = false, bool KVQ = false>
 __global__ __launch_bounds__(kStepThreads) void step_kernel(
@@ -151,6 +157,9 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     __shared__ float sm[kStepWaves], sl[kStepWaves];
     __shared__ float sacc[kStepWaves][kD];
     __shared__ float pml[kHB][2][kMaxChunks];
+    __shared__ uint32_t fbits[20 * kStepThreads / 32];  // forced tokens of this chunk, one bit per token
+    __shared__ int32_t s_fidx[kMaxForced];              // forced tokens of the KV head, -1: names no token
+    __shared__ uint32_t s_fcnt;
 
     SIK_TL(36);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, p = lane & 15;
@@ -207,6 +216,9 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         m8[0] = m0.x, m8[1] = m0.y, m8[2] = m0.z, m8[3] = m0.w;
         m8[4] = m1.x, m8[5] = m1.y, m8[6] = m1.z, m8[7] = m1.w;
     }
+    const int n_forced = a.n_forced;
+    int fi = -1;  // forced token of this KV head that thread tid looks after
+    if (tid < n_forced) fi = a.forced_idx[static_cast<size_t>(unit) * n_forced + tid];
     int L = seq_len[b];
     L = L < 0 ? 0 : (L > Lmax ? Lmax : L);
     const bool appended = a.k_new != nullptr;
@@ -231,10 +243,10 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     }
     const int end = min(L, start + kChunk);
     const bool holds_new = t_new >= start && t_new < start + kChunk;
-    if (holds_new && tid < 16) {
+    if ((holds_new || (n_forced > 0 && c == 0 && t_new >= 0)) && tid < 16) {
         // Every head block whose chunk holds the new row stores it (identical bytes), so that the gather below
         // never waits for another workgroup's store; write-through, because the last workgroup of a head may
-        // gather it from another XCD.
+        // gather it from another XCD.  Chunk 0 stores it too when there is a forced set, which may name it.
         float f[8];
         widen8<DT>(knew, f);
         uint32_t byte = 0;
@@ -254,6 +266,21 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             st_agent4(reinterpret_cast<uint4*>(a.Vw + rowi * kD) + tid, vnew);
         }
         if (hb == 0) a.codes_w[rowi * kCodeBytes + tid] = static_cast<uint8_t>(byte);
+    }
+    // Forced tokens take part in the attention of every head of the KV head whatever their scores and do not
+    // compete: they are left out of the histograms and of the classification (one LDS bit per token of the chunk),
+    // the budget and the competing population shrink by their number, and chunk 0 attends them.
+    int nfv = 0, fpos = 0;
+    if (n_forced > 0) {  // uniform
+        for (int e = tid; e < kChunk / 32; e += kStepThreads) fbits[e] = 0u;
+        const bool fv = fi >= 0 && fi < L;
+        fi = fv ? fi : -1;
+        if (tid < kMaxForced) s_fidx[tid] = fi;
+        const uint64_t bf = __ballot(fv);
+        if (tid == 0) s_fcnt = static_cast<uint32_t>(__popcll(bf));  // (the set spans the first two wavefronts)
+        nfv = __syncthreads_count(fv ? 1 : 0);
+        fpos = __popcll(bf & ((1ull << lane) - 1ull)) + (wv == 1 ? static_cast<int>(s_fcnt) : 0);
+        if (fv && fi >= start && fi < end) atomicOr(&fbits[(fi - start) >> 5], 1u << ((fi - start) & 31));
     }
     __syncthreads();
     SIK_TL(37);
@@ -369,6 +396,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     float4* const lsc = reinterpret_cast<float4*>(dyn + lists_bytes + static_cast<size_t>(kHB) * kCandCap * 8);
     float sc[T][kHB];
     uint32_t fx[FX ? TT : 1][2];  // FX: the 16-bit sums of a token, heads 0 | 1 << 16 and 2 | 3 << 16
+    uint32_t livemask = 0u;       // FX: token slots that hold a competing token
 #pragma unroll
     for (int it = 0; it < TT; ++it) {
         const int tok = start + it * kStepThreads + tid;
@@ -378,6 +406,8 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             cur[it & 1] = i < end ? cp[i] : make_uint4(0u, 0u, 0u, 0u);
         }
         if (tok == t_new) code = *reinterpret_cast<const uint4*>(newcode);
+        // (token slot it of thread tid is token it * 1024 + tid of the chunk)
+        const bool live = tok < end && !(n_forced > 0 && ((fbits[it * 32 + (tid >> 5)] >> (tid & 31)) & 1u));
         if constexpr (FX) {
             // 8-byte entries, two packed 16-bit adds per lookup: half the adds and half the LDS bytes of the
             // fp32 scan; the sums only place the token in a bin (exact scores follow for the band, below)
@@ -399,7 +429,8 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             const uint32_t w01 = __builtin_bit_cast(uint32_t, a01), w23 = __builtin_bit_cast(uint32_t, a23);
             fx[it][0] = w01;
             fx[it][1] = w23;
-            if (tok < end) {
+            livemask |= (live ? 1u : 0u) << it;
+            if (live) {
 #pragma unroll
                 for (int s = 0; s < kHB; ++s) {
                     const uint32_t w = s < 2 ? w01 : w23;
@@ -447,10 +478,11 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         }
 #pragma unroll
         for (int s = 0; s < kHB; ++s) {
-            if (tok < end && s < nh)
+            if (live && s < nh)
                 atomicAdd(&lhist[s * kBins + bin_of_coord(bin_coord_shifted(acc[s], bscale[s], bshift[s]))], 1u);
-            // slots at or beyond the sequence's end hold NaN: every comparison of the classification fails
-            acc[s] = tok < end ? acc[s] : __builtin_nanf("");
+            // slots at or beyond the sequence's end and forced tokens hold NaN: every comparison of the
+            // classification fails
+            acc[s] = live ? acc[s] : __builtin_nanf("");
             if (it < T) sc[it < T ? it : 0][s] = acc[s];
         }
         if (it >= T) lsc[(it - T) * kStepThreads + tid] = make_float4(acc[0], acc[1], acc[2], acc[3]);
@@ -459,11 +491,11 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
 
     SIK_TL(39);
     // ---- 2. histograms of the head block's chunks -----------------------------------------------------------------
-    const int Lc = L;                 // tokens that compete
+    const int Lc = L - nfv;           // tokens that compete
     const int kb = a.k_per_mille > 0
-                       ? min(a.k, max(1, static_cast<int>((static_cast<int64_t>(Lc) * a.k_per_mille + 999) / 1000)))
+                       ? min(a.k, max(1, static_cast<int>((static_cast<int64_t>(L) * a.k_per_mille + 999) / 1000)))
                        : a.k;
-    const int kk = min(kb, Lc);  // picks per head
+    const int kk = max(0, min(kb - nfv, Lc));  // dynamic picks per head (the forced tokens may use up the budget)
     bool alive = true;
     if (nact > 1) {
         if (tid < kHistWords)
@@ -511,7 +543,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         const uint32_t own = c0 + c1;
         uint32_t cum = group_suffix_sum(own, lds4[g]) - own;  // tokens in bins owned by higher threads
         const uint32_t ukk = static_cast<uint32_t>(kk);
-        if (g < nh && kk < Lc) {
+        if (g < nh && kk > 0 && kk < Lc) {
             if (cum < ukk && ukk <= cum + c1) bstar = 2 * gt + 1, cgt = static_cast<int>(cum), nb = static_cast<int>(c1);
             cum += c1;
             if (cum < ukk && ukk <= cum + c0) bstar = 2 * gt, cgt = static_cast<int>(cum), nb = static_cast<int>(c0);
@@ -583,14 +615,11 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
                 gmask[s] |= (f6 >= thr_c[s] ? 1u : 0u) << it;
             }
         }
-        // token slots at or beyond the sequence's end are in no mask
-        const int nv = end - start - tid;
-        const int nit = nv <= 0 ? 0 : min((nv + kStepThreads - 1) / kStepThreads, TT);
-        const uint32_t vmask = nit >= 32 ? 0xffffffffu : (1u << nit) - 1u;
+        // token slots at or beyond the sequence's end, and forced tokens, are in no mask
 #pragma unroll
         for (int s = 0; s < kHB; ++s) {
-            smask[s] &= vmask;
-            gmask[s] &= vmask;
+            smask[s] &= livemask;
+            gmask[s] &= livemask;
         }
         // a band too crowded to rank: the exact scores of its members go to memory for the radix selection of the
         // last phase, minus infinity for everything else
@@ -626,7 +655,8 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             const float x = bin_coord(v4[s], blo[s], bscale[s]);
             smask[s] |= (x >= hi_f[s] ? 1u : 0u) << it;
             gmask[s] |= (x >= lo_f[s] ? 1u : 0u) << it;
-            if (crowded[s] && tok < end) st_agent(&a.scores[(row0 + s) * a.sstride + tok], v4[s]);
+            if (crowded[s] && tok < end)  // (a forced token's NaN goes out as minus infinity: it does not compete)
+                st_agent(&a.scores[(row0 + s) * a.sstride + tok], v4[s] == v4[s] ? v4[s] : -INFINITY);
         }
     }
     }
@@ -788,6 +818,30 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
             attend_list<DT, true>(fetch, n, gj * 16, nslice * 16, Kp, Vp, qraw, a.scale_log2e, Lmax, st);
         else
             attend_list<DT, false>(fetch, n, gj * 16, nslice * 16, Kp, Vp, qraw, a.scale_log2e, Lmax, st);
+        // chunk 0 also attends the forced tokens of the KV head: from the cache like any other row, or, given as
+        // 16-bit side rows beside the 2-bit cache, with each logit shifted by -q . mu (the records they share the
+        // softmax with hold the centred key)
+        if (n_forced > 0 && c == 0) {
+            if (KVQ && a.fK != nullptr) {
+                float qf[8];
+                widen8<DT>(qraw, qf);
+                const float4 m0 = reinterpret_cast<const float4*>(a.mu + static_cast<size_t>(unit) * kD)[2 * p];
+                const float4 m1 = reinterpret_cast<const float4*>(a.mu + static_cast<size_t>(unit) * kD)[2 * p + 1];
+                const float mu_dot = qf[0] * m0.x + qf[1] * m0.y + qf[2] * m0.z + qf[3] * m0.w + qf[4] * m1.x +
+                                     qf[5] * m1.y + qf[6] * m1.z + qf[7] * m1.w;
+                const float zbias = -row16_sum(mu_dot) * a.scale_log2e;
+                attend_list<DT, false>([&](int j) { return s_fidx[j] >= 0 ? j : -1; }, n_forced, gj * 16, nslice * 16,
+                                       reinterpret_cast<const uint4*>(a.fK + static_cast<size_t>(unit) * n_forced * kD),
+                                       reinterpret_cast<const uint4*>(a.fV + static_cast<size_t>(unit) * n_forced * kD),
+                                       qraw, a.scale_log2e, n_forced, st, zbias);
+            } else if constexpr (KVQ) {
+                attend_list_q2([&](int j) { return s_fidx[j]; }, n_forced, gj * 32, nslice * 32, Rp,
+                               q2_prepare<DT>(qraw, al8), a.scale_log2e, Lmax, st);
+            } else {
+                attend_list<DT, false>([&](int j) { return s_fidx[j]; }, n_forced, gj * 16, nslice * 16, Kp, Vp, qraw,
+                                       a.scale_log2e, Lmax, st);
+            }
+        }
     }
     SIK_TL(44);
     // the four 16-lane rows of a wavefront hold four partial softmaxes; then the wavefronts of a head
@@ -817,12 +871,17 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     const int cgt_g = g < nh ? sthr[g][1] : 0, nb_g = g < nh ? sthr[g][2] : 0, bstar_g = g < nh ? sthr[g][0] : kBins;
     const bool ranked_g = nb_g <= kCandCap;
     const int need_g = g < nh ? kk - min(cgt_g, kk) : 0;
-    int32_t* const orow = (a.idx_out && g < nh) ? a.idx_out + (row0 + g) * a.k : nullptr;
+    // index row of head g: the forced tokens first (written by chunk 0), then the selected ones, then the winners
+    // among the candidates; orow starts behind the forced ones and has kfree slots
+    int32_t* const orow = (a.idx_out && g < nh) ? a.idx_out + (row0 + g) * a.k + nfv : nullptr;
+    const int kfree = a.k - nfv;
+    if (a.idx_out && c == 0 && tid < n_forced && fi >= 0)
+        for (int s = 0; s < nh; ++s) a.idx_out[(row0 + s) * a.k + fpos] = fi;
     if (orow) {  // the selected tokens of this chunk (any order inside the row)
         const uint32_t base = nact > 1 ? wcnt[g][0] : 0u;
         const int n = min(static_cast<int>(s_nsel[g]), a.listcap);
         for (int j = gt; j < n; j += kGroupThreads)
-            if (base + j < static_cast<uint32_t>(a.k)) orow[base + j] = start + static_cast<int>(lists[g * a.listcap + j]);
+            if (base + j < static_cast<uint32_t>(kfree)) orow[base + j] = start + static_cast<int>(lists[g * a.listcap + j]);
     }
     bool mine = g < nh;  // does this workgroup finish head g?
     float* const prow = a.partial + ((row0 + g) * kMaxChunks) * kPartStride;
@@ -860,7 +919,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     if (fast) {  // uniform: everything selected has been gathered, the partial of step 3 is the result
         if (g < nh && gt < kD) store_out<ODT>(a.out, (row0 + g) * kD + gt, Lsum > 0.0f ? o / Lsum : 0.0f);
         if (orow)
-            for (int j = kk + gt; j < a.k; j += kGroupThreads) orow[j] = -1;
+            for (int j = kk + gt; j < kfree; j += kGroupThreads) orow[j] = -1;
         SIK_TL_ANY(47);
     } else {
     SIK_TL_ANY(46);
@@ -949,7 +1008,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         const bool todo = (nact > 1 ? s_last[s] != 0 : true) && sthr[s][2] > kCandCap && sthr[s][0] >= 0 &&
                           sthr[s][0] < kBins && need_s > 0;
         if (todo) {  // uniform
-            int32_t* dst = (a.idx_out ? a.idx_out : a.idx_ws) + (row0 + s) * a.k + sthr[s][1];
+            int32_t* dst = (a.idx_out ? a.idx_out : a.idx_ws) + (row0 + s) * a.k + nfv + sthr[s][1];
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
             if constexpr (FX)
@@ -957,8 +1016,12 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
                                                          [](float v) { return v > -INFINITY; }, need_s, dst, lhist,
                                                          &lds4[0][0]);
             else
-                radix_select_in_bin<kStepThreads, true>(a.scores + (row0 + s) * a.sstride, L, blo[s], bscale[s],
-                                                        sthr[s][0], need_s, dst, lhist, &lds4[0][0]);
+                radix_select_members<kStepThreads, true>(
+                    a.scores + (row0 + s) * a.sstride, L,
+                    [lo = blo[s], sc_ = bscale[s], bst = sthr[s][0]](float v) {
+                        return v > -INFINITY && score_bin(v, lo, sc_) == bst;
+                    },
+                    need_s, dst, lhist, &lds4[0][0]);
             __threadfence_block();
             __syncthreads();
         }
@@ -968,7 +1031,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
     const bool radix_g = mine && need_g > 0 && !ranked_g && bstar_g >= 0 && bstar_g < kBins;
     if (mine && need_g > 0) {
         const uint4 qg = reinterpret_cast<const uint4*>(q + (row0 + g) * kD)[p];
-        const int32_t* gl = (a.idx_out ? a.idx_out : a.idx_ws) + (row0 + g) * a.k + cgt_g;
+        const int32_t* gl = (a.idx_out ? a.idx_out : a.idx_ws) + (row0 + g) * a.k + nfv + cgt_g;
         if constexpr (KVQ) {
             const Q2Query qq = q2_prepare<DT>(qg, al8);
             if (do_rank)
@@ -1035,7 +1098,7 @@ __global__ __launch_bounds__(kStepThreads) void step_kernel(
         store_out<ODT>(a.out, (row0 + g) * kD + gt, lt > 0.0f ? ot / lt : 0.0f);
     }
     if (mine && orow)
-        for (int j = kk + gt; j < a.k; j += kGroupThreads) orow[j] = -1;
+        for (int j = kk + gt; j < kfree; j += kGroupThreads) orow[j] = -1;
     SIK_TL_ANY(47);
     }
     // leave the head's counters at zero for the next call; the block's first head also clears the arrival counter
@@ -1202,12 +1265,15 @@ static hipError_t launch_step_t(const Dims& d, int T, int nchunk, size_t dyn, co
 
 hipError_t launch_step(const Dims& d, const Workspace& w, int T, int nchunk, size_t dyn, int listcap, const void* q,
                        const Append& ap, const float* codebook, const uint8_t* codes, int32_t* seq_len,
-                       const void* K, const void* V, const void* kvq, const float* alpha, int k, int k_per_mille,
-                       float scale, int spin_limit, int32_t* idx_out, void* out, hipStream_t s) {
+                       const void* K, const void* V, const void* kvq, const float* alpha, int k, const StepOptions& fo,
+                       float scale, int32_t* idx_out, void* out, hipStream_t s) {
     StepArgs a{};
-    a.k_per_mille = k_per_mille;
+    a.k_per_mille = fo.k_per_mille;
+    const int spin_limit = fo.spin_limit;
     a.k_new = ap.k_new, a.v_new = ap.v_new, a.Kw = ap.K, a.Vw = ap.V, a.mu = ap.mu, a.codes_w = ap.codes;
     a.kvq = static_cast<const uint2*>(kvq), a.kvq_w = static_cast<uint2*>(ap.kvq), a.alpha = alpha;
+    a.forced_idx = fo.idx, a.n_forced = fo.n, a.fK = fo.fK, a.fV = fo.fV;
+    if (fo.mu) a.mu = fo.mu;  // (the same vector the append uses)
     a.parthist = w.parthist, a.pool = w.cand, a.partial = w.partial, a.scores = w.scores, a.sync = w.sync;
     a.idx_out = idx_out, a.idx_ws = w.idx, a.out = out;
     a.sstride = w.sstride, a.k = k, a.spin_limit = spin_limit > 0 ? spin_limit : (1 << 20), a.listcap = listcap;

@@ -55,7 +55,11 @@ def check_sets(g_idx, ref_idx, s_ref, forced, sl, k, R):
     return n_diff
 
 
-def run_rows(oracle, cfg, capacity, steps, append, n_forced, seq_len=None, seed=1):
+# launches = 1: the one-launch step whenever its plan allows (the library takes it for large launches only)
+BOTH_PATHS = pytest.mark.parametrize("launches", [0, 1], ids=["auto", "one_launch"])
+
+
+def run_rows(oracle, cfg, capacity, steps, append, n_forced, seq_len=None, seed=1, launches=0):
     st = GpuState(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=0.8, out_dtype=torch.float32)
     B, Hq, k = cfg.batch, cfg.n_q_heads, cfg.top_k
     R = Hq // cfg.n_kv_heads
@@ -70,8 +74,9 @@ def run_rows(oracle, cfg, capacity, steps, append, n_forced, seq_len=None, seed=
         sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), k_new=dev(kn, cfg.dtype) if append else None,
                                v_new=dev(vn, cfg.dtype) if append else None, K=st.dK, V=st.dV, seq_len=st.dsl,
                                mu=st.dmu, codebook=st.dcb, codes=st.dcodes, k=k, out=out, idx_out=idx,
-                               forced_idx=torch.from_numpy(forced).cuda(), workspace=st.ws)
+                               forced_idx=torch.from_numpy(forced).cuda(), workspace=st.ws, launches=launches)
         sync()
+        assert sik.sik_workspace_status(st.ws) == 0
         ref_out, ref_idx = oracle.decode_step_forced(q, kn if append else None, vn if append else None, K, V,
                                                      cfg.dtype, sl, st.mu, st.cb, codes, k, forced)
         assert np.array_equal(st.dsl.cpu().numpy(), sl)
@@ -80,30 +85,35 @@ def run_rows(oracle, cfg, capacity, steps, append, n_forced, seq_len=None, seed=
         check_attention(out.cpu().numpy().astype(np.float64), oracle.sparse_attn(q, K, V, cfg.dtype, g_idx), True)
 
 
-def test_forced_rows_c1(oracle):
-    run_rows(oracle, W.CONFIGS["C1"], 4096, steps=2, append=False, n_forced=64)
+@BOTH_PATHS
+def test_forced_rows_c1(oracle, launches):
+    run_rows(oracle, W.CONFIGS["C1"], 4096, steps=2, append=False, n_forced=64, launches=launches)
 
 
-def test_forced_rows_c2_shape_with_append(oracle):
-    run_rows(oracle, cfg_small("C2", context=9000, top_k=160), 9004, steps=3, append=True, n_forced=64)
+@BOTH_PATHS
+def test_forced_rows_c2_shape_with_append(oracle, launches):
+    run_rows(oracle, cfg_small("C2", context=9000, top_k=160), 9004, steps=3, append=True, n_forced=64, launches=launches)
 
 
-def test_forced_rows_ragged_batch_gqa8_max_set(oracle):
+@BOTH_PATHS
+def test_forced_rows_ragged_batch_gqa8_max_set(oracle, launches):
     cfg = cfg_small("C5", batch=3, n_kv_heads=2, n_q_heads=16, context=5000, top_k=300)
-    run_rows(oracle, cfg, 5008, steps=2, append=True, n_forced=128, seq_len=[5000, 40, 777])
+    run_rows(oracle, cfg, 5008, steps=2, append=True, n_forced=128, seq_len=[5000, 40, 777], launches=launches)
 
 
-def test_forced_rows_everything_selected_and_tiny_sequences(oracle):
+@BOTH_PATHS
+def test_forced_rows_everything_selected_and_tiny_sequences(oracle, launches):
     # k above the context: forced plus all the others; sequences shorter than the forced set
     cfg = cfg_small("C2", batch=3, n_kv_heads=2, n_q_heads=4, context=600, top_k=700)
-    run_rows(oracle, cfg, 704, steps=1, append=False, n_forced=16, seq_len=[600, 5, 0])
+    run_rows(oracle, cfg, 704, steps=1, append=False, n_forced=16, seq_len=[600, 5, 0], launches=launches)
 
 
-def test_forced_rows_large_launch(oracle):
+@BOTH_PATHS
+def test_forced_rows_large_launch(oracle, launches):
     # more than 2 M keys in the launch: the scoring kernel's large-launch workgroups (512 threads, two per
     # compute unit) with the forced-token bitmap, ragged lengths, append
     cfg = cfg_small("C2", batch=5, n_kv_heads=8, n_q_heads=32, context=56000, top_k=300)
-    run_rows(oracle, cfg, 56008, steps=1, append=True, n_forced=64, seq_len=[56000, 31000, 56000, 9, 44444])
+    run_rows(oracle, cfg, 56008, steps=1, append=True, n_forced=64, seq_len=[56000, 31000, 56000, 9, 44444], launches=launches)
 
 
 def test_forced_empty_set_equals_plain_step(oracle):
@@ -112,11 +122,11 @@ def test_forced_empty_set_equals_plain_step(oracle):
     q, _, _ = W.make_step_inputs(cfg, 0)
     a, b_ = torch.empty(1, 8, 128, device="cuda"), torch.empty(1, 8, 128, device="cuda")
     none = torch.full((1, 2, 8), -1, dtype=torch.int32, device="cuda")
-    # (the same kernels on both sides: a forced set always takes the scoring + selection/attention launches)
+    # (the same kernels on both sides)
     sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
                            codebook=st.dcb, codes=st.dcodes, k=128, out=a, workspace=st.ws, launches=2)
     sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
-                           codebook=st.dcb, codes=st.dcodes, k=128, out=b_, forced_idx=none, workspace=st.ws)
+                           codebook=st.dcb, codes=st.dcodes, k=128, out=b_, forced_idx=none, workspace=st.ws, launches=2)
     sync()
     assert torch.equal(a, b_)
     # the one-launch step selects the same tokens and differs only in the order of its fp32 sums
@@ -126,7 +136,7 @@ def test_forced_empty_set_equals_plain_step(oracle):
     assert float((a - b_).abs().max()) <= 2e-5 * float(a.abs().max())   # each within 1e-5 of the exact result
 
 
-def run_q2(oracle, cfg, capacity, steps, append, n_forced, side_rows, seq_len=None, seed=5):
+def run_q2(oracle, cfg, capacity, steps, append, n_forced, side_rows, seq_len=None, seed=5, launches=0):
     st = Q2State(cfg, oracle, capacity=capacity, seq_len=seq_len, offset_std=0.8, out_dtype=torch.float32)
     B, Hkv, Hq, k = cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.top_k
     R = Hq // Hkv
@@ -150,8 +160,10 @@ def run_q2(oracle, cfg, capacity, steps, append, n_forced, side_rows, seq_len=No
                                mu=st.dmu, codebook=st.dcb, codes=st.dcodes, k=k, out=out, idx_out=idx,
                                forced_idx=torch.from_numpy(forced).cuda(),
                                forced_K=dev(fK, cfg.dtype) if side_rows else None,
-                               forced_V=dev(fV, cfg.dtype) if side_rows else None, workspace=st.ws)
+                               forced_V=dev(fV, cfg.dtype) if side_rows else None, workspace=st.ws,
+                               launches=launches)
         sync()
+        assert sik.sik_workspace_status(st.ws) == 0
         ref_out, ref_idx = oracle.decode_step_q2_forced(q, kn if append else None, vn if append else None, cfg.dtype,
                                                         sl, st.mu, st.alpha, st.cb, codes, qkv, k, forced,
                                                         fK if side_rows else None, fV if side_rows else None)
@@ -174,16 +186,18 @@ def run_q2(oracle, cfg, capacity, steps, append, n_forced, side_rows, seq_len=No
         check_attention(out.cpu().numpy().astype(np.float64), ref, True)
 
 
+@BOTH_PATHS
 @pytest.mark.parametrize("side_rows", [False, True])
-def test_forced_q2_c2_shape_with_append(oracle, side_rows):
+def test_forced_q2_c2_shape_with_append(oracle, side_rows, launches):
     run_q2(oracle, cfg_small("C2", context=9000, top_k=160), 9004, steps=3, append=True, n_forced=64,
-           side_rows=side_rows)
+           side_rows=side_rows, launches=launches)
 
 
+@BOTH_PATHS
 @pytest.mark.parametrize("side_rows", [False, True])
-def test_forced_q2_ragged_batch_fp16(oracle, side_rows):
+def test_forced_q2_ragged_batch_fp16(oracle, side_rows, launches):
     cfg = cfg_small("C4", batch=4, n_kv_heads=2, n_q_heads=8, context=2048, top_k=200, dtype="fp16")
-    run_q2(oracle, cfg, 2052, steps=2, append=True, n_forced=100, side_rows=side_rows, seq_len=[2048, 3, 511, 0])
+    run_q2(oracle, cfg, 2052, steps=2, append=True, n_forced=100, side_rows=side_rows, seq_len=[2048, 3, 511, 0], launches=launches)
 
 
 def test_forced_argument_errors(oracle):
@@ -221,7 +235,7 @@ def test_budget_per_mille_ragged_batch(oracle, per_mille, n_forced, launches):
     sik.sik_decode_step_ex(st.layout, q=dev(q, cfg.dtype), K=st.dK, V=st.dV, seq_len=st.dsl, mu=st.dmu,
                            codebook=st.dcb, codes=st.dcodes, k=500, k_per_mille=per_mille, out=out, idx_out=idx,
                            forced_idx=torch.from_numpy(forced).cuda() if n_forced else None, workspace=st.ws,
-                           launches=launches)   # (a forced set always runs as two launches)
+                           launches=launches)
     sync()
     sl = st.sl.copy()
     ref_out, ref_idx = oracle.decode_step_forced(q, None, None, st.K, st.V, cfg.dtype, sl, st.mu, st.cb, st.codes, 500,
