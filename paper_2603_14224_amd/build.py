@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsik.so")
-SOURCES = ["sik_api.hip", "sik_quantize.hip", "sik_score.hip", "sik_topk.hip", "sik_attn.hip", "sik_fused.hip", "sik_kvq.hip", "sik_step.hip"]
+SOURCES = ["sik_api.hip", "sik_quantize.hip", "sik_score.hip", "sik_topk.hip", "sik_attn.hip", "sik_fused.hip", "sik_kvq.hip", "sik_step.hip", "sik_step_bf16.hip", "sik_step_f16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",
          # the first kernel arguments arrive in scalar registers with the wavefront instead of through a load
@@ -30,7 +30,7 @@ def build(verbose: bool = False, defines=(), lib: str = LIB, objdir_name: str = 
             raise RuntimeError("hipcc failed on " + src)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(10, len(SOURCES))) as ex:
         objs = list(ex.map(cc, SOURCES))
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs],
                        capture_output=True, text=True)

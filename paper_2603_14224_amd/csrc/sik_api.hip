@@ -370,8 +370,8 @@ static int decode_step_impl(const sik_layout* layout, const void* q, const void*
         step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), true, false, &step_nchunk, &step_dyn,
                            &step_listcap);
     if (one_launch && step_T == 0)
-        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), false, kvq != nullptr, &step_nchunk,
-                           &step_dyn, &step_listcap);
+        step_T = step_plan(d, k, k_new != nullptr, device_compute_units(), false, kvq != nullptr || opt.n > 0,
+                           &step_nchunk, &step_dyn, &step_listcap);
     if (step_T > 0) {
         const Append ap{static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
                         static_cast<uint16_t*>(K), static_cast<uint16_t*>(V), mu, codes, alpha, kvq};
