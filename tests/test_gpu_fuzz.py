@@ -1,5 +1,6 @@
 """Seeded random shapes through the general decode step against the CPU oracle: batch, GQA ratio, ragged lengths,
-budget, cache format, append, forced sets and context-proportional budgets drawn together, a few steps each.
+budget, cache format, append, forced sets, context-proportional budgets and the launch structure drawn together, a
+few steps each.
 Same bars as the hand-picked cases (tests/test_gpu_parity.py, tests/test_gpu_kvq.py, tests/test_gpu_forced.py)."""
 import numpy as np
 import pytest
@@ -31,10 +32,12 @@ def draw_case(seed):
         nf = 0
     return dict(seed=seed, hkv=hkv, R=R, B=B, L=L, k=k, append=append, cap=cap, nf=nf,
                 q2=bool(r.integers(0, 2)), side=bool(r.integers(0, 2)), pm=int(r.choice([0, 0, 75, 500])),
-                dtype=str(r.choice(["bf16", "fp16"])), lens=[int(x) for x in r.integers(0, L + 1, B)])
+                dtype=str(r.choice(["bf16", "fp16"])), lens=[int(x) for x in r.integers(0, L + 1, B)],
+                # 0: the library's choice; 1: one launch whenever the plan allows; 3: with the 16-bit first pass
+                launches=int(np.random.default_rng(5000 + seed).choice([0, 1, 1, 3])))
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_decode_cases(oracle, seed):
     c = draw_case(seed)
     print(c)
@@ -67,7 +70,8 @@ def test_random_decode_cases(oracle, seed):
                     fK[b, h, :m], fV[b, h, :m] = st.K[b, h, forced[b, h, :m]], st.V[b, h, forced[b, h, :m]]
         kw = dict(q=dev(q, cfg.dtype), k_new=dev(kn, cfg.dtype) if ap else None, v_new=dev(vn, cfg.dtype) if ap else None,
                   seq_len=st.dsl, mu=st.dmu, codebook=st.dcb, codes=st.dcodes, k=k, k_per_mille=c["pm"], out=out,
-                  idx_out=idx, workspace=st.ws, forced_idx=torch.from_numpy(forced).cuda() if nf else None)
+                  idx_out=idx, workspace=st.ws, forced_idx=torch.from_numpy(forced).cuda() if nf else None,
+                  launches=c["launches"])
         if q2:
             kw.update(kvq=kvq, alpha=dal)
             if side:
@@ -76,6 +80,7 @@ def test_random_decode_cases(oracle, seed):
             kw.update(K=st.dK, V=st.dV)
         sik.sik_decode_step_ex(st.layout, **kw)
         sync()
+        assert sik.sik_workspace_status(st.ws) == 0
         if q2:
             # the oracle's budget rule lives in decode_step_forced / topk_with_forced; reuse it for both formats
             if ap:
