@@ -27,10 +27,10 @@ HBM_PEAK_GBPS = 8000.0
 # each; counter units x the factor a 256 MiB plain copy calibrates there).  Workloads or variants without such a
 # run report null.
 MEASURED_TRAFFIC = {
-    ("C2", "select_attend_kernel"): (29476564, "profiles/decode_step_two_launches_C2_C3.md"),
-    ("C3", "select_attend_kernel"): (58727360, "profiles/decode_step_two_launches_C2_C3.md"),
-    ("C4", "step_kernel"): (335017825, "profiles/decode_step_one_launch_C4_C5.md"),
-    ("C5", "step_kernel"): (277503376, "profiles/decode_step_one_launch_C4_C5.md"),
+    ("C2", "select_attend_kernel"): (29488988, "profiles/decode_step_two_launches_C2_C3.md"),
+    ("C3", "select_attend_kernel"): (58730732, "profiles/decode_step_two_launches_C2_C3.md"),
+    ("C4", "step_kernel"): (335015269, "profiles/decode_step_one_launch_C4_C5.md"),
+    ("C5", "step_kernel"): (277505678, "profiles/decode_step_one_launch_C4_C5.md"),
 }
 # execution times returned by sik_decode_step_profiled, in launch order: small launches run scoring, then fused
 # selection + attention; large ones run as one launch, reported in the last slot and named step_kernel here
