@@ -54,7 +54,7 @@ typedef enum {
     SIK_ERR_CAPACITY = -5,  /* token range outside [0, max_len]                              */
     SIK_ERR_WORKSPACE = -6, /* workspace NULL, misaligned or smaller than sik_workspace_bytes */
     SIK_ERR_LAUNCH = -7,    /* the HIP runtime reported an error while enqueueing           */
-    SIK_ERR_FLAGS = -8,     /* unknown quantiser mode                                        */
+    SIK_ERR_FLAGS = -8,     /* unknown quantiser mode, or an option value out of range      */
     SIK_ERR_STATIC_LIMIT = -9 /* sik_decode_step_static: the layout needs more scratch memory than the
                                  library's built-in buffer holds (SIK_STATIC_SCRATCH_BYTES)       */
 } sik_status;

@@ -117,7 +117,7 @@ const char* sik_strerror(int status) {
         case SIK_ERR_CAPACITY: return "token range outside [0, max_len]";
         case SIK_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or smaller than sik_workspace_bytes";
         case SIK_ERR_LAUNCH: return "HIP runtime error while enqueueing";
-        case SIK_ERR_FLAGS: return "unknown quantiser mode";
+        case SIK_ERR_FLAGS: return "unknown quantiser mode, or an option that does not apply (launches, spin_limit, side rows)";
         case SIK_ERR_STATIC_LIMIT:
             return "sik_decode_step_static: this layout / k needs more scratch memory than the library's built-in "
                    "buffer (SIK_STATIC_SCRATCH_BYTES); use sik_decode_step with a workspace";

@@ -77,6 +77,47 @@ def test_argument_errors_are_reported_before_any_launch():
                                FAKE, 1 << 30, None) == -1
 
 
+def test_argument_block_and_workspace_calls_validate_on_the_host():
+    lib = sik.lib()
+    lay = L()
+    ref = ctypes.byref(lay)
+    f = FAKE.value
+    base = dict(q=f, K=f, V=f, seq_len=f, mu=f, codebook=f, codes=f, k=16, out=f, workspace=f,
+                workspace_bytes=1 << 30)
+
+    def call(**kw):
+        a = sik.DecodeArgs(**{**base, **kw})
+        return lib.sik_decode_step_ex(ref, ctypes.byref(a))
+
+    assert lib.sik_decode_step_ex(ref, None) == -1
+    assert call(launches=4) == -8 and call(launches=-1) == -8 and call(spin_limit=-5) == -8
+    assert call(q=None, launches=1) == -1
+    assert call(k=0, launches=3) == -4
+    assert call(k_per_mille=1001) == -4
+    assert call(n_forced=4) == -1                       # a forced set without its indices
+    assert call(n_forced=200, forced_idx=f) == -2       # more than 128 forced tokens
+    assert call(n_forced=16, forced_idx=f, k=16) == -4  # the budget counts the forced tokens
+    assert call(forced_K=f, forced_V=f, n_forced=4, forced_idx=f) == -8   # side rows go with the 2-bit cache
+    assert call(K=None, V=None, kvq=f) == -1            # records without alpha
+    assert call(workspace_bytes=64, launches=1) == -6
+    # workspace initialisation and status
+    assert lib.sik_workspace_init(ref, 16, None, 1 << 30, None) == -6
+    assert lib.sik_workspace_init(ref, 16, FAKE, 64, None) == -6
+    assert lib.sik_workspace_init(ref, 5000, FAKE, 1 << 30, None) == -4
+    st = ctypes.c_uint32(0)
+    assert lib.sik_workspace_status(None, None, ctypes.byref(st)) == -1
+    assert lib.sik_workspace_status(FAKE, None, None) == -1
+    # prefill compression
+    assert lib.sik_prefill_compress(ref, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == -1
+    assert lib.sik_prefill_compress(ref, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 64, None) == -6
+    assert lib.sik_prefill_compress(ctypes.byref(L(head_dim=64)), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                    FAKE, 1 << 30, None) == -2
+    # the entry point on the built-in buffer rejects what does not fit before touching a device
+    big = L(batch=32, max_len=16384)
+    assert lib.sik_decode_step_static(ctypes.byref(big), FAKE, None, None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 512, 0.0,
+                                      FAKE, None, None) == -9
+
+
 def test_binding_raises_on_error_status():
     import torch
     lay = L()
