@@ -91,8 +91,10 @@ int sik_version(void);
  * chunk, [2] blocks of up to 4 query heads per KV head, [3] chunks per row of the stand-alone histogram pass of
  * sik_topk, [4] tokens per such chunk, [5] chunks per query head of the fused selection + attention launch (0: max_len
  * is beyond that path), [6] tokens per such chunk, [7] tokens per thread of the one-launch decode step on the
- * current device (its chunks hold 1024 times that; 0: the plain step of this layout takes two launches).  Every chunk holds at most 64512 tokens and
- * there are at most 64 per head; a layout that cannot be cut that way is SIK_ERR_SHAPE here and in every other call. */
+ * current device (its chunks hold 1024 times that; 0: no one-launch plan fits this layout, the step always runs as
+ * separate launches; sik_decode_step takes the one-launch step only for large launches, sik_decode_args.launches
+ * chooses).  Every chunk holds at most 64512 tokens and there are at most 64 per head; a layout that cannot be cut
+ * that way is SIK_ERR_SHAPE here and in every other call. */
 #define SIK_PLAN_INFO_LEN 8
 int sik_plan_info(const sik_layout *layout, int32_t *info);
 
