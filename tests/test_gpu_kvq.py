@@ -319,6 +319,61 @@ def test_decode_q2_graph_replay_and_profiled(oracle):
         assert torch.equal(torch.sort(idx, dim=-1).values, eager_idx), r
 
 
+@pytest.mark.parametrize("forced", [False, True])
+def test_decode_q2_one_launch_graph_replay_with_append(oracle, forced):
+    # the one-launch step on records (and with a forced set that names the appended token) under graph replay: its
+    # counters are left at zero by every replay, the appended record and the published length are the eager ones
+    cfg = cfg_small("C3", context=20000, top_k=600)
+    st = Q2State(cfg, oracle, capacity=20008, out_dtype=torch.float32)
+    kvq0 = torch.from_numpy(st.records()).cuda()
+    kvq, dal = kvq0.clone(), torch.from_numpy(st.alpha).cuda()
+    q, kn, vn = W.make_step_inputs(cfg, 0)
+    dq, dkn, dvn = dev(q, cfg.dtype), dev(kn, cfg.dtype), dev(vn, cfg.dtype)
+    out = torch.empty(1, 32, 128, device="cuda")
+    idx = torch.empty(1, 32, 600, dtype=torch.int32, device="cuda")
+    fidx = None
+    if forced:
+        f = np.tile(np.arange(0, 64 * 300, 300, dtype=np.int32), (1, 8, 1))
+        f[:, :, 0] = 20000                       # the token being appended
+        fidx = torch.from_numpy(f).cuda()
+
+    def body(launches=1):
+        st.dsl.fill_(20000)
+        sik.sik_decode_step_ex(st.layout, q=dq, k_new=dkn, v_new=dvn, kvq=kvq, alpha=dal, seq_len=st.dsl, mu=st.dmu,
+                               codebook=st.dcb, codes=st.dcodes, k=600, out=out, idx_out=idx, workspace=st.ws,
+                               forced_idx=fidx, launches=launches)
+
+    body(launches=2)
+    sync()
+    ref_out, ref_idx, ref_rec = out.clone(), torch.sort(idx, dim=-1).values.clone(), kvq[:, :, 20000].clone()
+    kvq.copy_(kvq0)
+    body()
+    sync()
+    assert sik.sik_workspace_status(st.ws) == 0 and int(st.dsl[0]) == 20001
+    eager_out = out.clone()
+    assert torch.equal(torch.sort(idx, dim=-1).values, ref_idx) and torch.equal(kvq[:, :, 20000], ref_rec)
+    assert float((eager_out - ref_out).abs().max()) <= 2e-5 * float(ref_out.abs().max())
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        body()
+        sync()
+        with torch.cuda.graph(g, stream=side):
+            body()
+    sync()
+    for r in range(3):
+        out.zero_()
+        idx.fill_(-3)
+        kvq.copy_(kvq0)
+        torch.randn(1 << 20, device="cuda").sum().item()
+        g.replay()
+        sync()
+        assert sik.sik_workspace_status(st.ws) == 0 and int(st.dsl[0]) == 20001
+        assert torch.equal(out, eager_out), r
+        assert torch.equal(torch.sort(idx, dim=-1).values, ref_idx), r
+        assert torch.equal(kvq[:, :, 20000], ref_rec), r
+
+
 def test_decode_q2_rejects_contexts_without_a_fused_plan(oracle):
     lay = sik.make_layout(1, 1, 1, 128, 600000, torch.bfloat16, torch.float32)
     ws = sik.alloc_workspace(lay, 16)
