@@ -466,7 +466,7 @@ def cpu_baseline(cfg, host0, budget_s, q2=False):
             one(q, None, None)
         t_total += time.perf_counter() - t
         n += 1
-        if t_total >= budget_s or n >= 64:
+        if t_total >= budget_s or n >= 128:  # (128 steps of the 32K workload: about 18 core-seconds)
             break
     oracle.set_threads(1)
     res = {"value": round(t_total / n * 1e6, 1), "unit": "us/step", "cores": used, "kind": "oracle",
