@@ -47,8 +47,8 @@ def parse():
     ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "T4"])
     ap.add_argument("--also", default=None,
                     help="comma-separated further workloads measured the same way and nested under \"also\" "
-                         "(default: C3, the 128K context of the metric, when --config is C2 and no variant is on; "
-                         "\"none\" switches it off)")
+                         "(default: C3, the 128K context of the metric, and C4, the large batch that takes the "
+                         "one-launch step, when --config is C2 and no variant is on; \"none\" switches it off)")
     ap.add_argument("--layers", type=int, default=0, help="distinct layer states to rotate over (0 = auto)")
     ap.add_argument("--no-graph", action="store_true", help="time plain stream launches only, no HIP-graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -93,7 +93,7 @@ def main():
     if args.fit:
         return bench_fit(args)
     variant = args.kv != "rows" or args.forced or args.shared
-    also = args.also if args.also is not None else ("C3" if args.config == "C2" and not variant else "none")
+    also = args.also if args.also is not None else ("C3,C4" if args.config == "C2" and not variant else "none")
     result = bench_decode(args, args.config, cpu=not args.no_cpu_baseline and not args.forced and not args.shared)
     extra = [bench_decode(args, name, cpu=False) for name in also.split(",") if name not in ("", "none", args.config)]
     if extra:
